@@ -1,0 +1,394 @@
+"""CPU-only pins of the oracle against what the paper and the mathematics fix.
+
+Each test names the equation or passage it holds the oracle to.  None of them
+re-types the oracle's own code path: they use closed forms, a dense-graph brute
+force written separately (tests/bruteforce_dense.py), library routines, special
+cases and a hand-worked example (tests/golden/hand_worked_6node.txt).
+"""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2509_00388_amd import synth
+from tests import bruteforce_dense as bf
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def tiny_cfg(**kw):
+    base = dict(n_tokens=56, window=8, n_kv_heads=2, n_q_heads=4, head_dim=16, pool_kernel=3,
+                budget=20, n_sources=4, n_neighbors=3, rounds=2, n_centroids=5)
+    base.update(kw)
+    return synth.scaled(synth.CONFIGS["c1"], **base)
+
+
+def f64(x, dtype):
+    return synth.storage_to_f64(x, dtype)
+
+
+# ------------------------------------------------------------------ top-k ---
+
+def test_topk_ties_go_to_lowest_index(oracle):
+    x = np.array([1.0, 3.0, 3.0, 2.0, 3.0, 0.5])
+    idx, gap = oracle.topk(x, 2)
+    assert idx.tolist() == [1, 2] and gap == 0.0
+    idx, _ = oracle.topk(x, 4)
+    assert idx.tolist() == [1, 2, 3, 4]
+    idx, _ = oracle.topk(x, 3, skip=1)
+    assert idx.tolist() == [2, 3, 4]
+    idx, gap = oracle.topk(x, 6)
+    assert idx.tolist() == list(range(6)) and gap == np.inf
+    # -0.0 and +0.0 are the same value: the lower index wins
+    idx, _ = oracle.topk(np.array([-1.0, 0.0, -0.0, -2.0]), 1)
+    assert idx.tolist() == [1]
+    idx, _ = oracle.topk(np.array([-1.0, -0.0, 0.0, -2.0]), 1)
+    assert idx.tolist() == [1]
+
+
+def test_topk_matches_stable_argsort(oracle):
+    rng = np.random.default_rng(7)
+    for _ in range(20):
+        n = int(rng.integers(1, 200))
+        x = rng.integers(0, 12, size=n).astype(np.float64)       # many ties
+        k = int(rng.integers(0, n + 1))
+        idx, _ = oracle.topk(x, k)
+        assert idx.tolist() == sorted(bf.stable_topk(x, k))
+
+
+# ---------------------------------------------------------------- stage I ---
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("pool_mode", [0, 1])
+def test_score_equals_library_softmax(oracle, dtype, pool_mode):
+    """Stage I against scipy's softmax with an explicit causal mask."""
+    cfg = tiny_cfg(dtype=dtype)
+    K, V, Q = synth.make_layer(cfg, 0)
+    s = oracle.score(K, Q, dtype, cfg.pool_kernel, pool_mode)
+    G = cfg.n_q_heads // cfg.n_kv_heads
+    for h in range(cfg.n_kv_heads):
+        ref = bf.score_dense(f64(K[h], dtype), f64(Q[h * G:(h + 1) * G], dtype), cfg.window,
+                             cfg.pool_kernel, pool_mode)
+        np.testing.assert_allclose(s[h], ref, rtol=1e-12, atol=1e-15)
+
+
+def test_score_zero_queries_closed_form(oracle):
+    """All-zero queries: every visible column gets 1/(P+r+1) from row r."""
+    cfg = tiny_cfg()
+    K, V, Q = synth.make_layer(cfg, 0)
+    Q[:] = 0
+    P, w, k = cfg.n_prefix, cfg.window, cfg.pool_kernel
+    s, votes = oracle.score(K, Q, "fp32", k, 0, want_votes=True)
+    const = sum(1.0 / (P + r + 1) for r in range(w))
+    np.testing.assert_allclose(votes, const, rtol=1e-13)
+    half = (k - 1) // 2
+    taps = np.array([min(j + half, P - 1) - max(j - half, 0) + 1 for j in range(P)])
+    np.testing.assert_allclose(s, np.broadcast_to(const * taps / k, s.shape), rtol=1e-13)
+
+
+def test_score_invariants(oracle):
+    """Softmax rows sum to one, so the votes of a query head sum to at most w;
+    scores are non-negative; a row shift of the logits changes nothing."""
+    cfg = tiny_cfg(dtype="bf16")
+    K, V, Q = synth.make_layer(cfg, 3)
+    s, votes = oracle.score(K, Q, "bf16", 1, 0, want_votes=True)
+    assert (votes >= 0).all() and (s >= 0).all()
+    assert (votes.sum(axis=1) <= cfg.window + 1e-12).all()
+    assert (votes.sum(axis=1) > 0).all()
+    # the last window row sees every column; with one row only, votes + window part = 1
+    cfg1 = tiny_cfg(window=1, n_tokens=40)
+    K, V, Q = synth.make_layer(cfg1, 0)
+    _, votes = oracle.score(K, Q, "fp32", 1, 0, want_votes=True)
+    G = cfg1.n_q_heads // cfg1.n_kv_heads
+    for q in range(cfg1.n_q_heads):
+        k = f64(K[q // G], "fp32")
+        logit = (k @ f64(Q[q, 0], "fp32")) / np.sqrt(cfg1.head_dim)
+        p_last = np.exp(logit[-1] - np.logaddexp.reduce(logit))
+        assert abs(votes[q].sum() + p_last - 1.0) < 1e-12
+
+
+def test_score_causal_mask_hides_later_window_keys(oracle):
+    """Changing window key P+r must not change the weights of rows r' < r."""
+    cfg = tiny_cfg(window=4, n_tokens=30, n_kv_heads=1, n_q_heads=1)
+    K, V, Q = synth.make_layer(cfg, 0)
+    P = cfg.n_prefix
+    Q2 = Q.copy()
+    Q2[:, 1:, :] = 0                      # only row 0 carries signal
+    _, v_a = oracle.score(K, Q2, "fp32", 1, 0, want_votes=True)
+    K2 = K.copy()
+    K2[0, P + 1:, :] *= 50.0              # keys only rows >= 1 may see
+    _, v_b = oracle.score(K2, Q2, "fp32", 1, 0, want_votes=True)
+    np.testing.assert_allclose(v_a, v_b, rtol=1e-13)
+    K3 = K.copy()
+    K3[0, P, :] *= 3.0                    # row 0 does see its own position
+    _, v_c = oracle.score(K3, Q2, "fp32", 1, 0, want_votes=True)
+    assert np.abs(v_a - v_c).max() > 1e-6
+
+
+def test_score_custom_scale_and_gqa_mean(oracle):
+    cfg = tiny_cfg(n_kv_heads=1, n_q_heads=4)
+    K, V, Q = synth.make_layer(cfg, 0)
+    s = oracle.score(K, Q, "fp32", 3, 0, scale=0.37)
+    ref = bf.score_dense(f64(K[0], "fp32"), f64(Q, "fp32"), cfg.window, 3, 0, scale=0.37)
+    np.testing.assert_allclose(s[0], ref, rtol=1e-12)
+    # group mean: scoring each query head alone and averaging gives the same
+    parts = [oracle.score(K, Q[g:g + 1].copy(), "fp32", 3, 0, scale=0.37)[0] for g in range(4)]
+    np.testing.assert_allclose(s[0], np.mean(parts, axis=0), rtol=1e-12)
+
+
+def test_knorm_score(oracle):
+    cfg = tiny_cfg(dtype="bf16")
+    K, _, _ = synth.make_layer(cfg, 0)
+    s = oracle.score_knorm(K, "bf16", cfg.window)
+    ref = -np.linalg.norm(f64(K, "bf16")[:, :cfg.n_prefix], axis=2)
+    np.testing.assert_allclose(s, ref, rtol=1e-13)
+
+
+# ------------------------------------------------------- stages II and III ---
+
+def test_cosine_row_against_numpy(oracle):
+    cfg = tiny_cfg(dtype="bf16")
+    K, _, _ = synth.make_layer(cfg, 1)
+    P = cfg.n_prefix
+    k = f64(K[1], "bf16")[:P]
+    E = bf.dense_cosine(k)
+    for i in (0, 5, P - 1):
+        e = oracle.cosine_row(K, "bf16", cfg.window, 1, i)
+        ref = E[i].copy(); ref[i] = 0.0
+        np.testing.assert_allclose(e, ref, rtol=1e-13, atol=1e-15)
+        assert abs(E[i, i] - 1.0) < 1e-12
+
+
+def test_hand_worked_example(oracle):
+    """tests/golden/hand_worked_6node.txt: Eq. 1, 3, 5 worked by hand."""
+    keys = np.array([[1, 0], [4, 3], [3, 4], [0, 1], [-1, 0], [8, 6]], dtype=np.float32)
+    s0 = np.array([[1.0, 0.9, 0.8, 0.5, 0.45, 0.7]])
+    K = np.concatenate([keys, np.ones((1, 2), np.float32)])[None]      # one window token
+    rows = [l.split() for l in open(os.path.join(GOLD, "hand_worked_6node.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        S, m = int(r[1]), int(r[2])
+        want = np.array([float(x) for x in r[3:9]])
+        keep = [int(x) for x in r[9:12]]
+        s, dbg = oracle.propagate(K, "fp32", 1, s0, S, m, 1, alpha=1.0, debug=True)
+        np.testing.assert_allclose(s[0], want, rtol=0, atol=1e-12)
+        idx, _ = oracle.select(s, 7, 1, 4)
+        assert idx[0].tolist() == keep + [6]
+    # the edge weights themselves (case iii: e01 = 0.8, e15 = 1.0)
+    s, dbg = oracle.propagate(K, "fp32", 1, s0, 2, 1, 1, debug=True)
+    assert dbg["src"][0, 0].tolist() == [0, 1]
+    assert dbg["nbr"][0, 0].ravel().tolist() == [1, 5]
+    np.testing.assert_allclose(dbg["e"][0, 0].ravel(), [0.8, 1.0], atol=1e-15)
+
+
+@pytest.mark.parametrize("reselect", [0, 1])
+@pytest.mark.parametrize("signal", [0, 1, 2])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_propagate_equals_dense_bruteforce(oracle, reselect, signal, dtype):
+    """Eq. 1-5 on the full P x P graph, literal set semantics, tiny P."""
+    cfg = tiny_cfg(dtype=dtype, n_tokens=48, window=6)
+    K, _, _ = synth.make_layer(cfg, 2)
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    for (S, m, T, alpha) in [(4, 3, 1, 1.0), (5, 6, 3, 0.6), (1, 41, 2, 1.0), (42, 2, 2, 0.9)]:
+        s = oracle.propagate(K, dtype, cfg.window, s0, S, m, T, alpha, reselect, signal)
+        for h in range(cfg.n_kv_heads):
+            ref = bf.propagate_dense(f64(K[h], dtype)[:cfg.n_prefix], s0[h], S, m, T, alpha,
+                                     reselect, signal)
+            np.testing.assert_allclose(s[h], ref, rtol=1e-12, atol=0)
+
+
+def test_bruteforce_with_ties(oracle):
+    """Exact duplicate keys and equal scores: the tie rule decides everything."""
+    rng = np.random.default_rng(11)
+    base = rng.integers(-2, 3, size=(6, 4)).astype(np.float32)
+    base[np.abs(base).sum(axis=1) == 0, 0] = 1
+    keys = base[rng.integers(0, 6, size=30)]                     # many exact duplicates
+    K = np.concatenate([keys, np.ones((2, 4), np.float32)])[None]
+    s0 = rng.integers(1, 5, size=(1, 30)).astype(np.float64)     # many equal scores
+    for (S, m, T) in [(3, 4, 2), (7, 2, 3)]:
+        s = oracle.propagate(K, "fp32", 2, s0, S, m, T, 0.5, 1, 0)
+        ref = bf.propagate_dense(keys.astype(np.float64), s0[0], S, m, T, 0.5, 1, 0)
+        np.testing.assert_allclose(s[0], ref, rtol=1e-12)
+
+
+def test_fixed_graph_closed_form_and_T1_equivalence(oracle):
+    """With the graph fixed from round 1, Eq. 5 gives s^(T) = s^(0) * f^T; at
+    T = 1 fixed and re-picked graphs are the same thing."""
+    cfg = tiny_cfg(dtype="bf16")
+    K, _, _ = synth.make_layer(cfg, 0)
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    s1 = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 1, 0.8, reselect=0)
+    s1b = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 1, 0.8, reselect=1)
+    assert np.array_equal(s1, s1b)
+    f = s1 / s0
+    s3 = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 3, 0.8, reselect=0)
+    np.testing.assert_allclose(s3, s0 * f ** 3, rtol=1e-13)
+    # re-picking really differs on this input (otherwise the pin is vacuous)
+    s3r = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 3, 0.8, reselect=1)
+    assert not np.allclose(s3, s3r)
+
+
+def test_orthogonal_keys_propagation_is_identity(oracle):
+    P, w = 24, 2
+    K = np.zeros((1, P + w, 32), np.float32)
+    for j in range(P + w):
+        K[0, j, j] = 1.0 + j
+    s0 = synth.random_scores(tiny_cfg(n_kv_heads=1, n_tokens=P + w, window=w)).astype(np.float64)
+    s = oracle.propagate(K, "fp32", w, s0, 5, 4, 3, 1.0)
+    assert np.array_equal(s, s0)
+
+
+def test_exact_duplicate_of_source_is_zeroed(oracle):
+    cfg = tiny_cfg(n_kv_heads=1, n_q_heads=1)
+    K, _, _ = synth.make_layer(cfg, 0)
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    top = int(np.argmax(s0[0]))
+    dup = (top + 7) % cfg.n_prefix
+    K[0, dup] = 2.0 * K[0, top]                               # same direction: e = 1
+    s = oracle.propagate(K, "fp32", cfg.window, s0, 1, 1, 1, 1.0)
+    assert abs(s[0, dup]) < 1e-15 * s0[0, dup] + 1e-18
+    changed = np.flatnonzero(s[0] != s0[0])
+    assert changed.tolist() == [dup]
+
+
+def test_scale_invariance_and_bounds(oracle):
+    """Eq. 1 is a cosine: positive row scalings change nothing.  With e in
+    [0,1] and alpha in [0,1] no score grows and at most S*m change per round."""
+    cfg = tiny_cfg(dtype="fp32", n_kv_heads=1, n_q_heads=1)
+    K, _, _ = synth.make_layer(cfg, 4)
+    K = np.abs(K)                                             # all cosines >= 0
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    S, m = 4, 3
+    s = oracle.propagate(K, "fp32", cfg.window, s0, S, m, 1, 0.7)
+    assert (s <= s0).all()
+    assert np.count_nonzero(s != s0) <= S * m
+    K2 = K.copy()
+    K2[0] *= (2.0 ** (np.arange(K.shape[1]) % 5))[:, None].astype(np.float32)   # exact in fp32
+    s2 = oracle.propagate(K2, "fp32", cfg.window, s0, S, m, 1, 0.7)
+    np.testing.assert_allclose(s2, s, rtol=1e-12)
+
+
+def test_permutation_equivariance(oracle):
+    cfg = tiny_cfg(n_kv_heads=1, n_q_heads=1)
+    K, _, _ = synth.make_layer(cfg, 5)
+    P = cfg.n_prefix
+    s0 = synth.random_scores(cfg).astype(np.float64)           # no ties (random floats)
+    perm = np.random.default_rng(3).permutation(P)
+    Kp = K.copy(); Kp[0, :P] = K[0, perm]
+    sp0 = s0[:, perm]
+    a = oracle.propagate(K, "fp32", cfg.window, s0, 4, 3, 2, 1.0)
+    b = oracle.propagate(Kp, "fp32", cfg.window, sp0, 4, 3, 2, 1.0)
+    np.testing.assert_allclose(b[0], a[0, perm], rtol=1e-12)
+
+
+def test_forced_sources(oracle):
+    cfg = tiny_cfg()
+    K, _, _ = synth.make_layer(cfg, 0)
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    s, dbg = oracle.propagate(K, "fp32", cfg.window, s0, 4, 3, 2, 1.0, debug=True)
+    s2, dbg2 = oracle.propagate(K, "fp32", cfg.window, s0, 4, 3, 2, 1.0, forced_src=dbg["src"], debug=True)
+    assert np.array_equal(s, s2) and np.array_equal(dbg["nbr"], dbg2["nbr"])
+
+
+# ---------------------------------------------------------------- stage IV ---
+
+def test_select_and_gather_invariants(oracle):
+    cfg = tiny_cfg(dtype="bf16")
+    K, V, Q = synth.make_layer(cfg, 0)
+    out = oracle.compress(K, V, Q, "bf16", cfg.pool_kernel, cfg.budget, 4, 3, 2)
+    idx = out["idx"]
+    N, w, B, P = cfg.n_tokens, cfg.window, cfg.budget, cfg.n_prefix
+    assert idx.shape == (cfg.n_kv_heads, B)
+    assert (np.diff(idx, axis=1) > 0).all() and idx.min() >= 0 and idx.max() < N
+    assert (idx[:, B - w:] == np.arange(P, N)).all()
+    for h in range(cfg.n_kv_heads):
+        assert np.array_equal(out["Kout"][h], K[h, idx[h]])
+        assert np.array_equal(out["Vout"][h], V[h, idx[h]])
+    # the kept prefix tokens are exactly the B-w best refined scores
+    for h in range(cfg.n_kv_heads):
+        assert idx[h, :B - w].tolist() == sorted(bf.stable_topk(out["scores"][h], B - w))
+
+
+@pytest.mark.parametrize("kw", [dict(T=0, alpha=1.0), dict(T=2, alpha=0.0)])
+def test_no_propagation_reduces_to_plain_topk(oracle, kw):
+    """T = 0 (the ablation's "no propagation") or zero decay strength leaves the
+    host method's selection untouched."""
+    cfg = tiny_cfg(dtype="bf16")
+    K, V, Q = synth.make_layer(cfg, 0)
+    out = oracle.compress(K, V, Q, "bf16", cfg.pool_kernel, cfg.budget, 4, 3, kw["T"], alpha=kw["alpha"])
+    s0 = oracle.score(K, Q, "bf16", cfg.pool_kernel)
+    assert np.array_equal(out["scores"], s0) and np.array_equal(out["s0"], s0)
+    B, w = cfg.budget, cfg.window
+    for h in range(cfg.n_kv_heads):
+        assert out["idx"][h, :B - w].tolist() == sorted(bf.stable_topk(s0[h], B - w))
+        assert np.array_equal(out["Kout"][h], K[h, out["idx"][h]])
+
+
+def test_budget_equals_n_is_identity(oracle):
+    cfg = tiny_cfg()
+    K, V, Q = synth.make_layer(cfg, 0)
+    out = oracle.compress(K, V, Q, "fp32", cfg.pool_kernel, cfg.n_tokens, 4, 3, 1)
+    assert (out["idx"] == np.arange(cfg.n_tokens)).all()
+    assert np.array_equal(out["Kout"], K) and np.array_equal(out["Vout"], V)
+
+
+def test_compress_is_the_staged_pipeline(oracle):
+    cfg = tiny_cfg(dtype="bf16")
+    K, V, Q = synth.make_layer(cfg, 6)
+    out = oracle.compress(K, V, Q, "bf16", cfg.pool_kernel, cfg.budget, 4, 3, 2, alpha=0.9)
+    s0 = oracle.score(K, Q, "bf16", cfg.pool_kernel)
+    sT = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 2, 0.9)
+    idx, gap = oracle.select(sT, cfg.n_tokens, cfg.window, cfg.budget)
+    Ko, Vo = oracle.gather(K, V, "bf16", idx)
+    assert np.array_equal(out["scores"], sT) and np.array_equal(out["idx"], idx)
+    assert np.array_equal(out["Kout"], Ko) and np.array_equal(out["Vout"], Vo)
+    assert out["min_gap"][2] == gap.min()
+
+
+def test_propagation_reduces_similarity_of_top_tokens(oracle):
+    """Statistical smoke, not a gate on exact numbers: on clustered keys the mean
+    pairwise cosine among the 10 best tokens drops after propagation (the
+    Observation section's point about redundancy among high scorers)."""
+    cfg = synth.scaled(synth.CONFIGS["c1"], key_scale=8.0)
+    K, V, Q = synth.make_layer(cfg, 0)
+    s0 = oracle.score(K, Q, "fp32", cfg.pool_kernel)
+    sT = oracle.propagate(K, "fp32", cfg.window, s0, cfg.n_sources, cfg.n_neighbors, 1, 1.0)
+
+    def mean_cos(s, h):
+        top = bf.stable_topk(s[h], 10)
+        k = f64(K[h], "fp32")[top]
+        k = k / np.linalg.norm(k, axis=1, keepdims=True)
+        c = k @ k.T
+        return (c.sum() - 10) / 90
+
+    before = np.mean([mean_cos(s0, h) for h in range(cfg.n_kv_heads)])
+    after = np.mean([mean_cos(sT, h) for h in range(cfg.n_kv_heads)])
+    assert after < before
+
+
+# ------------------------------------------------------------- generators ---
+
+def test_bf16_rounding_is_nearest_even():
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.14159], dtype=np.float32)
+    b = synth.f32_to_bf16_bits(x)
+    back = synth.bf16_bits_to_f32(b)
+    # 1 + 2^-8 is a tie between 1 and 1 + 2^-7: goes to the even mantissa (1.0)
+    assert back[0] == 1.0 and back[1] == 1.0
+    # 1 + 3*2^-8 is a tie between 1+2^-7 and 1+2^-6: even is 1+2^-6
+    assert back[2] == np.float32(1.015625)
+    assert back[3] == -2.5
+    assert abs(back[4] - 3.14159) <= 2.0 ** -7
+
+
+def test_generators_are_seeded_and_shaped():
+    cfg = synth.scaled(synth.CONFIGS["c2"], n_tokens=256)
+    a = synth.make_layer(cfg, 1)
+    b = synth.make_layer(cfg, 1)
+    c = synth.make_layer(cfg, 2)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    assert not np.array_equal(a[0], c[0])
+    assert a[0].shape == (8, 256, 128) and a[0].dtype == np.uint16 and a[2].shape == (32, 32, 128)
+    p = synth.CONFIGS["c4"]
+    assert p.budget_for_layer(0) == 4096 and p.budget_for_layer(31) == 512
+    assert p.budget_for_layer(15) == 4096 - (3584 * 15) // 31
