@@ -1,0 +1,222 @@
+"""Thin ctypes binding of libgraphkv.so (include/graphkv.h).
+
+Argument marshalling only: every step of the pass runs in the library's HIP
+kernels.  PyTorch supplies device memory and the current stream, nothing else.
+There is no fallback: if the library is missing or the GPU is absent the calls
+raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgraphkv.so")
+
+FP32, BF16 = 0, 1
+POOL_AVG, POOL_MAX = 0, 1
+SIGNAL_DECAY, SIGNAL_ENHANCED, SIGNAL_EVICTED = 0, 1, 2
+IMPL_AUTO, IMPL_GENERIC = 0, 1
+
+EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "graphkv_propagate",
+           "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma")
+
+
+class GraphKVError(RuntimeError):
+    pass
+
+
+class _CParams(ctypes.Structure):
+    _fields_ = [
+        ("n_kv_heads", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("n_tokens", ctypes.c_int32), ("window", ctypes.c_int32),
+        ("pool_kernel", ctypes.c_int32), ("pool_mode", ctypes.c_int32),
+        ("budget", ctypes.c_int32),
+        ("n_sources", ctypes.c_int32), ("n_neighbors", ctypes.c_int32), ("rounds", ctypes.c_int32),
+        ("decay", ctypes.c_float), ("reselect", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("signal", ctypes.c_int32), ("impl", ctypes.c_int32),
+    ]
+
+
+@dataclass
+class Params:
+    """Mirror of graphkv_params (see include/graphkv.h for the constraints)."""
+    n_kv_heads: int
+    n_q_heads: int
+    head_dim: int
+    n_tokens: int
+    window: int
+    pool_kernel: int = 1
+    pool_mode: int = POOL_AVG
+    budget: int = 0
+    n_sources: int = 0
+    n_neighbors: int = 0
+    rounds: int = 0
+    decay: float = 1.0
+    reselect: int = 1
+    dtype: int = BF16
+    softmax_scale: float = 0.0
+    signal: int = SIGNAL_DECAY
+    impl: int = IMPL_AUTO
+
+    @property
+    def n_prefix(self) -> int:
+        return self.n_tokens - self.window
+
+    def c(self) -> _CParams:
+        return _CParams(*(getattr(self, f[0]) for f in _CParams._fields_))
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == FP32 else torch.bfloat16
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libgraphkv.so built by paper_2509_00388_amd/build.py; raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise GraphKVError(f"{LIB_PATH} is missing: run `python -m paper_2509_00388_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+    pp = ctypes.POINTER(_CParams)
+    lib.graphkv_workspace_bytes.restype = sz
+    lib.graphkv_workspace_bytes.argtypes = [pp]
+    lib.graphkv_uses_mfma.restype = i32
+    lib.graphkv_uses_mfma.argtypes = [pp]
+    lib.graphkv_score.restype = i32
+    lib.graphkv_score.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.graphkv_score_knorm.restype = i32
+    lib.graphkv_score_knorm.argtypes = [pp, vp, vp, vp, sz, vp]
+    lib.graphkv_propagate.restype = i32
+    lib.graphkv_propagate.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.graphkv_select.restype = i32
+    lib.graphkv_select.argtypes = [pp, vp, vp, vp, sz, vp]
+    lib.graphkv_compress.restype = i32
+    lib.graphkv_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.graphkv_strerror.restype = ctypes.c_char_p
+    lib.graphkv_strerror.argtypes = [i32]
+    _lib = lib
+    return lib
+
+
+def graphkv_strerror(code: int) -> str:
+    return load_library().graphkv_strerror(code).decode()
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise GraphKVError(f"graphkv error {rc}: {graphkv_strerror(rc)}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise GraphKVError("tensors must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def graphkv_workspace_bytes(p: Params) -> int:
+    cp = p.c()
+    return int(load_library().graphkv_workspace_bytes(ctypes.byref(cp)))
+
+
+def graphkv_uses_mfma(p: Params) -> bool:
+    cp = p.c()
+    return bool(load_library().graphkv_uses_mfma(ctypes.byref(cp)))
+
+
+def alloc_workspace(p: Params, device="cuda") -> torch.Tensor:
+    n = graphkv_workspace_bytes(p)
+    if n == 0:
+        raise GraphKVError("invalid params: workspace size is 0")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def graphkv_score(p: Params, Kc, Qw, scores=None, ws=None):
+    """scores [H_kv, P] fp32 (allocated if None).  Stage I."""
+    if scores is None:
+        scores = torch.empty((p.n_kv_heads, p.n_prefix), dtype=torch.float32, device=Kc.device)
+    ws = alloc_workspace(p, Kc.device) if ws is None else ws
+    cp = p.c()
+    _check(load_library().graphkv_score(ctypes.byref(cp), _ptr(Kc), _ptr(Qw), _ptr(scores),
+                                        _ptr(ws), ws.numel(), _stream()))
+    return scores
+
+
+def graphkv_score_knorm(p: Params, Kc, scores=None, ws=None):
+    if scores is None:
+        scores = torch.empty((p.n_kv_heads, p.n_prefix), dtype=torch.float32, device=Kc.device)
+    cp = p.c()
+    _check(load_library().graphkv_score_knorm(ctypes.byref(cp), _ptr(Kc), _ptr(scores),
+                                              _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
+    return scores
+
+
+def graphkv_propagate(p: Params, Kc, scores, dbg_src=None, dbg_nbr=None, dbg_e=None, ws=None):
+    """Refines `scores` [H_kv, P] fp32 in place.  Stages II and III."""
+    ws = alloc_workspace(p, Kc.device) if ws is None else ws
+    cp = p.c()
+    _check(load_library().graphkv_propagate(ctypes.byref(cp), _ptr(Kc), _ptr(scores), _ptr(dbg_src),
+                                            _ptr(dbg_nbr), _ptr(dbg_e), _ptr(ws), ws.numel(),
+                                            _stream()))
+    return scores
+
+
+def graphkv_select(p: Params, scores, idx=None, ws=None):
+    """idx [H_kv, B] int32.  Stage IV, selection."""
+    if idx is None:
+        idx = torch.empty((p.n_kv_heads, p.budget), dtype=torch.int32, device=scores.device)
+    cp = p.c()
+    _check(load_library().graphkv_select(ctypes.byref(cp), _ptr(scores), _ptr(idx), _ptr(ws),
+                                         ws.numel() if ws is not None else 0, _stream()))
+    return idx
+
+
+def graphkv_compress(p: Params, Kc, Vc, Qw, Kout=None, Vout=None, idx=None, scores_out=None, ws=None):
+    """The whole pass for one layer.  Returns (Kout, Vout, idx)."""
+    dev = Kc.device
+    shape = (p.n_kv_heads, p.budget, p.head_dim)
+    if Kout is None:
+        Kout = torch.empty(shape, dtype=Kc.dtype, device=dev)
+    if Vout is None:
+        Vout = torch.empty(shape, dtype=Vc.dtype, device=dev)
+    if idx is None:
+        idx = torch.empty((p.n_kv_heads, p.budget), dtype=torch.int32, device=dev)
+    ws = alloc_workspace(p, dev) if ws is None else ws
+    cp = p.c()
+    _check(load_library().graphkv_compress(ctypes.byref(cp), _ptr(Kc), _ptr(Vc), _ptr(Qw), _ptr(Kout),
+                                           _ptr(Vout), _ptr(idx), _ptr(scores_out), _ptr(ws),
+                                           ws.numel(), _stream()))
+    return Kout, Vout, idx
+
+
+# ---- helpers to move the synthetic numpy tensors (fp32 / bf16 bits) to the device ----
+
+def to_device(arr, dtype: int, device="cuda") -> torch.Tensor:
+    import numpy as np
+    if dtype == FP32:
+        return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(device)
+    return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def to_host_bits(t: torch.Tensor):
+    """Device tensor -> numpy in the storage convention of synth.py."""
+    import numpy as np
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()

@@ -1,0 +1,320 @@
+// C ABI of the library (include/graphkv.h): argument checks, workspace carving
+// and the order in which the kernels of one layer call are enqueued.
+#include "../../include/graphkv.h"
+#include "kernels.hpp"
+
+#include <math.h>
+
+namespace {
+
+using namespace gkv;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
+
+struct Dims {
+    int H, Hq, G, d, N, w, P, B, S, m, T;
+    bool mfma;
+    float scale;
+    size_t esize;
+};
+
+// Workspace: a bump allocation of every scratch array any entry point may need.
+struct Workspace {
+    size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, inv_norm, part, total;
+};
+
+bool shape_allows_mfma(const graphkv_params *p)
+{
+    if (p->dtype != GRAPHKV_BF16 || p->head_dim != 128) return false;
+    const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
+    return rows % 32 == 0 && rows <= 128 && p->n_tokens - p->window >= 32;
+}
+
+bool use_mfma(const graphkv_params *p)
+{
+#ifdef GKV_HAVE_MFMA
+    return p->impl == GRAPHKV_IMPL_AUTO && shape_allows_mfma(p);
+#else
+    (void)p;
+    return false;
+#endif
+}
+
+// Constraints common to all entry points (see graphkv_params in the header).
+bool base_ok(const graphkv_params *p)
+{
+    if (!p) return false;
+    if (p->n_kv_heads < 1 || p->n_kv_heads > 65535) return false;
+    if (p->head_dim < 8 || p->head_dim % 8 || p->head_dim > 512) return false;
+    if (p->window < 1 || p->n_tokens <= p->window) return false;
+    if (p->dtype != GRAPHKV_FP32 && p->dtype != GRAPHKV_BF16) return false;
+    if (p->impl != GRAPHKV_IMPL_AUTO && p->impl != GRAPHKV_IMPL_GENERIC) return false;
+    if (p->rounds < 0) return false;
+    if (p->signal < 0 || p->signal > 2) return false;
+    if (!(p->decay >= 0.f && p->decay <= 1.f)) return false;
+    if (p->reselect != 0 && p->reselect != 1) return false;
+    if (p->rounds > 0) {
+        const long P = (long)p->n_tokens - p->window;
+        if (p->n_sources < 1 || p->n_sources > P || p->n_sources > 65535) return false;
+        if (p->n_neighbors < 1 || p->n_neighbors > P - 1) return false;
+    }
+    return true;
+}
+
+bool score_ok(const graphkv_params *p)
+{
+    if (p->n_q_heads < p->n_kv_heads || p->n_q_heads % p->n_kv_heads) return false;
+    if ((long)p->n_q_heads * p->window > 65535 * 16L) return false;
+    if (p->pool_kernel < 1 || p->pool_kernel % 2 == 0) return false;
+    if (p->pool_mode != GRAPHKV_POOL_AVG && p->pool_mode != GRAPHKV_POOL_MAX) return false;
+    if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) return false;
+    return true;
+}
+
+bool budget_ok(const graphkv_params *p)
+{
+    return p->budget > p->window && p->budget <= p->n_tokens;
+}
+
+Dims dims_of(const graphkv_params *p)
+{
+    Dims D;
+    D.H = p->n_kv_heads;
+    D.Hq = p->n_q_heads > 0 ? p->n_q_heads : p->n_kv_heads;
+    D.G = D.Hq / D.H > 0 ? D.Hq / D.H : 1;
+    D.d = p->head_dim;
+    D.N = p->n_tokens;
+    D.w = p->window;
+    D.P = D.N - D.w;
+    D.B = p->budget;
+    D.S = p->rounds > 0 ? p->n_sources : 0;
+    D.m = p->rounds > 0 ? p->n_neighbors : 0;
+    D.T = p->rounds;
+    D.mfma = use_mfma(p);
+    D.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
+    D.esize = p->dtype == GRAPHKV_FP32 ? 4 : 2;
+    return D;
+}
+
+Workspace carve(const graphkv_params *p, const Dims &D)
+{
+    Workspace W;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes > 0 ? bytes : 1); return o; };
+    const size_t rows = (size_t)D.Hq * D.w;
+    const bool scoring = p->n_q_heads >= p->n_kv_heads && p->pool_kernel >= 1;
+    W.logits = take(!D.mfma && scoring ? rows * D.N * 4 : 0);
+    W.row_max = take(rows * 4);
+    W.row_sum = take(rows * 4);
+    W.votes = take((size_t)D.Hq * D.P * 4);
+    W.E = take((size_t)D.H * D.S * D.P * 4);
+    W.src = take((size_t)D.H * D.S * 4);
+    W.nbr = take((size_t)D.H * D.S * D.m * 4);
+    W.nbr_e = take((size_t)D.H * D.S * D.m * 4);
+    W.scores = take((size_t)D.H * D.P * 4);
+    W.inv_norm = take((size_t)D.H * D.N * 4);
+#ifdef GKV_HAVE_MFMA
+    W.part = take(D.mfma ? mfma_score_plan(D.H, D.G * D.w, D.N).part_bytes : 0);
+#else
+    W.part = take(0);
+#endif
+    W.total = off;
+    return W;
+}
+
+inline bool aligned16(const void *ptr) { return ptr && ((uintptr_t)ptr & 15u) == 0; }
+inline bool aligned4(const void *ptr) { return ptr && ((uintptr_t)ptr & 3u) == 0; }
+
+int32_t check_ws(const Workspace &W, const void *ws, size_t ws_bytes)
+{
+    if (!ws || ((uintptr_t)ws & (kAlign - 1)) || ws_bytes < W.total) return GRAPHKV_EWORKSPACE;
+    return GRAPHKV_OK;
+}
+
+#define GKV_TRY(expr)                                   \
+    do {                                                \
+        if ((expr) != hipSuccess) return GRAPHKV_EHIP;  \
+    } while (0)
+
+template <typename T> T *at(void *ws, size_t off) { return reinterpret_cast<T *>((char *)ws + off); }
+
+int32_t run_score(const graphkv_params *p, const Dims &D, const Workspace &W, const void *Kc,
+                  const void *Qw, float *scores, void *ws, hipStream_t st)
+{
+    float *votes = at<float>(ws, W.votes);
+#ifdef GKV_HAVE_MFMA
+    if (D.mfma) {
+        const int per_q = p->pool_mode == GRAPHKV_POOL_MAX;
+        GKV_TRY(launch_mfma_score(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale, per_q,
+                                  at<float>(ws, W.part), votes, at<float>(ws, W.inv_norm), st));
+        GKV_TRY(launch_pool_group(votes, D.H, per_q ? D.G : 1, D.P, p->pool_kernel, p->pool_mode,
+                                  (float)D.G, scores, st));
+        return GRAPHKV_OK;
+    }
+#endif
+    GKV_TRY(launch_generic_logits(Kc, Qw, p->dtype, D.H, D.Hq, D.d, D.N, D.w, D.scale,
+                                  at<float>(ws, W.logits), at<float>(ws, W.row_max),
+                                  at<float>(ws, W.row_sum), st));
+    GKV_TRY(launch_generic_votes(at<float>(ws, W.logits), at<float>(ws, W.row_max),
+                                 at<float>(ws, W.row_sum), D.Hq, D.N, D.w, votes, st));
+    GKV_TRY(launch_pool_group(votes, D.H, D.G, D.P, p->pool_kernel, p->pool_mode, (float)D.G,
+                              scores, st));
+    return GRAPHKV_OK;
+}
+
+bool propagation_is_noop(const graphkv_params *p)
+{
+    return p->rounds == 0 || (p->decay == 0.f && p->signal != GRAPHKV_SIGNAL_EVICTED);
+}
+
+// have_inv_norm: the scoring pass of this call already filled ws.inv_norm.
+int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W, const void *Kc,
+                      float *scores, int32_t *dbg_src, int32_t *dbg_nbr, float *dbg_e, void *ws,
+                      bool have_inv_norm, hipStream_t st)
+{
+    if (propagation_is_noop(p)) return GRAPHKV_OK;
+    const size_t n_src = (size_t)D.H * D.S, n_nbr = n_src * D.m;
+    float *E = at<float>(ws, W.E);
+    int32_t *src0 = dbg_src ? dbg_src : at<int32_t>(ws, W.src);
+    int32_t *nbr0 = dbg_nbr ? dbg_nbr : at<int32_t>(ws, W.nbr);
+    float *e0 = dbg_e ? dbg_e : at<float>(ws, W.nbr_e);
+#ifdef GKV_HAVE_MFMA
+    if (D.mfma && !have_inv_norm)
+        GKV_TRY(launch_inv_norm(Kc, p->dtype, D.H, D.d, D.N, at<float>(ws, W.inv_norm), st));
+#else
+    (void)have_inv_norm;
+#endif
+    for (int t = 0; t < D.T; ++t) {
+        int32_t *src = src0, *nbr = nbr0;
+        float *ev = e0;
+        if (t == 0 || p->reselect) {
+            if (dbg_src) src = dbg_src + t * n_src;
+            if (dbg_nbr) nbr = dbg_nbr + t * n_nbr;
+            if (dbg_e) ev = dbg_e + t * n_nbr;
+            // Eq. 2: source nodes
+            GKV_TRY(launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, 0, 0, st));
+            // Eq. 1: edges from every source to every node
+#ifdef GKV_HAVE_MFMA
+            if (D.mfma)
+                GKV_TRY(launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, at<float>(ws, W.inv_norm), E, st));
+            else
+#endif
+                GKV_TRY(launch_generic_cosine(Kc, p->dtype, D.H, D.d, D.N, D.P, D.S, src, E, st));
+            // Eq. 3: neighbourhoods
+            GKV_TRY(launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, 0, 0, st));
+        } else {
+            if (dbg_src) GKV_TRY(launch_copy_i32(src0, dbg_src + t * n_src, (long)n_src, st));
+            if (dbg_nbr) GKV_TRY(launch_copy_i32(nbr0, dbg_nbr + t * n_nbr, (long)n_nbr, st));
+            if (dbg_e) GKV_TRY(launch_copy_f32(e0, dbg_e + t * n_nbr, (long)n_nbr, st));
+        }
+        // Eq. 5: one round of the signal
+        GKV_TRY(launch_decay(scores, D.H, D.P, D.S, D.m, nbr, ev, p->decay, p->signal, st));
+    }
+    return GRAPHKV_OK;
+}
+
+int32_t run_select(const Dims &D, const float *scores, int32_t *idx, hipStream_t st)
+{
+    GKV_TRY(launch_topk_rows(scores, D.P, D.P, D.H, D.B - D.w, idx, D.B, nullptr, 0, D.P, D.w, st));
+    return GRAPHKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t graphkv_workspace_bytes(const graphkv_params *p)
+{
+    if (!base_ok(p)) return 0;
+    const Dims D = dims_of(p);
+    return carve(p, D).total;
+}
+
+int32_t graphkv_uses_mfma(const graphkv_params *p)
+{
+    if (!base_ok(p) || !score_ok(p)) return 0;
+    return use_mfma(p) ? 1 : 0;
+}
+
+int32_t graphkv_score(const graphkv_params *p, const void *Kc, const void *Qw, float *scores,
+                      void *ws, size_t ws_bytes, void *stream)
+{
+    if (!base_ok(p) || !score_ok(p)) return GRAPHKV_EINVAL;
+    if (!aligned16(Kc) || !aligned16(Qw) || !aligned4(scores)) return GRAPHKV_EINVAL;
+    const Dims D = dims_of(p);
+    const Workspace W = carve(p, D);
+    if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
+    return run_score(p, D, W, Kc, Qw, scores, ws, (hipStream_t)stream);
+}
+
+int32_t graphkv_score_knorm(const graphkv_params *p, const void *Kc, float *scores, void *ws,
+                            size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!base_ok(p)) return GRAPHKV_EINVAL;
+    if (!aligned16(Kc) || !aligned4(scores)) return GRAPHKV_EINVAL;
+    const Dims D = dims_of(p);
+    GKV_TRY(launch_knorm(Kc, p->dtype, D.H, D.d, D.N, D.P, scores, (hipStream_t)stream));
+    return GRAPHKV_OK;
+}
+
+int32_t graphkv_propagate(const graphkv_params *p, const void *Kc, float *scores, int32_t *dbg_src,
+                          int32_t *dbg_nbr, float *dbg_e, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!base_ok(p)) return GRAPHKV_EINVAL;
+    if (!aligned16(Kc) || !aligned4(scores)) return GRAPHKV_EINVAL;
+    if ((dbg_src && !aligned4(dbg_src)) || (dbg_nbr && !aligned4(dbg_nbr)) ||
+        (dbg_e && !aligned4(dbg_e)))
+        return GRAPHKV_EINVAL;
+    const Dims D = dims_of(p);
+    const Workspace W = carve(p, D);
+    if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
+    return run_propagate(p, D, W, Kc, scores, dbg_src, dbg_nbr, dbg_e, ws, false,
+                         (hipStream_t)stream);
+}
+
+int32_t graphkv_select(const graphkv_params *p, const float *scores, int32_t *idx, void *ws,
+                       size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    if (!base_ok(p) || !budget_ok(p)) return GRAPHKV_EINVAL;
+    if (!aligned4(scores) || !aligned4(idx)) return GRAPHKV_EINVAL;
+    const Dims D = dims_of(p);
+    return run_select(D, scores, idx, (hipStream_t)stream);
+}
+
+int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc, const void *Qw,
+                         void *Kout, void *Vout, int32_t *idx, float *scores_out, void *ws,
+                         size_t ws_bytes, void *stream)
+{
+    if (!base_ok(p) || !score_ok(p) || !budget_ok(p)) return GRAPHKV_EINVAL;
+    if (!aligned16(Kc) || !aligned16(Vc) || !aligned16(Qw) || !aligned16(Kout) ||
+        !aligned16(Vout) || !aligned4(idx))
+        return GRAPHKV_EINVAL;
+    if (scores_out && !aligned4(scores_out)) return GRAPHKV_EINVAL;
+    const Dims D = dims_of(p);
+    const Workspace W = carve(p, D);
+    if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    float *scores = scores_out ? scores_out : at<float>(ws, W.scores);
+    if (int32_t rc = run_score(p, D, W, Kc, Qw, scores, ws, st)) return rc;
+    if (int32_t rc = run_propagate(p, D, W, Kc, scores, nullptr, nullptr, nullptr, ws, D.mfma, st))
+        return rc;
+    if (int32_t rc = run_select(D, scores, idx, st)) return rc;
+    GKV_TRY(launch_gather(Kc, Vc, idx, D.H, D.N, D.B, (int)(D.d * D.esize), Kout, Vout, st));
+    return GRAPHKV_OK;
+}
+
+const char *graphkv_strerror(int32_t code)
+{
+    switch (code) {
+        case GRAPHKV_OK: return "ok";
+        case GRAPHKV_EINVAL: return "invalid argument (a graphkv_params constraint is violated or a pointer is NULL/misaligned)";
+        case GRAPHKV_EWORKSPACE: return "workspace is NULL, misaligned or smaller than graphkv_workspace_bytes()";
+        case GRAPHKV_EHIP: return "a HIP kernel launch failed";
+        default: return "unknown graphkv error code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Device-side helpers shared by the GraphKV kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gkv {
+
+constexpr int kWave = 64;
+
+// bfloat16 <-> float: bf16 is the upper half of an IEEE float, widening is exact.
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPerVec = 4;  // elements in a 16-byte vector
+    __device__ static __forceinline__ void unpack(const uint4 &v, float *o) {
+        o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y);
+        o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
+    }
+};
+template <> struct Elem<uint16_t> {
+    static constexpr int kPerVec = 8;
+    __device__ static __forceinline__ void unpack(const uint4 &v, float *o) {
+        o[0] = bf16lo_to_f32(v.x); o[1] = bf16hi_to_f32(v.x);
+        o[2] = bf16lo_to_f32(v.y); o[3] = bf16hi_to_f32(v.y);
+        o[4] = bf16lo_to_f32(v.z); o[5] = bf16hi_to_f32(v.z);
+        o[6] = bf16lo_to_f32(v.w); o[7] = bf16hi_to_f32(v.w);
+    }
+};
+
+// Order-preserving map float -> uint32 (larger float <=> larger key).  -0.0 is
+// folded onto +0.0 first so that the two compare equal, as they do as numbers.
+__device__ __forceinline__ uint32_t ord_key(float f) {
+    f = f + 0.0f;
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+// Fixed butterfly order: the same inputs always give the same bits.
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// Block-wide reductions for blocks of up to 1024 threads; `red` holds >= 16 floats.
+__device__ __forceinline__ float block_max(float v, float *red) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    v = wave_max(v);
+    __syncthreads();
+    if (lane == 0) red[wv] = v;
+    __syncthreads();
+    float r = red[0];
+    for (int i = 1; i < nw; ++i) r = fmaxf(r, red[i]);
+    return r;
+}
+__device__ __forceinline__ float block_sum(float v, float *red) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) red[wv] = v;
+    __syncthreads();
+    float r = red[0];
+    for (int i = 1; i < nw; ++i) r += red[i];
+    return r;
+}
+
+}  // namespace gkv

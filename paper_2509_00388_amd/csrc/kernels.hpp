@@ -1,0 +1,64 @@
+// Host-side launchers of the GraphKV kernels.  Every launcher only enqueues
+// work on `st` and returns hipGetLastError() of its launches.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gkv {
+
+// ---- selection (select.hip) -------------------------------------------------
+// For each of `rows` rows of x (row r starts at x + r*ld, n entries): the k
+// entries that come first by (value descending, index ascending), written in
+// ascending index order to idx_out + r*idx_ld (and their values to val_out +
+// r*val_ld when val_out != nullptr).  After the k picks, `append_count`
+// consecutive integers starting at `append_from` are appended to idx_out.
+hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k,
+                            int32_t *idx_out, long idx_ld, float *val_out, long val_ld,
+                            int append_from, int append_count, hipStream_t st);
+
+// ---- scalar kernels for any dtype / shape (generic.hip) ----------------------
+// logits [Hq*w, N] (fp32, scaled), then per-row max and sum of exp.
+hipError_t launch_generic_logits(const void *Kc, const void *Qw, int dtype, int Hkv, int Hq, int d,
+                                 int N, int w, float scale, float *logits, float *row_max,
+                                 float *row_sum, hipStream_t st);
+// votes [Hq, P]: softmax weights summed over the window rows.
+hipError_t launch_generic_votes(const float *logits, const float *row_max, const float *row_sum,
+                                int Hq, int N, int w, float *votes, hipStream_t st);
+// E [Hkv, S, P] cosine of source src[h,a] against every prefix key; self = -inf.
+hipError_t launch_generic_cosine(const void *Kc, int dtype, int Hkv, int d, int N, int P, int S,
+                                 const int32_t *src, float *E, hipStream_t st);
+// scores[h,j] = -||k_j||
+hipError_t launch_knorm(const void *Kc, int dtype, int Hkv, int d, int N, int P, float *scores,
+                        hipStream_t st);
+
+// ---- pooling, signal propagation, gather (stages.hip) -----------------------
+// votes [Hkv*Gv, P] -> scores [Hkv, P]: pool each of the Gv rows of a head, sum, divide by div.
+hipError_t launch_pool_group(const float *votes, int Hkv, int Gv, int P, int pool_kernel,
+                             int pool_mode, float div, float *scores, hipStream_t st);
+// Eq. 5 for one round: scores[h, nbr] *= prod (1 -/+ alpha e), ascending source order.
+hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32_t *nbr,
+                        const float *nbr_e, float alpha, int signal, hipStream_t st);
+// Kout[h,t,:] = Kc[h, idx[h,t], :], same for V; row_bytes multiple of 16.
+hipError_t launch_gather(const void *Kc, const void *Vc, const int32_t *idx, int Hkv, int N, int B,
+                         int row_bytes, void *Kout, void *Vout, hipStream_t st);
+hipError_t launch_copy_i32(const int32_t *src, int32_t *dst, long n, hipStream_t st);
+hipError_t launch_copy_f32(const float *src, float *dst, long n, hipStream_t st);
+
+// ---- bf16 MFMA kernels, d = 128 (mfma_score.hip, mfma_cosine.hip) ----------
+struct MfmaScorePlan {
+    int chunks;        // key chunks per head in the streaming passes
+    size_t part_bytes; // bytes of per-chunk row statistics
+};
+MfmaScorePlan mfma_score_plan(int Hkv, int rows, int N);
+// Pass A: per (head, chunk, row) partial max and sum of exp2 over the chunk's visible keys.
+// Pass B: votes [Hkv, P] (avg mode, all rows summed) or [Hq, P] (per query head).
+hipError_t launch_mfma_score(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
+                             float scale, int per_qhead_votes, float *part, float *votes,
+                             float *inv_norm, hipStream_t st);
+// E [Hkv, S, P] from bf16 keys; inv_norm [Hkv, N] = 1/||k_j|| (0 for a zero key).
+hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
+                              const float *inv_norm, float *E, hipStream_t st);
+hipError_t launch_inv_norm(const void *Kc, int dtype, int Hkv, int d, int N, float *inv_norm,
+                           hipStream_t st);
+
+}  // namespace gkv

@@ -1,0 +1,208 @@
+// Pooling of the window votes, the signal-propagation update (Eq. 4 / Eq. 5)
+// and the K/V gather of the retained rows.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace gkv {
+
+// scores[h, j] = (1/div) * sum_g pool(votes[h*Gv + g, j-half .. j+half]).
+// Average pooling pads with zeros and divides by the kernel size; max pooling
+// ignores positions outside the row.
+__global__ __launch_bounds__(256) void pool_group_kernel(const float *__restrict__ votes, int Gv,
+                                                         int P, int pool_kernel, int pool_mode,
+                                                         float div, float *__restrict__ scores)
+{
+    const int h = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= P) return;
+    const int half = (pool_kernel - 1) / 2;
+    const int lo = max(0, j - half), hi = min(P - 1, j + half);
+    float total = 0.f;
+    for (int g = 0; g < Gv; ++g) {
+        const float *v = votes + ((long)h * Gv + g) * P;
+        float acc;
+        if (pool_mode == 0) {
+            acc = 0.f;
+            for (int t = lo; t <= hi; ++t) acc += v[t];
+            acc = acc / (float)pool_kernel;
+        } else {
+            acc = -INFINITY;
+            for (int t = lo; t <= hi; ++t) acc = fmaxf(acc, v[t]);
+        }
+        total += acc;
+    }
+    scores[(long)h * P + j] = total / div;
+}
+
+__device__ __forceinline__ float signal_factor(float e, float alpha, int signal)
+{
+    return signal == 1 ? fmaf(alpha, e, 1.0f) : fmaf(-alpha, e, 1.0f);
+}
+
+// One workgroup per head.  The S*m (source slot, node, edge) triples are sorted
+// by (node, slot) with a bitonic network in LDS; the first triple of every node
+// then multiplies that node's factors in ascending slot order -- sources are
+// stored in ascending index order, so this is Eq. 5's product with a fixed
+// floating-point order -- and writes the node's score once.  No float atomics.
+__global__ __launch_bounds__(1024) void decay_sorted_kernel(
+    float *__restrict__ scores, int P, int count, int npad, const int32_t *__restrict__ nbr,
+    const float *__restrict__ nbr_e, float alpha, int signal)
+{
+    extern __shared__ uint64_t keys[];     // (node << 32) | triple id
+    const int h = blockIdx.x, tid = threadIdx.x;
+    const int32_t *nb = nbr + (long)h * count;
+    const float *ne = nbr_e + (long)h * count;
+    float *s = scores + (long)h * P;
+    for (int t = tid; t < npad; t += 1024)
+        keys[t] = t < count ? (((uint64_t)(uint32_t)nb[t] << 32) | (uint32_t)t) : ~0ull;
+    __syncthreads();
+    for (int k = 2; k <= npad; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < npad; t += 1024) {
+                const int u = t ^ j;
+                if (u > t) {
+                    const uint64_t a = keys[t], b = keys[u];
+                    const bool up = (t & k) == 0;
+                    if ((a > b) == up) { keys[t] = b; keys[u] = a; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int t = tid; t < count; t += 1024) {
+        const uint64_t key = keys[t];
+        const uint32_t node = (uint32_t)(key >> 32);
+        if (t > 0 && (uint32_t)(keys[t - 1] >> 32) == node) continue;   // not the first of its node
+        if (signal == 2) { s[node] = -INFINITY; continue; }
+        float f = 1.0f;
+        for (int u = t; u < count; ++u) {
+            const uint64_t ku = keys[u];
+            if ((uint32_t)(ku >> 32) != node) break;
+            f *= signal_factor(ne[(uint32_t)ku], alpha, signal);
+        }
+        s[node] *= f;
+    }
+}
+
+// Same update without the sort, for S*m beyond the LDS capacity: sources are
+// applied one after the other; inside one source the m neighbours are distinct
+// nodes, so they can be updated in parallel.  Multiplying s_j by the factors one
+// at a time differs from multiplying by their product only in rounding order, so
+// here too the product is formed first, per node, by the lowest slot that holds it.
+__global__ __launch_bounds__(1024) void decay_sequential_kernel(
+    float *__restrict__ scores, int P, int S, int m, const int32_t *__restrict__ nbr,
+    const float *__restrict__ nbr_e, float alpha, int signal)
+{
+    const int h = blockIdx.x;
+    const int32_t *nb = nbr + (long)h * S * m;
+    const float *ne = nbr_e + (long)h * S * m;
+    float *s = scores + (long)h * P;
+    // Thread (a, u) owns node j = nb[a][u] if no earlier slot a' < a lists j.
+    // Neighbour lists are ascending, so membership is a binary search.
+    for (long t = threadIdx.x; t < (long)S * m; t += 1024) {
+        const int a = (int)(t / m);
+        const int32_t j = nb[t];
+        bool first = true;
+        for (int b = 0; b < a && first; ++b) {
+            int lo = 0, hi = m - 1;
+            while (lo <= hi) {
+                const int mid = (lo + hi) >> 1;
+                const int32_t v = nb[(long)b * m + mid];
+                if (v == j) { first = false; break; }
+                if (v < j) lo = mid + 1; else hi = mid - 1;
+            }
+        }
+        if (!first) continue;
+        if (signal == 2) { s[j] = -INFINITY; continue; }
+        float f = signal_factor(ne[t], alpha, signal);
+        for (int b = a + 1; b < S; ++b) {
+            int lo = 0, hi = m - 1;
+            while (lo <= hi) {
+                const int mid = (lo + hi) >> 1;
+                const int32_t v = nb[(long)b * m + mid];
+                if (v == j) { f *= signal_factor(ne[(long)b * m + mid], alpha, signal); break; }
+                if (v < j) lo = mid + 1; else hi = mid - 1;
+            }
+        }
+        s[j] *= f;
+    }
+}
+
+// 16 bytes per thread; rows of row_bytes (a multiple of 16).
+__global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ Kc,
+                                                     const uint4 *__restrict__ Vc,
+                                                     const int32_t *__restrict__ idx, int N, int B,
+                                                     int vec_per_row, uint4 *__restrict__ Kout,
+                                                     uint4 *__restrict__ Vout)
+{
+    const int h = blockIdx.y;
+    const long g = (long)blockIdx.x * 256 + threadIdx.x;
+    if (g >= (long)B * vec_per_row) return;
+    const int t = (int)(g / vec_per_row), c = (int)(g % vec_per_row);
+    const int32_t j = idx[(long)h * B + t];
+    const long src = ((long)h * N + j) * vec_per_row + c;
+    const long dst = ((long)h * B + t) * vec_per_row + c;
+    const uint4 *in = blockIdx.z == 0 ? Kc : Vc;
+    uint4 *out = blockIdx.z == 0 ? Kout : Vout;
+    out[dst] = in[src];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void copy_kernel(const T *__restrict__ src, T *__restrict__ dst,
+                                                   long n)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+hipError_t launch_pool_group(const float *votes, int Hkv, int Gv, int P, int pool_kernel,
+                             int pool_mode, float div, float *scores, hipStream_t st)
+{
+    hipLaunchKernelGGL(pool_group_kernel, dim3((P + 255) / 256, Hkv), dim3(256), 0, st, votes, Gv,
+                       P, pool_kernel, pool_mode, div, scores);
+    return hipGetLastError();
+}
+
+hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32_t *nbr,
+                        const float *nbr_e, float alpha, int signal, hipStream_t st)
+{
+    const long count = (long)S * m;
+    long npad = 2;
+    while (npad < count) npad <<= 1;
+    if (npad <= 8192) {   // 64 KiB of LDS: no opt-in needed
+        hipLaunchKernelGGL(decay_sorted_kernel, dim3(Hkv), dim3(1024), (size_t)npad * 8, st, scores,
+                           P, (int)count, (int)npad, nbr, nbr_e, alpha, signal);
+    } else {
+        hipLaunchKernelGGL(decay_sequential_kernel, dim3(Hkv), dim3(1024), 0, st, scores, P, S, m,
+                           nbr, nbr_e, alpha, signal);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(const void *Kc, const void *Vc, const int32_t *idx, int Hkv, int N, int B,
+                         int row_bytes, void *Kout, void *Vout, hipStream_t st)
+{
+    const int vpr = row_bytes / 16;
+    const long per_head = (long)B * vpr;
+    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((per_head + 255) / 256), Hkv, 2), dim3(256), 0,
+                       st, (const uint4 *)Kc, (const uint4 *)Vc, idx, N, B, vpr, (uint4 *)Kout,
+                       (uint4 *)Vout);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_i32(const int32_t *src, int32_t *dst, long n, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(copy_kernel<int32_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       src, dst, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_f32(const float *src, float *dst, long n, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(copy_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src,
+                       dst, n);
+    return hipGetLastError();
+}
+
+}  // namespace gkv
