@@ -13,7 +13,7 @@ OBJDIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "select.hip", "generic.hip", "stages.hip", "mfma_score.hip", "mfma_cosine.hip"]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-DGKV_HAVE_MFMA" if all(os.path.exists(os.path.join(CSRC, s)) for s in ("mfma_score.hip", "mfma_cosine.hip")) else "-DGKV_NO_MFMA",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", 
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
 ]

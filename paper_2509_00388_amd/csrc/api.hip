@@ -14,31 +14,31 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
 
 struct Dims {
     int H, Hq, G, d, N, w, P, B, S, m, T;
-    bool mfma;
+    bool mfma_score, mfma_cosine;
     float scale;
     size_t esize;
 };
 
 // Workspace: a bump allocation of every scratch array any entry point may need.
 struct Workspace {
-    size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, inv_norm, part, total;
+    size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, part, total;
 };
 
-bool shape_allows_mfma(const graphkv_params *p)
+// The MFMA kernels cover bf16 keys with d = 128.  Scoring additionally needs the
+// stacked query rows G*w to fill whole 32-row MFMA blocks (at most 4 of them);
+// per-query-head votes (max pooling) need w itself to be a multiple of 32.
+bool mfma_cosine_ok(const graphkv_params *p)
 {
-    if (p->dtype != GRAPHKV_BF16 || p->head_dim != 128) return false;
-    const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
-    return rows % 32 == 0 && rows <= 128 && p->n_tokens - p->window >= 32;
+    return p->impl == GRAPHKV_IMPL_AUTO && p->dtype == GRAPHKV_BF16 && p->head_dim == 128;
 }
 
-bool use_mfma(const graphkv_params *p)
+bool mfma_score_ok(const graphkv_params *p)
 {
-#ifdef GKV_HAVE_MFMA
-    return p->impl == GRAPHKV_IMPL_AUTO && shape_allows_mfma(p);
-#else
-    (void)p;
-    return false;
-#endif
+    if (!mfma_cosine_ok(p) || p->n_kv_heads < 1 || p->n_q_heads < p->n_kv_heads) return false;
+    const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
+    if (rows % 32 != 0 || rows > 128) return false;
+    if (p->pool_mode == GRAPHKV_POOL_MAX && p->window % 32 != 0) return false;
+    return true;
 }
 
 // Constraints common to all entry points (see graphkv_params in the header).
@@ -91,7 +91,8 @@ Dims dims_of(const graphkv_params *p)
     D.S = p->rounds > 0 ? p->n_sources : 0;
     D.m = p->rounds > 0 ? p->n_neighbors : 0;
     D.T = p->rounds;
-    D.mfma = use_mfma(p);
+    D.mfma_score = mfma_score_ok(p);
+    D.mfma_cosine = mfma_cosine_ok(p);
     D.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
     D.esize = p->dtype == GRAPHKV_FP32 ? 4 : 2;
     return D;
@@ -104,7 +105,7 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes > 0 ? bytes : 1); return o; };
     const size_t rows = (size_t)D.Hq * D.w;
     const bool scoring = p->n_q_heads >= p->n_kv_heads && p->pool_kernel >= 1;
-    W.logits = take(!D.mfma && scoring ? rows * D.N * 4 : 0);
+    W.logits = take(!D.mfma_score && scoring ? rows * D.N * 4 : 0);
     W.row_max = take(rows * 4);
     W.row_sum = take(rows * 4);
     W.votes = take((size_t)D.Hq * D.P * 4);
@@ -113,12 +114,7 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.nbr = take((size_t)D.H * D.S * D.m * 4);
     W.nbr_e = take((size_t)D.H * D.S * D.m * 4);
     W.scores = take((size_t)D.H * D.P * 4);
-    W.inv_norm = take((size_t)D.H * D.N * 4);
-#ifdef GKV_HAVE_MFMA
-    W.part = take(D.mfma ? mfma_score_plan(D.H, D.G * D.w, D.N).part_bytes : 0);
-#else
-    W.part = take(0);
-#endif
+    W.part = take(D.mfma_score ? mfma_score_plan(D.H, D.G * D.w, D.N).part_bytes : 0);
     W.total = off;
     return W;
 }
@@ -143,16 +139,14 @@ int32_t run_score(const graphkv_params *p, const Dims &D, const Workspace &W, co
                   const void *Qw, float *scores, void *ws, hipStream_t st)
 {
     float *votes = at<float>(ws, W.votes);
-#ifdef GKV_HAVE_MFMA
-    if (D.mfma) {
+    if (D.mfma_score) {
         const int per_q = p->pool_mode == GRAPHKV_POOL_MAX;
         GKV_TRY(launch_mfma_score(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale, per_q,
-                                  at<float>(ws, W.part), votes, at<float>(ws, W.inv_norm), st));
+                                  at<float>(ws, W.part), votes, st));
         GKV_TRY(launch_pool_group(votes, D.H, per_q ? D.G : 1, D.P, p->pool_kernel, p->pool_mode,
                                   (float)D.G, scores, st));
         return GRAPHKV_OK;
     }
-#endif
     GKV_TRY(launch_generic_logits(Kc, Qw, p->dtype, D.H, D.Hq, D.d, D.N, D.w, D.scale,
                                   at<float>(ws, W.logits), at<float>(ws, W.row_max),
                                   at<float>(ws, W.row_sum), st));
@@ -168,10 +162,9 @@ bool propagation_is_noop(const graphkv_params *p)
     return p->rounds == 0 || (p->decay == 0.f && p->signal != GRAPHKV_SIGNAL_EVICTED);
 }
 
-// have_inv_norm: the scoring pass of this call already filled ws.inv_norm.
 int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W, const void *Kc,
                       float *scores, int32_t *dbg_src, int32_t *dbg_nbr, float *dbg_e, void *ws,
-                      bool have_inv_norm, hipStream_t st)
+                      hipStream_t st)
 {
     if (propagation_is_noop(p)) return GRAPHKV_OK;
     const size_t n_src = (size_t)D.H * D.S, n_nbr = n_src * D.m;
@@ -179,12 +172,6 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
     int32_t *src0 = dbg_src ? dbg_src : at<int32_t>(ws, W.src);
     int32_t *nbr0 = dbg_nbr ? dbg_nbr : at<int32_t>(ws, W.nbr);
     float *e0 = dbg_e ? dbg_e : at<float>(ws, W.nbr_e);
-#ifdef GKV_HAVE_MFMA
-    if (D.mfma && !have_inv_norm)
-        GKV_TRY(launch_inv_norm(Kc, p->dtype, D.H, D.d, D.N, at<float>(ws, W.inv_norm), st));
-#else
-    (void)have_inv_norm;
-#endif
     for (int t = 0; t < D.T; ++t) {
         int32_t *src = src0, *nbr = nbr0;
         float *ev = e0;
@@ -195,11 +182,9 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
             // Eq. 2: source nodes
             GKV_TRY(launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, 0, 0, st));
             // Eq. 1: edges from every source to every node
-#ifdef GKV_HAVE_MFMA
-            if (D.mfma)
-                GKV_TRY(launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, at<float>(ws, W.inv_norm), E, st));
+            if (D.mfma_cosine)
+                GKV_TRY(launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, st));
             else
-#endif
                 GKV_TRY(launch_generic_cosine(Kc, p->dtype, D.H, D.d, D.N, D.P, D.S, src, E, st));
             // Eq. 3: neighbourhoods
             GKV_TRY(launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, 0, 0, st));
@@ -234,7 +219,7 @@ size_t graphkv_workspace_bytes(const graphkv_params *p)
 int32_t graphkv_uses_mfma(const graphkv_params *p)
 {
     if (!base_ok(p) || !score_ok(p)) return 0;
-    return use_mfma(p) ? 1 : 0;
+    return mfma_score_ok(p) ? 1 : 0;
 }
 
 int32_t graphkv_score(const graphkv_params *p, const void *Kc, const void *Qw, float *scores,
@@ -270,7 +255,7 @@ int32_t graphkv_propagate(const graphkv_params *p, const void *Kc, float *scores
     const Dims D = dims_of(p);
     const Workspace W = carve(p, D);
     if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
-    return run_propagate(p, D, W, Kc, scores, dbg_src, dbg_nbr, dbg_e, ws, false,
+    return run_propagate(p, D, W, Kc, scores, dbg_src, dbg_nbr, dbg_e, ws,
                          (hipStream_t)stream);
 }
 
@@ -299,7 +284,7 @@ int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc
     hipStream_t st = (hipStream_t)stream;
     float *scores = scores_out ? scores_out : at<float>(ws, W.scores);
     if (int32_t rc = run_score(p, D, W, Kc, Qw, scores, ws, st)) return rc;
-    if (int32_t rc = run_propagate(p, D, W, Kc, scores, nullptr, nullptr, nullptr, ws, D.mfma, st))
+    if (int32_t rc = run_propagate(p, D, W, Kc, scores, nullptr, nullptr, nullptr, ws, st))
         return rc;
     if (int32_t rc = run_select(D, scores, idx, st)) return rc;
     GKV_TRY(launch_gather(Kc, Vc, idx, D.H, D.N, D.B, (int)(D.d * D.esize), Kout, Vout, st));

@@ -87,7 +87,6 @@ __global__ __launch_bounds__(256) void generic_cosine_kernel(
     float *__restrict__ E)
 {
     __shared__ float s_f32[512];
-    __shared__ float red[16];
     const int a = blockIdx.y, h = blockIdx.z;
     const int i = src[h * S + a];
     const T *kh = Kc + (long)h * N * d;
@@ -101,7 +100,6 @@ __global__ __launch_bounds__(256) void generic_cosine_kernel(
     __syncthreads();
     // |k_i|^2 in a fixed order (every thread computes the same sum)
     for (int c = 0; c < d; ++c) part = fmaf(s_f32[c], s_f32[c], part);
-    (void)red;
     const int j = blockIdx.x * 256 + threadIdx.x;
     if (j >= P) return;
     float sq;
@@ -129,24 +127,6 @@ __global__ __launch_bounds__(256) void knorm_kernel(const T *__restrict__ Kc, in
         for (int u = 0; u < V; ++u) sq = fmaf(t[u], t[u], sq);
     }
     scores[(long)h * P + j] = -sqrtf(sq);
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void inv_norm_kernel(const T *__restrict__ Kc, int d, long rows,
-                                                       float *__restrict__ inv_norm)
-{
-    const long j = (long)blockIdx.x * 256 + threadIdx.x;
-    if (j >= rows) return;
-    constexpr int V = Elem<T>::kPerVec;
-    const uint4 *bv = reinterpret_cast<const uint4 *>(Kc + j * d);
-    float sq = 0.f;
-    for (int c = 0; c < d / V; ++c) {
-        float t[V];
-        Elem<T>::unpack(bv[c], t);
-#pragma unroll
-        for (int u = 0; u < V; ++u) sq = fmaf(t[u], t[u], sq);
-    }
-    inv_norm[j] = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
 }
 
 hipError_t launch_generic_logits(const void *Kc, const void *Qw, int dtype, int Hkv, int Hq, int d,
@@ -197,20 +177,6 @@ hipError_t launch_knorm(const void *Kc, int dtype, int Hkv, int d, int N, int P,
     else
         hipLaunchKernelGGL(knorm_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)Kc, d,
                            N, P, scores);
-    return hipGetLastError();
-}
-
-hipError_t launch_inv_norm(const void *Kc, int dtype, int Hkv, int d, int N, float *inv_norm,
-                           hipStream_t st)
-{
-    const long rows = (long)Hkv * N;
-    dim3 grid((unsigned)((rows + 255) / 256));
-    if (dtype == 0)
-        hipLaunchKernelGGL(inv_norm_kernel<float>, grid, dim3(256), 0, st, (const float *)Kc, d,
-                           rows, inv_norm);
-    else
-        hipLaunchKernelGGL(inv_norm_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)Kc,
-                           d, rows, inv_norm);
     return hipGetLastError();
 }
 

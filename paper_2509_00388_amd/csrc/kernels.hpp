@@ -54,11 +54,9 @@ MfmaScorePlan mfma_score_plan(int Hkv, int rows, int N);
 // Pass B: votes [Hkv, P] (avg mode, all rows summed) or [Hq, P] (per query head).
 hipError_t launch_mfma_score(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
                              float scale, int per_qhead_votes, float *part, float *votes,
-                             float *inv_norm, hipStream_t st);
-// E [Hkv, S, P] from bf16 keys; inv_norm [Hkv, N] = 1/||k_j|| (0 for a zero key).
+                             hipStream_t st);
+// E [Hkv, S, P] from bf16 keys (same contract as launch_generic_cosine).
 hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
-                              const float *inv_norm, float *E, hipStream_t st);
-hipError_t launch_inv_norm(const void *Kc, int dtype, int Hkv, int d, int N, float *inv_norm,
-                           hipStream_t st);
+                              float *E, hipStream_t st);
 
 }  // namespace gkv
