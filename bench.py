@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the GraphKV eviction pass on one MI355X.
+
+One "step" compresses a whole prompt: L per-layer graphkv_compress calls (score
+-> propagate -> select -> gather) on one stream, over seeded synthetic
+Llama-3-8B-shaped K/V/Q already resident in HBM.  Prints ONE JSON line.
+
+  value            prompt tokens whose cache is compressed per second (N / step
+                   time; every layer and KV head of the model is processed)
+  roofline         for the kernel that takes the most time: algorithmic bytes
+                   per launch / average launch duration, measured with HIP
+                   events on the launch stream during extra profiled steps that
+                   follow the timed region (event records would perturb the
+                   whole-step time if they were inside it)
+  cpu_baseline     the CPU oracle, unchanged, on a bounded sample of the same
+                   layers, extrapolated to the full model
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def _gen_layer(args):
+    name, layer = args
+    from paper_2509_00388_amd import synth
+    return layer, synth.make_layer(synth.CONFIGS[name], layer)
+
+
+def generate_layers(name, layers):
+    """Seeded inputs of the requested layers, drawn in worker processes (numpy only)."""
+    import multiprocessing as mp
+    out = {}
+    workers = max(1, min(8, len(layers), (os.cpu_count() or 2) // 2))
+    if workers == 1:
+        for l in layers:
+            out[l] = _gen_layer((name, l))[1]
+        return out
+    with mp.get_context("spawn").Pool(workers) as pool:
+        for layer, data in pool.imap_unordered(_gen_layer, [(name, l) for l in layers]):
+            out[layer] = data
+    return out
+
+
+def algorithmic_bytes(cfg, B):
+    """Bytes one launch of each kernel must move for one layer (e = 2 for bf16):
+    the streaming model of the pass, with the S x P edge block not counted
+    because the method does not need it in memory."""
+    H, Hq, d, N, w = cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.n_tokens, cfg.window
+    P, S, m = N - w, cfg.n_sources, cfg.n_neighbors
+    e = 4 if cfg.dtype == "fp32" else 2
+    return {
+        "score_stats": H * N * d * e + Hq * w * d * e,
+        "score_votes": H * P * d * e + Hq * w * d * e + H * P * 4,
+        "pool_group": 2 * H * P * 4,
+        "topk_sources": H * P * 4 + H * S * 4,
+        "cosine": H * P * d * e + H * S * d * e,
+        "topk_neighbors": H * S * m * 8,
+        "decay": 2 * H * S * m * 8,
+        "topk_final": H * P * 4 + H * B * 4,
+        "gather": 4 * H * B * d * e,
+    }
+
+
+def model_flops(cfg):
+    H, Hq, d, N, w = cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.n_tokens, cfg.window
+    P, S, T = N - w, cfg.n_sources, cfg.rounds
+    return 2 * (2 * Hq * w * d * N) + T * 2 * H * S * d * P
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--layers", type=int, default=0, help="use only the first LAYERS layers (debug)")
+    ap.add_argument("--cpu-layers", type=int, default=4, help="layers the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--profile-steps", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the eviction pass of one sequence); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    from paper_2509_00388_amd import synth
+    cfg = synth.CONFIGS[args.workload]
+    L = args.layers if args.layers > 0 else cfg.n_layers
+    t_gen = time.time()
+    host = generate_layers(args.workload, list(range(L)))
+    t_gen = time.time() - t_gen
+
+    import numpy as np
+    import torch
+    from paper_2509_00388_amd import binding as gk
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU: the HIP library has no CPU fallback")
+    gk.load_library()
+    dev = torch.device("cuda:0")
+    dt = gk.FP32 if cfg.dtype == "fp32" else gk.BF16
+
+    params, Kd, Vd, Qd, Ko, Vo, Io = [], [], [], [], [], [], []
+    for l in range(L):
+        K, V, Q = host[l]
+        p = gk.Params(n_kv_heads=cfg.n_kv_heads, n_q_heads=cfg.n_q_heads, head_dim=cfg.head_dim,
+                      n_tokens=cfg.n_tokens, window=cfg.window, pool_kernel=cfg.pool_kernel,
+                      pool_mode=cfg.pool_mode, budget=cfg.budget_for_layer(l), n_sources=cfg.n_sources,
+                      n_neighbors=cfg.n_neighbors, rounds=cfg.rounds, decay=cfg.decay,
+                      reselect=cfg.reselect, dtype=dt)
+        params.append(p)
+        Kd.append(gk.to_device(K, dt, dev)); Vd.append(gk.to_device(V, dt, dev)); Qd.append(gk.to_device(Q, dt, dev))
+        shape = (p.n_kv_heads, p.budget, p.head_dim)
+        Ko.append(torch.empty(shape, dtype=Kd[-1].dtype, device=dev))
+        Vo.append(torch.empty(shape, dtype=Kd[-1].dtype, device=dev))
+        Io.append(torch.empty((p.n_kv_heads, p.budget), dtype=torch.int32, device=dev))
+    ws_bytes = max(gk.graphkv_workspace_bytes(p) for p in params)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step():
+        for l in range(L):
+            gk.graphkv_compress(params[l], Kd[l], Vd[l], Qd[l], Ko[l], Vo[l], Io[l], None, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = cfg.n_tokens / (ms_per_step * 1e-3 * cfg.n_layers / L)   # L < n_layers only in debug runs
+
+    # ---- per-kernel durations (HIP events on the launch stream), after the timed region ----
+    kernels = {}
+    roofline = None
+    if args.profile_steps > 0:
+        gk.graphkv_profile_begin()
+        for _ in range(args.profile_steps):
+            step()
+        prof = gk.graphkv_profile_end()
+        torch.cuda.synchronize()
+        alg = [algorithmic_bytes(cfg, p.budget) for p in params]
+        for name, (ms, cnt) in prof.items():
+            per_step = cnt / args.profile_steps
+            avg_us = ms * 1e3 / cnt
+            bytes_per_launch = float(np.mean([a.get(name, 0) for a in alg]))
+            kernels[name] = {
+                "avg_us": round(avg_us, 3), "launches_per_step": per_step,
+                "us_per_step": round(avg_us * per_step, 1),
+                "alg_bytes_per_launch": int(bytes_per_launch),
+                "alg_GBps": round(bytes_per_launch / (avg_us * 1e-6) / 1e9, 1) if avg_us > 0 else None,
+            }
+        dom = max(kernels, key=lambda k: kernels[k]["us_per_step"])
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get(f"{args.workload}:{dom}")
+        roofline = {
+            "kernel": dom, "bound": "hbm", "achieved": kernels[dom]["alg_GBps"], "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": round(kernels[dom]["alg_GBps"] / HBM_PEAK_GBS, 4),
+            "traffic": traffic, "avg_launch_us": kernels[dom]["avg_us"],
+            "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"],
+            "measured_over": f"{args.profile_steps} profiled steps after the timed region",
+        }
+
+    # whole-pass view against the streaming model (2 + T passes over K, plus the gather)
+    model_bytes = sum(sum(v for k, v in algorithmic_bytes(cfg, p.budget).items()
+                          if k in ("score_stats", "score_votes", "gather")) +
+                      cfg.rounds * algorithmic_bytes(cfg, p.budget)["cosine"] for p in params)
+    pass_view = {
+        "model_bytes_per_step": int(model_bytes),
+        "model_GBps": round(model_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "frac_of_hbm_peak": round(model_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "mfma_TFLOPs": round(model_flops(cfg) * L / (ms_per_step * 1e-3) / 1e12, 2),
+        "frac_of_bf16_mfma_peak": round(model_flops(cfg) * L / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+    }
+
+    # ---- CPU baseline: the oracle on a bounded sample of the same layers ----
+    cpu = None
+    parity = None
+    if args.cpu_layers > 0:
+        import oracle
+        n_s = min(args.cpu_layers, L)
+        oracle.lib()
+        differing = 0
+        t_cpu = 0.0
+        for l in range(n_s):
+            K, V, Q = host[l]
+            p = params[l]
+            tc = time.perf_counter()
+            ref = oracle.compress(K, V, Q, cfg.dtype, p.pool_kernel, p.budget, p.n_sources,
+                                  p.n_neighbors, p.rounds, alpha=p.decay, reselect=p.reselect)
+            t_cpu += time.perf_counter() - tc
+            differing += int((Io[l].cpu().numpy() != ref["idx"]).any(axis=1).sum())
+        threads = min(cfg.n_kv_heads, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+        cpu = {
+            "value": round(cfg.n_tokens / (t_cpu / n_s * cfg.n_layers), 2), "unit": "prompt tokens/s",
+            "cores": threads, "kind": "oracle",
+            "sample": f"layers 0..{n_s - 1} of {cfg.n_layers} in {t_cpu:.1f} s, extrapolated x{cfg.n_layers / n_s:g}",
+        }
+        parity = {"layers_checked": n_s, "heads_with_differing_retained_set": differing,
+                  "heads_checked": n_s * cfg.n_kv_heads}
+
+    out = {
+        "metric": "prefix tokens compressed/sec (all layers+heads)",
+        "value": round(tokens_per_s, 1), "unit": "prompt tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {L} layers x {cfg.n_kv_heads} KV heads ({cfg.n_q_heads} Q heads), "
+                               f"d={cfg.head_dim}, N={cfg.n_tokens}, w={cfg.window}, pool={cfg.pool_kernel}, "
+                               f"B={cfg.budget_for_layer(0)}..{cfg.budget_for_layer(L - 1)}, S={cfg.n_sources}, "
+                               f"m={cfg.n_neighbors}, T={cfg.rounds}, reselect={cfg.reselect}, alpha={cfg.decay}",
+                   "token_head_units_per_s": round(tokens_per_s * cfg.n_layers * cfg.n_kv_heads, 1),
+                   "input_generation_s": round(t_gen, 1)},
+        "roofline": roofline, "cpu_baseline": cpu, "pass_vs_streaming_model": pass_view,
+        "kernels": kernels, "parity_sample": parity,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

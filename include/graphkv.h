@@ -54,9 +54,9 @@ enum { GRAPHKV_POOL_AVG = 0, GRAPHKV_POOL_MAX = 1 };
  * evicted sets the score to -infinity. */
 enum { GRAPHKV_SIGNAL_DECAY = 0, GRAPHKV_SIGNAL_ENHANCED = 1, GRAPHKV_SIGNAL_EVICTED = 2 };
 /* Kernel family: AUTO picks the bf16 MFMA kernels when the shape allows them
- * (bf16, d = 128, G*w a multiple of 32 and at most 128) and the scalar kernels
- * otherwise; GENERIC forces the scalar kernels (same results up to fp32
- * rounding order). */
+ * (bf16 and d = 128; for scoring also G*w a multiple of 32 and at most 128, and
+ * w a multiple of 32 with max pooling) and the scalar kernels otherwise; GENERIC
+ * forces the scalar kernels (same results up to fp32 rounding order). */
 enum { GRAPHKV_IMPL_AUTO = 0, GRAPHKV_IMPL_GENERIC = 1 };
 
 typedef struct graphkv_params {
@@ -68,7 +68,7 @@ typedef struct graphkv_params {
     int32_t pool_kernel;   /* odd, >= 1 (1 = no pooling)                             */
     int32_t pool_mode;     /* GRAPHKV_POOL_*                                         */
     int32_t budget;        /* B, w < B <= N (select/compress only)                   */
-    int32_t n_sources;     /* S, 1 <= S <= min(P, 1024) when rounds > 0              */
+    int32_t n_sources;     /* S, 1 <= S <= min(P, 65535) when rounds > 0             */
     int32_t n_neighbors;   /* m, 1 <= m <= P - 1 when rounds > 0                     */
     int32_t rounds;        /* T >= 0                                                 */
     float   decay;         /* alpha in [0, 1]                                        */
@@ -158,6 +158,26 @@ int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc
 
 /* Host string for a return code (static storage). */
 const char *graphkv_strerror(int32_t code);
+
+/*
+ * Measurement aid (not part of the method): per-kernel timing with HIP events.
+ * Between graphkv_profile_begin() and graphkv_profile_end() every kernel the
+ * library launches is bracketed by two events on the caller's stream (the event
+ * pool is created on first use and kept; this is the one piece of process-wide
+ * state, and it is not thread-safe).  graphkv_profile_end() waits for the
+ * recorded events and adds up, per kernel id, the elapsed milliseconds into
+ * ms[GRAPHKV_N_KERNELS] and the number of launches into launches[...] (HOST
+ * arrays, either may be NULL).
+ */
+enum {
+    GRAPHKV_K_SCORE_STATS = 0, GRAPHKV_K_SCORE_VOTES, GRAPHKV_K_POOL, GRAPHKV_K_TOPK_SOURCES,
+    GRAPHKV_K_COSINE, GRAPHKV_K_TOPK_NEIGHBORS, GRAPHKV_K_DECAY, GRAPHKV_K_TOPK_FINAL,
+    GRAPHKV_K_GATHER, GRAPHKV_K_GENERIC_LOGITS, GRAPHKV_K_GENERIC_VOTES, GRAPHKV_K_GENERIC_COSINE,
+    GRAPHKV_K_KNORM, GRAPHKV_K_COPY, GRAPHKV_N_KERNELS
+};
+int32_t graphkv_profile_begin(void);
+int32_t graphkv_profile_end(double *ms, int64_t *launches);
+const char *graphkv_kernel_name(int32_t id);
 
 /* 1 if AUTO would run the MFMA kernels for these params, 0 otherwise. */
 int32_t graphkv_uses_mfma(const graphkv_params *p);

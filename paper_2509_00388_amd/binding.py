@@ -23,7 +23,9 @@ SIGNAL_DECAY, SIGNAL_ENHANCED, SIGNAL_EVICTED = 0, 1, 2
 IMPL_AUTO, IMPL_GENERIC = 0, 1
 
 EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "graphkv_propagate",
-           "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma")
+           "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma",
+           "graphkv_profile_begin", "graphkv_profile_end", "graphkv_kernel_name")
+N_KERNELS = 14
 
 
 class GraphKVError(RuntimeError):
@@ -105,6 +107,12 @@ def load_library() -> ctypes.CDLL:
     lib.graphkv_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.graphkv_strerror.restype = ctypes.c_char_p
     lib.graphkv_strerror.argtypes = [i32]
+    lib.graphkv_profile_begin.restype = i32
+    lib.graphkv_profile_begin.argtypes = []
+    lib.graphkv_profile_end.restype = i32
+    lib.graphkv_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.graphkv_kernel_name.restype = ctypes.c_char_p
+    lib.graphkv_kernel_name.argtypes = [i32]
     _lib = lib
     return lib
 
@@ -203,6 +211,19 @@ def graphkv_compress(p: Params, Kc, Vc, Qw, Kout=None, Vout=None, idx=None, scor
                                            _ptr(Vout), _ptr(idx), _ptr(scores_out), _ptr(ws),
                                            ws.numel(), _stream()))
     return Kout, Vout, idx
+
+
+def graphkv_profile_begin():
+    _check(load_library().graphkv_profile_begin())
+
+
+def graphkv_profile_end():
+    """{kernel name: (total ms, launches)} for the kernels launched since profile_begin."""
+    ms = (ctypes.c_double * N_KERNELS)()
+    cnt = (ctypes.c_int64 * N_KERNELS)()
+    _check(load_library().graphkv_profile_end(ms, cnt))
+    lib = load_library()
+    return {lib.graphkv_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(N_KERNELS) if cnt[i]}
 
 
 # ---- helpers to move the synthetic numpy tensors (fp32 / bf16 bits) to the device ----

@@ -4,6 +4,7 @@
 #include "kernels.hpp"
 
 #include <math.h>
+#include <vector>
 
 namespace {
 
@@ -128,9 +129,46 @@ int32_t check_ws(const Workspace &W, const void *ws, size_t ws_bytes)
     return GRAPHKV_OK;
 }
 
-#define GKV_TRY(expr)                                   \
-    do {                                                \
-        if ((expr) != hipSuccess) return GRAPHKV_EHIP;  \
+// ---- optional per-kernel timing (graphkv_profile_begin / _end) ----------------
+// While profiling is on, every kernel launch is bracketed by two HIP events on
+// the caller's stream.  Process-wide and not thread-safe: a measurement aid.
+struct ProfRec { int id; hipEvent_t e0, e1; };
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> pool;
+    size_t used = 0;
+    std::vector<ProfRec> recs;
+    hipEvent_t next()
+    {
+        if (used == pool.size()) {
+            hipEvent_t e = nullptr;
+            if (hipEventCreate(&e) != hipSuccess) return nullptr;
+            pool.push_back(e);
+        }
+        return pool[used++];
+    }
+};
+Profiler g_prof;
+
+const char *const kKernelNames[GRAPHKV_N_KERNELS] = {
+    "score_stats", "score_votes", "pool_group", "topk_sources", "cosine", "topk_neighbors",
+    "decay", "topk_final", "gather", "generic_logits", "generic_votes", "generic_cosine",
+    "knorm", "copy"};
+
+#define GKV_LAUNCH(id, expr)                                              \
+    do {                                                                  \
+        hipEvent_t e0_ = nullptr, e1_ = nullptr;                          \
+        if (g_prof.on) {                                                  \
+            e0_ = g_prof.next();                                          \
+            e1_ = g_prof.next();                                          \
+            if (e0_ && e1_) (void)hipEventRecord(e0_, st);                \
+        }                                                                 \
+        const hipError_t err_ = (expr);                                   \
+        if (g_prof.on && e0_ && e1_) {                                    \
+            (void)hipEventRecord(e1_, st);                                \
+            g_prof.recs.push_back({(id), e0_, e1_});                      \
+        }                                                                 \
+        if (err_ != hipSuccess) return GRAPHKV_EHIP;                      \
     } while (0)
 
 template <typename T> T *at(void *ws, size_t off) { return reinterpret_cast<T *>((char *)ws + off); }
@@ -141,18 +179,21 @@ int32_t run_score(const graphkv_params *p, const Dims &D, const Workspace &W, co
     float *votes = at<float>(ws, W.votes);
     if (D.mfma_score) {
         const int per_q = p->pool_mode == GRAPHKV_POOL_MAX;
-        GKV_TRY(launch_mfma_score(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale, per_q,
-                                  at<float>(ws, W.part), votes, st));
-        GKV_TRY(launch_pool_group(votes, D.H, per_q ? D.G : 1, D.P, p->pool_kernel, p->pool_mode,
+        GKV_LAUNCH(GRAPHKV_K_SCORE_STATS, launch_mfma_score_stats(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale,
+                                                                  at<float>(ws, W.part), st));
+        GKV_LAUNCH(GRAPHKV_K_SCORE_VOTES,
+                   launch_mfma_score_votes(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale, per_q,
+                                           at<float>(ws, W.part), votes, st));
+        GKV_LAUNCH(GRAPHKV_K_POOL, launch_pool_group(votes, D.H, per_q ? D.G : 1, D.P, p->pool_kernel, p->pool_mode,
                                   (float)D.G, scores, st));
         return GRAPHKV_OK;
     }
-    GKV_TRY(launch_generic_logits(Kc, Qw, p->dtype, D.H, D.Hq, D.d, D.N, D.w, D.scale,
+    GKV_LAUNCH(GRAPHKV_K_GENERIC_LOGITS, launch_generic_logits(Kc, Qw, p->dtype, D.H, D.Hq, D.d, D.N, D.w, D.scale,
                                   at<float>(ws, W.logits), at<float>(ws, W.row_max),
                                   at<float>(ws, W.row_sum), st));
-    GKV_TRY(launch_generic_votes(at<float>(ws, W.logits), at<float>(ws, W.row_max),
+    GKV_LAUNCH(GRAPHKV_K_GENERIC_VOTES, launch_generic_votes(at<float>(ws, W.logits), at<float>(ws, W.row_max),
                                  at<float>(ws, W.row_sum), D.Hq, D.N, D.w, votes, st));
-    GKV_TRY(launch_pool_group(votes, D.H, D.G, D.P, p->pool_kernel, p->pool_mode, (float)D.G,
+    GKV_LAUNCH(GRAPHKV_K_POOL, launch_pool_group(votes, D.H, D.G, D.P, p->pool_kernel, p->pool_mode, (float)D.G,
                               scores, st));
     return GRAPHKV_OK;
 }
@@ -180,28 +221,32 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
             if (dbg_nbr) nbr = dbg_nbr + t * n_nbr;
             if (dbg_e) ev = dbg_e + t * n_nbr;
             // Eq. 2: source nodes
-            GKV_TRY(launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, 0, 0, st));
+            GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES,
+                       launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, 0, 0, st));
             // Eq. 1: edges from every source to every node
             if (D.mfma_cosine)
-                GKV_TRY(launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, st));
+                GKV_LAUNCH(GRAPHKV_K_COSINE, launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, st));
             else
-                GKV_TRY(launch_generic_cosine(Kc, p->dtype, D.H, D.d, D.N, D.P, D.S, src, E, st));
+                GKV_LAUNCH(GRAPHKV_K_GENERIC_COSINE,
+                           launch_generic_cosine(Kc, p->dtype, D.H, D.d, D.N, D.P, D.S, src, E, st));
             // Eq. 3: neighbourhoods
-            GKV_TRY(launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, 0, 0, st));
+            GKV_LAUNCH(GRAPHKV_K_TOPK_NEIGHBORS,
+                       launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, 0, 0, st));
         } else {
-            if (dbg_src) GKV_TRY(launch_copy_i32(src0, dbg_src + t * n_src, (long)n_src, st));
-            if (dbg_nbr) GKV_TRY(launch_copy_i32(nbr0, dbg_nbr + t * n_nbr, (long)n_nbr, st));
-            if (dbg_e) GKV_TRY(launch_copy_f32(e0, dbg_e + t * n_nbr, (long)n_nbr, st));
+            if (dbg_src) GKV_LAUNCH(GRAPHKV_K_COPY, launch_copy_i32(src0, dbg_src + t * n_src, (long)n_src, st));
+            if (dbg_nbr) GKV_LAUNCH(GRAPHKV_K_COPY, launch_copy_i32(nbr0, dbg_nbr + t * n_nbr, (long)n_nbr, st));
+            if (dbg_e) GKV_LAUNCH(GRAPHKV_K_COPY, launch_copy_f32(e0, dbg_e + t * n_nbr, (long)n_nbr, st));
         }
         // Eq. 5: one round of the signal
-        GKV_TRY(launch_decay(scores, D.H, D.P, D.S, D.m, nbr, ev, p->decay, p->signal, st));
+        GKV_LAUNCH(GRAPHKV_K_DECAY, launch_decay(scores, D.H, D.P, D.S, D.m, nbr, ev, p->decay, p->signal, st));
     }
     return GRAPHKV_OK;
 }
 
 int32_t run_select(const Dims &D, const float *scores, int32_t *idx, hipStream_t st)
 {
-    GKV_TRY(launch_topk_rows(scores, D.P, D.P, D.H, D.B - D.w, idx, D.B, nullptr, 0, D.P, D.w, st));
+    GKV_LAUNCH(GRAPHKV_K_TOPK_FINAL,
+               launch_topk_rows(scores, D.P, D.P, D.H, D.B - D.w, idx, D.B, nullptr, 0, D.P, D.w, st));
     return GRAPHKV_OK;
 }
 
@@ -240,7 +285,8 @@ int32_t graphkv_score_knorm(const graphkv_params *p, const void *Kc, float *scor
     if (!base_ok(p)) return GRAPHKV_EINVAL;
     if (!aligned16(Kc) || !aligned4(scores)) return GRAPHKV_EINVAL;
     const Dims D = dims_of(p);
-    GKV_TRY(launch_knorm(Kc, p->dtype, D.H, D.d, D.N, D.P, scores, (hipStream_t)stream));
+    hipStream_t st = (hipStream_t)stream;
+    GKV_LAUNCH(GRAPHKV_K_KNORM, launch_knorm(Kc, p->dtype, D.H, D.d, D.N, D.P, scores, st));
     return GRAPHKV_OK;
 }
 
@@ -287,8 +333,43 @@ int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc
     if (int32_t rc = run_propagate(p, D, W, Kc, scores, nullptr, nullptr, nullptr, ws, st))
         return rc;
     if (int32_t rc = run_select(D, scores, idx, st)) return rc;
-    GKV_TRY(launch_gather(Kc, Vc, idx, D.H, D.N, D.B, (int)(D.d * D.esize), Kout, Vout, st));
+    GKV_LAUNCH(GRAPHKV_K_GATHER, launch_gather(Kc, Vc, idx, D.H, D.N, D.B, (int)(D.d * D.esize), Kout, Vout, st));
     return GRAPHKV_OK;
+}
+
+int32_t graphkv_profile_begin(void)
+{
+    g_prof.used = 0;
+    g_prof.recs.clear();
+    g_prof.on = true;
+    return GRAPHKV_OK;
+}
+
+int32_t graphkv_profile_end(double *ms, int64_t *launches)
+{
+    g_prof.on = false;
+    for (int i = 0; i < GRAPHKV_N_KERNELS; ++i) {
+        if (ms) ms[i] = 0.0;
+        if (launches) launches[i] = 0;
+    }
+    int32_t rc = GRAPHKV_OK;
+    for (const ProfRec &r : g_prof.recs) {
+        float t = 0.f;
+        if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&t, r.e0, r.e1) != hipSuccess) {
+            rc = GRAPHKV_EHIP;
+            continue;
+        }
+        if (ms) ms[r.id] += t;
+        if (launches) launches[r.id] += 1;
+    }
+    g_prof.recs.clear();
+    g_prof.used = 0;
+    return rc;
+}
+
+const char *graphkv_kernel_name(int32_t id)
+{
+    return (id >= 0 && id < GRAPHKV_N_KERNELS) ? kKernelNames[id] : "unknown";
 }
 
 const char *graphkv_strerror(int32_t code)

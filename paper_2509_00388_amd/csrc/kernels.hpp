@@ -52,9 +52,11 @@ struct MfmaScorePlan {
 MfmaScorePlan mfma_score_plan(int Hkv, int rows, int N);
 // Pass A: per (head, chunk, row) partial max and sum of exp2 over the chunk's visible keys.
 // Pass B: votes [Hkv, P] (avg mode, all rows summed) or [Hq, P] (per query head).
-hipError_t launch_mfma_score(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
-                             float scale, int per_qhead_votes, float *part, float *votes,
-                             hipStream_t st);
+hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
+                                  float scale, float *part, hipStream_t st);
+hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
+                                  float scale, int per_qhead_votes, const float *part, float *votes,
+                                  hipStream_t st);
 // E [Hkv, S, P] from bf16 keys (same contract as launch_generic_cosine).
 hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
                               float *E, hipStream_t st);

@@ -254,26 +254,6 @@ __global__ __launch_bounds__(256) void score_votes_kernel(
     }
 }
 
-template <int NB>
-hipError_t launch_nb(const uint16_t *Kc, const uint16_t *Qw, int Hkv, int G, int N, int w, float c,
-                     int per_q, const MfmaScorePlan &plan, int chunk_keys, float *part,
-                     float *votes, hipStream_t st)
-{
-    const int P = N - w;
-    dim3 grid(plan.chunks, Hkv), block(256);
-    hipLaunchKernelGGL(score_stats_kernel<NB>, grid, block, 0, st, Kc, Qw, N, P, w, chunk_keys, c,
-                       part);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (per_q)
-        hipLaunchKernelGGL((score_votes_kernel<NB, true>), grid, block, 0, st, Kc, Qw, N, P, w, G,
-                           chunk_keys, c, part, plan.chunks, votes);
-    else
-        hipLaunchKernelGGL((score_votes_kernel<NB, false>), grid, block, 0, st, Kc, Qw, N, P, w, G,
-                           chunk_keys, c, part, plan.chunks, votes);
-    return hipGetLastError();
-}
-
 int chunk_keys_for(int Hkv, int N)
 {
     const int target = Hkv >= 256 ? 1 : 256 / Hkv;           // about one workgroup per CU
@@ -293,22 +273,56 @@ MfmaScorePlan mfma_score_plan(int Hkv, int rows, int N)
     return pl;
 }
 
-hipError_t launch_mfma_score(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
-                             float scale, int per_qhead_votes, float *part, float *votes,
-                             hipStream_t st)
+hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
+                                  float scale, float *part, hipStream_t st)
 {
-    const int G = Hq / Hkv, R = G * w;
+    const int G = Hq / Hkv, R = G * w, P = N - w;
     const MfmaScorePlan plan = mfma_score_plan(Hkv, R, N);
     const int ck = chunk_keys_for(Hkv, N);
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
+    dim3 grid(plan.chunks, Hkv), block(256);
     switch (R / 32) {
-        case 1: return launch_nb<1>(K, Q, Hkv, G, N, w, c, per_qhead_votes, plan, ck, part, votes, st);
-        case 2: return launch_nb<2>(K, Q, Hkv, G, N, w, c, per_qhead_votes, plan, ck, part, votes, st);
-        case 3: return launch_nb<3>(K, Q, Hkv, G, N, w, c, per_qhead_votes, plan, ck, part, votes, st);
-        case 4: return launch_nb<4>(K, Q, Hkv, G, N, w, c, per_qhead_votes, plan, ck, part, votes, st);
+        case 1: hipLaunchKernelGGL(score_stats_kernel<1>, grid, block, 0, st, K, Q, N, P, w, ck, c, part); break;
+        case 2: hipLaunchKernelGGL(score_stats_kernel<2>, grid, block, 0, st, K, Q, N, P, w, ck, c, part); break;
+        case 3: hipLaunchKernelGGL(score_stats_kernel<3>, grid, block, 0, st, K, Q, N, P, w, ck, c, part); break;
+        case 4: hipLaunchKernelGGL(score_stats_kernel<4>, grid, block, 0, st, K, Q, N, P, w, ck, c, part); break;
         default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+template <int NB>
+static void launch_votes_nb(dim3 grid, const uint16_t *K, const uint16_t *Q, int N, int P, int w, int G,
+                            int ck, float c, const float *part, int chunks, int per_q, float *votes,
+                            hipStream_t st)
+{
+    if (per_q)
+        hipLaunchKernelGGL((score_votes_kernel<NB, true>), grid, dim3(256), 0, st, K, Q, N, P, w, G, ck,
+                           c, part, chunks, votes);
+    else
+        hipLaunchKernelGGL((score_votes_kernel<NB, false>), grid, dim3(256), 0, st, K, Q, N, P, w, G, ck,
+                           c, part, chunks, votes);
+}
+
+hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
+                                  float scale, int per_qhead_votes, const float *part, float *votes,
+                                  hipStream_t st)
+{
+    const int G = Hq / Hkv, R = G * w, P = N - w;
+    const MfmaScorePlan plan = mfma_score_plan(Hkv, R, N);
+    const int ck = chunk_keys_for(Hkv, N);
+    const float c = scale * 1.4426950408889634f;
+    const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
+    dim3 grid(plan.chunks, Hkv);
+    switch (R / 32) {
+        case 1: launch_votes_nb<1>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st); break;
+        case 2: launch_votes_nb<2>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st); break;
+        case 3: launch_votes_nb<3>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st); break;
+        case 4: launch_votes_nb<4>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 }  // namespace gkv
