@@ -25,7 +25,7 @@ IMPL_AUTO, IMPL_GENERIC = 0, 1
 EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "graphkv_propagate",
            "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma",
            "graphkv_profile_begin", "graphkv_profile_end", "graphkv_kernel_name")
-N_KERNELS = 14
+N_KERNELS = 20
 
 
 class GraphKVError(RuntimeError):

@@ -15,14 +15,15 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
 
 struct Dims {
     int H, Hq, G, d, N, w, P, B, S, m, T;
-    bool mfma_score, mfma_cosine;
+    bool mfma_score, mfma_cosine, filter;
     float scale;
     size_t esize;
 };
 
 // Workspace: a bump allocation of every scratch array any entry point may need.
 struct Workspace {
-    size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, part, total;
+    size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, part;
+    size_t E_sample, tau, cand, cand_cnt, overflow, total;
 };
 
 // The MFMA kernels cover bf16 keys with d = 128.  Scoring additionally needs the
@@ -94,6 +95,7 @@ Dims dims_of(const graphkv_params *p)
     D.T = p->rounds;
     D.mfma_score = mfma_score_ok(p);
     D.mfma_cosine = mfma_cosine_ok(p);
+    D.filter = D.mfma_cosine && D.T > 0 && mfma_filter_applies(D.P, D.m);
     D.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
     D.esize = p->dtype == GRAPHKV_FP32 ? 4 : 2;
     return D;
@@ -116,6 +118,11 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.nbr_e = take((size_t)D.H * D.S * D.m * 4);
     W.scores = take((size_t)D.H * D.P * 4);
     W.part = take(D.mfma_score ? mfma_score_plan(D.H, D.G * D.w, D.N).part_bytes : 0);
+    W.E_sample = take(D.filter ? (size_t)D.H * D.S * mfma_sample_cols(D.P) * 4 : 0);
+    W.tau = take((size_t)D.H * D.S * 4);
+    W.cand = take(D.filter ? (size_t)D.H * D.S * mfma_cand_cap(D.P, D.m) * 8 : 0);
+    W.cand_cnt = take((size_t)D.H * D.S * 4);
+    W.overflow = take((size_t)D.H * 4);
     W.total = off;
     return W;
 }
@@ -153,7 +160,8 @@ Profiler g_prof;
 const char *const kKernelNames[GRAPHKV_N_KERNELS] = {
     "score_stats", "score_votes", "pool_group", "topk_sources", "cosine", "topk_neighbors",
     "decay", "topk_final", "gather", "generic_logits", "generic_votes", "generic_cosine",
-    "knorm", "copy"};
+    "knorm", "copy", "cosine_sample", "topk_bound", "cosine_filter", "nbr_select",
+    "redo_cosine", "redo_topk"};
 
 #define GKV_LAUNCH(id, expr)                                              \
     do {                                                                  \
@@ -222,16 +230,42 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
             if (dbg_e) ev = dbg_e + t * n_nbr;
             // Eq. 2: source nodes
             GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES,
-                       launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, 0, 0, st));
-            // Eq. 1: edges from every source to every node
-            if (D.mfma_cosine)
-                GKV_LAUNCH(GRAPHKV_K_COSINE, launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, st));
-            else
-                GKV_LAUNCH(GRAPHKV_K_GENERIC_COSINE,
-                           launch_generic_cosine(Kc, p->dtype, D.H, D.d, D.N, D.P, D.S, src, E, st));
-            // Eq. 3: neighbourhoods
-            GKV_LAUNCH(GRAPHKV_K_TOPK_NEIGHBORS,
-                       launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, 0, 0, st));
+                       launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, nullptr, 0, 0,
+                                        nullptr, 1, st));
+            if (D.filter) {
+                // Eq. 1 + Eq. 3 in one streaming pass over the keys: a bound on each source's
+                // m-th largest edge from a strided sample, then only edges above it are kept.
+                float *Es = at<float>(ws, W.E_sample), *tau = at<float>(ws, W.tau);
+                int32_t *cnt = at<int32_t>(ws, W.cand_cnt), *ovf = at<int32_t>(ws, W.overflow);
+                void *cand = at<char>(ws, W.cand);
+                const int ps = mfma_sample_cols(D.P);
+                GKV_LAUNCH(GRAPHKV_K_COSINE_SAMPLE,
+                           launch_mfma_cosine_sample(Kc, D.H, D.N, D.P, D.S, src, Es, cnt, ovf, st));
+                GKV_LAUNCH(GRAPHKV_K_TOPK_BOUND,
+                           launch_topk_rows(Es, ps, ps, D.H * D.S, D.m, nullptr, 0, nullptr, 0, tau, 0, 0,
+                                            nullptr, 1, st));
+                GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
+                           launch_mfma_cosine_filter(Kc, D.H, D.N, D.P, D.S, D.m, src, tau, cand, cnt,
+                                                     ovf, st));
+                GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
+                           launch_nbr_select(cand, cnt, ovf, D.H, D.P, D.S, D.m, nbr, ev, st));
+                // heads whose lists overflowed are redone through the dense block
+                GKV_LAUNCH(GRAPHKV_K_REDO_COSINE, launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, ovf, st));
+                GKV_LAUNCH(GRAPHKV_K_REDO_TOPK,
+                           launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, nullptr, 0, 0,
+                                            ovf, D.S, st));
+            } else {
+                // Eq. 1: edges from every source to every node
+                if (D.mfma_cosine)
+                    GKV_LAUNCH(GRAPHKV_K_COSINE, launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, nullptr, st));
+                else
+                    GKV_LAUNCH(GRAPHKV_K_GENERIC_COSINE,
+                               launch_generic_cosine(Kc, p->dtype, D.H, D.d, D.N, D.P, D.S, src, E, st));
+                // Eq. 3: neighbourhoods
+                GKV_LAUNCH(GRAPHKV_K_TOPK_NEIGHBORS,
+                           launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, nullptr, 0, 0,
+                                            nullptr, 1, st));
+            }
         } else {
             if (dbg_src) GKV_LAUNCH(GRAPHKV_K_COPY, launch_copy_i32(src0, dbg_src + t * n_src, (long)n_src, st));
             if (dbg_nbr) GKV_LAUNCH(GRAPHKV_K_COPY, launch_copy_i32(nbr0, dbg_nbr + t * n_nbr, (long)n_nbr, st));
@@ -246,7 +280,8 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
 int32_t run_select(const Dims &D, const float *scores, int32_t *idx, hipStream_t st)
 {
     GKV_LAUNCH(GRAPHKV_K_TOPK_FINAL,
-               launch_topk_rows(scores, D.P, D.P, D.H, D.B - D.w, idx, D.B, nullptr, 0, D.P, D.w, st));
+               launch_topk_rows(scores, D.P, D.P, D.H, D.B - D.w, idx, D.B, nullptr, 0, nullptr, D.P,
+                                D.w, nullptr, 1, st));
     return GRAPHKV_OK;
 }
 

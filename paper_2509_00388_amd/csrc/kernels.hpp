@@ -12,9 +12,12 @@ namespace gkv {
 // ascending index order to idx_out + r*idx_ld (and their values to val_out +
 // r*val_ld when val_out != nullptr).  After the k picks, `append_count`
 // consecutive integers starting at `append_from` are appended to idx_out.
+// tau_out (optional) receives the k-th largest value of each row; idx_out may
+// then be nullptr.  gate (optional): row r is skipped when gate[r / rows_per_gate] == 0.
 hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k,
                             int32_t *idx_out, long idx_ld, float *val_out, long val_ld,
-                            int append_from, int append_count, hipStream_t st);
+                            float *tau_out, int append_from, int append_count,
+                            const int32_t *gate, int rows_per_gate, hipStream_t st);
 
 // ---- scalar kernels for any dtype / shape (generic.hip) ----------------------
 // logits [Hq*w, N] (fp32, scaled), then per-row max and sum of exp.
@@ -57,8 +60,25 @@ hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int 
 hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
                                   float scale, int per_qhead_votes, const float *part, float *votes,
                                   hipStream_t st);
-// E [Hkv, S, P] from bf16 keys (same contract as launch_generic_cosine).
+// E [Hkv, S, P] from bf16 keys (same contract as launch_generic_cosine); heads with
+// gate[h] == 0 are skipped when gate != nullptr.
 hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
-                              float *E, hipStream_t st);
+                              float *E, const int32_t *gate, hipStream_t st);
+// Neighbourhoods without the dense block (see mfma_cosine.hip):
+bool mfma_filter_applies(int P, int m);
+int mfma_sample_cols(int P);          // keys in the strided sample
+int mfma_cand_cap(int P, int m);      // entries per source in the candidate lists
+// E_sample [Hkv, S, sample_cols] on every (P / sample_cols)-th key; clears cand_cnt, overflow.
+hipError_t launch_mfma_cosine_sample(const void *Kc, int Hkv, int N, int P, int S,
+                                     const int32_t *src, float *E_sample, int32_t *cand_cnt,
+                                     int32_t *overflow, hipStream_t st);
+// Streams all keys; edges >= tau[h, a] go to cand [Hkv, S, cap] x 8 bytes, counts to cand_cnt.
+hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int S, int m,
+                                     const int32_t *src, const float *tau, void *cand,
+                                     int32_t *cand_cnt, int32_t *overflow, hipStream_t st);
+// Exact top-m of each candidate list -> nbr / nbr_e [Hkv, S, m]; skips heads with overflow[h].
+hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, const int32_t *overflow,
+                             int Hkv, int P, int S, int m, int32_t *nbr, float *nbr_e,
+                             hipStream_t st);
 
 }  // namespace gkv

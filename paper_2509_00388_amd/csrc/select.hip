@@ -3,91 +3,255 @@
 // (Eq. 3) and the final budgeted selection.
 //
 // One workgroup per row.  The k-th largest value is found by a most-significant-
-// digit-first radix select over an order-preserving 32-bit key (4 passes of 8
-// bits, integer histograms in LDS), which also tells how many entries equal to
-// the threshold are still needed.  A last sweep emits, in index order, every
-// entry above the threshold and the first `need` entries equal to it: that is
-// exactly "first k by (value desc, index asc)".  All counting is integer, so the
-// result does not depend on scheduling.
+// digit-first radix select over an order-preserving 32-bit key (digits of 11,
+// 11 and 10 bits, integer histograms in LDS), which also tells how many entries
+// equal to the threshold are still needed.  A last sweep emits, in index order,
+// every entry above the threshold and the first `need` entries equal to it:
+// that is exactly "first k by (value desc, index asc)".  All counting is
+// integer, so the result does not depend on scheduling.
+//
+// Rows of up to 32768 entries are read once, coalesced, and kept in LDS for all
+// sweeps; longer rows are re-read from L2 in every sweep.
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace gkv {
 
+namespace {
+
+constexpr int kBins = 2048;
+
+__device__ __forceinline__ float key_to_float(uint32_t key)   // inverse of ord_key
+{
+    return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
+// Histogram one digit of the keys that still match the prefix.  `in` says
+// whether this lane's key takes part.  A wave whose keys all share the digit
+// (usual in the top digit) issues a single add.
+__device__ __forceinline__ void hist_add(uint32_t *hist, bool in, uint32_t dig, int lane)
+{
+    const uint64_t act = __ballot(in);
+    if (!act) return;
+    const int first = __ffsll((long long)act) - 1;
+    const uint32_t d0 = __shfl(dig, first, kWave);
+    const uint64_t same = __ballot(in && dig == d0);
+    if (same == act) {
+        if (lane == first) atomicAdd(&hist[d0], (uint32_t)__popcll(act));
+    } else if (in) {
+        atomicAdd(&hist[dig], 1u);
+    }
+}
+
+// Wave 0: find the bin where the count of larger-or-equal digits reaches `need`.
+// Lane L owns bins 32L .. 32L+31.  Writes {bin, need - (entries in higher bins)}.
+__device__ __forceinline__ void find_bin(const uint32_t *hist, uint32_t need, int lane,
+                                         uint32_t *s_bin, uint32_t *s_need)
+{
+    uint32_t t = 0;
+#pragma unroll
+    for (int b = 0; b < 32; ++b) t += hist[32 * lane + b];
+    uint32_t incl = t;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_down(incl, o, kWave);
+        if (lane + o < 64) incl += v;
+    }
+    const uint32_t excl = incl - t;   // entries in strictly higher lanes
+    if (excl < need && need <= incl) {
+        uint32_t cum = excl;
+        int b = 31;
+        for (; b > 0; --b) {
+            const uint32_t c = hist[32 * lane + b];
+            if (cum + c >= need) break;
+            cum += c;
+        }
+        *s_bin = 32 * lane + b;
+        *s_need = need - cum;
+    }
+}
+
+}  // namespace
+
+// ---- rows kept in LDS ---------------------------------------------------------
+// The row is read once, coalesced, and its keys stay in LDS (up to 32768 entries
+// = 128 KiB) for all sweeps.  Thread t handles entries i*BLOCK + t; index order is
+// therefore (i, wave, lane), and the emit sweep counts per (i, wave) cell with
+// ballots and scans the cells once.
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void topk_rows_kernel(
+__global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
-    float *__restrict__ val_out, long val_ld, int append_from, int append_count)
+    float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
+    int append_count, const int32_t *__restrict__ gate, int rows_per_gate)
 {
     constexpr int NW = BLOCK / kWave;
-    __shared__ uint32_t hist[256];
+    extern __shared__ uint32_t dyn[];
+    __shared__ uint32_t hist[kBins];
+    __shared__ uint32_t s_bin, s_need;
+
+    if (gate && gate[blockIdx.x / rows_per_gate] == 0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int items = (n + BLOCK - 1) / BLOCK;
+    const int ncell = items * NW;
+    uint32_t *keys = dyn;                    // [items * BLOCK]
+    uint32_t *cg = dyn + items * BLOCK;      // [ncell]
+    uint32_t *ce = cg + ncell;               // [ncell]
+    const float *xr = x + (long)blockIdx.x * ld;
+    int32_t *out = idx_out ? idx_out + (long)blockIdx.x * idx_ld : nullptr;
+    float *vout = val_out ? val_out + (long)blockIdx.x * val_ld : nullptr;
+
+    if (out)
+        for (int r = tid; r < append_count; r += BLOCK) out[k + r] = append_from + r;
+    if (k <= 0) return;
+
+    // Keys to LDS; the row's key range [kmin, kmax] on the way.
+    __shared__ uint32_t s_min[NW], s_max[NW];
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll 8
+    for (int i = 0; i < items; ++i) {
+        const int j = i * BLOCK + tid;
+        const uint32_t key = ord_key(j < n ? xr[j] : 0.f);
+        keys[j] = key;
+        if (j < n) { kmin = min(kmin, key); kmax = max(kmax, key); }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+    }
+    if (lane == 0) { s_min[wv] = kmin; s_max[wv] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < NW; ++u) { kmin = min(kmin, s_min[u]); kmax = max(kmax, s_max[u]); }
+
+    // Radix select on (key - kmin): only the bits in which the row's keys differ
+    // are swept, and the top digit is spread over the bins whatever the value range.
+    const uint32_t range = kmax - kmin;
+    int remaining = range ? 32 - __clz(range) : 0;
+    uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
+    while (remaining > 0) {
+        const int bits = remaining < 11 ? remaining : 11;
+        const int shift = remaining - bits;
+        const uint32_t dmask = (1u << bits) - 1u;
+        for (int b = tid; b < kBins; b += BLOCK) hist[b] = 0;
+        __syncthreads();
+        for (int i = 0; i < items; ++i) {
+            const int j = i * BLOCK + tid;
+            const uint32_t rel = keys[j] - kmin;
+            if (j < n && (rel & mask) == prefix) atomicAdd(&hist[(rel >> shift) & dmask], 1u);
+        }
+        __syncthreads();
+        if (wv == 0) find_bin(hist, need, lane, &s_bin, &s_need);
+        __syncthreads();
+        prefix |= s_bin << shift;
+        mask |= dmask << shift;
+        need = s_need;
+        remaining = shift;
+    }
+    const uint32_t tau = kmin + prefix;   // key of the k-th largest entry; take `need` entries equal to it
+    if (tau_out && tid == 0) tau_out[blockIdx.x] = key_to_float(tau);
+    if (!out) return;
+
+
+    for (int i = 0; i < items; ++i) {
+        const int j = i * BLOCK + tid;
+        const uint32_t key = keys[j];
+        const uint32_t ng = __popcll(__ballot(j < n && key > tau));
+        const uint32_t ne = __popcll(__ballot(j < n && key == tau));
+        if (lane == 0) { cg[i * NW + wv] = ng; ce[i * NW + wv] = ne; }
+    }
+    __syncthreads();
+    if (wv == 0) {   // exclusive scan of the cells in index order; lane L owns a contiguous run
+        const int per = (ncell + 63) / 64;
+        const int c0 = min(lane * per, ncell), c1 = min(c0 + per, ncell);
+        uint32_t sg = 0, se = 0;
+        for (int c = c0; c < c1; ++c) { sg += cg[c]; se += ce[c]; }
+        uint32_t ig = sg, ie = se;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t a = __shfl_up(ig, o, kWave), b = __shfl_up(ie, o, kWave);
+            if (lane >= o) { ig += a; ie += b; }
+        }
+        uint32_t bg = ig - sg, be = ie - se;
+        for (int c = c0; c < c1; ++c) {
+            const uint32_t tg = cg[c], te = ce[c];
+            cg[c] = bg; ce[c] = be;
+            bg += tg; be += te;
+        }
+    }
+    __syncthreads();
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+
+    for (int i = 0; i < items; ++i) {
+        const int j = i * BLOCK + tid;
+        const uint32_t key = keys[j];
+        const bool g = j < n && key > tau, e = j < n && key == tau;
+        const uint64_t mg = __ballot(g), me = __ballot(e);
+        if (g || e) {
+            const uint32_t g_before = cg[i * NW + wv] + __popcll(mg & lt_mask);
+            const uint32_t e_before = ce[i * NW + wv] + __popcll(me & lt_mask);
+            if (g || e_before < need) {
+                const uint32_t pos = g_before + min(e_before, need);
+                out[pos] = j;
+                if (vout) vout[pos] = key_to_float(key);
+            }
+        }
+    }
+}
+
+// ---- rows of any length: every sweep re-reads the row ------------------------
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
+    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
+    float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
+    int append_count, const int32_t *__restrict__ gate, int rows_per_gate)
+{
+    constexpr int NW = BLOCK / kWave;
+    constexpr int U = 8;   // loads in flight per thread
+    __shared__ uint32_t hist[kBins];
     __shared__ uint32_t s_bin, s_need;
     __shared__ uint32_t w_gt[NW], w_eq[NW];
 
+    if (gate && gate[blockIdx.x / rows_per_gate] == 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const float *xr = x + (long)blockIdx.x * ld;
-    int32_t *out = idx_out + (long)blockIdx.x * idx_ld;
+    int32_t *out = idx_out ? idx_out + (long)blockIdx.x * idx_ld : nullptr;
     float *vout = val_out ? val_out + (long)blockIdx.x * val_ld : nullptr;
 
-    for (int r = tid; r < append_count; r += BLOCK) out[k + r] = append_from + r;
+    if (out)
+        for (int r = tid; r < append_count; r += BLOCK) out[k + r] = append_from + r;
     if (k <= 0) return;
 
     uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        if (tid < 256) hist[tid] = 0;
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+        const uint32_t dmask = pass == 2 ? 1023u : 2047u;
+        for (int b = tid; b < kBins; b += BLOCK) hist[b] = 0;
         __syncthreads();
-        for (int j0 = 0; j0 < n; j0 += BLOCK) {
-            const int j = j0 + tid;
-            const bool live = j < n;
-            const uint32_t key = live ? ord_key(xr[j]) : 0u;
-            const bool in = live && ((key & mask) == prefix);
-            const uint32_t dig = (key >> shift) & 255u;
-            // Same digit in the whole wave (common in the top pass): one add.
-            const uint64_t act = __ballot(in);
-            if (act) {
-                const int first = __ffsll((long long)act) - 1;
-                const uint32_t d0 = __shfl(dig, first, kWave);
-                const uint64_t same = __ballot(in && dig == d0);
-                if (same == act) {
-                    if (lane == first) atomicAdd(&hist[d0], (uint32_t)__popcll(act));
-                } else if (in) {
-                    atomicAdd(&hist[dig], 1u);
-                }
-            }
-        }
-        __syncthreads();
-        if (wv == 0) {
-            // bins 4*lane .. 4*lane+3; suffix sums over higher lanes
-            const uint32_t c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2],
-                           c3 = hist[4 * lane + 3];
-            const uint32_t t = c0 + c1 + c2 + c3;
-            uint32_t incl = t;
+        for (int j0 = 0; j0 < n; j0 += BLOCK * U) {
+            float t[U];
 #pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t v = __shfl_down(incl, o, kWave);
-                if (lane + o < 64) incl += v;
+            for (int u = 0; u < U; ++u) {
+                const int j = j0 + u * BLOCK + tid;
+                t[u] = j < n ? xr[j] : 0.f;
             }
-            const uint32_t excl = incl - t;            // entries in strictly higher lanes
-            if (excl < need && need <= incl) {
-                uint32_t cum = excl, bin, c[4] = {c0, c1, c2, c3};
-                int b = 3;
-                for (; b > 0; --b) {
-                    if (cum + c[b] >= need) break;
-                    cum += c[b];
-                }
-                bin = 4 * lane + b;
-                s_bin = bin;
-                s_need = need - cum;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t key = ord_key(t[u]);
+                const bool in = (j0 + u * BLOCK + tid < n) && ((key & mask) == prefix);
+                hist_add(hist, in, (key >> shift) & dmask, lane);
             }
         }
+        __syncthreads();
+        if (wv == 0) find_bin(hist, need, lane, &s_bin, &s_need);
         __syncthreads();
         prefix |= s_bin << shift;
-        mask |= 255u << shift;
+        mask |= dmask << shift;
         need = s_need;
-        __syncthreads();
     }
-    const uint32_t tau = prefix;   // key of the k-th largest entry; take `need` entries equal to it
+    const uint32_t tau = prefix;
+    if (tau_out && tid == 0) tau_out[blockIdx.x] = key_to_float(tau);
+    if (!out) return;
 
     // Each wave owns a contiguous, 64-aligned segment of the row.
     int seg = (n + NW - 1) / NW;
@@ -95,50 +259,91 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_kernel(
     const int beg = wv * seg;
     const int end = min(n, beg + seg);
 
-    uint32_t cg = 0, ce = 0;
-    for (int j0 = beg; j0 < end; j0 += kWave) {
-        const int j = j0 + lane;
-        const uint32_t key = (j < end) ? ord_key(xr[j]) : 0u;
-        cg += __popcll(__ballot(j < end && key > tau));
-        ce += __popcll(__ballot(j < end && key == tau));
+    uint32_t cgt = 0, ceq = 0;
+    for (int j0 = beg; j0 < end; j0 += kWave * U) {
+        float t[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * kWave + lane;
+            t[u] = j < end ? xr[j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * kWave + lane;
+            const uint32_t key = ord_key(t[u]);
+            cgt += __popcll(__ballot(j < end && key > tau));
+            ceq += __popcll(__ballot(j < end && key == tau));
+        }
     }
-    if (lane == 0) { w_gt[wv] = cg; w_eq[wv] = ce; }
+    if (lane == 0) { w_gt[wv] = cgt; w_eq[wv] = ceq; }
     __syncthreads();
     uint32_t base_g = 0, base_e = 0;
     for (int i = 0; i < wv; ++i) { base_g += w_gt[i]; base_e += w_eq[i]; }
 
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    for (int j0 = beg; j0 < end; j0 += kWave) {
-        const int j = j0 + lane;
-        const bool live = j < end;
-        const float v = live ? xr[j] : 0.0f;
-        const uint32_t key = live ? ord_key(v) : 0u;
-        const bool g = live && key > tau, e = live && key == tau;
-        const uint64_t mg = __ballot(g), me = __ballot(e);
-        const uint32_t g_before = base_g + __popcll(mg & lt_mask);
-        const uint32_t e_before = base_e + __popcll(me & lt_mask);
-        if (g || (e && e_before < need)) {
-            const uint32_t pos = g_before + min(e_before, need);
-            out[pos] = j;
-            if (vout) vout[pos] = v;
+    for (int j0 = beg; j0 < end; j0 += kWave * U) {
+        float t[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * kWave + lane;
+            t[u] = j < end ? xr[j] : 0.f;
         }
-        base_g += __popcll(mg);
-        base_e += __popcll(me);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * kWave + lane;
+            const bool live = j < end;
+            const uint32_t key = ord_key(t[u]);
+            const bool g = live && key > tau, e = live && key == tau;
+            const uint64_t mg = __ballot(g), me = __ballot(e);
+            const uint32_t g_before = base_g + __popcll(mg & lt_mask);
+            const uint32_t e_before = base_e + __popcll(me & lt_mask);
+            if (g || (e && e_before < need)) {
+                const uint32_t pos = g_before + min(e_before, need);
+                out[pos] = j;
+                if (vout) vout[pos] = t[u];
+            }
+            base_g += __popcll(mg);
+            base_e += __popcll(me);
+        }
     }
 }
 
+template <int BLOCK>
+static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
+                             long idx_ld, float *val_out, long val_ld, float *tau_out,
+                             int append_from, int append_count, const int32_t *gate,
+                             int rows_per_gate, hipStream_t st)
+{
+    const int items = (n + BLOCK - 1) / BLOCK;
+    const size_t lds = ((size_t)items * BLOCK + 2 * (size_t)items * (BLOCK / kWave)) * 4;
+    static bool opt_in = false;   // more than 64 KiB of dynamic LDS needs a one-time opt-in
+    if (lds > 65536 && !opt_in) {
+        if (hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess)
+            return hipGetLastError();
+        opt_in = true;
+    }
+    hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK>), dim3(rows), dim3(BLOCK), lds, st, x, ld, n, k,
+                       idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
+                       rows_per_gate);
+    return hipGetLastError();
+}
+
 hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
-                            long idx_ld, float *val_out, long val_ld, int append_from,
-                            int append_count, hipStream_t st)
+                            long idx_ld, float *val_out, long val_ld, float *tau_out,
+                            int append_from, int append_count, const int32_t *gate,
+                            int rows_per_gate, hipStream_t st)
 {
     if (rows <= 0) return hipSuccess;
-    if (n >= 4096) {
-        hipLaunchKernelGGL(topk_rows_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, k,
-                           idx_out, idx_ld, val_out, val_ld, append_from, append_count);
-    } else {
-        hipLaunchKernelGGL(topk_rows_kernel<256>, dim3(rows), dim3(256), 0, st, x, ld, n, k,
-                           idx_out, idx_ld, val_out, val_ld, append_from, append_count);
-    }
+    if (n <= 4096)
+        return launch_lds<256>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
+                               append_from, append_count, gate, rows_per_gate, st);
+    if (n <= 32768)
+        return launch_lds<1024>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
+                                append_from, append_count, gate, rows_per_gate, st);
+    hipLaunchKernelGGL((topk_rows_stream_kernel<1024>), dim3(rows), dim3(1024), 0, st, x, ld, n, k,
+                       idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
+                       rows_per_gate);
     return hipGetLastError();
 }
 

@@ -38,37 +38,106 @@ __device__ __forceinline__ float signal_factor(float e, float alpha, int signal)
     return signal == 1 ? fmaf(alpha, e, 1.0f) : fmaf(-alpha, e, 1.0f);
 }
 
-// One workgroup per head.  The S*m (source slot, node, edge) triples are sorted
-// by (node, slot) with a bitonic network in LDS; the first triple of every node
-// then multiplies that node's factors in ascending slot order -- sources are
-// stored in ascending index order, so this is Eq. 5's product with a fixed
-// floating-point order -- and writes the node's score once.  No float atomics.
-__global__ __launch_bounds__(1024) void decay_sorted_kernel(
+// Bitonic sort of npad 64-bit keys in LDS by one workgroup of 4 waves.  Wave w
+// owns pairs [w*Q, (w+1)*Q), Q = npad/8.  For compare distances j <= Q those pairs
+// touch only elements [2wQ, 2(w+1)Q), so such stages need no workgroup barrier:
+// LDS operations of one wave complete in order.  Only the 3 stages with j > Q
+// synchronise the workgroup.
+__device__ __forceinline__ void bitonic_sort_lds(uint64_t *keys, int npad, int lane, int wv)
+{
+    const int Q = npad >> 3;
+    for (int k = 2; k <= npad; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const bool wide = j > Q;
+            if (wide) __syncthreads();
+            for (int e = wv * Q + lane; e < (wv + 1) * Q; e += kWave) {
+                const int t = ((e & ~(j - 1)) << 1) | (e & (j - 1)), u = t + j;
+                const uint64_t a = keys[t], b = keys[u];
+                const bool up = (t & k) == 0;
+                if ((a > b) == up) { keys[t] = b; keys[u] = a; }
+            }
+            if (wide) __syncthreads();
+            else __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        }
+    }
+    __syncthreads();
+}
+
+// Eq. 5 for one round, S*m <= 4096.  One workgroup per head.  The (source slot,
+// node, edge) triples are sorted by (node, slot); the first triple of every node
+// multiplies that node's factors in ascending slot order -- sources are stored in
+// ascending index order, so this is Eq. 5's product with a fixed floating-point
+// order -- and the node's score is written once.  No float atomics.  Edge weights
+// and the per-node products stay in LDS, so the only dependent global accesses are
+// the final read-modify-writes of the scores, issued 8 at a time.
+__global__ __launch_bounds__(256) void decay_small_kernel(
+    float *__restrict__ scores, int P, int count, int npad, const int32_t *__restrict__ nbr,
+    const float *__restrict__ nbr_e, float alpha, int signal)
+{
+    extern __shared__ uint64_t keys[];                 // (node << 32) | triple id   [npad]
+    float *ev = reinterpret_cast<float *>(keys + npad);   // edge of triple id          [npad]
+    float *hf = ev + npad;                                // product at a node's first triple
+    int32_t *hn = reinterpret_cast<int32_t *>(hf + npad); // node there, -1 elsewhere
+    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int32_t *nb = nbr + (long)h * count;
+    const float *ne = nbr_e + (long)h * count;
+    float *s = scores + (long)h * P;
+    for (int t = tid; t < npad; t += 256) {
+        keys[t] = t < count ? (((uint64_t)(uint32_t)nb[t] << 32) | (uint32_t)t) : ~0ull;
+        ev[t] = t < count ? ne[t] : 0.f;
+    }
+    __syncthreads();
+    bitonic_sort_lds(keys, npad, lane, wv);
+    for (int t = tid; t < npad; t += 256) {
+        int32_t node = -1;
+        float f = 1.0f;
+        if (t < count) {
+            const uint32_t nd = (uint32_t)(keys[t] >> 32);
+            if (t == 0 || (uint32_t)(keys[t - 1] >> 32) != nd) {
+                node = (int32_t)nd;
+                for (int u = t; u < count; ++u) {
+                    const uint64_t ku = keys[u];
+                    if ((uint32_t)(ku >> 32) != nd) break;
+                    f *= signal_factor(ev[(uint32_t)ku], alpha, signal);
+                }
+            }
+        }
+        hn[t] = node;
+        hf[t] = f;
+    }
+    __syncthreads();
+    for (int base = 0; base < npad; base += 256 * 8) {
+        int32_t nd[8];
+        float sv[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int t = base + q * 256 + tid;
+            nd[q] = t < npad ? hn[t] : -1;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) sv[q] = nd[q] >= 0 ? s[nd[q]] : 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (nd[q] >= 0) s[nd[q]] = signal == 2 ? -INFINITY : sv[q] * hf[base + q * 256 + tid];
+    }
+}
+
+// Same as decay_small_kernel for 4096 < S*m <= 16384: only the sort keys fit in LDS
+// (128 KiB), edge weights are fetched from global memory.
+__global__ __launch_bounds__(256) void decay_sorted_kernel(
     float *__restrict__ scores, int P, int count, int npad, const int32_t *__restrict__ nbr,
     const float *__restrict__ nbr_e, float alpha, int signal)
 {
     extern __shared__ uint64_t keys[];     // (node << 32) | triple id
-    const int h = blockIdx.x, tid = threadIdx.x;
+    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int32_t *nb = nbr + (long)h * count;
     const float *ne = nbr_e + (long)h * count;
     float *s = scores + (long)h * P;
-    for (int t = tid; t < npad; t += 1024)
+    for (int t = tid; t < npad; t += 256)
         keys[t] = t < count ? (((uint64_t)(uint32_t)nb[t] << 32) | (uint32_t)t) : ~0ull;
     __syncthreads();
-    for (int k = 2; k <= npad; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < npad; t += 1024) {
-                const int u = t ^ j;
-                if (u > t) {
-                    const uint64_t a = keys[t], b = keys[u];
-                    const bool up = (t & k) == 0;
-                    if ((a > b) == up) { keys[t] = b; keys[u] = a; }
-                }
-            }
-            __syncthreads();
-        }
-    }
-    for (int t = tid; t < count; t += 1024) {
+    bitonic_sort_lds(keys, npad, lane, wv);
+    for (int t = tid; t < count; t += 256) {
         const uint64_t key = keys[t];
         const uint32_t node = (uint32_t)(key >> 32);
         if (t > 0 && (uint32_t)(keys[t - 1] >> 32) == node) continue;   // not the first of its node
@@ -166,10 +235,28 @@ hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32
                         const float *nbr_e, float alpha, int signal, hipStream_t st)
 {
     const long count = (long)S * m;
-    long npad = 2;
+    long npad = 512;
     while (npad < count) npad <<= 1;
-    if (npad <= 8192) {   // 64 KiB of LDS: no opt-in needed
-        hipLaunchKernelGGL(decay_sorted_kernel, dim3(Hkv), dim3(1024), (size_t)npad * 8, st, scores,
+    if (npad <= 4096) {
+        static bool small_opt_in = false;
+        const size_t lds = (size_t)npad * 20;
+        if (lds > 65536 && !small_opt_in) {
+            if (hipFuncSetAttribute((const void *)decay_small_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 4096 * 20) != hipSuccess)
+                return hipGetLastError();
+            small_opt_in = true;
+        }
+        hipLaunchKernelGGL(decay_small_kernel, dim3(Hkv), dim3(256), lds, st, scores, P, (int)count,
+                           (int)npad, nbr, nbr_e, alpha, signal);
+    } else if (npad <= 16384) {
+        static bool lds_opt_in = false;   // 128 KiB of dynamic LDS needs a one-time opt-in
+        if (npad * 8 > 65536 && !lds_opt_in) {
+            if (hipFuncSetAttribute((const void *)decay_sorted_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 8) != hipSuccess)
+                return hipGetLastError();
+            lds_opt_in = true;
+        }
+        hipLaunchKernelGGL(decay_sorted_kernel, dim3(Hkv), dim3(256), (size_t)npad * 8, st, scores,
                            P, (int)count, (int)npad, nbr, nbr_e, alpha, signal);
     } else {
         hipLaunchKernelGGL(decay_sequential_kernel, dim3(Hkv), dim3(1024), 0, st, scores, P, S, m,

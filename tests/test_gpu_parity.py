@@ -221,6 +221,48 @@ def test_propagate_degenerate(oracle, impl):
     assert nbr[0, 0, 0, 0] == dup and abs(ev[0, 0, 0, 0] - 1.0) < 1e-6 and abs(s1[0, dup]) < 1e-6 * s0[0, dup]
 
 
+# ---------------------------------- neighbourhoods without the dense block ---
+
+@pytest.mark.parametrize("S,m", [(40, 20), (64, 32), (130, 7)])
+def test_filtered_neighbourhoods_staged(oracle, S, m):
+    """P >= 8192 on the MFMA path takes the sampled-bound + filter route; source
+    counts that do not fill the 64-row groups, ragged key tail."""
+    cfg = small_bf16_cfg(n_tokens=10007, n_sources=S, n_neighbors=m)
+    say(f"filtered neighbourhoods S={S} m={m}")
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 4)
+    s0 = synth.random_scores(cfg)
+    p = util.params_from_cfg(cfg, rounds=1)
+    s1, src, nbr, ev = run_propagate(p, Kd, s0)
+    flips = util.check_round_staged(oracle, K, "bf16", cfg.window, s0, s1, src[0], nbr[0], ev[0], S, m, 1.0)
+    say(f"  neighbour lists differing from the oracle's (near-ties): {flips}")
+    # the scalar kernels (dense block) must pick the same neighbours up to fp32 near-ties
+    pg = util.params_from_cfg(cfg, rounds=1, impl=gk.IMPL_GENERIC)
+    _, src_g, nbr_g, ev_g = run_propagate(pg, Kd, s0)
+    assert np.array_equal(src, src_g)
+    assert np.count_nonzero((nbr != nbr_g).any(axis=-1)) <= 2 + flips
+
+
+def test_filtered_neighbourhoods_overflow_falls_back(oracle):
+    """Masses of exactly equal edges defeat any bound: those heads must be redone
+    through the dense block and still give the exact lowest-index answer."""
+    cfg = small_bf16_cfg(n_tokens=12000, n_sources=8, n_neighbors=16, n_kv_heads=2, n_q_heads=8)
+    (K, V, Q), _ = util.device_layer(cfg, 1)
+    P = cfg.n_prefix
+    rng = np.random.default_rng(5)
+    dup = rng.choice(P, size=P // 2, replace=False)
+    K[0, dup] = K[0, dup[0]]                      # head 0: half of the keys are one vector
+    Kd = gk.to_device(K, gk.BF16)
+    s0 = synth.random_scores(cfg)
+    s0[0, dup[:4]] = 50.0                         # make duplicates sources
+    p = util.params_from_cfg(cfg, rounds=1)
+    s1, src, nbr, ev = run_propagate(p, Kd, s0)
+    util.check_round_staged(oracle, K, "bf16", cfg.window, s0, s1, src[0], nbr[0], ev[0], 8, 16, 1.0)
+    a = src[0, 0].tolist().index(int(np.sort(dup[:4])[0]))
+    want = np.sort(dup)[:17]
+    want = want[want != src[0, 0, a]][:16]
+    assert np.array_equal(nbr[0, 0, a], want) and (np.abs(ev[0, 0, a] - 1.0) < 1e-6).all()
+
+
 # ----------------------------------------------------------- whole pass ---
 
 def run_compress(p, dev, want_scores=True):
