@@ -1,9 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the GraphKV eviction pass on one MI355X.
 
-One "step" compresses a whole prompt: L per-layer graphkv_compress calls (score
--> propagate -> select -> gather) on one stream, over seeded synthetic
-Llama-3-8B-shaped K/V/Q already resident in HBM.  Prints ONE JSON line.
+One "step" compresses a whole prompt: score -> propagate -> select -> gather for
+all L layers x H_kv heads, on one stream, over seeded synthetic Llama-3-8B-shaped
+K/V/Q already resident in HBM as one slab per tensor.  By default the layers go
+through graphkv_compress_batched (every kernel sees all layers at once);
+--mode per-layer issues one graphkv_compress call per layer instead.  Prints ONE
+JSON line.
 
   value            prompt tokens whose cache is compressed per second (N / step
                    time; every layer and KV head of the model is processed)
@@ -63,6 +66,8 @@ def algorithmic_bytes(cfg, B):
         "pool_group": 2 * H * P * 4,
         "topk_sources": H * P * 4 + H * S * 4,
         "cosine": H * P * d * e + H * S * d * e,
+        "cosine_filter": H * P * d * e + H * S * d * e,
+        "cosine_sample": H * (P // 16) * d * e + H * S * d * e,
         "topk_neighbors": H * S * m * 8,
         "decay": 2 * H * S * m * 8,
         "topk_final": H * P * 4 + H * B * 4,
@@ -85,6 +90,10 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="use only the first LAYERS layers (debug)")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--mode", default="batched", choices=["batched", "per-layer"],
+                    help="batched: graphkv_compress_batched over the model's contiguous cache; "
+                         "per-layer: one graphkv_compress call per layer")
+    ap.add_argument("--group", type=int, default=0, help="layers per batched call (0 = all)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the eviction pass of one sequence); "
@@ -108,26 +117,45 @@ def main():
     dev = torch.device("cuda:0")
     dt = gk.FP32 if cfg.dtype == "fp32" else gk.BF16
 
-    params, Kd, Vd, Qd, Ko, Vo, Io = [], [], [], [], [], [], []
+    # The model's cache as one slab per tensor: [L, H_kv, N, d] (and [L, H_q, w, d] for the queries).
+    H, Hq, d, N, w = cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.n_tokens, cfg.window
+    tdt = torch.float32 if dt == gk.FP32 else torch.bfloat16
+    Kall = torch.empty((L, H, N, d), dtype=tdt, device=dev)
+    Vall = torch.empty((L, H, N, d), dtype=tdt, device=dev)
+    Qall = torch.empty((L, Hq, w, d), dtype=tdt, device=dev)
+    params = []
     for l in range(L):
         K, V, Q = host[l]
-        p = gk.Params(n_kv_heads=cfg.n_kv_heads, n_q_heads=cfg.n_q_heads, head_dim=cfg.head_dim,
-                      n_tokens=cfg.n_tokens, window=cfg.window, pool_kernel=cfg.pool_kernel,
-                      pool_mode=cfg.pool_mode, budget=cfg.budget_for_layer(l), n_sources=cfg.n_sources,
-                      n_neighbors=cfg.n_neighbors, rounds=cfg.rounds, decay=cfg.decay,
-                      reselect=cfg.reselect, dtype=dt)
-        params.append(p)
-        Kd.append(gk.to_device(K, dt, dev)); Vd.append(gk.to_device(V, dt, dev)); Qd.append(gk.to_device(Q, dt, dev))
-        shape = (p.n_kv_heads, p.budget, p.head_dim)
-        Ko.append(torch.empty(shape, dtype=Kd[-1].dtype, device=dev))
-        Vo.append(torch.empty(shape, dtype=Kd[-1].dtype, device=dev))
-        Io.append(torch.empty((p.n_kv_heads, p.budget), dtype=torch.int32, device=dev))
-    ws_bytes = max(gk.graphkv_workspace_bytes(p) for p in params)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        Kall[l].copy_(gk.to_device(K, dt, dev)); Vall[l].copy_(gk.to_device(V, dt, dev))
+        Qall[l].copy_(gk.to_device(Q, dt, dev))
+        params.append(gk.Params(n_kv_heads=H, n_q_heads=Hq, head_dim=d, n_tokens=N, window=w,
+                                pool_kernel=cfg.pool_kernel, pool_mode=cfg.pool_mode,
+                                budget=cfg.budget_for_layer(l), n_sources=cfg.n_sources,
+                                n_neighbors=cfg.n_neighbors, rounds=cfg.rounds, decay=cfg.decay,
+                                reselect=cfg.reselect, dtype=dt))
+    budgets = [p.budget for p in params]
+    row_off = [H * sum(budgets[:l]) for l in range(L + 1)]
+    Kout = torch.empty((row_off[L], d), dtype=tdt, device=dev)
+    Vout = torch.empty((row_off[L], d), dtype=tdt, device=dev)
+    Iout = torch.empty((row_off[L],), dtype=torch.int32, device=dev)
+    group = args.group if args.group > 0 else L
+    if args.mode == "batched":
+        ws = torch.empty(gk.graphkv_workspace_bytes_batched(params[0], min(group, L)), dtype=torch.uint8, device=dev)
 
-    def step():
-        for l in range(L):
-            gk.graphkv_compress(params[l], Kd[l], Vd[l], Qd[l], Ko[l], Vo[l], Io[l], None, ws)
+        def step():
+            for l0 in range(0, L, group):
+                l1 = min(L, l0 + group)
+                gk.graphkv_compress_batched(params[0], l1 - l0, budgets[l0:l1], Kall[l0:l1], Vall[l0:l1],
+                                            Qall[l0:l1], Kout[row_off[l0]:row_off[l1]],
+                                            Vout[row_off[l0]:row_off[l1]], Iout[row_off[l0]:row_off[l1]],
+                                            None, ws)
+    else:
+        ws = torch.empty(max(gk.graphkv_workspace_bytes(p) for p in params), dtype=torch.uint8, device=dev)
+
+        def step():
+            for l in range(L):
+                gk.graphkv_compress(params[l], Kall[l], Vall[l], Qall[l], Kout[row_off[l]:row_off[l + 1]],
+                                    Vout[row_off[l]:row_off[l + 1]], Iout[row_off[l]:row_off[l + 1]], None, ws)
 
     for _ in range(args.warmup):
         step()
@@ -153,7 +181,8 @@ def main():
         for name, (ms, cnt) in prof.items():
             per_step = cnt / args.profile_steps
             avg_us = ms * 1e3 / cnt
-            bytes_per_launch = float(np.mean([a.get(name, 0) for a in alg]))
+            layers_per_launch = min(group, L) if args.mode == "batched" else 1
+            bytes_per_launch = float(np.mean([a.get(name, 0) for a in alg])) * layers_per_launch
             kernels[name] = {
                 "avg_us": round(avg_us, 3), "launches_per_step": per_step,
                 "us_per_step": round(avg_us * per_step, 1),
@@ -176,7 +205,7 @@ def main():
     # whole-pass view against the streaming model (2 + T passes over K, plus the gather)
     model_bytes = sum(sum(v for k, v in algorithmic_bytes(cfg, p.budget).items()
                           if k in ("score_stats", "score_votes", "gather")) +
-                      cfg.rounds * algorithmic_bytes(cfg, p.budget)["cosine"] for p in params)
+                      cfg.rounds * algorithmic_bytes(cfg, p.budget)["cosine"] for p in params)   # (2 + T) |K| + gather
     pass_view = {
         "model_bytes_per_step": int(model_bytes),
         "model_GBps": round(model_bytes / (ms_per_step * 1e-3) / 1e9, 1),
@@ -201,7 +230,8 @@ def main():
             ref = oracle.compress(K, V, Q, cfg.dtype, p.pool_kernel, p.budget, p.n_sources,
                                   p.n_neighbors, p.rounds, alpha=p.decay, reselect=p.reselect)
             t_cpu += time.perf_counter() - tc
-            differing += int((Io[l].cpu().numpy() != ref["idx"]).any(axis=1).sum())
+            got = Iout[row_off[l]:row_off[l + 1]].cpu().numpy().reshape(H, p.budget)
+            differing += int((got != ref["idx"]).any(axis=1).sum())
         threads = min(cfg.n_kv_heads, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
         cpu = {
             "value": round(cfg.n_tokens / (t_cpu / n_s * cfg.n_layers), 2), "unit": "prompt tokens/s",
@@ -221,6 +251,7 @@ def main():
                                f"d={cfg.head_dim}, N={cfg.n_tokens}, w={cfg.window}, pool={cfg.pool_kernel}, "
                                f"B={cfg.budget_for_layer(0)}..{cfg.budget_for_layer(L - 1)}, S={cfg.n_sources}, "
                                f"m={cfg.n_neighbors}, T={cfg.rounds}, reselect={cfg.reselect}, alpha={cfg.decay}",
+                   "mode": args.mode + (f" (groups of {group} layers)" if args.mode == "batched" else ""),
                    "token_head_units_per_s": round(tokens_per_s * cfg.n_layers * cfg.n_kv_heads, 1),
                    "input_generation_s": round(t_gen, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "pass_vs_streaming_model": pass_view,

@@ -156,6 +156,30 @@ int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc
                          const void *Qw, void *Kout, void *Vout, int32_t *idx,
                          float *scores_out, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * The same pass for n_layers layers in one go.  The per-layer call keeps only H_kv
+ * workgroups busy in its selection and update kernels and pays every launch per
+ * layer; since all (layer, head) pairs are independent instances of the paper's
+ * per-layer problem, a whole model can be pushed through each kernel at once
+ * when its cache is one slab.
+ *   Kc, Vc     [n_layers, H_kv, N, d]   in   contiguous
+ *   Qw         [n_layers, H_q, w, d]    in
+ *   budgets    HOST array [n_layers] of per-layer budgets B_l (w < B_l <= N), or
+ *              NULL for p->budget everywhere (p->budget is ignored otherwise)
+ *   Kout, Vout packed: layer l occupies rows [H_kv * sum_{l'<l} B_l', +H_kv * B_l),
+ *              each layer laid out [H_kv, B_l, d]
+ *   idx        packed the same way, [H_kv, B_l] per layer
+ *   scores_out [n_layers, H_kv, P] or NULL
+ *   ws         graphkv_workspace_bytes_batched(p, n_layers) bytes
+ * Layers are processed in groups of at most 64.  Results are identical to
+ * n_layers per-layer calls.
+ */
+size_t graphkv_workspace_bytes_batched(const graphkv_params *p, int32_t n_layers);
+int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, const int32_t *budgets,
+                                 const void *Kc, const void *Vc, const void *Qw, void *Kout,
+                                 void *Vout, int32_t *idx, float *scores_out, void *ws,
+                                 size_t ws_bytes, void *stream);
+
 /* Host string for a return code (static storage). */
 const char *graphkv_strerror(int32_t code);
 

@@ -24,7 +24,8 @@ IMPL_AUTO, IMPL_GENERIC = 0, 1
 
 EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "graphkv_propagate",
            "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma",
-           "graphkv_profile_begin", "graphkv_profile_end", "graphkv_kernel_name")
+           "graphkv_profile_begin", "graphkv_profile_end", "graphkv_kernel_name",
+           "graphkv_workspace_bytes_batched", "graphkv_compress_batched")
 N_KERNELS = 20
 
 
@@ -105,6 +106,10 @@ def load_library() -> ctypes.CDLL:
     lib.graphkv_select.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.graphkv_compress.restype = i32
     lib.graphkv_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.graphkv_workspace_bytes_batched.restype = sz
+    lib.graphkv_workspace_bytes_batched.argtypes = [pp, i32]
+    lib.graphkv_compress_batched.restype = i32
+    lib.graphkv_compress_batched.argtypes = [pp, i32, ctypes.POINTER(i32), vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.graphkv_strerror.restype = ctypes.c_char_p
     lib.graphkv_strerror.argtypes = [i32]
     lib.graphkv_profile_begin.restype = i32
@@ -210,6 +215,37 @@ def graphkv_compress(p: Params, Kc, Vc, Qw, Kout=None, Vout=None, idx=None, scor
     _check(load_library().graphkv_compress(ctypes.byref(cp), _ptr(Kc), _ptr(Vc), _ptr(Qw), _ptr(Kout),
                                            _ptr(Vout), _ptr(idx), _ptr(scores_out), _ptr(ws),
                                            ws.numel(), _stream()))
+    return Kout, Vout, idx
+
+
+def graphkv_workspace_bytes_batched(p: Params, n_layers: int) -> int:
+    cp = p.c()
+    return int(load_library().graphkv_workspace_bytes_batched(ctypes.byref(cp), n_layers))
+
+
+def graphkv_compress_batched(p: Params, n_layers: int, budgets, Kc, Vc, Qw, Kout=None, Vout=None,
+                             idx=None, scores_out=None, ws=None):
+    """The whole pass for n_layers contiguous layers: Kc, Vc [L, H_kv, N, d], Qw [L, H_q, w, d].
+    budgets: per-layer budgets (sequence of ints) or None for p.budget everywhere.  Outputs are
+    packed layer after layer: Kout, Vout [sum_l H_kv * B_l, d], idx [sum_l H_kv * B_l].
+    Returns (Kout, Vout, idx)."""
+    dev = Kc.device
+    bl = list(budgets) if budgets is not None else [p.budget] * n_layers
+    assert len(bl) == n_layers
+    rows = p.n_kv_heads * sum(bl)
+    if Kout is None:
+        Kout = torch.empty((rows, p.head_dim), dtype=Kc.dtype, device=dev)
+    if Vout is None:
+        Vout = torch.empty((rows, p.head_dim), dtype=Vc.dtype, device=dev)
+    if idx is None:
+        idx = torch.empty((rows,), dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = torch.empty(graphkv_workspace_bytes_batched(p, n_layers), dtype=torch.uint8, device=dev)
+    cp = p.c()
+    carr = (ctypes.c_int32 * n_layers)(*bl) if budgets is not None else None
+    _check(load_library().graphkv_compress_batched(ctypes.byref(cp), n_layers, carr, _ptr(Kc), _ptr(Vc),
+                                                   _ptr(Qw), _ptr(Kout), _ptr(Vout), _ptr(idx),
+                                                   _ptr(scores_out), _ptr(ws), ws.numel(), _stream()))
     return Kout, Vout, idx
 
 

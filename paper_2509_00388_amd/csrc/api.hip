@@ -13,8 +13,9 @@ using namespace gkv;
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
 
+// H and Hq count the heads of the whole batch (layers x heads per layer).
 struct Dims {
-    int H, Hq, G, d, N, w, P, B, S, m, T;
+    int L, H, Hq, G, d, N, w, P, B, S, m, T;
     bool mfma_score, mfma_cosine, filter;
     float scale;
     size_t esize;
@@ -79,11 +80,12 @@ bool budget_ok(const graphkv_params *p)
     return p->budget > p->window && p->budget <= p->n_tokens;
 }
 
-Dims dims_of(const graphkv_params *p)
+Dims dims_of(const graphkv_params *p, int n_layers = 1)
 {
     Dims D;
-    D.H = p->n_kv_heads;
-    D.Hq = p->n_q_heads > 0 ? p->n_q_heads : p->n_kv_heads;
+    D.L = n_layers;
+    D.H = p->n_kv_heads * n_layers;
+    D.Hq = (p->n_q_heads > 0 ? p->n_q_heads : p->n_kv_heads) * n_layers;
     D.G = D.Hq / D.H > 0 ? D.Hq / D.H : 1;
     D.d = p->head_dim;
     D.N = p->n_tokens;
@@ -277,12 +279,56 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
     return GRAPHKV_OK;
 }
 
-int32_t run_select(const Dims &D, const float *scores, int32_t *idx, hipStream_t st)
+// Budgets of the layers of a batch and where each layer's rows start in the packed outputs.
+LayerPlan make_plan(const graphkv_params *p, int n_layers, const int32_t *budgets, int *max_budget)
 {
-    GKV_LAUNCH(GRAPHKV_K_TOPK_FINAL,
-               launch_topk_rows(scores, D.P, D.P, D.H, D.B - D.w, idx, D.B, nullptr, 0, nullptr, D.P,
-                                D.w, nullptr, 1, st));
+    LayerPlan plan{};
+    plan.heads_per_layer = p->n_kv_heads;
+    int64_t rows = 0;
+    int mx = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int B = budgets ? budgets[l] : p->budget;
+        plan.budget[l] = B;
+        plan.row_off[l] = rows;
+        rows += (int64_t)p->n_kv_heads * B;
+        if (B > mx) mx = B;
+    }
+    if (max_budget) *max_budget = mx;
+    return plan;
+}
+
+int32_t run_select(const Dims &D, const LayerPlan &plan, const float *scores, int32_t *idx,
+                   hipStream_t st)
+{
+    GKV_LAUNCH(GRAPHKV_K_TOPK_FINAL, launch_topk_final(scores, D.P, D.H, plan, D.w, idx, st));
     return GRAPHKV_OK;
+}
+
+// The whole pass for a batch of n_layers contiguous layers (n_layers <= kMaxLayers).
+int32_t run_compress(const graphkv_params *p, int n_layers, const int32_t *budgets, const void *Kc,
+                     const void *Vc, const void *Qw, void *Kout, void *Vout, int32_t *idx,
+                     float *scores_out, void *ws, hipStream_t st)
+{
+    const Dims D = dims_of(p, n_layers);
+    const Workspace W = carve(p, D);
+    int max_budget = 0;
+    const LayerPlan plan = make_plan(p, n_layers, budgets, &max_budget);
+    float *scores = scores_out ? scores_out : at<float>(ws, W.scores);
+    if (int32_t rc = run_score(p, D, W, Kc, Qw, scores, ws, st)) return rc;
+    if (int32_t rc = run_propagate(p, D, W, Kc, scores, nullptr, nullptr, nullptr, ws, st)) return rc;
+    if (int32_t rc = run_select(D, plan, scores, idx, st)) return rc;
+    GKV_LAUNCH(GRAPHKV_K_GATHER, launch_gather(Kc, Vc, idx, D.H, D.N, plan, max_budget,
+                                               (int)(D.d * D.esize), Kout, Vout, st));
+    return GRAPHKV_OK;
+}
+
+bool budgets_ok(const graphkv_params *p, int n_layers, const int32_t *budgets)
+{
+    for (int l = 0; l < n_layers; ++l) {
+        const int B = budgets ? budgets[l] : p->budget;
+        if (B <= p->window || B > p->n_tokens) return false;
+    }
+    return true;
 }
 
 }  // namespace
@@ -291,9 +337,7 @@ extern "C" {
 
 size_t graphkv_workspace_bytes(const graphkv_params *p)
 {
-    if (!base_ok(p)) return 0;
-    const Dims D = dims_of(p);
-    return carve(p, D).total;
+    return graphkv_workspace_bytes_batched(p, 1);
 }
 
 int32_t graphkv_uses_mfma(const graphkv_params *p)
@@ -347,28 +391,57 @@ int32_t graphkv_select(const graphkv_params *p, const float *scores, int32_t *id
     if (!base_ok(p) || !budget_ok(p)) return GRAPHKV_EINVAL;
     if (!aligned4(scores) || !aligned4(idx)) return GRAPHKV_EINVAL;
     const Dims D = dims_of(p);
-    return run_select(D, scores, idx, (hipStream_t)stream);
+    return run_select(D, make_plan(p, 1, nullptr, nullptr), scores, idx, (hipStream_t)stream);
 }
 
 int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc, const void *Qw,
                          void *Kout, void *Vout, int32_t *idx, float *scores_out, void *ws,
                          size_t ws_bytes, void *stream)
 {
-    if (!base_ok(p) || !score_ok(p) || !budget_ok(p)) return GRAPHKV_EINVAL;
+    return graphkv_compress_batched(p, 1, nullptr, Kc, Vc, Qw, Kout, Vout, idx, scores_out, ws,
+                                    ws_bytes, stream);
+}
+
+size_t graphkv_workspace_bytes_batched(const graphkv_params *p, int32_t n_layers)
+{
+    if (!base_ok(p) || n_layers < 1) return 0;
+    const int group = n_layers < kMaxLayers ? n_layers : kMaxLayers;
+    if ((long)p->n_kv_heads * group > 65535) return 0;
+    return carve(p, dims_of(p, group)).total;
+}
+
+int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, const int32_t *budgets,
+                                 const void *Kc, const void *Vc, const void *Qw, void *Kout,
+                                 void *Vout, int32_t *idx, float *scores_out, void *ws,
+                                 size_t ws_bytes, void *stream)
+{
+    if (!base_ok(p) || !score_ok(p) || n_layers < 1) return GRAPHKV_EINVAL;
+    if (!budgets_ok(p, n_layers, budgets)) return GRAPHKV_EINVAL;
     if (!aligned16(Kc) || !aligned16(Vc) || !aligned16(Qw) || !aligned16(Kout) ||
         !aligned16(Vout) || !aligned4(idx))
         return GRAPHKV_EINVAL;
     if (scores_out && !aligned4(scores_out)) return GRAPHKV_EINVAL;
-    const Dims D = dims_of(p);
-    const Workspace W = carve(p, D);
+    const int group = n_layers < kMaxLayers ? n_layers : kMaxLayers;
+    if ((long)p->n_kv_heads * group > 65535) return GRAPHKV_EINVAL;
+    const Workspace W = carve(p, dims_of(p, group));
     if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
     hipStream_t st = (hipStream_t)stream;
-    float *scores = scores_out ? scores_out : at<float>(ws, W.scores);
-    if (int32_t rc = run_score(p, D, W, Kc, Qw, scores, ws, st)) return rc;
-    if (int32_t rc = run_propagate(p, D, W, Kc, scores, nullptr, nullptr, nullptr, ws, st))
-        return rc;
-    if (int32_t rc = run_select(D, scores, idx, st)) return rc;
-    GKV_LAUNCH(GRAPHKV_K_GATHER, launch_gather(Kc, Vc, idx, D.H, D.N, D.B, (int)(D.d * D.esize), Kout, Vout, st));
+    const size_t esize = p->dtype == GRAPHKV_FP32 ? 4 : 2;
+    const size_t kv_layer = (size_t)p->n_kv_heads * p->n_tokens * p->head_dim * esize;
+    const size_t q_layer = (size_t)p->n_q_heads * p->window * p->head_dim * esize;
+    const size_t s_layer = (size_t)p->n_kv_heads * (p->n_tokens - p->window);
+    size_t out_rows = 0;   // rows of Kout / Vout / idx written so far
+    for (int l0 = 0; l0 < n_layers; l0 += group) {
+        const int nl = n_layers - l0 < group ? n_layers - l0 : group;
+        const int32_t *bl = budgets ? budgets + l0 : nullptr;
+        const int32_t rc = run_compress(
+            p, nl, bl, (const char *)Kc + l0 * kv_layer, (const char *)Vc + l0 * kv_layer,
+            (const char *)Qw + l0 * q_layer, (char *)Kout + out_rows * p->head_dim * esize,
+            (char *)Vout + out_rows * p->head_dim * esize, idx + out_rows,
+            scores_out ? scores_out + l0 * s_layer : nullptr, ws, st);
+        if (rc) return rc;
+        for (int l = 0; l < nl; ++l) out_rows += (size_t)p->n_kv_heads * (bl ? bl[l] : p->budget);
+    }
     return GRAPHKV_OK;
 }
 

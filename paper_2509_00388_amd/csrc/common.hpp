@@ -7,6 +7,17 @@ namespace gkv {
 
 constexpr int kWave = 64;
 
+// Per-layer quantities of a batched call, passed to kernels by value.  A batch is
+// a run of layers whose tensors are contiguous ([L, H, ...]), so every (layer,
+// head) pair is simply head q = l * H + h of a layer with L*H heads; only the
+// budget, and with it the place of a layer's rows in the packed outputs, varies.
+constexpr int kMaxLayers = 64;
+struct LayerPlan {
+    int32_t heads_per_layer;          // H
+    int32_t budget[kMaxLayers];       // B_l
+    int64_t row_off[kMaxLayers];      // H * sum_{l' < l} B_l': first output row of layer l
+};
+
 // bfloat16 <-> float: bf16 is the upper half of an IEEE float, widening is exact.
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "common.hpp"
+
 namespace gkv {
 
 // ---- selection (select.hip) -------------------------------------------------
@@ -41,9 +43,15 @@ hipError_t launch_pool_group(const float *votes, int Hkv, int Gv, int P, int poo
 // Eq. 5 for one round: scores[h, nbr] *= prod (1 -/+ alpha e), ascending source order.
 hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32_t *nbr,
                         const float *nbr_e, float alpha, int signal, hipStream_t st);
-// Kout[h,t,:] = Kc[h, idx[h,t], :], same for V; row_bytes multiple of 16.
-hipError_t launch_gather(const void *Kc, const void *Vc, const int32_t *idx, int Hkv, int N, int B,
-                         int row_bytes, void *Kout, void *Vout, hipStream_t st);
+// Kout[q,t,:] = Kc[q, idx[q,t], :] for the heads q of a batch, same for V; packed
+// outputs, per-layer budgets from the plan; row_bytes multiple of 16.
+hipError_t launch_gather(const void *Kc, const void *Vc, const int32_t *idx, int heads, int N,
+                         const LayerPlan &plan, int max_budget, int row_bytes, void *Kout, void *Vout,
+                         hipStream_t st);
+// Final selection of a batch: row q keeps budget[l] - w entries and writes them,
+// followed by the window tokens P .. P + w - 1, to its packed idx row.
+hipError_t launch_topk_final(const float *scores, int P, int rows, const LayerPlan &plan, int w,
+                             int32_t *idx, hipStream_t st);
 hipError_t launch_copy_i32(const int32_t *src, int32_t *dst, long n, hipStream_t st);
 hipError_t launch_copy_f32(const float *src, float *dst, long n, hipStream_t st);
 

@@ -289,15 +289,16 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     }
 }
 
-// Columns per workgroup: about one workgroup per CU, and at least `min_chunks`
-// chunks per head.
+// Columns per workgroup: about 1024 workgroups in flight over all heads and source
+// groups, at least 8 key blocks per wave, and at least `min_chunks` chunks per head.
 int chunk_cols_for(int Hkv, int sgroups, int n_cols, int min_chunks = 1)
 {
-    int target = 256 / (Hkv * sgroups);
-    if (target < min_chunks) target = min_chunks;
-    int ck = (n_cols + target - 1) / target;
+    long ck = ((long)Hkv * sgroups * n_cols + 1023) / 1024;
+    if (ck < 1024) ck = 1024;
+    const long cap = (n_cols + min_chunks - 1) / min_chunks;
+    if (ck > cap) ck = cap;
     ck = ((ck + 127) / 128) * 128;
-    return ck < 128 ? 128 : ck;
+    return (int)(ck < 128 ? 128 : ck);
 }
 
 }  // namespace

@@ -254,12 +254,14 @@ __global__ __launch_bounds__(256) void score_votes_kernel(
     }
 }
 
+// Keys per workgroup: about 1024 workgroups in flight over all heads, but at least
+// 8 key blocks per wave so that loading the query operand is amortised.
 int chunk_keys_for(int Hkv, int N)
 {
-    const int target = Hkv >= 256 ? 1 : 256 / Hkv;           // about one workgroup per CU
-    int ck = (N + target - 1) / target;
+    long ck = ((long)Hkv * N + 1023) / 1024;
+    if (ck < 1024) ck = 1024;
     ck = ((ck + 127) / 128) * 128;                            // 4 waves x 32 keys
-    return ck < 128 ? 128 : ck;
+    return (int)ck;
 }
 
 }  // namespace

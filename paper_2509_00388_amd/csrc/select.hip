@@ -15,6 +15,8 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <type_traits>
+
 namespace gkv {
 
 namespace {
@@ -78,11 +80,12 @@ __device__ __forceinline__ void find_bin(const uint32_t *hist, uint32_t need, in
 // = 128 KiB) for all sweeps.  Thread t handles entries i*BLOCK + t; index order is
 // therefore (i, wave, lane), and the emit sweep counts per (i, wave) cell with
 // ballots and scans the cells once.
-template <int BLOCK>
+template <int BLOCK, bool PLAN>
 __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
     float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
-    int append_count, const int32_t *__restrict__ gate, int rows_per_gate)
+    int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
+    typename std::conditional<PLAN, LayerPlan, int>::type plan)
 {
     constexpr int NW = BLOCK / kWave;
     extern __shared__ uint32_t dyn[];
@@ -99,6 +102,11 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     const float *xr = x + (long)blockIdx.x * ld;
     int32_t *out = idx_out ? idx_out + (long)blockIdx.x * idx_ld : nullptr;
     float *vout = val_out ? val_out + (long)blockIdx.x * val_ld : nullptr;
+    if constexpr (PLAN) {   // per-layer budget: k and the output row come from the plan
+        const int g = blockIdx.x / plan.heads_per_layer, hl = blockIdx.x % plan.heads_per_layer;
+        k = plan.budget[g] - append_count;
+        out = idx_out + (plan.row_off[g] + (long)hl * plan.budget[g]);
+    }
 
     if (out)
         for (int r = tid; r < append_count; r += BLOCK) out[k + r] = append_from + r;
@@ -200,11 +208,12 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
 }
 
 // ---- rows of any length: every sweep re-reads the row ------------------------
-template <int BLOCK>
+template <int BLOCK, bool PLAN>
 __global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
     const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
     float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
-    int append_count, const int32_t *__restrict__ gate, int rows_per_gate)
+    int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
+    typename std::conditional<PLAN, LayerPlan, int>::type plan)
 {
     constexpr int NW = BLOCK / kWave;
     constexpr int U = 8;   // loads in flight per thread
@@ -217,6 +226,11 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
     const float *xr = x + (long)blockIdx.x * ld;
     int32_t *out = idx_out ? idx_out + (long)blockIdx.x * idx_ld : nullptr;
     float *vout = val_out ? val_out + (long)blockIdx.x * val_ld : nullptr;
+    if constexpr (PLAN) {   // per-layer budget: k and the output row come from the plan
+        const int g = blockIdx.x / plan.heads_per_layer, hl = blockIdx.x % plan.heads_per_layer;
+        k = plan.budget[g] - append_count;
+        out = idx_out + (plan.row_off[g] + (long)hl * plan.budget[g]);
+    }
 
     if (out)
         for (int r = tid; r < append_count; r += BLOCK) out[k + r] = append_from + r;
@@ -308,24 +322,43 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
     }
 }
 
-template <int BLOCK>
+template <int BLOCK, bool PLAN, typename PlanArg>
 static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
                              long idx_ld, float *val_out, long val_ld, float *tau_out,
                              int append_from, int append_count, const int32_t *gate,
-                             int rows_per_gate, hipStream_t st)
+                             int rows_per_gate, PlanArg plan, hipStream_t st)
 {
     const int items = (n + BLOCK - 1) / BLOCK;
     const size_t lds = ((size_t)items * BLOCK + 2 * (size_t)items * (BLOCK / kWave)) * 4;
     static bool opt_in = false;   // more than 64 KiB of dynamic LDS needs a one-time opt-in
     if (lds > 65536 && !opt_in) {
-        if (hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK>,
+        if (hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK, PLAN>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess)
             return hipGetLastError();
         opt_in = true;
     }
-    hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK>), dim3(rows), dim3(BLOCK), lds, st, x, ld, n, k,
-                       idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
-                       rows_per_gate);
+    hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN>), dim3(rows), dim3(BLOCK), lds, st, x, ld, n,
+                       k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
+                       rows_per_gate, plan);
+    return hipGetLastError();
+}
+
+template <bool PLAN, typename PlanArg>
+static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
+                             long idx_ld, float *val_out, long val_ld, float *tau_out,
+                             int append_from, int append_count, const int32_t *gate,
+                             int rows_per_gate, PlanArg plan, hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    if (n <= 4096)
+        return launch_lds<256, PLAN>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
+                                     append_from, append_count, gate, rows_per_gate, plan, st);
+    if (n <= 32768)
+        return launch_lds<1024, PLAN>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
+                                      append_from, append_count, gate, rows_per_gate, plan, st);
+    hipLaunchKernelGGL((topk_rows_stream_kernel<1024, PLAN>), dim3(rows), dim3(1024), 0, st, x, ld, n,
+                       k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
+                       rows_per_gate, plan);
     return hipGetLastError();
 }
 
@@ -334,17 +367,15 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k, int
                             int append_from, int append_count, const int32_t *gate,
                             int rows_per_gate, hipStream_t st)
 {
-    if (rows <= 0) return hipSuccess;
-    if (n <= 4096)
-        return launch_lds<256>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                               append_from, append_count, gate, rows_per_gate, st);
-    if (n <= 32768)
-        return launch_lds<1024>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                                append_from, append_count, gate, rows_per_gate, st);
-    hipLaunchKernelGGL((topk_rows_stream_kernel<1024>), dim3(rows), dim3(1024), 0, st, x, ld, n, k,
-                       idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
-                       rows_per_gate);
-    return hipGetLastError();
+    return launch_any<false, int>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
+                                  append_from, append_count, gate, rows_per_gate, 0, st);
+}
+
+hipError_t launch_topk_final(const float *scores, int P, int rows, const LayerPlan &plan, int w,
+                             int32_t *idx, hipStream_t st)
+{
+    return launch_any<true, LayerPlan>(scores, P, P, rows, 0, idx, 0, nullptr, 0, nullptr, P, w,
+                                       nullptr, 1, plan, st);
 }
 
 }  // namespace gkv

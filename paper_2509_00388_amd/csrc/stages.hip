@@ -196,20 +196,25 @@ __global__ __launch_bounds__(1024) void decay_sequential_kernel(
     }
 }
 
-// 16 bytes per thread; rows of row_bytes (a multiple of 16).
+// Kout[q, t, :] = Kc[q, idx[q, t], :] for head q = l * H + h of a batch, same for V;
+// 16 bytes per thread, rows of 16 * vec_per_row bytes.  Outputs and idx are packed
+// layer after layer (layer l holds H * B_l rows).
 __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ Kc,
                                                      const uint4 *__restrict__ Vc,
-                                                     const int32_t *__restrict__ idx, int N, int B,
+                                                     const int32_t *__restrict__ idx, int N,
                                                      int vec_per_row, uint4 *__restrict__ Kout,
-                                                     uint4 *__restrict__ Vout)
+                                                     uint4 *__restrict__ Vout, LayerPlan plan)
 {
-    const int h = blockIdx.y;
+    const int q = blockIdx.y;
+    const int l = q / plan.heads_per_layer, hl = q % plan.heads_per_layer;
+    const int B = plan.budget[l];
     const long g = (long)blockIdx.x * 256 + threadIdx.x;
     if (g >= (long)B * vec_per_row) return;
     const int t = (int)(g / vec_per_row), c = (int)(g % vec_per_row);
-    const int32_t j = idx[(long)h * B + t];
-    const long src = ((long)h * N + j) * vec_per_row + c;
-    const long dst = ((long)h * B + t) * vec_per_row + c;
+    const long out_row = plan.row_off[l] + (long)hl * B + t;
+    const int32_t j = idx[out_row];
+    const long src = ((long)q * N + j) * vec_per_row + c;
+    const long dst = out_row * vec_per_row + c;
     const uint4 *in = blockIdx.z == 0 ? Kc : Vc;
     uint4 *out = blockIdx.z == 0 ? Kout : Vout;
     out[dst] = in[src];
@@ -265,14 +270,15 @@ hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32
     return hipGetLastError();
 }
 
-hipError_t launch_gather(const void *Kc, const void *Vc, const int32_t *idx, int Hkv, int N, int B,
-                         int row_bytes, void *Kout, void *Vout, hipStream_t st)
+hipError_t launch_gather(const void *Kc, const void *Vc, const int32_t *idx, int heads, int N,
+                         const LayerPlan &plan, int max_budget, int row_bytes, void *Kout, void *Vout,
+                         hipStream_t st)
 {
     const int vpr = row_bytes / 16;
-    const long per_head = (long)B * vpr;
-    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((per_head + 255) / 256), Hkv, 2), dim3(256), 0,
-                       st, (const uint4 *)Kc, (const uint4 *)Vc, idx, N, B, vpr, (uint4 *)Kout,
-                       (uint4 *)Vout);
+    const long per_head = (long)max_budget * vpr;
+    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)((per_head + 255) / 256), heads, 2), dim3(256), 0,
+                       st, (const uint4 *)Kc, (const uint4 *)Vc, idx, N, vpr, (uint4 *)Kout,
+                       (uint4 *)Vout, plan);
     return hipGetLastError();
 }
 

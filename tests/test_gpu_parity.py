@@ -361,6 +361,61 @@ def test_non_default_stream_and_workspace_reuse(oracle):
     assert np.array_equal(idx.cpu().numpy(), ref[2]) and np.array_equal(gk.to_host_bits(Kout), ref[0])
 
 
+# ------------------------------------------------------------ batched call ---
+
+@pytest.mark.parametrize("impl", IMPLS)
+@pytest.mark.parametrize("budgets", [None, [300, 200, 97, 33, 1500]])
+def test_batched_equals_per_layer(oracle, impl, budgets):
+    """One batched call over L contiguous layers, per-layer budgets included, gives
+    byte for byte what L per-layer calls give (and so what the oracle gives)."""
+    L = 5
+    cfg = small_bf16_cfg(rounds=2)
+    say(f"batched L={L} impl={impl} budgets={budgets}")
+    layers = [util.device_layer(cfg, l) for l in range(L)]
+    p = util.params_from_cfg(cfg, impl=impl)
+    Kall = torch.stack([d[1][0] for d in layers]).contiguous()
+    Vall = torch.stack([d[1][1] for d in layers]).contiguous()
+    Qall = torch.stack([d[1][2] for d in layers]).contiguous()
+    sc = torch.empty((L, p.n_kv_heads, p.n_prefix), dtype=torch.float32, device="cuda")
+    Ko, Vo, idx = gk.graphkv_compress_batched(p, L, budgets, Kall, Vall, Qall, scores_out=sc)
+    Ko, Vo, idx = gk.to_host_bits(Ko), gk.to_host_bits(Vo), idx.cpu().numpy()
+    row = 0
+    for l in range(L):
+        B = budgets[l] if budgets else p.budget
+        pl = util.params_from_cfg(cfg, impl=impl, budget=B)
+        (ko, vo, io), s_l = run_compress(pl, layers[l][1])
+        n = p.n_kv_heads * B
+        assert np.array_equal(idx[row:row + n].reshape(p.n_kv_heads, B), io)
+        assert np.array_equal(Ko[row:row + n].reshape(p.n_kv_heads, B, -1), ko)
+        assert np.array_equal(Vo[row:row + n].reshape(p.n_kv_heads, B, -1), vo)
+        assert np.array_equal(sc[l].cpu().numpy(), s_l)
+        row += n
+    assert row == idx.size
+
+
+def test_batched_more_layers_than_one_group(oracle):
+    """70 tiny layers: two groups (64 + 6) inside one call."""
+    L = 70
+    cfg = small_bf16_cfg(n_tokens=200, budget=64, n_kv_heads=1, n_q_heads=4, n_sources=4, n_neighbors=3)
+    p = util.params_from_cfg(cfg)
+    layers = [util.device_layer(cfg, l) for l in (0, 1, 2)]
+    pick = [l % 3 for l in range(L)]
+    Kall = torch.stack([layers[i][1][0] for i in pick]).contiguous()
+    Vall = torch.stack([layers[i][1][1] for i in pick]).contiguous()
+    Qall = torch.stack([layers[i][1][2] for i in pick]).contiguous()
+    budgets = [64 - (l % 5) for l in range(L)]
+    Ko, Vo, idx = gk.graphkv_compress_batched(p, L, budgets, Kall, Vall, Qall)
+    idx = idx.cpu().numpy()
+    row = 0
+    for l in range(L):
+        (K, V, Q) = layers[pick[l]][0]
+        ref = oracle.compress(K, V, Q, "bf16", cfg.pool_kernel, budgets[l], cfg.n_sources, cfg.n_neighbors, cfg.rounds)
+        got = idx[row:row + budgets[l]]
+        if not np.array_equal(got, ref["idx"][0]):
+            assert ref["min_gap"].min() < util.REL_TOL
+        row += budgets[l]
+
+
 # ---------------------------------------------- full-size launch shapes ---
 
 @pytest.mark.parametrize("name,layer", [("c3", 0), ("c4", 31)])
