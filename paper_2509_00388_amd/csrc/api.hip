@@ -194,8 +194,9 @@ int32_t run_score(const graphkv_params *p, const Dims &D, const Workspace &W, co
         GKV_LAUNCH(GRAPHKV_K_SCORE_VOTES,
                    launch_mfma_score_votes(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale, per_q,
                                            at<float>(ws, W.part), votes, st));
-        GKV_LAUNCH(GRAPHKV_K_POOL, launch_pool_group(votes, D.H, per_q ? D.G : 1, D.P, p->pool_kernel, p->pool_mode,
-                                  (float)D.G, scores, st));
+        GKV_LAUNCH(GRAPHKV_K_POOL,
+                   launch_pool_group(votes, D.H, mfma_score_vote_rows(D.G, D.w, per_q), D.P, p->pool_kernel,
+                                     p->pool_mode, (float)D.G, scores, st));
         return GRAPHKV_OK;
     }
     GKV_LAUNCH(GRAPHKV_K_GENERIC_LOGITS, launch_generic_logits(Kc, Qw, p->dtype, D.H, D.Hq, D.d, D.N, D.w, D.scale,
@@ -250,7 +251,7 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                            launch_mfma_cosine_filter(Kc, D.H, D.N, D.P, D.S, D.m, src, tau, cand, cnt,
                                                      ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
-                           launch_nbr_select(cand, cnt, ovf, D.H, D.P, D.S, D.m, nbr, ev, st));
+                           launch_nbr_select(cand, cnt, ovf, src, D.H, D.P, D.S, D.m, nbr, ev, st));
                 // heads whose lists overflowed are redone through the dense block
                 GKV_LAUNCH(GRAPHKV_K_REDO_COSINE, launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_REDO_TOPK,

@@ -62,7 +62,9 @@ struct MfmaScorePlan {
 };
 MfmaScorePlan mfma_score_plan(int Hkv, int rows, int N);
 // Pass A: per (head, chunk, row) partial max and sum of exp2 over the chunk's visible keys.
-// Pass B: votes [Hkv, P] (avg mode, all rows summed) or [Hq, P] (per query head).
+// Pass B: votes [Hkv * rows, P] with rows = mfma_score_vote_rows(): partial sums over
+// groups of query rows (to be added up), or one row per query head.
+int mfma_score_vote_rows(int G, int w, int per_qhead_votes);
 hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
                                   float scale, float *part, hipStream_t st);
 hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
@@ -86,7 +88,7 @@ hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int 
                                      int32_t *cand_cnt, int32_t *overflow, hipStream_t st);
 // Exact top-m of each candidate list -> nbr / nbr_e [Hkv, S, m]; skips heads with overflow[h].
 hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, const int32_t *overflow,
-                             int Hkv, int P, int S, int m, int32_t *nbr, float *nbr_e,
-                             hipStream_t st);
+                             const int32_t *src, int Hkv, int P, int S, int m, int32_t *nbr,
+                             float *nbr_e, hipStream_t st);
 
 }  // namespace gkv

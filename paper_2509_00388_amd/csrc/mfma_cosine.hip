@@ -19,35 +19,30 @@
 // a per-head flag and that head is redone through the dense block instead.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "mfma_tile.hpp"
+
+#include <unordered_set>
 
 namespace gkv {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 namespace {
 
-constexpr int kD = 128, kSteps = 8, kBlk = 32;
-constexpr int kSB = 2;            // source blocks of 32 per workgroup
+constexpr int kSB = 2;            // source blocks of 32 per workgroup = row groups of waves
 constexpr int kRows = kSB * kBlk; // source rows per workgroup
+constexpr int kThreads = 256 * kSB;
 constexpr int kRing = 6144;       // candidates a workgroup can stage in LDS (48 KiB)
 
-__device__ __forceinline__ bf16x8 load8(const uint16_t *p)
-{
-    return *reinterpret_cast<const bf16x8 *>(p);
-}
-__device__ __forceinline__ int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
-
-// Sum of squares of the 64 elements a lane holds of its row (8 k-steps x 8).
+// Sum of squares of the 64 elements a lane holds of its row (8 k-steps x 8),
+// two bf16 products per instruction, fp32 accumulation.
 __device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
 {
     float a = 0.f;
 #pragma unroll
     for (int s = 0; s < kSteps; ++s)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float v = (float)r[s][e];
-            a = fmaf(v, v, a);
+        for (int e = 0; e < 8; e += 2) {
+            const bf16x2 v = {r[s][e], r[s][e + 1]};
+            a = __builtin_amdgcn_fdot2_f32_bf16(v, v, a, false);
         }
     return a;
 }
@@ -62,26 +57,37 @@ struct FilterArgs {
     int cap;
 };
 
+// A workgroup has 4 key streams (wave & 3) and 2 source row groups (wave >> 2):
+// wave (stream, g) multiplies source rows 32g .. 32g+31 of its 64-row group with
+// the key blocks stream, stream+4, ...  Two waves share a SIMD and overlap each
+// other's MFMA and vector work.  The edge is e = (dot * 1/|k_j|) * 1/|k_i| in every
+// mode, so the sample pass and the filter pass produce the same bits.
+//
 // Column c of the output is key c * key_stride (key_stride = 1: every key).
-// kDense: E[h, slot, c] = cosine, -inf where the key is the source itself.
-// kFilter: edges >= tau[h, slot] (self excluded) are appended to cand[h, slot, :].
-// zero_cnt (dense only, may be null): the first chunk also clears cand_cnt /
-// overflow of its head for the filter pass that follows.
+// kDense: E[h, slot, c] = e, -inf where the key is the source itself; if
+//   fa.cand_cnt is set, chunk 0 also clears cand_cnt / overflow of its head for
+//   the filter pass that follows.
+// kFilter: edges that reach the source's bound are appended to cand[h, slot, :]
+//   (the source's own column included: the exact select drops it).
 template <int MODE>
-__global__ __launch_bounds__(256) void cosine_kernel(const uint16_t *__restrict__ Kc, int N,
-                                                     int n_cols, int key_stride, int S,
-                                                     const int32_t *__restrict__ src,
-                                                     int chunk_cols, float *__restrict__ E,
-                                                     FilterArgs fa, const int32_t *__restrict__ gate)
+__global__ __launch_bounds__(kThreads) void cosine_kernel(const uint16_t *__restrict__ Kc, int N,
+                                                          int n_cols, int key_stride, int S,
+                                                          const int32_t *__restrict__ src,
+                                                          int chunk_cols, float *__restrict__ E,
+                                                          FilterArgs fa,
+                                                          const int32_t *__restrict__ gate)
 {
     __shared__ float inv_s[kRows];
     __shared__ int32_t idx_s[kRows];
     __shared__ float tau_s[kRows];
-    __shared__ uint2 ring[MODE == kFilter ? kRing : 1];
+    extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the candidate ring
+    unsigned char *kt = smem;
+    uint2 *ring = reinterpret_cast<uint2 *>(smem + 2 * kTileBytes);
     __shared__ int32_t ring_n, row_cnt[kRows], row_base[kRows], row_pos[kRows];
 
     const int h = blockIdx.y, chunk = blockIdx.x, s_base = blockIdx.z * kRows;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
+    const int stream = wv & 3, grp = wv >> 2;
     if (gate && gate[h] == 0) return;
     const uint16_t *Kh = Kc + (long)h * N * kD;
     const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
@@ -94,22 +100,27 @@ __global__ __launch_bounds__(256) void cosine_kernel(const uint16_t *__restrict_
         }
     }
 
-    // source rows -> registers (slots beyond S repeat the last source; never written out)
-    bf16x8 q[kSB][kSteps];
-#pragma unroll
-    for (int b = 0; b < kSB; ++b) {
-        const int slot = min(s_base + kBlk * b + l32, S - 1);
+    // this wave's 32 source rows -> registers (slots beyond S repeat the last source)
+    bf16x8 q[kSteps];
+    {
+        const int slot = min(s_base + kBlk * grp + l32, S - 1);
         const int32_t i = src[(long)h * S + slot];
         const uint16_t *p = Kh + (long)i * kD + 8 * hh;
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) q[b][s] = load8(p + 16 * s);
-        float sq = half_row_sumsq(q[b]);
+        for (int s = 0; s < kSteps; ++s) q[s] = load8(p + 16 * s);
+        float sq = half_row_sumsq(q);
         sq += __shfl_xor(sq, 32, kWave);
-        if (wv == 0 && hh == 0) {
-            inv_s[kBlk * b + l32] = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
-            idx_s[kBlk * b + l32] = i;
-            if constexpr (MODE == kFilter)   // a hair below the bound: never lose an edge to rounding
-                tau_s[kBlk * b + l32] = fa.tau[(long)h * S + slot] - 4e-6f;
+        if (stream == 0 && hh == 0) {
+            const float inv = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
+            inv_s[kBlk * grp + l32] = inv;
+            idx_s[kBlk * grp + l32] = i;
+            if constexpr (MODE == kFilter) {
+                // The filter compares dot/|k_j| with bound/(1/|k_i|), a hair lowered so that
+                // rounding can never lose an edge; a zero source has e = 0 everywhere.
+                const float t = fa.tau[(long)h * S + slot];
+                const float lo = t - 4e-6f - 1e-5f * fabsf(t);
+                tau_s[kBlk * grp + l32] = inv > 0.f ? lo / inv : (lo <= 0.f ? -INFINITY : INFINITY);
+            }
         }
     }
     if constexpr (MODE == kFilter) {
@@ -117,102 +128,81 @@ __global__ __launch_bounds__(256) void cosine_kernel(const uint16_t *__restrict_
         if (tid < kRows) { row_cnt[tid] = 0; row_pos[tid] = 0; }
     }
     __syncthreads();
-    float inv_src[kSB][16], tau[MODE == kFilter ? kSB : 1][16];
-    int32_t idx_src[kSB][16];
+    float inv_src[16], thr[MODE == kFilter ? 16 : 1];
+    int32_t idx_src[MODE == kDense ? 16 : 1];
 #pragma unroll
-    for (int b = 0; b < kSB; ++b)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            inv_src[b][i] = inv_s[kBlk * b + acc_row(i, hh)];
-            idx_src[b][i] = idx_s[kBlk * b + acc_row(i, hh)];
-            if constexpr (MODE == kFilter) {
-                // rows past S never pass the filter
-                tau[b][i] = (s_base + kBlk * b + acc_row(i, hh) < S) ? tau_s[kBlk * b + acc_row(i, hh)]
-                                                                      : INFINITY;
-            }
-        }
+    for (int i = 0; i < 16; ++i) {
+        const int r = kBlk * grp + acc_row(i, hh);
+        inv_src[i] = inv_s[r];
+        if constexpr (MODE == kDense) idx_src[i] = idx_s[r];
+        if constexpr (MODE == kFilter) thr[i] = (s_base + r < S) ? tau_s[r] : INFINITY;   // rows past S never pass
+    }
 
-    const int nblk = (c1 - c0 + kBlk - 1) / kBlk;
-    bf16x8 kn[kSteps];
-    int t = wv;
-    auto load_keys = [&](int col, bf16x8(&kr)[kSteps]) {
-        const uint16_t *p = Kh + (long)min(col, n_cols - 1) * key_stride * kD + 8 * hh;
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s) kr[s] = load8(p + 16 * s);
-    };
-    if (t < nblk) load_keys(c0 + kBlk * t + l32, kn);
-    for (; t < nblk; t += 4) {
+    const int ntile = (c1 - c0 + kTileKeys - 1) / kTileKeys;
+    u32x4 stage[tile_pieces<kThreads>()];
+    tile_load<kThreads>(Kh, c0, n_cols - 1, key_stride, tid, stage);
+    tile_store<kThreads>(kt, tid, stage);
+    __syncthreads();
+    for (int t = 0; t < ntile; ++t) {
+        if (t + 1 < ntile) tile_load<kThreads>(Kh, c0 + kTileKeys * (t + 1), n_cols - 1, key_stride, tid, stage);
         bf16x8 kc[kSteps];
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s) kc[s] = kn[s];
-        if (t + 4 < nblk) load_keys(c0 + kBlk * (t + 4) + l32, kn);
+        tile_read(kt + (t & 1) * kTileBytes, stream, l32, hh, kc);
 
-        f32x16 acc[kSB];
+        f32x16 acc;
 #pragma unroll
-        for (int b = 0; b < kSB; ++b)
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s)
-#pragma unroll
-            for (int b = 0; b < kSB; ++b)   // rows = sources, columns = keys
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[b][s], kc[s], acc[b], 0, 0, 0);
+        for (int s = 0; s < kSteps; ++s)   // rows = sources, columns = keys
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[s], kc[s], acc, 0, 0, 0);
 
         float sq = half_row_sumsq(kc);
         sq += __shfl_xor(sq, 32, kWave);
         const float inv_k = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
-        const int col = c0 + kBlk * t + l32;
+        const int col = c0 + kTileKeys * t + kBlk * stream + l32;
         const int key = col * key_stride;
         if constexpr (MODE == kDense) {
             if (col < c1) {
 #pragma unroll
-                for (int b = 0; b < kSB; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int slot = s_base + kBlk * b + acc_row(i, hh);
-                        if (slot < S) {
-                            float e = acc[b][i] * inv_src[b][i] * inv_k;
-                            if (key == idx_src[b][i]) e = -INFINITY;
-                            E[((long)h * S + slot) * n_cols + col] = e;
-                        }
+                for (int i = 0; i < 16; ++i) {
+                    const int slot = s_base + kBlk * grp + acc_row(i, hh);
+                    if (slot < S) {
+                        float e = (acc[i] * inv_k) * inv_src[i];
+                        if (key == idx_src[i]) e = -INFINITY;
+                        E[((long)h * S + slot) * n_cols + col] = e;
                     }
+                }
             }
         } else {
-            uint32_t pass = 0;   // bit (16 b + i): edge of that accumulator reaches its bound
-            float ev[kSB][16];
+            float tv[16];
+            int cnt = 0;
 #pragma unroll
-            for (int b = 0; b < kSB; ++b)
+            for (int i = 0; i < 16; ++i) {
+                tv[i] = acc[i] * inv_k;
+                cnt += (tv[i] >= thr[i]) ? 1 : 0;
+            }
+            if (col >= c1) cnt = 0;
+            if (cnt) {
+                int at = atomicAdd(&ring_n, cnt);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    ev[b][i] = acc[b][i] * inv_src[b][i] * inv_k;
-                    if (ev[b][i] >= tau[b][i] && key != idx_src[b][i]) pass |= 1u << (16 * b + i);
-                }
-            if (col >= c1) pass = 0;
-            if (pass) {
-                const int cnt = __popc(pass);
-                const int at = atomicAdd(&ring_n, cnt);
-                int w = 0;
-#pragma unroll
-                for (int b = 0; b < kSB; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        if (pass & (1u << (16 * b + i))) {
-                            if (at + w < kRing)
-                                ring[at + w] = make_uint2(__float_as_uint(ev[b][i]),
-                                                          ((uint32_t)(kBlk * b + acc_row(i, hh)) << 24) | (uint32_t)key);
-                            ++w;
-                        }
+                for (int i = 0; i < 16; ++i)
+                    if (tv[i] >= thr[i]) {
+                        if (at < kRing)
+                            ring[at] = make_uint2(__float_as_uint(tv[i] * inv_src[i]),
+                                                  ((uint32_t)(kBlk * grp + acc_row(i, hh)) << 24) | (uint32_t)key);
+                        ++at;
+                    }
             }
         }
+        if (t + 1 < ntile) tile_store<kThreads>(kt + ((t + 1) & 1) * kTileBytes, tid, stage);
+        __syncthreads();
     }
 
     if constexpr (MODE == kFilter) {
         // Flush: count per source row, reserve room in the global lists, scatter.
-        __syncthreads();
         const int n_stage = ring_n;
         const bool lost = n_stage > kRing;
         const int n_ring = lost ? kRing : n_stage;
-        for (int r = tid; r < n_ring; r += 256) atomicAdd(&row_cnt[ring[r].y >> 24], 1);
+        for (int r = tid; r < n_ring; r += kThreads) atomicAdd(&row_cnt[ring[r].y >> 24], 1);
         __syncthreads();
         if (tid < kRows) {
             const int c = row_cnt[tid];
@@ -222,7 +212,7 @@ __global__ __launch_bounds__(256) void cosine_kernel(const uint16_t *__restrict_
             if (base + c > fa.cap || lost) fa.overflow[h] = 1;
         }
         __syncthreads();
-        for (int r = tid; r < n_ring; r += 256) {
+        for (int r = tid; r < n_ring; r += kThreads) {
             const uint2 v = ring[r];
             const int row = v.y >> 24;
             const int at = row_base[row] + atomicAdd(&row_pos[row], 1);
@@ -243,50 +233,137 @@ __device__ __forceinline__ uint32_t ord_key_u(uint32_t bits)
 // written in ascending key order.  One workgroup per (source, head); heads whose
 // overflow flag is set are left to the dense path.
 //
-// The list is short (a few hundred entries) and all composite keys
-// (edge, -index) are distinct, so the rank of an entry is the number of entries
-// that beat it; entries of rank < m are the neighbourhood, and their output
-// position is their rank by key index among themselves.
+// The m-th largest edge value is found by a radix select over the order-
+// preserving keys of the (short) list, as in the row top-k; entries above it are
+// in, and of the entries equal to it the `need` lowest key indices are in.  The
+// winners' output position is their rank by key index among themselves.
 __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict__ cand,
                                                          const int32_t *__restrict__ cand_cnt,
                                                          const int32_t *__restrict__ overflow,
-                                                         int S, int cap, int m,
-                                                         int32_t *__restrict__ nbr,
+                                                         const int32_t *__restrict__ src, int S,
+                                                         int cap, int m, int32_t *__restrict__ nbr,
                                                          float *__restrict__ nbr_e)
 {
-    extern __shared__ uint64_t comp[];          // [cap] composite keys, then the winners
-    __shared__ int32_t n_win;
-    const int a = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    extern __shared__ uint32_t dyn[];
+    __shared__ uint32_t hist[2048];
+    __shared__ uint32_t s_bin, s_need, s_min[4], s_max[4];
+    __shared__ int32_t n_win, n_eq;
+    const int a = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     if (overflow[h]) return;
     const long row = (long)h * S + a;
     const int n = min(cand_cnt[row], cap);
     const uint2 *c = cand + row * cap;
-    uint64_t *win = comp + cap;                 // [m] winners as (key index << 32 | edge bits)
-    if (tid == 0) n_win = 0;
+    const uint32_t self = (uint32_t)src[row];
+    uint32_t *ek = dyn;                 // [cap] order-preserving edge keys (0 = dropped)
+    uint32_t *kj = dyn + cap;           // [cap] key indices
+    uint32_t *eq = kj + cap;            // [cap] key indices of the entries equal to the threshold
+    uint64_t *win = reinterpret_cast<uint64_t *>(eq + cap + (cap & 1));   // [m] (key index << 32 | edge bits)
+    if (tid == 0) { n_win = 0; n_eq = 0; }
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
     for (int r = tid; r < n; r += 256) {
         const uint2 v = c[r];
-        comp[r] = ((uint64_t)ord_key_u(v.x) << 32) | (uint32_t)(0xffffffffu - v.y);
+        // the source's own column is no neighbour (Eq. 3: j != i): key 0 sorts below every edge
+        const uint32_t k = v.y == self ? 0u : ord_key_u(v.x);
+        ek[r] = k;
+        kj[r] = v.y;
+        if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
     }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+    }
+    if (lane == 0) { s_min[wv] = kmin; s_max[wv] = kmax; }
     __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) { kmin = min(kmin, s_min[u]); kmax = max(kmax, s_max[u]); }
+
+    const uint32_t range = kmax - kmin;
+    int remaining = (kmax >= kmin && range) ? 32 - __clz(range) : 0;
+    uint32_t prefix = 0, mask = 0, need = (uint32_t)m;
+    while (remaining > 0) {
+        const int bits = remaining < 11 ? remaining : 11;
+        const int shift = remaining - bits;
+        const uint32_t dmask = (1u << bits) - 1u;
+        for (int b = tid; b < 2048; b += 256) hist[b] = 0;
+        __syncthreads();
+        for (int r = tid; r < n; r += 256) {
+            const uint32_t k = ek[r];
+            if (k) {
+                const uint32_t rel = k - kmin;
+                if ((rel & mask) == prefix) atomicAdd(&hist[(rel >> shift) & dmask], 1u);
+            }
+        }
+        __syncthreads();
+        if (wv == 0) {   // bin where the count of larger-or-equal digits reaches `need`
+            uint32_t tsum = 0;
+            for (int b = 0; b < 32; ++b) tsum += hist[32 * lane + b];
+            uint32_t incl = tsum;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t v = __shfl_down(incl, o, kWave);
+                if (lane + o < 64) incl += v;
+            }
+            const uint32_t excl = incl - tsum;
+            if (excl < need && need <= incl) {
+                uint32_t cum = excl;
+                int b = 31;
+                for (; b > 0; --b) {
+                    const uint32_t cb = hist[32 * lane + b];
+                    if (cum + cb >= need) break;
+                    cum += cb;
+                }
+                s_bin = 32 * lane + b;
+                s_need = need - cum;
+            }
+        }
+        __syncthreads();
+        prefix |= s_bin << shift;
+        mask |= dmask << shift;
+        need = s_need;
+        remaining = shift;
+    }
+    const uint32_t tau = kmin + prefix;
+    // winners above the threshold; entries equal to it are ranked by key index
     for (int r = tid; r < n; r += 256) {
-        const uint64_t mine = comp[r];
-        int rank = 0;
-        for (int u = 0; u < n; ++u) rank += comp[u] > mine;
-        if (rank < m) {
+        const uint32_t k = ek[r];
+        if (k > tau) {
             const int at = atomicAdd(&n_win, 1);
-            const uint2 v = c[r];
-            win[at] = ((uint64_t)v.y << 32) | v.x;
+            win[at] = ((uint64_t)kj[r] << 32) | c[r].x;
+        } else if (k == tau && k) {
+            eq[atomicAdd(&n_eq, 1)] = kj[r];
         }
     }
     __syncthreads();
-    const int nw = n_win;                       // == m whenever n >= m
-    for (int r = tid; r < nw; r += 256) {
+    const int ne = n_eq, base = n_win;
+    for (int r = tid; r < n; r += 256) {
+        if (ek[r] == tau && ek[r]) {
+            const uint32_t mine = kj[r];
+            uint32_t rank = 0;
+            for (int u = 0; u < ne; ++u) rank += eq[u] < mine;
+            if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | c[r].x;
+        }
+    }
+    __syncthreads();
+    for (int r = tid; r < m; r += 256) {
         const uint64_t mine = win[r];
         int pos = 0;
-        for (int u = 0; u < nw; ++u) pos += win[u] < mine;
+        for (int u = 0; u < m; ++u) pos += win[u] < mine;
         nbr[row * m + pos] = (int32_t)(mine >> 32);
         nbr_e[row * m + pos] = __uint_as_float((uint32_t)mine);
     }
+}
+
+// Kernels that use more than 64 KiB of dynamic LDS need a one-time opt-in per kernel.
+bool allow_big_lds(const void *kernel)
+{
+    static std::unordered_set<const void *> done;   // host-side, filled on first use of each kernel
+    if (done.count(kernel)) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 8192) !=
+        hipSuccess)
+        return false;
+    done.insert(kernel);
+    return true;
 }
 
 // Columns per workgroup: about 1024 workgroups in flight over all heads and source
@@ -326,7 +403,7 @@ bool mfma_filter_applies(int P, int m)
     // the select kernel's LDS must hold a full list.
     if (P < 8192 || P >= (1 << 24)) return false;
     if (m > mfma_sample_cols(P) / 8) return false;
-    return (size_t)mfma_cand_cap(P, m) * 8 + (size_t)m * 8 <= 96 * 1024;
+    return (size_t)mfma_cand_cap(P, m) * 12 + (size_t)m * 8 + 8 <= 110 * 1024;
 }
 
 hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
@@ -336,8 +413,9 @@ hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, cons
     const int ck = chunk_cols_for(Hkv, sgroups, P);
     const int chunks = (P + ck - 1) / ck;
     FilterArgs fa{};
-    hipLaunchKernelGGL(cosine_kernel<kDense>, dim3(chunks, Hkv, sgroups), dim3(256), 0, st,
-                       (const uint16_t *)Kc, N, P, 1, S, src, ck, E, fa, gate);
+    if (!allow_big_lds((const void *)cosine_kernel<kDense>)) return hipGetLastError();
+    hipLaunchKernelGGL(cosine_kernel<kDense>, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
+                       st, (const uint16_t *)Kc, N, P, 1, S, src, ck, E, fa, gate);
     return hipGetLastError();
 }
 
@@ -352,8 +430,9 @@ hipError_t launch_mfma_cosine_sample(const void *Kc, int Hkv, int N, int P, int 
     FilterArgs fa{};
     fa.cand_cnt = cand_cnt;
     fa.overflow = overflow;
-    hipLaunchKernelGGL(cosine_kernel<kDense>, dim3(chunks, Hkv, sgroups), dim3(256), 0, st,
-                       (const uint16_t *)Kc, N, ps, stride, S, src, ck, E_sample, fa,
+    if (!allow_big_lds((const void *)cosine_kernel<kDense>)) return hipGetLastError();
+    hipLaunchKernelGGL(cosine_kernel<kDense>, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
+                       st, (const uint16_t *)Kc, N, ps, stride, S, src, ck, E_sample, fa,
                        (const int32_t *)nullptr);
     return hipGetLastError();
 }
@@ -369,27 +448,28 @@ hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int 
     const int ck = chunk_cols_for(Hkv, sgroups, P, min_chunks);
     const int chunks = (P + ck - 1) / ck;
     FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, mfma_cand_cap(P, m)};
-    hipLaunchKernelGGL(cosine_kernel<kFilter>, dim3(chunks, Hkv, sgroups), dim3(256), 0, st,
-                       (const uint16_t *)Kc, N, P, 1, S, src, ck, (float *)nullptr, fa,
-                       (const int32_t *)nullptr);
+    if (!allow_big_lds((const void *)cosine_kernel<kFilter>)) return hipGetLastError();
+    hipLaunchKernelGGL(cosine_kernel<kFilter>, dim3(chunks, Hkv, sgroups), dim3(kThreads),
+                       2 * kTileBytes + kRing * sizeof(uint2), st, (const uint16_t *)Kc, N, P, 1, S, src, ck,
+                       (float *)nullptr, fa, (const int32_t *)nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, const int32_t *overflow,
-                             int Hkv, int P, int S, int m, int32_t *nbr, float *nbr_e,
-                             hipStream_t st)
+                             const int32_t *src, int Hkv, int P, int S, int m, int32_t *nbr,
+                             float *nbr_e, hipStream_t st)
 {
     const int cap = mfma_cand_cap(P, m);
-    const size_t lds = (size_t)cap * 8 + (size_t)m * 8;
+    const size_t lds = ((size_t)3 * cap + (cap & 1)) * 4 + (size_t)m * 8;
     static bool opt_in = false;   // more than 64 KiB of dynamic LDS needs a one-time opt-in
     if (lds > 65536 && !opt_in) {
         if (hipFuncSetAttribute((const void *)nbr_select_kernel,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024) != hipSuccess)
             return hipGetLastError();
         opt_in = true;
     }
     hipLaunchKernelGGL(nbr_select_kernel, dim3(S, Hkv), dim3(256), lds, st, (const uint2 *)cand,
-                       cand_cnt, overflow, S, cap, m, nbr, nbr_e);
+                       cand_cnt, overflow, src, S, cap, m, nbr, nbr_e);
     return hipGetLastError();
 }
 

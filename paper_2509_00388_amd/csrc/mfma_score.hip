@@ -1,12 +1,11 @@
 // Stage I on the matrix cores (bf16 inputs, d = 128, fp32 accumulation).
 //
 // Per KV head the window queries of its G query heads are stacked into one
-// R x 128 operand (R = G*w <= 128 rows), held in registers by every wave for
-// the whole kernel.  Keys stream from HBM in blocks of 32 rows straight into
-// MFMA operand registers (each lane loads 16-byte pieces of "its" key row; the
-// 8 pieces cover the row's half that belongs to the lane's half-wave), so one
-// key block costs R/32 x 8 v_mfma_f32_32x32x16_bf16 and is read exactly once
-// per pass.  Each wave walks its own key blocks: no barrier in the main loop.
+// R x 128 operand (R = G*w <= 128 rows), held in registers for the whole kernel.
+// Keys stream from HBM in tiles of 128 rows through LDS (mfma_tile.hpp); each of
+// the 4 key streams of a workgroup multiplies 32 of those rows, so one key block
+// costs R/32 x 8 v_mfma_f32_32x32x16_bf16 and every key is read from HBM exactly
+// once per pass.
 //
 // The column sums of a row softmax need the row statistics first, so there are
 // two passes over the keys:
@@ -19,22 +18,13 @@
 // Everything is done in the base-2 domain: c = scale * log2(e).
 #include "common.hpp"
 #include "kernels.hpp"
+#include "mfma_tile.hpp"
+
+#include <unordered_set>
 
 namespace gkv {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 namespace {
-
-constexpr int kD = 128;      // head dimension
-constexpr int kSteps = 8;    // k-steps of 16 per 128
-constexpr int kBlk = 32;     // keys per MFMA block
-
-__device__ __forceinline__ bf16x8 load8(const uint16_t *p)
-{
-    return *reinterpret_cast<const bf16x8 *>(p);
-}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -47,10 +37,6 @@ __device__ __forceinline__ void merge_stats(float &m1, float &z1, float m2, floa
     m1 = mn;
 }
 
-// Row of the 32x32 MFMA result held in accumulator register i of a lane in
-// half-wave hh (the column is lane % 32).
-__device__ __forceinline__ int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
-
 template <int NB>
 __device__ __forceinline__ void load_queries(const uint16_t *Qb, int l32, int hh, bf16x8 (&q)[NB][kSteps])
 {
@@ -61,66 +47,65 @@ __device__ __forceinline__ void load_queries(const uint16_t *Qb, int l32, int hh
             q[b][s] = load8(Qb + (long)(kBlk * b + l32) * kD + 16 * s + 8 * hh);
 }
 
-// Key block t of the chunk: lane (l32, hh) takes row k0 + 32 t + l32, clamped
-// to the last row of the head (clamped rows are masked by the caller).
-__device__ __forceinline__ void load_keys(const uint16_t *Kh, int key, int last_row, int hh,
-                                          bf16x8 (&kr)[kSteps])
-{
-    const uint16_t *p = Kh + (long)min(key, last_row) * kD + 8 * hh;
-#pragma unroll
-    for (int s = 0; s < kSteps; ++s) kr[s] = load8(p + 16 * s);
-}
+// The R query rows are split over SPLIT waves per key stream: a workgroup has 4
+// key streams (wave & 3) and SPLIT row groups (wave >> 2), i.e. 4*SPLIT waves.  The
+// waves of one stream load the same key block (the second load hits L1) and each
+// handles NB/SPLIT of the 32-row query blocks.  With SPLIT = 2 a wave needs under
+// 256 registers, two waves share a SIMD, and one wave's exp2 work overlaps the
+// other's MFMAs.
 
 // ---------------------------------------------------------------- pass A ---
-template <int NB>
-__global__ __launch_bounds__(256) void score_stats_kernel(
+template <int NB, int SPLIT>
+__global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w,
     int chunk_keys, float c, float *__restrict__ part)
 {
-    constexpr int R = NB * kBlk;
+    constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
+    extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
     __shared__ float sm[4][R], sz[4][R];
     const int h = blockIdx.y, chunk = blockIdx.x, nchunks = gridDim.x;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
+    const int stream = wv & 3, row0 = (wv >> 2) * NBW * kBlk;   // first query row of this wave
 
-    bf16x8 q[NB][kSteps];
-    load_queries<NB>(Qw + (long)h * R * kD, l32, hh, q);
-    int last_vis[NB];   // last key the lane's query of block b may see (causal window)
-    float m[NB], z[NB];
+    bf16x8 q[NBW][kSteps];
+    load_queries<NBW>(Qw + ((long)h * R + row0) * kD, l32, hh, q);
+    int last_vis[NBW];   // last key the lane's query of block b may see (causal window)
+    float m[NBW], z[NBW];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        last_vis[b] = P + (kBlk * b + l32) % w;
+    for (int b = 0; b < NBW; ++b) {
+        last_vis[b] = P + (row0 + kBlk * b + l32) % w;
         m[b] = -INFINITY;
         z[b] = 0.f;
     }
 
     const uint16_t *Kh = Kc + (long)h * N * kD;
     const int k0 = chunk * chunk_keys, k1 = min(N, k0 + chunk_keys);
-    const int nblk = (k1 - k0 + kBlk - 1) / kBlk;
+    const int ntile = (k1 - k0 + kTileKeys - 1) / kTileKeys;
 
-    bf16x8 kn[kSteps];
-    int t = wv;
-    if (t < nblk) load_keys(Kh, k0 + kBlk * t + l32, N - 1, hh, kn);
-    for (; t < nblk; t += 4) {
+    u32x4 stage[tile_pieces<NT>()];
+    tile_load<NT>(Kh, k0, N - 1, 1, tid, stage);
+    tile_store<NT>(kt, tid, stage);
+    __syncthreads();
+    for (int t = 0; t < ntile; ++t) {
+        if (t + 1 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 1), N - 1, 1, tid, stage);
         bf16x8 kc[kSteps];
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s) kc[s] = kn[s];
-        if (t + 4 < nblk) load_keys(Kh, k0 + kBlk * (t + 4) + l32, N - 1, hh, kn);
+        tile_read(kt + (t & 1) * kTileBytes, stream, l32, hh, kc);
 
-        f32x16 acc[NB];
+        f32x16 acc[NBW];
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < NBW; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 #pragma unroll
         for (int s = 0; s < kSteps; ++s)
 #pragma unroll
-            for (int b = 0; b < NB; ++b)   // rows = keys, columns = queries
+            for (int b = 0; b < NBW; ++b)   // rows = keys, columns = queries
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[s], q[b][s], acc[b], 0, 0, 0);
 
-        const int kb = k0 + kBlk * t;
+        const int kb = k0 + kTileKeys * t + kBlk * stream;
         if (kb + kBlk <= P) {   // every key of the block is a prefix key: visible to all rows
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
+            for (int b = 0; b < NBW; ++b) {
                 float tm = acc[b][0];
 #pragma unroll
                 for (int i = 1; i < 16; ++i) tm = fmaxf(tm, acc[b][i]);
@@ -133,7 +118,7 @@ __global__ __launch_bounds__(256) void score_stats_kernel(
             }
         } else {                // the block touches the window (or the end of the head): mask
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
+            for (int b = 0; b < NBW; ++b) {
                 float tm = -INFINITY;
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
@@ -149,14 +134,16 @@ __global__ __launch_bounds__(256) void score_stats_kernel(
                 }
             }
         }
+        if (t + 1 < ntile) tile_store<NT>(kt + ((t + 1) & 1) * kTileBytes, tid, stage);
+        __syncthreads();
     }
 
-    // merge the two half-waves (same query, other key rows), then the 4 waves
+    // merge the two half-waves (same query, other key rows), then the 4 key streams
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
+    for (int b = 0; b < NBW; ++b) {
         const float m2 = __shfl_xor(m[b], 32, kWave), z2 = __shfl_xor(z[b], 32, kWave);
         merge_stats(m[b], z[b], m2, z2);
-        if (hh == 0) { sm[wv][kBlk * b + l32] = m[b]; sz[wv][kBlk * b + l32] = z[b]; }
+        if (hh == 0) { sm[stream][row0 + kBlk * b + l32] = m[b]; sz[stream][row0 + kBlk * b + l32] = z[b]; }
     }
     __syncthreads();
     if (tid < R) {
@@ -170,16 +157,21 @@ __global__ __launch_bounds__(256) void score_stats_kernel(
 }
 
 // ---------------------------------------------------------------- pass B ---
-template <int NB, bool PERQ>
-__global__ __launch_bounds__(256) void score_votes_kernel(
+// votes: PERQ = false: [Hkv * SPLIT, P], row h*SPLIT + g holds the sum over the
+// query rows of row group g; PERQ = true: [Hkv * G, P], one row per query head
+// (needs every query head's rows inside one row group).
+template <int NB, int SPLIT, bool PERQ>
+__global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w, int G,
     int chunk_keys, float c, const float *__restrict__ part, int part_chunks,
     float *__restrict__ votes)
 {
-    constexpr int R = NB * kBlk;
+    constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
+    extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
     __shared__ float bias_s[R];
     const int h = blockIdx.y, chunk = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
+    const int stream = wv & 3, grp = wv >> 2, row0 = grp * NBW * kBlk;
 
     const int k0 = chunk * chunk_keys, k1 = min(P, k0 + chunk_keys);
     if (k0 >= P) return;
@@ -194,64 +186,80 @@ __global__ __launch_bounds__(256) void score_votes_kernel(
     }
     __syncthreads();
 
-    bf16x8 q[NB][kSteps];
-    load_queries<NB>(Qw + (long)h * R * kD, l32, hh, q);
-    float bias[NB][16];
+    bf16x8 q[NBW][kSteps];
+    load_queries<NBW>(Qw + ((long)h * R + row0) * kD, l32, hh, q);
+    float bias[NBW][16];
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < NBW; ++b)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) bias[b][i] = bias_s[kBlk * b + acc_row(i, hh)];
+        for (int i = 0; i < 16; ++i) bias[b][i] = bias_s[row0 + kBlk * b + acc_row(i, hh)];
 
     const uint16_t *Kh = Kc + (long)h * N * kD;
-    const int nblk = (k1 - k0 + kBlk - 1) / kBlk;
+    const int ntile = (k1 - k0 + kTileKeys - 1) / kTileKeys;
     const int bpq = PERQ ? w / kBlk : 1;   // MFMA row blocks per query head
 
-    bf16x8 kn[kSteps];
-    int t = wv;
-    if (t < nblk) load_keys(Kh, k0 + kBlk * t + l32, P - 1, hh, kn);
-    for (; t < nblk; t += 4) {
+    u32x4 stage[tile_pieces<NT>()];
+    tile_load<NT>(Kh, k0, P - 1, 1, tid, stage);
+    tile_store<NT>(kt, tid, stage);
+    __syncthreads();
+    for (int t = 0; t < ntile; ++t) {
+        if (t + 1 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 1), P - 1, 1, tid, stage);
         bf16x8 kc[kSteps];
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s) kc[s] = kn[s];
-        if (t + 4 < nblk) load_keys(Kh, k0 + kBlk * (t + 4) + l32, P - 1, hh, kn);
+        tile_read(kt + (t & 1) * kTileBytes, stream, l32, hh, kc);
 
-        f32x16 acc[NB];
+        f32x16 acc[NBW];
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < NBW; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 #pragma unroll
         for (int s = 0; s < kSteps; ++s)
 #pragma unroll
-            for (int b = 0; b < NB; ++b)   // rows = queries, columns = keys
+            for (int b = 0; b < NBW; ++b)   // rows = queries, columns = keys
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[b][s], kc[s], acc[b], 0, 0, 0);
 
-        float pb[NB];
+        float pb[NBW];
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
+        for (int b = 0; b < NBW; ++b) {
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s += fast_exp2(fmaf(acc[b][i], c, -bias[b][i]));
             pb[b] = s;
         }
-        const int key = k0 + kBlk * t + l32;
+        const int key = k0 + kTileKeys * t + kBlk * stream + l32;
         if constexpr (!PERQ) {
             float p = pb[0];
 #pragma unroll
-            for (int b = 1; b < NB; ++b) p += pb[b];
+            for (int b = 1; b < NBW; ++b) p += pb[b];
             p += __shfl_xor(p, 32, kWave);
-            if (hh == 0 && key < k1) votes[(long)h * P + key] = p;
+            if (hh == 0 && key < k1) votes[((long)h * SPLIT + grp) * P + key] = p;
         } else {
+            const int g0 = grp * NBW / bpq;   // first query head of this row group
 #pragma unroll
-            for (int g = 0; g < NB; ++g) {
+            for (int g = 0; g < NBW; ++g) {
                 float p = 0.f;
 #pragma unroll
-                for (int b = 0; b < NB; ++b) p += (b / bpq == g) ? pb[b] : 0.f;
+                for (int b = 0; b < NBW; ++b) p += (b / bpq == g) ? pb[b] : 0.f;
                 p += __shfl_xor(p, 32, kWave);
-                if (g < G && hh == 0 && key < k1) votes[((long)h * G + g) * P + key] = p;
+                if (g0 + g < G && g * bpq < NBW && hh == 0 && key < k1)
+                    votes[((long)h * G + g0 + g) * P + key] = p;
             }
         }
+        if (t + 1 < ntile) tile_store<NT>(kt + ((t + 1) & 1) * kTileBytes, tid, stage);
+        __syncthreads();
     }
+}
+
+// Kernels that use more than 64 KiB of dynamic LDS need a one-time opt-in per kernel.
+bool allow_big_lds(const void *kernel)
+{
+    static std::unordered_set<const void *> done;   // host-side, filled on first use of each kernel
+    if (done.count(kernel)) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 8192) !=
+        hipSuccess)
+        return false;
+    done.insert(kernel);
+    return true;
 }
 
 // Keys per workgroup: about 1024 workgroups in flight over all heads, but at least
@@ -275,6 +283,22 @@ MfmaScorePlan mfma_score_plan(int Hkv, int rows, int N)
     return pl;
 }
 
+// Row groups per key stream: 2 when the 32-row blocks split evenly (and, for
+// per-query-head votes, every query head stays inside one group), else 1.
+int mfma_score_split(int G, int w, int per_qhead_votes)
+{
+    const int nb = G * w / 32;
+    if (nb % 2) return 1;
+    if (per_qhead_votes && (w / 32) > nb / 2) return 1;
+    return 2;
+}
+
+// Rows of the votes array per KV head.
+int mfma_score_vote_rows(int G, int w, int per_qhead_votes)
+{
+    return per_qhead_votes ? G : mfma_score_split(G, w, 0);
+}
+
 hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
                                   float scale, float *part, hipStream_t st)
 {
@@ -283,28 +307,38 @@ hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int 
     const int ck = chunk_keys_for(Hkv, N);
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
-    dim3 grid(plan.chunks, Hkv), block(256);
+    dim3 grid(plan.chunks, Hkv);
+#define GKV_STATS(NB, SP)                                                                          \
+    do {                                                                                           \
+        if (!allow_big_lds((const void *)score_stats_kernel<NB, SP>)) return hipGetLastError();    \
+        hipLaunchKernelGGL((score_stats_kernel<NB, SP>), grid, dim3(256 * SP), 2 * kTileBytes, st, \
+                           K, Q, N, P, w, ck, c, part);                                            \
+    } while (0)
     switch (R / 32) {
-        case 1: hipLaunchKernelGGL(score_stats_kernel<1>, grid, block, 0, st, K, Q, N, P, w, ck, c, part); break;
-        case 2: hipLaunchKernelGGL(score_stats_kernel<2>, grid, block, 0, st, K, Q, N, P, w, ck, c, part); break;
-        case 3: hipLaunchKernelGGL(score_stats_kernel<3>, grid, block, 0, st, K, Q, N, P, w, ck, c, part); break;
-        case 4: hipLaunchKernelGGL(score_stats_kernel<4>, grid, block, 0, st, K, Q, N, P, w, ck, c, part); break;
+        case 1: GKV_STATS(1, 1); break;
+        case 2: GKV_STATS(2, 2); break;
+        case 3: GKV_STATS(3, 1); break;
+        case 4: GKV_STATS(4, 2); break;
         default: return hipErrorInvalidValue;
     }
+#undef GKV_STATS
     return hipGetLastError();
 }
 
-template <int NB>
+template <int NB, int SPLIT>
 static void launch_votes_nb(dim3 grid, const uint16_t *K, const uint16_t *Q, int N, int P, int w, int G,
                             int ck, float c, const float *part, int chunks, int per_q, float *votes,
                             hipStream_t st)
 {
-    if (per_q)
-        hipLaunchKernelGGL((score_votes_kernel<NB, true>), grid, dim3(256), 0, st, K, Q, N, P, w, G, ck,
-                           c, part, chunks, votes);
-    else
-        hipLaunchKernelGGL((score_votes_kernel<NB, false>), grid, dim3(256), 0, st, K, Q, N, P, w, G, ck,
-                           c, part, chunks, votes);
+    if (per_q) {
+        if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, true>)) return;
+        hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, true>), grid, dim3(256 * SPLIT),
+                           2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes);
+    } else {
+        if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, false>)) return;
+        hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, false>), grid, dim3(256 * SPLIT),
+                           2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes);
+    }
 }
 
 hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
@@ -317,13 +351,16 @@ hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int 
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
     dim3 grid(plan.chunks, Hkv);
+    const int split = mfma_score_split(G, w, per_qhead_votes);
+#define GKV_VOTES(NB, SP) launch_votes_nb<NB, SP>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st)
     switch (R / 32) {
-        case 1: launch_votes_nb<1>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st); break;
-        case 2: launch_votes_nb<2>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st); break;
-        case 3: launch_votes_nb<3>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st); break;
-        case 4: launch_votes_nb<4>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st); break;
+        case 1: GKV_VOTES(1, 1); break;
+        case 2: if (split == 2) GKV_VOTES(2, 2); else GKV_VOTES(2, 1); break;
+        case 3: GKV_VOTES(3, 1); break;
+        case 4: if (split == 2) GKV_VOTES(4, 2); else GKV_VOTES(4, 1); break;
         default: return hipErrorInvalidValue;
     }
+#undef GKV_VOTES
     return hipGetLastError();
 }
 

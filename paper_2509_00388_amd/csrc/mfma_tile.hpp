@@ -1,0 +1,79 @@
+// Key tiles for the bf16 MFMA kernels (d = 128): coalesced global loads, a padded
+// LDS tile, and reads in the operand layout of v_mfma_f32_32x32x16_bf16.
+//
+// A 32x32x16 MFMA wants from lane (l32 = lane % 32, hh = lane / 32) eight bf16
+// of row l32 per k-step.  Loading that straight from global memory makes every
+// load instruction touch 32 different rows, 32 bytes each, and the texture
+// addresser then caps the stream far below HBM speed.  Instead a workgroup
+// copies tiles of 128 consecutive key rows (32 KiB) with fully coalesced
+// 16-byte loads (one wave instruction = 1 KiB contiguous), parks them in LDS
+// with a row pitch of 272 bytes (the 16 bytes of padding spread the rows over
+// the banks), and each wave reads its 32 rows back with ds_read_b128.  Tiles are
+// double buffered: the global loads of tile t+1 are in flight while tile t is
+// multiplied, and one barrier per tile separates writers from readers.
+#pragma once
+#include "common.hpp"
+
+namespace gkv {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes, a plain vector register group
+
+constexpr int kD = 128;          // head dimension
+constexpr int kSteps = 8;        // k-steps of 16 per 128
+constexpr int kBlk = 32;         // rows per MFMA block
+constexpr int kTileKeys = 128;   // key rows per LDS tile: 4 streams of 32
+constexpr int kPitch = 272;      // bytes per key row in LDS (256 + 16 of padding)
+constexpr int kTileBytes = kTileKeys * kPitch;
+constexpr int kTileChunks = kTileKeys * 16;   // 16-byte pieces per tile
+
+__device__ __forceinline__ bf16x8 load8(const uint16_t *p)
+{
+    return *reinterpret_cast<const bf16x8 *>(p);
+}
+
+// Row of the 32x32 MFMA result held in accumulator register i of a lane in
+// half-wave hh (the column is lane % 32).
+__device__ __forceinline__ int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
+
+// A thread of an NT-thread workgroup moves kTileChunks / NT 16-byte pieces per tile.
+template <int NT> constexpr int tile_pieces() { return kTileChunks / NT; }
+
+// Global -> registers.  Tile row t is key (first + t) * stride, clamped to
+// last_key (rows past the range are loaded from a valid address and masked later).
+template <int NT, int PER>
+__device__ __forceinline__ void tile_load(const uint16_t *Kh, int first, int last_key, int stride,
+                                          int tid, u32x4 (&r)[PER])
+{
+    static_assert(PER == kTileChunks / NT, "pieces per thread");
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int g = tid + u * NT, row = g >> 4, c = g & 15;
+        const long key = (long)min(first + row, last_key) * stride;
+        r[u] = *reinterpret_cast<const u32x4 *>(Kh + key * kD + c * 8);
+    }
+}
+
+// Registers -> LDS tile.
+template <int NT, int PER>
+__device__ __forceinline__ void tile_store(unsigned char *buf, int tid, const u32x4 (&r)[PER])
+{
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int g = tid + u * NT, row = g >> 4, c = g & 15;
+        *reinterpret_cast<u32x4 *>(buf + row * kPitch + c * 16) = r[u];
+    }
+}
+
+// LDS tile -> MFMA operand registers of rows 32*stream .. 32*stream+31.
+__device__ __forceinline__ void tile_read(const unsigned char *buf, int stream, int l32, int hh,
+                                          bf16x8 (&kc)[kSteps])
+{
+    const unsigned char *p = buf + (kBlk * stream + l32) * kPitch + 16 * hh;
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s) kc[s] = *reinterpret_cast<const bf16x8 *>(p + 32 * s);
+}
+
+}  // namespace gkv
