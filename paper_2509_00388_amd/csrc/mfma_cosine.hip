@@ -21,6 +21,7 @@
 #include "kernels.hpp"
 #include "mfma_tile.hpp"
 
+#include <math.h>
 #include <unordered_set>
 
 namespace gkv {
@@ -30,7 +31,6 @@ namespace {
 constexpr int kSB = 2;            // source blocks of 32 per workgroup = row groups of waves
 constexpr int kRows = kSB * kBlk; // source rows per workgroup
 constexpr int kThreads = 256 * kSB;
-constexpr int kRing = 6144;       // candidates a workgroup can stage in LDS (48 KiB)
 
 // Sum of squares of the 64 elements a lane holds of its row (8 k-steps x 8),
 // two bf16 products per instruction, fp32 accumulation.
@@ -47,43 +47,53 @@ __device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
     return a;
 }
 
-enum { kDense = 0, kFilter = 1 };
-
 struct FilterArgs {
     const float *tau;      // [Hkv, S] lower bound of each source's m-th largest edge
     uint2 *cand;           // [Hkv, S, cap] (edge bits, key index)
     int32_t *cand_cnt;     // [Hkv, S]
     int32_t *overflow;     // [Hkv]
     int cap;
+    int flush_every;       // tiles between two flushes of the LDS staging area
 };
 
-// A workgroup has 4 key streams (wave & 3) and 2 source row groups (wave >> 2):
-// wave (stream, g) multiplies source rows 32g .. 32g+31 of its 64-row group with
-// the key blocks stream, stream+4, ...  Two waves share a SIMD and overlap each
-// other's MFMA and vector work.  The edge is e = (dot * 1/|k_j|) * 1/|k_i| in every
-// mode, so the sample pass and the filter pass produce the same bits.
-//
-// Column c of the output is key c * key_stride (key_stride = 1: every key).
-// kDense: E[h, slot, c] = e, -inf where the key is the source itself; if
-//   fa.cand_cnt is set, chunk 0 also clears cand_cnt / overflow of its head for
-//   the filter pass that follows.
-// kFilter: edges that reach the source's bound are appended to cand[h, slot, :]
-//   (the source's own column included: the exact select drops it).
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void cosine_kernel(const uint16_t *__restrict__ Kc, int N,
-                                                          int n_cols, int key_stride, int S,
-                                                          const int32_t *__restrict__ src,
-                                                          int chunk_cols, float *__restrict__ E,
-                                                          FilterArgs fa,
-                                                          const int32_t *__restrict__ gate)
+// Both kernels below: a workgroup has 4 key streams (wave & 3) and 2 source row
+// groups (wave >> 2): wave (stream, g) multiplies source rows 32g .. 32g+31 of its
+// 64-row group with rows 32*stream .. +31 of every key tile.  Two waves share a
+// SIMD and overlap each other's MFMA and vector work.  The edge is
+// e = (dot * 1/|k_j|) * 1/|k_i| in both, so the sample pass and the filter pass
+// produce the same bits.
+
+// This wave's 32 source rows -> MFMA operand registers (slots beyond S repeat the
+// last source); 1/|k_i| and the source index of the 64 rows of the group go to LDS.
+__device__ __forceinline__ void load_sources(const uint16_t *Kh, const int32_t *src_h, int S,
+                                             int s_base, int grp, int stream, int l32, int hh,
+                                             bf16x8 (&q)[kSteps], float *inv_s, int32_t *idx_s)
+{
+    const int slot = min(s_base + kBlk * grp + l32, S - 1);
+    const int32_t i = src_h[slot];
+    const uint16_t *p = Kh + (long)i * kD + 8 * hh;
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s) q[s] = load8(p + 16 * s);
+    float sq = half_row_sumsq(q);
+    sq += __shfl_xor(sq, 32, kWave);
+    if (stream == 0 && hh == 0) {
+        inv_s[kBlk * grp + l32] = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
+        idx_s[kBlk * grp + l32] = i;
+    }
+}
+
+// Dense block: E[h, slot, c] = e for column c = key c * key_stride (key_stride = 1:
+// every key), -inf where the key is the source itself.  If fa.cand_cnt is set, chunk 0
+// also clears cand_cnt / overflow of its head for the filter pass that follows.
+__global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
+    const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride, int S,
+    const int32_t *__restrict__ src, int chunk_cols, float *__restrict__ E, FilterArgs fa,
+    const int32_t *__restrict__ gate)
 {
     __shared__ float inv_s[kRows];
     __shared__ int32_t idx_s[kRows];
-    __shared__ float tau_s[kRows];
-    extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the candidate ring
+    extern __shared__ __align__(16) unsigned char smem[];   // two key tiles
     unsigned char *kt = smem;
-    uint2 *ring = reinterpret_cast<uint2 *>(smem + 2 * kTileBytes);
-    __shared__ int32_t ring_n, row_cnt[kRows], row_base[kRows], row_pos[kRows];
 
     const int h = blockIdx.y, chunk = blockIdx.x, s_base = blockIdx.z * kRows;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
@@ -93,61 +103,27 @@ __global__ __launch_bounds__(kThreads) void cosine_kernel(const uint16_t *__rest
     const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
     if (c0 >= n_cols) return;
 
-    if constexpr (MODE == kDense) {
-        if (fa.cand_cnt && chunk == 0) {
-            if (tid < kRows && s_base + tid < S) fa.cand_cnt[(long)h * S + s_base + tid] = 0;
-            if (tid == 0 && blockIdx.z == 0) fa.overflow[h] = 0;
-        }
+    if (fa.cand_cnt && chunk == 0) {
+        if (tid < kRows && s_base + tid < S) fa.cand_cnt[(long)h * S + s_base + tid] = 0;
+        if (tid == 0 && blockIdx.z == 0) fa.overflow[h] = 0;
     }
 
-    // this wave's 32 source rows -> registers (slots beyond S repeat the last source)
     bf16x8 q[kSteps];
-    {
-        const int slot = min(s_base + kBlk * grp + l32, S - 1);
-        const int32_t i = src[(long)h * S + slot];
-        const uint16_t *p = Kh + (long)i * kD + 8 * hh;
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s) q[s] = load8(p + 16 * s);
-        float sq = half_row_sumsq(q);
-        sq += __shfl_xor(sq, 32, kWave);
-        if (stream == 0 && hh == 0) {
-            const float inv = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
-            inv_s[kBlk * grp + l32] = inv;
-            idx_s[kBlk * grp + l32] = i;
-            if constexpr (MODE == kFilter) {
-                // The filter compares dot/|k_j| with bound/(1/|k_i|), a hair lowered so that
-                // rounding can never lose an edge; a zero source has e = 0 everywhere.
-                const float t = fa.tau[(long)h * S + slot];
-                const float lo = t - 4e-6f - 1e-5f * fabsf(t);
-                tau_s[kBlk * grp + l32] = inv > 0.f ? lo / inv : (lo <= 0.f ? -INFINITY : INFINITY);
-            }
-        }
-    }
-    if constexpr (MODE == kFilter) {
-        if (tid == 0) ring_n = 0;
-        if (tid < kRows) { row_cnt[tid] = 0; row_pos[tid] = 0; }
-    }
+    load_sources(Kh, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
     __syncthreads();
-    float inv_src[16], thr[MODE == kFilter ? 16 : 1];
-    int32_t idx_src[MODE == kDense ? 16 : 1];
+    float inv_src[16];
+    int32_t idx_src[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int r = kBlk * grp + acc_row(i, hh);
         inv_src[i] = inv_s[r];
-        if constexpr (MODE == kDense) idx_src[i] = idx_s[r];
-        if constexpr (MODE == kFilter) thr[i] = (s_base + r < S) ? tau_s[r] : INFINITY;   // rows past S never pass
+        idx_src[i] = idx_s[r];
     }
 
     const int ntile = (c1 - c0 + kTileKeys - 1) / kTileKeys;
-    u32x4 stage[tile_pieces<kThreads>()];
-    tile_load<kThreads>(Kh, c0, n_cols - 1, key_stride, tid, stage);
-    tile_store<kThreads>(kt, tid, stage);
-    __syncthreads();
-    for (int t = 0; t < ntile; ++t) {
-        if (t + 1 < ntile) tile_load<kThreads>(Kh, c0 + kTileKeys * (t + 1), n_cols - 1, key_stride, tid, stage);
+    auto multiply_tile = [&](const unsigned char *buf, int t) {
         bf16x8 kc[kSteps];
-        tile_read(kt + (t & 1) * kTileBytes, stream, l32, hh, kc);
-
+        tile_read(buf, stream, l32, hh, kc);
         f32x16 acc;
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
@@ -160,66 +136,175 @@ __global__ __launch_bounds__(kThreads) void cosine_kernel(const uint16_t *__rest
         const float inv_k = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
         const int col = c0 + kTileKeys * t + kBlk * stream + l32;
         const int key = col * key_stride;
-        if constexpr (MODE == kDense) {
-            if (col < c1) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int slot = s_base + kBlk * grp + acc_row(i, hh);
-                    if (slot < S) {
-                        float e = (acc[i] * inv_k) * inv_src[i];
-                        if (key == idx_src[i]) e = -INFINITY;
-                        E[((long)h * S + slot) * n_cols + col] = e;
-                    }
-                }
-            }
-        } else {
-            float tv[16];
-            int cnt = 0;
+        if (col < c1) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                tv[i] = acc[i] * inv_k;
-                cnt += (tv[i] >= thr[i]) ? 1 : 0;
-            }
-            if (col >= c1) cnt = 0;
-            if (cnt) {
-                int at = atomicAdd(&ring_n, cnt);
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (tv[i] >= thr[i]) {
-                        if (at < kRing)
-                            ring[at] = make_uint2(__float_as_uint(tv[i] * inv_src[i]),
-                                                  ((uint32_t)(kBlk * grp + acc_row(i, hh)) << 24) | (uint32_t)key);
-                        ++at;
-                    }
+                const int slot = s_base + kBlk * grp + acc_row(i, hh);
+                if (slot < S) {
+                    float e = (acc[i] * inv_k) * inv_src[i];
+                    if (key == idx_src[i]) e = -INFINITY;
+                    E[((long)h * S + slot) * n_cols + col] = e;
+                }
             }
         }
-        if (t + 1 < ntile) tile_store<kThreads>(kt + ((t + 1) & 1) * kTileBytes, tid, stage);
-        __syncthreads();
-    }
+    };
+    GKV_TILE_PIPELINE(kThreads, Kh, c0, n_cols - 1, key_stride, ntile, multiply_tile, (void)0);
+}
 
-    if constexpr (MODE == kFilter) {
-        // Flush: count per source row, reserve room in the global lists, scatter.
-        const int n_stage = ring_n;
-        const bool lost = n_stage > kRing;
-        const int n_ring = lost ? kRing : n_stage;
-        for (int r = tid; r < n_ring; r += kThreads) atomicAdd(&row_cnt[ring[r].y >> 24], 1);
+// Filter pass over all keys.  A lane holds, per key block, the 16 dots of its key
+// with 16 of the wave's sources.  It tests them all at once against the sources'
+// bounds (dot >= bound_i * |k_j|, bounds a hair lowered so that rounding can never
+// lose an edge) with 16 fused multiply-adds and a max tree; the few lanes that
+// have a hit park their 16 dots, the key's squared norm and the key index in an
+// LDS staging area.  Every `flush_every` tiles, and at the end, the workgroup turns
+// the staged rows into exact edges (the dense kernel's formula, bit for bit),
+// keeps those that reach the bound and appends them to the per-source global
+// lists (one reservation per source and flush).  The source's own column may be
+// among them: the exact select drops it.  The flush schedule is fixed by the
+// host from the expected hit rate; if the staging area or a list overflows
+// anyway, the head's overflow flag is raised and the head is redone densely.
+constexpr int kStageCap = 1024;    // staged rows per workgroup
+constexpr int kStagePitch = 80;    // bytes per staged row: 16 dots, |k|^2, key + lane bits, hit bits
+
+__global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
+    const uint16_t *__restrict__ Kc, int N, int n_cols, int S, const int32_t *__restrict__ src,
+    int chunk_cols, FilterArgs fa)
+{
+    __shared__ float inv_s[kRows], lo_s[kRows], det_s[kRows];
+    __shared__ int32_t idx_s[kRows];
+    __shared__ int32_t stage_n, row_cnt[kRows], row_base[kRows], row_pos[kRows];
+    extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the staging area
+    unsigned char *kt = smem;
+    unsigned char *stage_mem = smem + 2 * kTileBytes;
+
+    const int h = blockIdx.y, chunk = blockIdx.x, s_base = blockIdx.z * kRows;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
+    const int stream = wv & 3, grp = wv >> 2;
+    const uint16_t *Kh = Kc + (long)h * N * kD;
+    const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
+    if (c0 >= n_cols) return;
+
+    bf16x8 q[kSteps];
+    load_sources(Kh, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
+    if (tid == 0) stage_n = 0;
+    if (tid < kRows) { row_cnt[tid] = 0; row_pos[tid] = 0; }
+    __syncthreads();
+    if (tid < kRows) {
+        // lo: what an exact edge must reach to be listed; det: the still lower bound of the
+        // in-loop test, expressed for dot / |k_j| (i.e. divided by 1/|k_i|).  Rows past S
+        // and impossible bounds never hit; a zero source (all edges 0) hits everywhere.
+        const int slot = s_base + tid;
+        const float t = fa.tau[(long)h * S + min(slot, S - 1)];
+        const float slack = 4e-6f + 1e-5f * fabsf(t);
+        const float inv = inv_s[tid];
+        const float lo = t - slack, lo2 = t - 2.f * slack;
+        lo_s[tid] = slot < S ? lo : INFINITY;
+        det_s[tid] = slot >= S ? INFINITY : (inv > 0.f ? lo2 / inv : (lo2 <= 0.f ? -INFINITY : INFINITY));
+    }
+    __syncthreads();
+    float det[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) det[i] = det_s[kBlk * grp + acc_row(i, hh)];
+
+    // Staged rows -> exact edges -> global candidate lists.  Called by all threads; one
+    // thread per staged row walks the row's hit bits.
+    auto flush = [&]() {
+        const int n_stage = stage_n;
+        const int n = n_stage < kStageCap ? n_stage : kStageCap;
+        for (int r = tid; r < n; r += kThreads) {
+            unsigned char *row_mem = stage_mem + r * kStagePitch;
+            float *vals = reinterpret_cast<float *>(row_mem);
+            const float sq = vals[16];
+            const float inv_k = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);   // the dense kernel's formula
+            const uint32_t meta = *reinterpret_cast<const uint32_t *>(row_mem + 68);
+            const int rgrp = kBlk * ((meta >> 25) & 1), rhh = (meta >> 24) & 1;
+            uint32_t hits = *reinterpret_cast<const uint32_t *>(row_mem + 72), keep = 0;
+            while (hits) {
+                const int i = __ffs(hits) - 1;
+                hits &= hits - 1;
+                const int row = rgrp + acc_row(i, rhh);
+                const float e = (vals[i] * inv_k) * inv_s[row];
+                if (e >= lo_s[row]) {
+                    vals[i] = e;
+                    keep |= 1u << i;
+                    atomicAdd(&row_cnt[row], 1);
+                }
+            }
+            *reinterpret_cast<uint32_t *>(row_mem + 72) = keep;
+        }
         __syncthreads();
         if (tid < kRows) {
             const int c = row_cnt[tid];
             int base = 0;
             if (c > 0) base = atomicAdd(&fa.cand_cnt[(long)h * S + s_base + tid], c);
             row_base[tid] = base;
-            if (base + c > fa.cap || lost) fa.overflow[h] = 1;
+            if (base + c > fa.cap || n_stage > kStageCap) fa.overflow[h] = 1;
         }
         __syncthreads();
-        for (int r = tid; r < n_ring; r += kThreads) {
-            const uint2 v = ring[r];
-            const int row = v.y >> 24;
-            const int at = row_base[row] + atomicAdd(&row_pos[row], 1);
-            if (at < fa.cap)
-                fa.cand[((long)h * S + s_base + row) * fa.cap + at] = make_uint2(v.x, v.y & 0xffffffu);
+        for (int r = tid; r < n; r += kThreads) {
+            const unsigned char *row_mem = stage_mem + r * kStagePitch;
+            const float *vals = reinterpret_cast<const float *>(row_mem);
+            const uint32_t meta = *reinterpret_cast<const uint32_t *>(row_mem + 68);
+            const int rgrp = kBlk * ((meta >> 25) & 1), rhh = (meta >> 24) & 1;
+            uint32_t keep = *reinterpret_cast<const uint32_t *>(row_mem + 72);
+            while (keep) {
+                const int i = __ffs(keep) - 1;
+                keep &= keep - 1;
+                const int row = rgrp + acc_row(i, rhh);
+                const int at = row_base[row] + atomicAdd(&row_pos[row], 1);
+                if (at < fa.cap)
+                    fa.cand[((long)h * S + s_base + row) * fa.cap + at] =
+                        make_uint2(__float_as_uint(vals[i]), meta & 0xffffffu);
+            }
         }
-    }
+        __syncthreads();
+        if (tid == 0) stage_n = 0;
+        if (tid < kRows) { row_cnt[tid] = 0; row_pos[tid] = 0; }
+        __syncthreads();
+    };
+
+    const int ntile = (c1 - c0 + kTileKeys - 1) / kTileKeys;
+    auto multiply_tile = [&](const unsigned char *buf, int t) {
+        bf16x8 kc[kSteps];
+        tile_read(buf, stream, l32, hh, kc);
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s)   // rows = sources, columns = keys
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[s], kc[s], acc, 0, 0, 0);
+
+        float sq = half_row_sumsq(kc);
+        sq += __shfl_xor(sq, 32, kWave);
+        const float norm_k = __builtin_amdgcn_sqrtf(sq);
+        float d[16];   // dot - bound * |k_j|: >= 0 means the edge may reach the bound
+#pragma unroll
+        for (int i = 0; i < 16; ++i) d[i] = fmaf(-det[i], norm_k, acc[i]);
+        float best = d[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) best = fmaxf(best, d[i]);
+        const int key = c0 + kTileKeys * t + kBlk * stream + l32;
+        if (best >= 0.f && key < c1) {
+            uint32_t hits = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) hits |= (d[i] >= 0.f ? 1u : 0u) << i;
+            const int at = atomicAdd(&stage_n, 1);
+            if (at < kStageCap) {
+                unsigned char *row_mem = stage_mem + at * kStagePitch;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    *reinterpret_cast<float4 *>(row_mem + 16 * v) =
+                        make_float4(acc[4 * v], acc[4 * v + 1], acc[4 * v + 2], acc[4 * v + 3]);
+                *reinterpret_cast<float4 *>(row_mem + 64) =
+                    make_float4(sq, __uint_as_float((uint32_t)key | ((uint32_t)hh << 24) | ((uint32_t)grp << 25)),
+                                __uint_as_float(hits), 0.f);
+            }
+        }
+    };
+    const int fe = fa.flush_every;
+    GKV_TILE_PIPELINE(kThreads, Kh, c0, n_cols - 1, 1, ntile, multiply_tile,
+                      if ((tile_done % fe) == 0) flush());
+    flush();
 }
 
 __device__ __forceinline__ uint32_t ord_key_u(uint32_t bits)
@@ -413,8 +498,8 @@ hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, cons
     const int ck = chunk_cols_for(Hkv, sgroups, P);
     const int chunks = (P + ck - 1) / ck;
     FilterArgs fa{};
-    if (!allow_big_lds((const void *)cosine_kernel<kDense>)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_kernel<kDense>, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
+    if (!allow_big_lds((const void *)cosine_dense_kernel)) return hipGetLastError();
+    hipLaunchKernelGGL(cosine_dense_kernel, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
                        st, (const uint16_t *)Kc, N, P, 1, S, src, ck, E, fa, gate);
     return hipGetLastError();
 }
@@ -430,8 +515,8 @@ hipError_t launch_mfma_cosine_sample(const void *Kc, int Hkv, int N, int P, int 
     FilterArgs fa{};
     fa.cand_cnt = cand_cnt;
     fa.overflow = overflow;
-    if (!allow_big_lds((const void *)cosine_kernel<kDense>)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_kernel<kDense>, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
+    if (!allow_big_lds((const void *)cosine_dense_kernel)) return hipGetLastError();
+    hipLaunchKernelGGL(cosine_dense_kernel, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
                        st, (const uint16_t *)Kc, N, ps, stride, S, src, ck, E_sample, fa,
                        (const int32_t *)nullptr);
     return hipGetLastError();
@@ -442,16 +527,21 @@ hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int 
                                      int32_t *cand_cnt, int32_t *overflow, hipStream_t st)
 {
     const int sgroups = (S + kRows - 1) / kRows;
-    // expected staged candidates per workgroup = rows * m * stride / chunks: keep it under half the ring
     const int stride = P / mfma_sample_cols(P);
-    const int min_chunks = (int)(((long)kRows * m * stride + kRing / 2 - 1) / (kRing / 2));
-    const int ck = chunk_cols_for(Hkv, sgroups, P, min_chunks);
+    const int ck = chunk_cols_for(Hkv, sgroups, P);
     const int chunks = (P + ck - 1) / ck;
-    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, mfma_cand_cap(P, m)};
-    if (!allow_big_lds((const void *)cosine_kernel<kFilter>)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_kernel<kFilter>, dim3(chunks, Hkv, sgroups), dim3(kThreads),
-                       2 * kTileBytes + kRing * sizeof(uint2), st, (const uint16_t *)Kc, N, P, 1, S, src, ck,
-                       (float *)nullptr, fa, (const int32_t *)nullptr);
+    // Expected staged rows per tile: 512 lanes x P(a lane's 16 edges hold a hit), with a
+    // per-edge hit rate of about m * stride / P (each source keeps ~m * stride candidates).
+    const double rate = (double)m * stride / (double)P;
+    const double per_tile = 512.0 * (1.0 - pow(1.0 - (rate < 1.0 ? rate : 1.0), 16.0));
+    int flush_every = (int)((kStageCap / 2) / (per_tile > 1.0 ? per_tile : 1.0));
+    if (flush_every < 1) flush_every = 1;
+    if (flush_every > 64) flush_every = 64;
+    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, mfma_cand_cap(P, m), flush_every};
+    if (!allow_big_lds((const void *)cosine_filter_kernel)) return hipGetLastError();
+    hipLaunchKernelGGL(cosine_filter_kernel, dim3(chunks, Hkv, sgroups), dim3(kThreads),
+                       2 * kTileBytes + kStageCap * kStagePitch, st, (const uint16_t *)Kc, N, P, S, src,
+                       ck, fa);
     return hipGetLastError();
 }
 

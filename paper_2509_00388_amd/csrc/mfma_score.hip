@@ -82,14 +82,9 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
     const int k0 = chunk * chunk_keys, k1 = min(N, k0 + chunk_keys);
     const int ntile = (k1 - k0 + kTileKeys - 1) / kTileKeys;
 
-    u32x4 stage[tile_pieces<NT>()];
-    tile_load<NT>(Kh, k0, N - 1, 1, tid, stage);
-    tile_store<NT>(kt, tid, stage);
-    __syncthreads();
-    for (int t = 0; t < ntile; ++t) {
-        if (t + 1 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 1), N - 1, 1, tid, stage);
+    auto multiply_tile = [&](const unsigned char *buf, int t) {
         bf16x8 kc[kSteps];
-        tile_read(kt + (t & 1) * kTileBytes, stream, l32, hh, kc);
+        tile_read(buf, stream, l32, hh, kc);
 
         f32x16 acc[NBW];
 #pragma unroll
@@ -134,7 +129,24 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
                 }
             }
         }
-        if (t + 1 < ntile) tile_store<NT>(kt + ((t + 1) & 1) * kTileBytes, tid, stage);
+    };
+    // Tile t is multiplied out of LDS while tiles t+1 and t+2 are on their way from HBM
+    // in two sets of staging registers: two tiles (64 KiB) in flight per workgroup.
+    u32x4 stage[tile_pieces<NT>()], stage_b[tile_pieces<NT>()];
+    tile_load<NT>(Kh, k0, N - 1, 1, tid, stage);
+    tile_store<NT>(kt, tid, stage);
+    if (1 < ntile) tile_load<NT>(Kh, k0 + kTileKeys, N - 1, 1, tid, stage);
+    if (2 < ntile) tile_load<NT>(Kh, k0 + 2 * kTileKeys, N - 1, 1, tid, stage_b);
+    __syncthreads();
+    for (int t = 0; t < ntile; t += 2) {
+        multiply_tile(kt, t);
+        if (t + 1 < ntile) tile_store<NT>(kt + kTileBytes, tid, stage);
+        if (t + 3 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 3), N - 1, 1, tid, stage);
+        __syncthreads();
+        if (t + 1 >= ntile) break;
+        multiply_tile(kt + kTileBytes, t + 1);
+        if (t + 2 < ntile) tile_store<NT>(kt, tid, stage_b);
+        if (t + 4 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 4), N - 1, 1, tid, stage_b);
         __syncthreads();
     }
 
@@ -198,14 +210,9 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     const int ntile = (k1 - k0 + kTileKeys - 1) / kTileKeys;
     const int bpq = PERQ ? w / kBlk : 1;   // MFMA row blocks per query head
 
-    u32x4 stage[tile_pieces<NT>()];
-    tile_load<NT>(Kh, k0, P - 1, 1, tid, stage);
-    tile_store<NT>(kt, tid, stage);
-    __syncthreads();
-    for (int t = 0; t < ntile; ++t) {
-        if (t + 1 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 1), P - 1, 1, tid, stage);
+    auto multiply_tile = [&](const unsigned char *buf, int t) {
         bf16x8 kc[kSteps];
-        tile_read(kt + (t & 1) * kTileBytes, stream, l32, hh, kc);
+        tile_read(buf, stream, l32, hh, kc);
 
         f32x16 acc[NBW];
 #pragma unroll
@@ -245,7 +252,24 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
                     votes[((long)h * G + g0 + g) * P + key] = p;
             }
         }
-        if (t + 1 < ntile) tile_store<NT>(kt + ((t + 1) & 1) * kTileBytes, tid, stage);
+    };
+    // Tile t is multiplied out of LDS while tiles t+1 and t+2 are on their way from HBM
+    // in two sets of staging registers: two tiles (64 KiB) in flight per workgroup.
+    u32x4 stage[tile_pieces<NT>()], stage_b[tile_pieces<NT>()];
+    tile_load<NT>(Kh, k0, P - 1, 1, tid, stage);
+    tile_store<NT>(kt, tid, stage);
+    if (1 < ntile) tile_load<NT>(Kh, k0 + kTileKeys, P - 1, 1, tid, stage);
+    if (2 < ntile) tile_load<NT>(Kh, k0 + 2 * kTileKeys, P - 1, 1, tid, stage_b);
+    __syncthreads();
+    for (int t = 0; t < ntile; t += 2) {
+        multiply_tile(kt, t);
+        if (t + 1 < ntile) tile_store<NT>(kt + kTileBytes, tid, stage);
+        if (t + 3 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 3), P - 1, 1, tid, stage);
+        __syncthreads();
+        if (t + 1 >= ntile) break;
+        multiply_tile(kt + kTileBytes, t + 1);
+        if (t + 2 < ntile) tile_store<NT>(kt, tid, stage_b);
+        if (t + 4 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 4), P - 1, 1, tid, stage_b);
         __syncthreads();
     }
 }

@@ -76,4 +76,35 @@ __device__ __forceinline__ void tile_read(const unsigned char *buf, int stream, 
     for (int s = 0; s < kSteps; ++s) kc[s] = *reinterpret_cast<const bf16x8 *>(p + 32 * s);
 }
 
+// The tile loop shared by the streaming kernels.  Tile t is multiplied out of LDS
+// while tiles t+1 and t+2 are on their way from HBM in two sets of staging
+// registers: two tiles (64 KiB) in flight per workgroup.  One barrier per tile
+// separates the writers of an LDS buffer from its readers.  `body(buf, t)` multiplies
+// tile t; AFTER_TILE runs right after each tile's barrier with `tile_done` = number
+// of tiles finished (it may contain barriers: every thread reaches it).
+#define GKV_TILE_PIPELINE(NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE)                 \
+    do {                                                                                               \
+        u32x4 stage_a[tile_pieces<NT_>()], stage_b[tile_pieces<NT_>()];                                \
+        tile_load<NT_>(Kh_, first_, clamp_, stride_, tid, stage_a);                                    \
+        tile_store<NT_>(kt, tid, stage_a);                                                             \
+        if (1 < ntile_) tile_load<NT_>(Kh_, first_ + kTileKeys, clamp_, stride_, tid, stage_a);        \
+        if (2 < ntile_) tile_load<NT_>(Kh_, first_ + 2 * kTileKeys, clamp_, stride_, tid, stage_b);    \
+        __syncthreads();                                                                               \
+        for (int t_ = 0; t_ < ntile_; t_ += 2) {                                                       \
+            body(kt, t_);                                                                              \
+            if (t_ + 1 < ntile_) tile_store<NT_>(kt + kTileBytes, tid, stage_a);                       \
+            if (t_ + 3 < ntile_)                                                                       \
+                tile_load<NT_>(Kh_, first_ + kTileKeys * (t_ + 3), clamp_, stride_, tid, stage_a);     \
+            __syncthreads();                                                                           \
+            { const int tile_done = t_ + 1; (void)tile_done; AFTER_TILE; }                             \
+            if (t_ + 1 >= ntile_) break;                                                               \
+            body(kt + kTileBytes, t_ + 1);                                                             \
+            if (t_ + 2 < ntile_) tile_store<NT_>(kt, tid, stage_b);                                    \
+            if (t_ + 4 < ntile_)                                                                       \
+                tile_load<NT_>(Kh_, first_ + kTileKeys * (t_ + 4), clamp_, stride_, tid, stage_b);     \
+            __syncthreads();                                                                           \
+            { const int tile_done = t_ + 2; (void)tile_done; AFTER_TILE; }                             \
+        }                                                                                              \
+    } while (0)
+
 }  // namespace gkv
