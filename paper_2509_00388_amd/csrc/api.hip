@@ -245,8 +245,7 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                 GKV_LAUNCH(GRAPHKV_K_COSINE_SAMPLE,
                            launch_mfma_cosine_sample(Kc, D.H, D.N, D.P, D.S, src, Es, cnt, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_TOPK_BOUND,
-                           launch_topk_rows(Es, ps, ps, D.H * D.S, D.m, nullptr, 0, nullptr, 0, tau, 0, 0,
-                                            nullptr, 1, st));
+                           launch_topk_bound(Es, ps, ps, D.H * D.S, D.m, tau, st));
                 GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
                            launch_mfma_cosine_filter(Kc, D.H, D.N, D.P, D.S, D.m, src, tau, cand, cnt,
                                                      ovf, st));

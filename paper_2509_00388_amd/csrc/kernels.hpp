@@ -21,6 +21,11 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k,
                             float *tau_out, int append_from, int append_count,
                             const int32_t *gate, int rows_per_gate, hipStream_t st);
 
+// A lower bound of each row's k-th largest value (exact up to a sliver of the row's value
+// range): enough for the candidate filter, cheaper than the exact selection.
+hipError_t launch_topk_bound(const float *x, long ld, int n, int rows, int k, float *tau_out,
+                             hipStream_t st);
+
 // ---- scalar kernels for any dtype / shape (generic.hip) ----------------------
 // logits [Hq*w, N] (fp32, scaled), then per-row max and sum of exp.
 hipError_t launch_generic_logits(const void *Kc, const void *Qw, int dtype, int Hkv, int Hq, int d,

@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
                                                          float *__restrict__ nbr_e)
 {
     extern __shared__ uint32_t dyn[];
-    __shared__ uint32_t hist[2048];
+    __shared__ uint32_t hist[256];   // 8-bit digits: the lists are short
     __shared__ uint32_t s_bin, s_need, s_min[4], s_max[4];
     __shared__ int32_t n_win, n_eq;
     const int a = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -367,10 +367,10 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     int remaining = (kmax >= kmin && range) ? 32 - __clz(range) : 0;
     uint32_t prefix = 0, mask = 0, need = (uint32_t)m;
     while (remaining > 0) {
-        const int bits = remaining < 11 ? remaining : 11;
+        const int bits = remaining < 8 ? remaining : 8;
         const int shift = remaining - bits;
         const uint32_t dmask = (1u << bits) - 1u;
-        for (int b = tid; b < 2048; b += 256) hist[b] = 0;
+        hist[tid] = 0;
         __syncthreads();
         for (int r = tid; r < n; r += 256) {
             const uint32_t k = ek[r];
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
         __syncthreads();
         if (wv == 0) {   // bin where the count of larger-or-equal digits reaches `need`
             uint32_t tsum = 0;
-            for (int b = 0; b < 32; ++b) tsum += hist[32 * lane + b];
+            for (int b = 0; b < 4; ++b) tsum += hist[4 * lane + b];
             uint32_t incl = tsum;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
@@ -392,13 +392,13 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
             const uint32_t excl = incl - tsum;
             if (excl < need && need <= incl) {
                 uint32_t cum = excl;
-                int b = 31;
+                int b = 3;
                 for (; b > 0; --b) {
-                    const uint32_t cb = hist[32 * lane + b];
+                    const uint32_t cb = hist[4 * lane + b];
                     if (cum + cb >= need) break;
                     cum += cb;
                 }
-                s_bin = 32 * lane + b;
+                s_bin = 4 * lane + b;
                 s_need = need - cum;
             }
         }

@@ -21,7 +21,7 @@ namespace gkv {
 
 namespace {
 
-constexpr int kBins = 2048;
+constexpr int kBins = 2048;   // bins of the streaming variant (11-bit digits)
 
 __device__ __forceinline__ float key_to_float(uint32_t key)   // inverse of ord_key
 {
@@ -46,13 +46,15 @@ __device__ __forceinline__ void hist_add(uint32_t *hist, bool in, uint32_t dig, 
 }
 
 // Wave 0: find the bin where the count of larger-or-equal digits reaches `need`.
-// Lane L owns bins 32L .. 32L+31.  Writes {bin, need - (entries in higher bins)}.
+// Lane L owns bins BPL*L .. BPL*L+BPL-1 (64*BPL bins in all).  Writes
+// {bin, need - (entries in higher bins)}.
+template <int BPL>
 __device__ __forceinline__ void find_bin(const uint32_t *hist, uint32_t need, int lane,
                                          uint32_t *s_bin, uint32_t *s_need)
 {
     uint32_t t = 0;
 #pragma unroll
-    for (int b = 0; b < 32; ++b) t += hist[32 * lane + b];
+    for (int b = 0; b < BPL; ++b) t += hist[BPL * lane + b];
     uint32_t incl = t;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -62,13 +64,13 @@ __device__ __forceinline__ void find_bin(const uint32_t *hist, uint32_t need, in
     const uint32_t excl = incl - t;   // entries in strictly higher lanes
     if (excl < need && need <= incl) {
         uint32_t cum = excl;
-        int b = 31;
+        int b = BPL - 1;
         for (; b > 0; --b) {
-            const uint32_t c = hist[32 * lane + b];
+            const uint32_t c = hist[BPL * lane + b];
             if (cum + c >= need) break;
             cum += c;
         }
-        *s_bin = 32 * lane + b;
+        *s_bin = BPL * lane + b;
         *s_need = need - cum;
     }
 }
@@ -80,16 +82,21 @@ __device__ __forceinline__ void find_bin(const uint32_t *hist, uint32_t need, in
 // = 128 KiB) for all sweeps.  Thread t handles entries i*BLOCK + t; index order is
 // therefore (i, wave, lane), and the emit sweep counts per (i, wave) cell with
 // ballots and scans the cells once.
-template <int BLOCK, bool PLAN>
+// DIG = bits per radix sweep (11 for long rows, 8 for short ones: fewer bins to clear
+// and scan).  max_sweeps > 0 stops after that many sweeps: tau_out then receives a
+// value at most (row range) / 2^(DIG * max_sweeps) below the k-th largest -- a valid,
+// slightly loose lower bound (idx_out must be nullptr in that case).
+template <int BLOCK, bool PLAN, int DIG>
 __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
     float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
     int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
-    typename std::conditional<PLAN, LayerPlan, int>::type plan)
+    typename std::conditional<PLAN, LayerPlan, int>::type plan, int max_sweeps)
 {
     constexpr int NW = BLOCK / kWave;
+    constexpr int NBINS = 1 << DIG;
     extern __shared__ uint32_t dyn[];
-    __shared__ uint32_t hist[kBins];
+    __shared__ uint32_t hist[NBINS];
     __shared__ uint32_t s_bin, s_need;
 
     if (gate && gate[blockIdx.x / rows_per_gate] == 0) return;
@@ -137,11 +144,12 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     const uint32_t range = kmax - kmin;
     int remaining = range ? 32 - __clz(range) : 0;
     uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
-    while (remaining > 0) {
-        const int bits = remaining < 11 ? remaining : 11;
+    int sweeps = 0;
+    while (remaining > 0 && (max_sweeps <= 0 || sweeps < max_sweeps)) {
+        const int bits = remaining < DIG ? remaining : DIG;
         const int shift = remaining - bits;
         const uint32_t dmask = (1u << bits) - 1u;
-        for (int b = tid; b < kBins; b += BLOCK) hist[b] = 0;
+        for (int b = tid; b < NBINS; b += BLOCK) hist[b] = 0;
         __syncthreads();
         for (int i = 0; i < items; ++i) {
             const int j = i * BLOCK + tid;
@@ -149,13 +157,15 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
             if (j < n && (rel & mask) == prefix) atomicAdd(&hist[(rel >> shift) & dmask], 1u);
         }
         __syncthreads();
-        if (wv == 0) find_bin(hist, need, lane, &s_bin, &s_need);
+        if (wv == 0) find_bin<NBINS / 64>(hist, need, lane, &s_bin, &s_need);
         __syncthreads();
         prefix |= s_bin << shift;
         mask |= dmask << shift;
         need = s_need;
         remaining = shift;
+        ++sweeps;
     }
+    // If sweeps were cut short the unresolved low bits are 0: the lower edge of the bin.
     const uint32_t tau = kmin + prefix;   // key of the k-th largest entry; take `need` entries equal to it
     if (tau_out && tid == 0) tau_out[blockIdx.x] = key_to_float(tau);
     if (!out) return;
@@ -257,7 +267,7 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
             }
         }
         __syncthreads();
-        if (wv == 0) find_bin(hist, need, lane, &s_bin, &s_need);
+        if (wv == 0) find_bin<32>(hist, need, lane, &s_bin, &s_need);
         __syncthreads();
         prefix |= s_bin << shift;
         mask |= dmask << shift;
@@ -322,24 +332,24 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
     }
 }
 
-template <int BLOCK, bool PLAN, typename PlanArg>
+template <int BLOCK, bool PLAN, int DIG, typename PlanArg>
 static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
                              long idx_ld, float *val_out, long val_ld, float *tau_out,
                              int append_from, int append_count, const int32_t *gate,
-                             int rows_per_gate, PlanArg plan, hipStream_t st)
+                             int rows_per_gate, PlanArg plan, int max_sweeps, hipStream_t st)
 {
     const int items = (n + BLOCK - 1) / BLOCK;
     const size_t lds = ((size_t)items * BLOCK + 2 * (size_t)items * (BLOCK / kWave)) * 4;
     static bool opt_in = false;   // more than 64 KiB of dynamic LDS needs a one-time opt-in
     if (lds > 65536 && !opt_in) {
-        if (hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK, PLAN>,
+        if (hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK, PLAN, DIG>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess)
             return hipGetLastError();
         opt_in = true;
     }
-    hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN>), dim3(rows), dim3(BLOCK), lds, st, x, ld, n,
-                       k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
-                       rows_per_gate, plan);
+    hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN, DIG>), dim3(rows), dim3(BLOCK), lds, st, x, ld,
+                       n, k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
+                       rows_per_gate, plan, max_sweeps);
     return hipGetLastError();
 }
 
@@ -347,15 +357,17 @@ template <bool PLAN, typename PlanArg>
 static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
                              long idx_ld, float *val_out, long val_ld, float *tau_out,
                              int append_from, int append_count, const int32_t *gate,
-                             int rows_per_gate, PlanArg plan, hipStream_t st)
+                             int rows_per_gate, PlanArg plan, int max_sweeps, hipStream_t st)
 {
     if (rows <= 0) return hipSuccess;
     if (n <= 4096)
-        return launch_lds<256, PLAN>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                                     append_from, append_count, gate, rows_per_gate, plan, st);
+        return launch_lds<256, PLAN, 8>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
+                                        append_from, append_count, gate, rows_per_gate, plan,
+                                        max_sweeps, st);
     if (n <= 32768)
-        return launch_lds<1024, PLAN>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                                      append_from, append_count, gate, rows_per_gate, plan, st);
+        return launch_lds<1024, PLAN, 11>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
+                                          append_from, append_count, gate, rows_per_gate, plan,
+                                          max_sweeps, st);
     hipLaunchKernelGGL((topk_rows_stream_kernel<1024, PLAN>), dim3(rows), dim3(1024), 0, st, x, ld, n,
                        k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
                        rows_per_gate, plan);
@@ -368,14 +380,23 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k, int
                             int rows_per_gate, hipStream_t st)
 {
     return launch_any<false, int>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                                  append_from, append_count, gate, rows_per_gate, 0, st);
+                                  append_from, append_count, gate, rows_per_gate, 0, 0, st);
+}
+
+hipError_t launch_topk_bound(const float *x, long ld, int n, int rows, int k, float *tau_out,
+                             hipStream_t st)
+{
+    // 2 sweeps of 8 bits on rows of at most 4096 entries: the bound is within 1/65536 of the
+    // row's value range below the exact k-th largest.  Longer rows get the exact value.
+    return launch_any<false, int>(x, ld, n, rows, k, nullptr, 0, nullptr, 0, tau_out, 0, 0, nullptr,
+                                  1, 0, n <= 4096 ? 2 : 0, st);
 }
 
 hipError_t launch_topk_final(const float *scores, int P, int rows, const LayerPlan &plan, int w,
                              int32_t *idx, hipStream_t st)
 {
     return launch_any<true, LayerPlan>(scores, P, P, rows, 0, idx, 0, nullptr, 0, nullptr, P, w,
-                                       nullptr, 1, plan, st);
+                                       nullptr, 1, plan, 0, st);
 }
 
 }  // namespace gkv

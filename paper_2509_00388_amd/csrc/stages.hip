@@ -33,6 +33,32 @@ __global__ __launch_bounds__(256) void pool_group_kernel(const float *__restrict
     scores[(long)h * P + j] = total / div;
 }
 
+// Average pooling is linear, so the Gv vote rows of a head are added first (one
+// coalesced load per row and thread) and the sum is pooled once out of an LDS tile
+// with a halo.  Same value as pooling each row and adding, up to fp32 rounding order.
+constexpr int kPoolHalo = 16;
+__global__ __launch_bounds__(256) void pool_avg_kernel(const float *__restrict__ votes, int Gv, int P,
+                                                       int pool_kernel, float div,
+                                                       float *__restrict__ scores)
+{
+    __shared__ float tile[256 + 2 * kPoolHalo];
+    const int h = blockIdx.y, j0 = blockIdx.x * 256, tid = threadIdx.x;
+    const int half = (pool_kernel - 1) / 2;
+    for (int u = tid; u < 256 + 2 * kPoolHalo; u += 256) {
+        const int j = j0 - kPoolHalo + u;
+        float v = 0.f;                               // zero padding outside the row
+        if (j >= 0 && j < P && u >= kPoolHalo - half && u < 256 + kPoolHalo + half)
+            for (int g = 0; g < Gv; ++g) v += votes[((long)h * Gv + g) * P + j];
+        tile[u] = v;
+    }
+    __syncthreads();
+    const int j = j0 + tid;
+    if (j >= P) return;
+    float acc = 0.f;
+    for (int t = -half; t <= half; ++t) acc += tile[kPoolHalo + tid + t];
+    scores[(long)h * P + j] = acc / (float)pool_kernel / div;
+}
+
 __device__ __forceinline__ float signal_factor(float e, float alpha, int signal)
 {
     return signal == 1 ? fmaf(alpha, e, 1.0f) : fmaf(-alpha, e, 1.0f);
@@ -231,8 +257,12 @@ __global__ __launch_bounds__(256) void copy_kernel(const T *__restrict__ src, T 
 hipError_t launch_pool_group(const float *votes, int Hkv, int Gv, int P, int pool_kernel,
                              int pool_mode, float div, float *scores, hipStream_t st)
 {
-    hipLaunchKernelGGL(pool_group_kernel, dim3((P + 255) / 256, Hkv), dim3(256), 0, st, votes, Gv,
-                       P, pool_kernel, pool_mode, div, scores);
+    if (pool_mode == 0 && pool_kernel <= 2 * kPoolHalo + 1)
+        hipLaunchKernelGGL(pool_avg_kernel, dim3((P + 255) / 256, Hkv), dim3(256), 0, st, votes, Gv, P,
+                           pool_kernel, div, scores);
+    else
+        hipLaunchKernelGGL(pool_group_kernel, dim3((P + 255) / 256, Hkv), dim3(256), 0, st, votes, Gv,
+                           P, pool_kernel, pool_mode, div, scores);
     return hipGetLastError();
 }
 
