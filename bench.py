@@ -19,6 +19,7 @@ JSON line.
                    layers, extrapolated to the full model
 """
 import argparse
+import contextlib
 import json
 import os
 import sys
@@ -94,6 +95,8 @@ def main():
                     help="batched: graphkv_compress_batched over the model's contiguous cache; "
                          "per-layer: one graphkv_compress call per layer")
     ap.add_argument("--group", type=int, default=0, help="layers per batched call (0 = all)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the batched calls are spread over (each with its own workspace)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the eviction pass of one sequence); "
@@ -140,15 +143,28 @@ def main():
     Iout = torch.empty((row_off[L],), dtype=torch.int32, device=dev)
     group = args.group if args.group > 0 else L
     if args.mode == "batched":
-        ws = torch.empty(gk.graphkv_workspace_bytes_batched(params[0], min(group, L)), dtype=torch.uint8, device=dev)
+        if args.streams > 1 and args.group <= 0:
+            group = (L + args.streams - 1) // args.streams
+        n_str = max(1, args.streams)
+        wss = [torch.empty(gk.graphkv_workspace_bytes_batched(params[0], min(group, L)), dtype=torch.uint8,
+                           device=dev) for _ in range(n_str)]
+        streams = [torch.cuda.Stream() for _ in range(n_str)] if n_str > 1 else [None]
 
         def step():
-            for l0 in range(0, L, group):
+            cur = torch.cuda.current_stream()
+            for i, l0 in enumerate(range(0, L, group)):
                 l1 = min(L, l0 + group)
-                gk.graphkv_compress_batched(params[0], l1 - l0, budgets[l0:l1], Kall[l0:l1], Vall[l0:l1],
-                                            Qall[l0:l1], Kout[row_off[l0]:row_off[l1]],
-                                            Vout[row_off[l0]:row_off[l1]], Iout[row_off[l0]:row_off[l1]],
-                                            None, ws)
+                st = streams[i % n_str]
+                if st is not None:
+                    st.wait_stream(cur)
+                with torch.cuda.stream(st) if st is not None else contextlib.nullcontext():
+                    gk.graphkv_compress_batched(params[0], l1 - l0, budgets[l0:l1], Kall[l0:l1], Vall[l0:l1],
+                                                Qall[l0:l1], Kout[row_off[l0]:row_off[l1]],
+                                                Vout[row_off[l0]:row_off[l1]], Iout[row_off[l0]:row_off[l1]],
+                                                None, wss[i % n_str])
+            for st in streams:
+                if st is not None:
+                    cur.wait_stream(st)
     else:
         ws = torch.empty(max(gk.graphkv_workspace_bytes(p) for p in params), dtype=torch.uint8, device=dev)
 
@@ -167,6 +183,18 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = cfg.n_tokens / (ms_per_step * 1e-3 * cfg.n_layers / L)   # L < n_layers only in debug runs
+
+    # ---- what a plain device-to-device copy of the key slab reaches on this machine (context for
+    # the roofline: published peak vs what the memory system delivers to a trivial kernel) ----
+    scratch = torch.empty_like(Kall)
+    scratch.copy_(Kall)
+    torch.cuda.synchronize()
+    tcp = time.perf_counter()
+    for _ in range(5):
+        scratch.copy_(Kall)
+    torch.cuda.synchronize()
+    copy_gbps = 2 * Kall.numel() * Kall.element_size() * 5 / (time.perf_counter() - tcp) / 1e9
+    del scratch
 
     # ---- per-kernel durations (HIP events on the launch stream), after the timed region ----
     kernels = {}
@@ -210,6 +238,7 @@ def main():
         "model_bytes_per_step": int(model_bytes),
         "model_GBps": round(model_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "frac_of_hbm_peak": round(model_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "plain_copy_GBps_read_plus_write": round(copy_gbps, 1),
         "mfma_TFLOPs": round(model_flops(cfg) * L / (ms_per_step * 1e-3) / 1e12, 2),
         "frac_of_bf16_mfma_peak": round(model_flops(cfg) * L / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
     }
@@ -251,7 +280,7 @@ def main():
                                f"d={cfg.head_dim}, N={cfg.n_tokens}, w={cfg.window}, pool={cfg.pool_kernel}, "
                                f"B={cfg.budget_for_layer(0)}..{cfg.budget_for_layer(L - 1)}, S={cfg.n_sources}, "
                                f"m={cfg.n_neighbors}, T={cfg.rounds}, reselect={cfg.reselect}, alpha={cfg.decay}",
-                   "mode": args.mode + (f" (groups of {group} layers)" if args.mode == "batched" else ""),
+                   "mode": args.mode + (f" (groups of {group} layers, {args.streams} stream(s))" if args.mode == "batched" else ""),
                    "token_head_units_per_s": round(tokens_per_s * cfg.n_layers * cfg.n_kv_heads, 1),
                    "input_generation_s": round(t_gen, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "pass_vs_streaming_model": pass_view,

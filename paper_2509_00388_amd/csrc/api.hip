@@ -122,8 +122,9 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.part = take(D.mfma_score ? mfma_score_plan(D.H, D.G * D.w, D.N).part_bytes : 0);
     W.E_sample = take(D.filter ? (size_t)D.H * D.S * mfma_sample_cols(D.P) * 4 : 0);
     W.tau = take((size_t)D.H * D.S * 4);
-    W.cand = take(D.filter ? (size_t)D.H * D.S * mfma_cand_cap(D.P, D.m) * 8 : 0);
-    W.cand_cnt = take((size_t)D.H * D.S * 4);
+    const MfmaFilterGeom fg = D.filter ? mfma_filter_geom(D.H, D.P, D.S, D.m) : MfmaFilterGeom{0, 0, 0};
+    W.cand = take((size_t)D.H * D.S * fg.chunks * fg.slice_cap * 8);
+    W.cand_cnt = take((size_t)D.H * D.S * fg.chunks * 4);
     W.overflow = take((size_t)D.H * 4);
     W.total = off;
     return W;
@@ -243,7 +244,7 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                 void *cand = at<char>(ws, W.cand);
                 const int ps = mfma_sample_cols(D.P);
                 GKV_LAUNCH(GRAPHKV_K_COSINE_SAMPLE,
-                           launch_mfma_cosine_sample(Kc, D.H, D.N, D.P, D.S, src, Es, cnt, ovf, st));
+                           launch_mfma_cosine_sample(Kc, D.H, D.N, D.P, D.S, src, Es, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_TOPK_BOUND,
                            launch_topk_bound(Es, ps, ps, D.H * D.S, D.m, tau, st));
                 GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,

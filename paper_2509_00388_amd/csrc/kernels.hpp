@@ -82,17 +82,25 @@ hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, cons
 // Neighbourhoods without the dense block (see mfma_cosine.hip):
 bool mfma_filter_applies(int P, int m);
 int mfma_sample_cols(int P);          // keys in the strided sample
-int mfma_cand_cap(int P, int m);      // entries per source in the candidate lists
-// E_sample [Hkv, S, sample_cols] on every (P / sample_cols)-th key; clears cand_cnt, overflow.
+int mfma_cand_cap(int P, int m);      // candidates per source the exact select can take
+struct MfmaFilterGeom {
+    int chunk_cols;   // keys per workgroup of the filter pass
+    int chunks;       // workgroups (= candidate slices) per head
+    int slice_cap;    // entries per (source, chunk) slice
+};
+MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m);
+// E_sample [Hkv, S, sample_cols] on every (P / sample_cols)-th key; clears overflow [Hkv].
 hipError_t launch_mfma_cosine_sample(const void *Kc, int Hkv, int N, int P, int S,
-                                     const int32_t *src, float *E_sample, int32_t *cand_cnt,
-                                     int32_t *overflow, hipStream_t st);
-// Streams all keys; edges >= tau[h, a] go to cand [Hkv, S, cap] x 8 bytes, counts to cand_cnt.
+                                     const int32_t *src, float *E_sample, int32_t *overflow,
+                                     hipStream_t st);
+// Streams all keys; edges that reach tau[h, a] go to cand [Hkv, S, chunks, slice_cap] x 8
+// bytes, their number per slice to cand_cnt [Hkv, S, chunks].
 hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int S, int m,
                                      const int32_t *src, const float *tau, void *cand,
                                      int32_t *cand_cnt, int32_t *overflow, hipStream_t st);
-// Exact top-m of each candidate list -> nbr / nbr_e [Hkv, S, m]; skips heads with overflow[h].
-hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, const int32_t *overflow,
+// Exact top-m over each source's slices -> nbr / nbr_e [Hkv, S, m]; skips heads with
+// overflow[h], and raises overflow[h] itself if a source has more candidates than it can take.
+hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t *overflow,
                              const int32_t *src, int Hkv, int P, int S, int m, int32_t *nbr,
                              float *nbr_e, hipStream_t st);
 

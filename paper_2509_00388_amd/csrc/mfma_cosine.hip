@@ -32,6 +32,14 @@ constexpr int kSB = 2;            // source blocks of 32 per workgroup = row gro
 constexpr int kRows = kSB * kBlk; // source rows per workgroup
 constexpr int kThreads = 256 * kSB;
 
+// 1/|k| from |k|^2 with the hardware reciprocal square root (1 ulp), 0 for a zero key.
+// Every MFMA-path edge uses this one function, so the sampled bound and the filtered
+// edges are computed bit for bit alike.
+__device__ __forceinline__ float inv_norm(float sq)
+{
+    return sq == 0.f ? 0.f : __builtin_amdgcn_rsqf(sq);
+}
+
 // Sum of squares of the 64 elements a lane holds of its row (8 k-steps x 8),
 // two bf16 products per instruction, fp32 accumulation.
 __device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
@@ -49,10 +57,10 @@ __device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
 
 struct FilterArgs {
     const float *tau;      // [Hkv, S] lower bound of each source's m-th largest edge
-    uint2 *cand;           // [Hkv, S, cap] (edge bits, key index)
-    int32_t *cand_cnt;     // [Hkv, S]
+    uint2 *cand;           // [Hkv, S, chunks, slice_cap] (edge bits, key index): one slice per key chunk
+    int32_t *cand_cnt;     // [Hkv, S, chunks] entries in each slice
     int32_t *overflow;     // [Hkv]
-    int cap;
+    int slice_cap;
     int flush_every;       // tiles between two flushes of the LDS staging area
 };
 
@@ -77,14 +85,14 @@ __device__ __forceinline__ void load_sources(const uint16_t *Kh, const int32_t *
     float sq = half_row_sumsq(q);
     sq += __shfl_xor(sq, 32, kWave);
     if (stream == 0 && hh == 0) {
-        inv_s[kBlk * grp + l32] = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
+        inv_s[kBlk * grp + l32] = inv_norm(sq);
         idx_s[kBlk * grp + l32] = i;
     }
 }
 
 // Dense block: E[h, slot, c] = e for column c = key c * key_stride (key_stride = 1:
-// every key), -inf where the key is the source itself.  If fa.cand_cnt is set, chunk 0
-// also clears cand_cnt / overflow of its head for the filter pass that follows.
+// every key), -inf where the key is the source itself.  If fa.overflow is set, the first
+// workgroup of a head also clears the head's overflow flag for the filter pass that follows.
 __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
     const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride, int S,
     const int32_t *__restrict__ src, int chunk_cols, float *__restrict__ E, FilterArgs fa,
@@ -103,22 +111,14 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
     const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
     if (c0 >= n_cols) return;
 
-    if (fa.cand_cnt && chunk == 0) {
-        if (tid < kRows && s_base + tid < S) fa.cand_cnt[(long)h * S + s_base + tid] = 0;
-        if (tid == 0 && blockIdx.z == 0) fa.overflow[h] = 0;
-    }
+    if (fa.overflow && chunk == 0 && blockIdx.z == 0 && tid == 0) fa.overflow[h] = 0;
 
     bf16x8 q[kSteps];
     load_sources(Kh, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
     __syncthreads();
     float inv_src[16];
-    int32_t idx_src[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = kBlk * grp + acc_row(i, hh);
-        inv_src[i] = inv_s[r];
-        idx_src[i] = idx_s[r];
-    }
+    for (int i = 0; i < 16; ++i) inv_src[i] = inv_s[kBlk * grp + acc_row(i, hh)];
 
     const int ntile = (c1 - c0 + kTileKeys - 1) / kTileKeys;
     auto multiply_tile = [&](const unsigned char *buf, int t) {
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
 
         float sq = half_row_sumsq(kc);
         sq += __shfl_xor(sq, 32, kWave);
-        const float inv_k = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);
+        const float inv_k = inv_norm(sq);
         const int col = c0 + kTileKeys * t + kBlk * stream + l32;
         const int key = col * key_stride;
         if (col < c1) {
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
                 const int slot = s_base + kBlk * grp + acc_row(i, hh);
                 if (slot < S) {
                     float e = (acc[i] * inv_k) * inv_src[i];
-                    if (key == idx_src[i]) e = -INFINITY;
+                    if (key == idx_s[kBlk * grp + acc_row(i, hh)]) e = -INFINITY;
                     E[((long)h * S + slot) * n_cols + col] = e;
                 }
             }
@@ -158,10 +158,11 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
 // have a hit park their 16 dots, the key's squared norm and the key index in an
 // LDS staging area.  Every `flush_every` tiles, and at the end, the workgroup turns
 // the staged rows into exact edges (the dense kernel's formula, bit for bit),
-// keeps those that reach the bound and appends them to the per-source global
-// lists (one reservation per source and flush).  The source's own column may be
-// among them: the exact select drops it.  The flush schedule is fixed by the
-// host from the expected hit rate; if the staging area or a list overflows
+// keeps those that reach the bound and appends them to its own slice of each
+// source's global candidate list (one slice per key chunk, so no workgroup ever
+// waits for another: positions come from LDS counters).  The source's own column
+// may be among them: the exact select drops it.  The flush schedule is fixed by
+// the host from the expected hit rate; if the staging area or a slice overflows
 // anyway, the head's overflow flag is raised and the head is redone densely.
 constexpr int kStageCap = 1024;    // staged rows per workgroup
 constexpr int kStagePitch = 80;    // bytes per staged row: 16 dots, |k|^2, key + lane bits, hit bits
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
 {
     __shared__ float inv_s[kRows], lo_s[kRows], det_s[kRows];
     __shared__ int32_t idx_s[kRows];
-    __shared__ int32_t stage_n, row_cnt[kRows], row_base[kRows], row_pos[kRows];
+    __shared__ int32_t stage_n, lost, row_pos[kRows];   // row_pos: entries written to each source's slice
     extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the staging area
     unsigned char *kt = smem;
     unsigned char *stage_mem = smem + 2 * kTileBytes;
@@ -186,8 +187,8 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
 
     bf16x8 q[kSteps];
     load_sources(Kh, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
-    if (tid == 0) stage_n = 0;
-    if (tid < kRows) { row_cnt[tid] = 0; row_pos[tid] = 0; }
+    if (tid == 0) { stage_n = 0; lost = 0; }
+    if (tid < kRows) row_pos[tid] = 0;
     __syncthreads();
     if (tid < kRows) {
         // lo: what an exact edge must reach to be listed; det: the still lower bound of the
@@ -206,60 +207,36 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) det[i] = det_s[kBlk * grp + acc_row(i, hh)];
 
-    // Staged rows -> exact edges -> global candidate lists.  Called by all threads; one
-    // thread per staged row walks the row's hit bits.
+    // Staged rows -> exact edges -> this workgroup's slices of the candidate lists.  Called
+    // by all threads; one thread per staged row walks the row's hit bits.
+    uint2 *slice0 = fa.cand + (((long)h * S + s_base) * gridDim.x + chunk) * fa.slice_cap;
+    const long slice_row_stride = (long)gridDim.x * fa.slice_cap;
     auto flush = [&]() {
         const int n_stage = stage_n;
         const int n = n_stage < kStageCap ? n_stage : kStageCap;
+        if (n_stage > kStageCap && tid == 0) lost = 1;
         for (int r = tid; r < n; r += kThreads) {
-            unsigned char *row_mem = stage_mem + r * kStagePitch;
-            float *vals = reinterpret_cast<float *>(row_mem);
+            const unsigned char *row_mem = stage_mem + r * kStagePitch;
+            const float *vals = reinterpret_cast<const float *>(row_mem);
             const float sq = vals[16];
-            const float inv_k = sq == 0.f ? 0.f : 1.0f / sqrtf(sq);   // the dense kernel's formula
+            const float inv_k = inv_norm(sq);   // the dense kernel's formula
             const uint32_t meta = *reinterpret_cast<const uint32_t *>(row_mem + 68);
             const int rgrp = kBlk * ((meta >> 25) & 1), rhh = (meta >> 24) & 1;
-            uint32_t hits = *reinterpret_cast<const uint32_t *>(row_mem + 72), keep = 0;
+            uint32_t hits = *reinterpret_cast<const uint32_t *>(row_mem + 72);
             while (hits) {
                 const int i = __ffs(hits) - 1;
                 hits &= hits - 1;
                 const int row = rgrp + acc_row(i, rhh);
                 const float e = (vals[i] * inv_k) * inv_s[row];
                 if (e >= lo_s[row]) {
-                    vals[i] = e;
-                    keep |= 1u << i;
-                    atomicAdd(&row_cnt[row], 1);
+                    const int at = atomicAdd(&row_pos[row], 1);
+                    if (at < fa.slice_cap)
+                        slice0[row * slice_row_stride + at] = make_uint2(__float_as_uint(e), meta & 0xffffffu);
                 }
-            }
-            *reinterpret_cast<uint32_t *>(row_mem + 72) = keep;
-        }
-        __syncthreads();
-        if (tid < kRows) {
-            const int c = row_cnt[tid];
-            int base = 0;
-            if (c > 0) base = atomicAdd(&fa.cand_cnt[(long)h * S + s_base + tid], c);
-            row_base[tid] = base;
-            if (base + c > fa.cap || n_stage > kStageCap) fa.overflow[h] = 1;
-        }
-        __syncthreads();
-        for (int r = tid; r < n; r += kThreads) {
-            const unsigned char *row_mem = stage_mem + r * kStagePitch;
-            const float *vals = reinterpret_cast<const float *>(row_mem);
-            const uint32_t meta = *reinterpret_cast<const uint32_t *>(row_mem + 68);
-            const int rgrp = kBlk * ((meta >> 25) & 1), rhh = (meta >> 24) & 1;
-            uint32_t keep = *reinterpret_cast<const uint32_t *>(row_mem + 72);
-            while (keep) {
-                const int i = __ffs(keep) - 1;
-                keep &= keep - 1;
-                const int row = rgrp + acc_row(i, rhh);
-                const int at = row_base[row] + atomicAdd(&row_pos[row], 1);
-                if (at < fa.cap)
-                    fa.cand[((long)h * S + s_base + row) * fa.cap + at] =
-                        make_uint2(__float_as_uint(vals[i]), meta & 0xffffffu);
             }
         }
         __syncthreads();
         if (tid == 0) stage_n = 0;
-        if (tid < kRows) { row_cnt[tid] = 0; row_pos[tid] = 0; }
         __syncthreads();
     };
 
@@ -305,6 +282,11 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     GKV_TILE_PIPELINE(kThreads, Kh, c0, n_cols - 1, 1, ntile, multiply_tile,
                       if ((tile_done % fe) == 0) flush());
     flush();
+    if (tid < kRows && s_base + tid < S) {
+        const int c = row_pos[tid];
+        fa.cand_cnt[((long)h * S + s_base + tid) * gridDim.x + chunk] = c < fa.slice_cap ? c : fa.slice_cap;
+        if (c > fa.slice_cap || lost) fa.overflow[h] = 1;
+    }
 }
 
 __device__ __forceinline__ uint32_t ord_key_u(uint32_t bits)
@@ -324,9 +306,10 @@ __device__ __forceinline__ uint32_t ord_key_u(uint32_t bits)
 // winners' output position is their rank by key index among themselves.
 __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict__ cand,
                                                          const int32_t *__restrict__ cand_cnt,
-                                                         const int32_t *__restrict__ overflow,
+                                                         int32_t *__restrict__ overflow,
                                                          const int32_t *__restrict__ src, int S,
-                                                         int cap, int m, int32_t *__restrict__ nbr,
+                                                         int chunks, int slice_cap, int cap, int m,
+                                                         int32_t *__restrict__ nbr,
                                                          float *__restrict__ nbr_e)
 {
     extern __shared__ uint32_t dyn[];
@@ -334,23 +317,36 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     __shared__ uint32_t s_bin, s_need, s_min[4], s_max[4];
     __shared__ int32_t n_win, n_eq;
     const int a = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (overflow[h]) return;
     const long row = (long)h * S + a;
-    const int n = min(cand_cnt[row], cap);
-    const uint2 *c = cand + row * cap;
-    const uint32_t self = (uint32_t)src[row];
+    // slice sizes, the overflow flag and the source index: independent loads, one round trip
+    __shared__ int32_t cnt_s[256], s_ovf;
+    __shared__ uint32_t s_self;
+    for (int c = tid; c < chunks; c += 256) cnt_s[c] = cand_cnt[row * chunks + c];
+    if (tid == 0) { s_ovf = overflow[h]; s_self = (uint32_t)src[row]; n_win = 0; n_eq = 0; }
+    __syncthreads();
+    if (s_ovf) return;
+    int n = 0;
+    for (int c = 0; c < chunks; ++c) n += cnt_s[c];
+    if (n > cap) {          // more candidates than the select can hold: redo the head densely
+        if (tid == 0) overflow[h] = 1;
+        return;
+    }
+    const uint32_t self = s_self;
     uint32_t *ek = dyn;                 // [cap] order-preserving edge keys (0 = dropped)
     uint32_t *kj = dyn + cap;           // [cap] key indices
     uint32_t *eq = kj + cap;            // [cap] key indices of the entries equal to the threshold
-    uint64_t *win = reinterpret_cast<uint64_t *>(eq + cap + (cap & 1));   // [m] (key index << 32 | edge bits)
-    if (tid == 0) { n_win = 0; n_eq = 0; }
+    uint32_t *eb = eq + cap;            // [cap] edge bits
+    uint64_t *win = reinterpret_cast<uint64_t *>(eb + cap);   // [m] (key index << 32 | edge bits)
     uint32_t kmin = 0xffffffffu, kmax = 0u;
     for (int r = tid; r < n; r += 256) {
-        const uint2 v = c[r];
+        int c = 0, local = r;                 // entry r of the concatenated slices
+        while (local >= cnt_s[c]) { local -= cnt_s[c]; ++c; }
+        const uint2 v = cand[(row * chunks + c) * (long)slice_cap + local];
         // the source's own column is no neighbour (Eq. 3: j != i): key 0 sorts below every edge
         const uint32_t k = v.y == self ? 0u : ord_key_u(v.x);
         ek[r] = k;
         kj[r] = v.y;
+        eb[r] = v.x;
         if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
     }
 #pragma unroll
@@ -414,7 +410,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
         const uint32_t k = ek[r];
         if (k > tau) {
             const int at = atomicAdd(&n_win, 1);
-            win[at] = ((uint64_t)kj[r] << 32) | c[r].x;
+            win[at] = ((uint64_t)kj[r] << 32) | eb[r];
         } else if (k == tau && k) {
             eq[atomicAdd(&n_eq, 1)] = kj[r];
         }
@@ -426,7 +422,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
             const uint32_t mine = kj[r];
             uint32_t rank = 0;
             for (int u = 0; u < ne; ++u) rank += eq[u] < mine;
-            if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | c[r].x;
+            if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | eb[r];
         }
     }
     __syncthreads();
@@ -488,7 +484,29 @@ bool mfma_filter_applies(int P, int m)
     // the select kernel's LDS must hold a full list.
     if (P < 8192 || P >= (1 << 24)) return false;
     if (m > mfma_sample_cols(P) / 8) return false;
-    return (size_t)mfma_cand_cap(P, m) * 12 + (size_t)m * 8 + 8 <= 110 * 1024;
+    return (size_t)mfma_cand_cap(P, m) * 16 + (size_t)m * 8 + 8 <= 140 * 1024;
+}
+
+// Key chunks per head of the filter pass and the capacity of one (source, chunk) slice:
+// four times the expected share of a chunk, at least 2 m (and 64) entries.
+MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m)
+{
+    MfmaFilterGeom g;
+    const int sgroups = (S + kRows - 1) / kRows;
+    g.chunk_cols = chunk_cols_for(Hkv, sgroups, P);
+    g.chunks = (P + g.chunk_cols - 1) / g.chunk_cols;
+    if (g.chunks > 256) {   // the exact select keeps the slice sizes of a source in LDS
+        g.chunk_cols = (((P + 255) / 256 + 127) / 128) * 128;
+        g.chunks = (P + g.chunk_cols - 1) / g.chunk_cols;
+    }
+    const int stride = P / mfma_sample_cols(P);
+    long sc = 4L * ((long)m * stride + g.chunks - 1) / g.chunks;
+    if (sc < 2L * m) sc = 2L * m;
+    if (sc < 64) sc = 64;
+    const int cap = mfma_cand_cap(P, m);
+    if (sc > cap) sc = cap;
+    g.slice_cap = (int)sc;
+    return g;
 }
 
 hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
@@ -505,15 +523,14 @@ hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, cons
 }
 
 hipError_t launch_mfma_cosine_sample(const void *Kc, int Hkv, int N, int P, int S,
-                                     const int32_t *src, float *E_sample, int32_t *cand_cnt,
-                                     int32_t *overflow, hipStream_t st)
+                                     const int32_t *src, float *E_sample, int32_t *overflow,
+                                     hipStream_t st)
 {
     const int ps = mfma_sample_cols(P), stride = P / ps;
     const int sgroups = (S + kRows - 1) / kRows;
     const int ck = chunk_cols_for(Hkv, sgroups, ps);
     const int chunks = (ps + ck - 1) / ck;
     FilterArgs fa{};
-    fa.cand_cnt = cand_cnt;
     fa.overflow = overflow;
     if (!allow_big_lds((const void *)cosine_dense_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(cosine_dense_kernel, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
@@ -528,8 +545,7 @@ hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int 
 {
     const int sgroups = (S + kRows - 1) / kRows;
     const int stride = P / mfma_sample_cols(P);
-    const int ck = chunk_cols_for(Hkv, sgroups, P);
-    const int chunks = (P + ck - 1) / ck;
+    const MfmaFilterGeom g = mfma_filter_geom(Hkv, P, S, m);
     // Expected staged rows per tile: 512 lanes x P(a lane's 16 edges hold a hit), with a
     // per-edge hit rate of about m * stride / P (each source keeps ~m * stride candidates).
     const double rate = (double)m * stride / (double)P;
@@ -537,29 +553,24 @@ hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int 
     int flush_every = (int)((kStageCap / 2) / (per_tile > 1.0 ? per_tile : 1.0));
     if (flush_every < 1) flush_every = 1;
     if (flush_every > 64) flush_every = 64;
-    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, mfma_cand_cap(P, m), flush_every};
+    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, flush_every};
     if (!allow_big_lds((const void *)cosine_filter_kernel)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_filter_kernel, dim3(chunks, Hkv, sgroups), dim3(kThreads),
+    hipLaunchKernelGGL(cosine_filter_kernel, dim3(g.chunks, Hkv, sgroups), dim3(kThreads),
                        2 * kTileBytes + kStageCap * kStagePitch, st, (const uint16_t *)Kc, N, P, S, src,
-                       ck, fa);
+                       g.chunk_cols, fa);
     return hipGetLastError();
 }
 
-hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, const int32_t *overflow,
+hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t *overflow,
                              const int32_t *src, int Hkv, int P, int S, int m, int32_t *nbr,
                              float *nbr_e, hipStream_t st)
 {
     const int cap = mfma_cand_cap(P, m);
-    const size_t lds = ((size_t)3 * cap + (cap & 1)) * 4 + (size_t)m * 8;
-    static bool opt_in = false;   // more than 64 KiB of dynamic LDS needs a one-time opt-in
-    if (lds > 65536 && !opt_in) {
-        if (hipFuncSetAttribute((const void *)nbr_select_kernel,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024) != hipSuccess)
-            return hipGetLastError();
-        opt_in = true;
-    }
+    const MfmaFilterGeom g = mfma_filter_geom(Hkv, P, S, m);
+    const size_t lds = (size_t)4 * cap * 4 + (size_t)m * 8;
+    if (!allow_big_lds((const void *)nbr_select_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(nbr_select_kernel, dim3(S, Hkv), dim3(256), lds, st, (const uint2 *)cand,
-                       cand_cnt, overflow, src, S, cap, m, nbr, nbr_e);
+                       cand_cnt, overflow, src, S, g.chunks, g.slice_cap, cap, m, nbr, nbr_e);
     return hipGetLastError();
 }
 

@@ -130,25 +130,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
             }
         }
     };
-    // Tile t is multiplied out of LDS while tiles t+1 and t+2 are on their way from HBM
-    // in two sets of staging registers: two tiles (64 KiB) in flight per workgroup.
-    u32x4 stage[tile_pieces<NT>()], stage_b[tile_pieces<NT>()];
-    tile_load<NT>(Kh, k0, N - 1, 1, tid, stage);
-    tile_store<NT>(kt, tid, stage);
-    if (1 < ntile) tile_load<NT>(Kh, k0 + kTileKeys, N - 1, 1, tid, stage);
-    if (2 < ntile) tile_load<NT>(Kh, k0 + 2 * kTileKeys, N - 1, 1, tid, stage_b);
-    __syncthreads();
-    for (int t = 0; t < ntile; t += 2) {
-        multiply_tile(kt, t);
-        if (t + 1 < ntile) tile_store<NT>(kt + kTileBytes, tid, stage);
-        if (t + 3 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 3), N - 1, 1, tid, stage);
-        __syncthreads();
-        if (t + 1 >= ntile) break;
-        multiply_tile(kt + kTileBytes, t + 1);
-        if (t + 2 < ntile) tile_store<NT>(kt, tid, stage_b);
-        if (t + 4 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 4), N - 1, 1, tid, stage_b);
-        __syncthreads();
-    }
+    GKV_TILE_PIPELINE(NT, Kh, k0, N - 1, 1, ntile, multiply_tile, (void)0);
 
     // merge the two half-waves (same query, other key rows), then the 4 key streams
 #pragma unroll
@@ -253,25 +235,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
             }
         }
     };
-    // Tile t is multiplied out of LDS while tiles t+1 and t+2 are on their way from HBM
-    // in two sets of staging registers: two tiles (64 KiB) in flight per workgroup.
-    u32x4 stage[tile_pieces<NT>()], stage_b[tile_pieces<NT>()];
-    tile_load<NT>(Kh, k0, P - 1, 1, tid, stage);
-    tile_store<NT>(kt, tid, stage);
-    if (1 < ntile) tile_load<NT>(Kh, k0 + kTileKeys, P - 1, 1, tid, stage);
-    if (2 < ntile) tile_load<NT>(Kh, k0 + 2 * kTileKeys, P - 1, 1, tid, stage_b);
-    __syncthreads();
-    for (int t = 0; t < ntile; t += 2) {
-        multiply_tile(kt, t);
-        if (t + 1 < ntile) tile_store<NT>(kt + kTileBytes, tid, stage);
-        if (t + 3 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 3), P - 1, 1, tid, stage);
-        __syncthreads();
-        if (t + 1 >= ntile) break;
-        multiply_tile(kt + kTileBytes, t + 1);
-        if (t + 2 < ntile) tile_store<NT>(kt, tid, stage_b);
-        if (t + 4 < ntile) tile_load<NT>(Kh, k0 + kTileKeys * (t + 4), P - 1, 1, tid, stage_b);
-        __syncthreads();
-    }
+    GKV_TILE_PIPELINE(NT, Kh, k0, P - 1, 1, ntile, multiply_tile, (void)0);
 }
 
 // Kernels that use more than 64 KiB of dynamic LDS need a one-time opt-in per kernel.

@@ -78,10 +78,12 @@ __device__ __forceinline__ void tile_read(const unsigned char *buf, int stream, 
 
 // The tile loop shared by the streaming kernels.  Tile t is multiplied out of LDS
 // while tiles t+1 and t+2 are on their way from HBM in two sets of staging
-// registers: two tiles (64 KiB) in flight per workgroup.  One barrier per tile
-// separates the writers of an LDS buffer from its readers.  `body(buf, t)` multiplies
-// tile t; AFTER_TILE runs right after each tile's barrier with `tile_done` = number
-// of tiles finished (it may contain barriers: every thread reaches it).
+// registers: two tiles (64 KiB) in flight per workgroup (a third set brought no
+// gain when measured).  One barrier per tile separates the writers of an LDS
+// buffer from its readers.  `body(buf, t)` multiplies tile t; AFTER_TILE runs
+// right after each tile's barrier with `tile_done` = number of tiles finished (it
+// may contain barriers: every thread reaches it).  The loop is unrolled twice so
+// that the LDS buffer and the register set of a tile are compile-time choices.
 #define GKV_TILE_PIPELINE(NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE)                 \
     do {                                                                                               \
         u32x4 stage_a[tile_pieces<NT_>()], stage_b[tile_pieces<NT_>()];                                \

@@ -87,11 +87,11 @@ __device__ __forceinline__ void find_bin(const uint32_t *hist, uint32_t need, in
 // value at most (row range) / 2^(DIG * max_sweeps) below the k-th largest -- a valid,
 // slightly loose lower bound (idx_out must be nullptr in that case).
 template <int BLOCK, bool PLAN, int DIG>
-__global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
-    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
-    float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
-    int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
-    typename std::conditional<PLAN, LayerPlan, int>::type plan, int max_sweeps)
+__device__ __forceinline__ void topk_row_lds(
+    int row, const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out,
+    long idx_ld, float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out,
+    int append_from, int append_count,
+    const typename std::conditional<PLAN, LayerPlan, int>::type &plan, int max_sweeps)
 {
     constexpr int NW = BLOCK / kWave;
     constexpr int NBINS = 1 << DIG;
@@ -99,18 +99,17 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     __shared__ uint32_t hist[NBINS];
     __shared__ uint32_t s_bin, s_need;
 
-    if (gate && gate[blockIdx.x / rows_per_gate] == 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int items = (n + BLOCK - 1) / BLOCK;
     const int ncell = items * NW;
     uint32_t *keys = dyn;                    // [items * BLOCK]
     uint32_t *cg = dyn + items * BLOCK;      // [ncell]
     uint32_t *ce = cg + ncell;               // [ncell]
-    const float *xr = x + (long)blockIdx.x * ld;
-    int32_t *out = idx_out ? idx_out + (long)blockIdx.x * idx_ld : nullptr;
-    float *vout = val_out ? val_out + (long)blockIdx.x * val_ld : nullptr;
+    const float *xr = x + (long)row * ld;
+    int32_t *out = idx_out ? idx_out + (long)row * idx_ld : nullptr;
+    float *vout = val_out ? val_out + (long)row * val_ld : nullptr;
     if constexpr (PLAN) {   // per-layer budget: k and the output row come from the plan
-        const int g = blockIdx.x / plan.heads_per_layer, hl = blockIdx.x % plan.heads_per_layer;
+        const int g = row / plan.heads_per_layer, hl = row % plan.heads_per_layer;
         k = plan.budget[g] - append_count;
         out = idx_out + (plan.row_off[g] + (long)hl * plan.budget[g]);
     }
@@ -167,7 +166,7 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     }
     // If sweeps were cut short the unresolved low bits are 0: the lower edge of the bin.
     const uint32_t tau = kmin + prefix;   // key of the k-th largest entry; take `need` entries equal to it
-    if (tau_out && tid == 0) tau_out[blockIdx.x] = key_to_float(tau);
+    if (tau_out && tid == 0) tau_out[row] = key_to_float(tau);
     if (!out) return;
 
 
@@ -214,6 +213,29 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
                 if (vout) vout[pos] = key_to_float(key);
             }
         }
+    }
+}
+
+// One workgroup per row (WALK = false); with a gate, a smaller grid whose workgroups walk
+// the rows and skip those whose gate is 0 (WALK = true: a launch that mostly skips then
+// costs next to nothing).
+template <int BLOCK, bool PLAN, int DIG, bool WALK>
+__global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
+    const float *__restrict__ x, long ld, int n, int rows, int k, int32_t *__restrict__ idx_out,
+    long idx_ld, float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out,
+    int append_from, int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
+    typename std::conditional<PLAN, LayerPlan, int>::type plan, int max_sweeps)
+{
+    if constexpr (WALK) {
+        for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+            if (gate[row / rows_per_gate] == 0) continue;
+            __syncthreads();   // LDS is reused from row to row
+            topk_row_lds<BLOCK, PLAN, DIG>(row, x, ld, n, k, idx_out, idx_ld, val_out, val_ld, tau_out,
+                                           append_from, append_count, plan, max_sweeps);
+        }
+    } else {
+        topk_row_lds<BLOCK, PLAN, DIG>(blockIdx.x, x, ld, n, k, idx_out, idx_ld, val_out, val_ld,
+                                       tau_out, append_from, append_count, plan, max_sweeps);
     }
 }
 
@@ -342,14 +364,21 @@ static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, in
     const size_t lds = ((size_t)items * BLOCK + 2 * (size_t)items * (BLOCK / kWave)) * 4;
     static bool opt_in = false;   // more than 64 KiB of dynamic LDS needs a one-time opt-in
     if (lds > 65536 && !opt_in) {
-        if (hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK, PLAN, DIG>,
+        if (hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK, PLAN, DIG, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess ||
+            hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK, PLAN, DIG, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess)
             return hipGetLastError();
         opt_in = true;
     }
-    hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN, DIG>), dim3(rows), dim3(BLOCK), lds, st, x, ld,
-                       n, k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
-                       rows_per_gate, plan, max_sweeps);
+    if (gate)
+        hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN, DIG, true>), dim3(rows > 1024 ? 1024 : rows),
+                           dim3(BLOCK), lds, st, x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld,
+                           tau_out, append_from, append_count, gate, rows_per_gate, plan, max_sweeps);
+    else
+        hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN, DIG, false>), dim3(rows), dim3(BLOCK), lds,
+                           st, x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from,
+                           append_count, gate, rows_per_gate, plan, max_sweeps);
     return hipGetLastError();
 }
 
