@@ -54,7 +54,7 @@ enum { GRAPHKV_POOL_AVG = 0, GRAPHKV_POOL_MAX = 1 };
  * evicted sets the score to -infinity. */
 enum { GRAPHKV_SIGNAL_DECAY = 0, GRAPHKV_SIGNAL_ENHANCED = 1, GRAPHKV_SIGNAL_EVICTED = 2 };
 /* Kernel family: AUTO picks the bf16 MFMA kernels when the shape allows them
- * (bf16 and d = 128; for scoring also G*w a multiple of 32 and at most 128, and
+ * (bf16 and d = 128; for scoring also G*w a multiple of 32 and at most 256, and
  * w a multiple of 32 with max pooling) and the scalar kernels otherwise; GENERIC
  * forces the scalar kernels (same results up to fp32 rounding order). */
 enum { GRAPHKV_IMPL_AUTO = 0, GRAPHKV_IMPL_GENERIC = 1 };

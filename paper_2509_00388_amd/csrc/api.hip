@@ -28,8 +28,9 @@ struct Workspace {
 };
 
 // The MFMA kernels cover bf16 keys with d = 128.  Scoring additionally needs the
-// stacked query rows G*w to fill whole 32-row MFMA blocks (at most 4 of them);
-// per-query-head votes (max pooling) need w itself to be a multiple of 32.
+// stacked query rows G*w to fill whole 32-row MFMA blocks (at most 256 rows, handled
+// in parts of 128); per-query-head votes (max pooling) need w itself to be a multiple
+// of 32.
 bool mfma_cosine_ok(const graphkv_params *p)
 {
     return p->impl == GRAPHKV_IMPL_AUTO && p->dtype == GRAPHKV_BF16 && p->head_dim == 128;
@@ -39,8 +40,10 @@ bool mfma_score_ok(const graphkv_params *p)
 {
     if (!mfma_cosine_ok(p) || p->n_kv_heads < 1 || p->n_q_heads < p->n_kv_heads) return false;
     const int rows = (p->n_q_heads / p->n_kv_heads) * p->window;
-    if (rows % 32 != 0 || rows > 128) return false;
-    if (p->pool_mode == GRAPHKV_POOL_MAX && p->window % 32 != 0) return false;
+    if (rows % 32 != 0 || rows > 256) return false;
+    // per-query-head votes: a query head's rows must not straddle a 128-row part
+    if (p->pool_mode == GRAPHKV_POOL_MAX && (p->window % 32 != 0 || (rows > 128 && 128 % p->window != 0)))
+        return false;
     return true;
 }
 

@@ -58,7 +58,7 @@ __device__ __forceinline__ void load_queries(const uint16_t *Qb, int l32, int hh
 template <int NB, int SPLIT>
 __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w,
-    int chunk_keys, float c, float *__restrict__ part)
+    int chunk_keys, float c, float *__restrict__ part, int R_total, int row_base)
 {
     constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
@@ -68,12 +68,12 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
     const int stream = wv & 3, row0 = (wv >> 2) * NBW * kBlk;   // first query row of this wave
 
     bf16x8 q[NBW][kSteps];
-    load_queries<NBW>(Qw + ((long)h * R + row0) * kD, l32, hh, q);
+    load_queries<NBW>(Qw + ((long)h * R_total + row_base + row0) * kD, l32, hh, q);
     int last_vis[NBW];   // last key the lane's query of block b may see (causal window)
     float m[NBW], z[NBW];
 #pragma unroll
     for (int b = 0; b < NBW; ++b) {
-        last_vis[b] = P + (row0 + kBlk * b + l32) % w;
+        last_vis[b] = P + (row_base + row0 + kBlk * b + l32) % w;
         m[b] = -INFINITY;
         z[b] = 0.f;
     }
@@ -144,21 +144,25 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
         float mm = sm[0][tid], zz = sz[0][tid];
 #pragma unroll
         for (int u = 1; u < 4; ++u) merge_stats(mm, zz, sm[u][tid], sz[u][tid]);
-        float *o = part + (((long)h * nchunks + chunk) * R + tid) * 2;
+        float *o = part + (((long)h * nchunks + chunk) * R_total + row_base + tid) * 2;
         o[0] = mm;
         o[1] = zz;
     }
 }
 
 // ---------------------------------------------------------------- pass B ---
-// votes: PERQ = false: [Hkv * SPLIT, P], row h*SPLIT + g holds the sum over the
-// query rows of row group g; PERQ = true: [Hkv * G, P], one row per query head
-// (needs every query head's rows inside one row group).
+// votes: PERQ = false: [Hkv * vote_rows, P], row h*vote_rows + vote_row_base + g holds
+// the sum over the query rows of row group g; PERQ = true: [Hkv * G, P], one row per
+// query head (needs every query head's rows inside one row group).
+//
+// Heads with more than 128 stacked query rows are handled in parts of at most 128
+// rows (row_base .. row_base + R of R_total), one launch per part: the keys are then
+// streamed once per part.
 template <int NB, int SPLIT, bool PERQ>
 __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w, int G,
     int chunk_keys, float c, const float *__restrict__ part, int part_chunks,
-    float *__restrict__ votes)
+    float *__restrict__ votes, int R_total, int row_base, int vote_rows, int vote_row_base)
 {
     constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
@@ -173,7 +177,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     if (tid < R) {   // row statistics of the whole head: merge the chunks of pass A
         float mm = -INFINITY, zz = 0.f;
         for (int ch = 0; ch < part_chunks; ++ch) {
-            const float *o = part + (((long)h * part_chunks + ch) * R + tid) * 2;
+            const float *o = part + (((long)h * part_chunks + ch) * R_total + row_base + tid) * 2;
             merge_stats(mm, zz, o[0], o[1]);
         }
         bias_s[tid] = mm + __log2f(zz);   // zz >= 1: the row maximum itself contributes exp2(0)
@@ -181,7 +185,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     __syncthreads();
 
     bf16x8 q[NBW][kSteps];
-    load_queries<NBW>(Qw + ((long)h * R + row0) * kD, l32, hh, q);
+    load_queries<NBW>(Qw + ((long)h * R_total + row_base + row0) * kD, l32, hh, q);
     float bias[NBW][16];
 #pragma unroll
     for (int b = 0; b < NBW; ++b)
@@ -221,9 +225,9 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
 #pragma unroll
             for (int b = 1; b < NBW; ++b) p += pb[b];
             p += __shfl_xor(p, 32, kWave);
-            if (hh == 0 && key < k1) votes[((long)h * SPLIT + grp) * P + key] = p;
+            if (hh == 0 && key < k1) votes[((long)h * vote_rows + vote_row_base + grp) * P + key] = p;
         } else {
-            const int g0 = grp * NBW / bpq;   // first query head of this row group
+            const int g0 = (row_base / kBlk + grp * NBW) / bpq;   // first query head of this row group
 #pragma unroll
             for (int g = 0; g < NBW; ++g) {
                 float p = 0.f;
@@ -271,20 +275,30 @@ MfmaScorePlan mfma_score_plan(int Hkv, int rows, int N)
     return pl;
 }
 
-// Row groups per key stream: 2 when the 32-row blocks split evenly (and, for
-// per-query-head votes, every query head stays inside one group), else 1.
-int mfma_score_split(int G, int w, int per_qhead_votes)
+namespace {
+
+// The stacked query rows of a head are cut into parts of at most 128 rows; a part of
+// nb 32-row blocks runs with 2 row groups per key stream when nb is even (and, for
+// per-query-head votes, every query head stays inside one group), else with 1.
+int part_rows(int R_total, int part) { return R_total - 128 * part < 128 ? R_total - 128 * part : 128; }
+int part_split(int rows, int w, int per_qhead_votes)
 {
-    const int nb = G * w / 32;
+    const int nb = rows / 32;
     if (nb % 2) return 1;
     if (per_qhead_votes && (w / 32) > nb / 2) return 1;
     return 2;
 }
 
+}  // namespace
+
 // Rows of the votes array per KV head.
 int mfma_score_vote_rows(int G, int w, int per_qhead_votes)
 {
-    return per_qhead_votes ? G : mfma_score_split(G, w, 0);
+    if (per_qhead_votes) return G;
+    const int R = G * w;
+    int rows = 0;
+    for (int part = 0; 128 * part < R; ++part) rows += part_split(part_rows(R, part), w, 0);
+    return rows;
 }
 
 hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
@@ -300,14 +314,18 @@ hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int 
     do {                                                                                           \
         if (!allow_big_lds((const void *)score_stats_kernel<NB, SP>)) return hipGetLastError();    \
         hipLaunchKernelGGL((score_stats_kernel<NB, SP>), grid, dim3(256 * SP), 2 * kTileBytes, st, \
-                           K, Q, N, P, w, ck, c, part);                                            \
+                           K, Q, N, P, w, ck, c, part, R, row_base);                               \
     } while (0)
-    switch (R / 32) {
-        case 1: GKV_STATS(1, 1); break;
-        case 2: GKV_STATS(2, 2); break;
-        case 3: GKV_STATS(3, 1); break;
-        case 4: GKV_STATS(4, 2); break;
-        default: return hipErrorInvalidValue;
+    for (int pt = 0; 128 * pt < R; ++pt) {
+        const int row_base = 128 * pt;
+        switch (part_rows(R, pt) / 32) {
+            case 1: GKV_STATS(1, 1); break;
+            case 2: GKV_STATS(2, 2); break;
+            case 3: GKV_STATS(3, 1); break;
+            case 4: GKV_STATS(4, 2); break;
+            default: return hipErrorInvalidValue;
+        }
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     }
 #undef GKV_STATS
     return hipGetLastError();
@@ -316,16 +334,18 @@ hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int 
 template <int NB, int SPLIT>
 static void launch_votes_nb(dim3 grid, const uint16_t *K, const uint16_t *Q, int N, int P, int w, int G,
                             int ck, float c, const float *part, int chunks, int per_q, float *votes,
-                            hipStream_t st)
+                            int R_total, int row_base, int vote_rows, int vote_row_base, hipStream_t st)
 {
     if (per_q) {
         if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, true>)) return;
         hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, true>), grid, dim3(256 * SPLIT),
-                           2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes);
+                           2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
+                           row_base, vote_rows, vote_row_base);
     } else {
         if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, false>)) return;
         hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, false>), grid, dim3(256 * SPLIT),
-                           2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes);
+                           2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
+                           row_base, vote_rows, vote_row_base);
     }
 }
 
@@ -339,14 +359,23 @@ hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int 
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
     dim3 grid(plan.chunks, Hkv);
-    const int split = mfma_score_split(G, w, per_qhead_votes);
-#define GKV_VOTES(NB, SP) launch_votes_nb<NB, SP>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, st)
-    switch (R / 32) {
-        case 1: GKV_VOTES(1, 1); break;
-        case 2: if (split == 2) GKV_VOTES(2, 2); else GKV_VOTES(2, 1); break;
-        case 3: GKV_VOTES(3, 1); break;
-        case 4: if (split == 2) GKV_VOTES(4, 2); else GKV_VOTES(4, 1); break;
-        default: return hipErrorInvalidValue;
+    const int vote_rows = mfma_score_vote_rows(G, w, per_qhead_votes);
+    int vote_row_base = 0;
+#define GKV_VOTES(NB, SP)                                                                             \
+    launch_votes_nb<NB, SP>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, R, \
+                            row_base, vote_rows, vote_row_base, st)
+    for (int pt = 0; 128 * pt < R; ++pt) {
+        const int row_base = 128 * pt, rows = part_rows(R, pt);
+        const int split = part_split(rows, w, per_qhead_votes);
+        switch (rows / 32) {
+            case 1: GKV_VOTES(1, 1); break;
+            case 2: if (split == 2) GKV_VOTES(2, 2); else GKV_VOTES(2, 1); break;
+            case 3: GKV_VOTES(3, 1); break;
+            case 4: if (split == 2) GKV_VOTES(4, 2); else GKV_VOTES(4, 1); break;
+            default: return hipErrorInvalidValue;
+        }
+        vote_row_base += split;
+        if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     }
 #undef GKV_VOTES
     return hipGetLastError();

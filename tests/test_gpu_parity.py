@@ -75,6 +75,20 @@ def test_score_bf16(oracle, impl, pool_mode, n_tokens):
     util.assert_scores_close(s, ref)
 
 
+@pytest.mark.parametrize("pool_mode", [0, 1])
+@pytest.mark.parametrize("G,w", [(4, 64), (2, 96), (6, 32), (1, 128), (3, 32), (2, 32)])
+def test_score_bf16_row_shapes(oracle, G, w, pool_mode):
+    """Stacked query rows G*w from 64 to 256 (parts of 128, odd block counts, query
+    heads that span several 32-row blocks)."""
+    cfg = small_bf16_cfg(n_tokens=1100, window=w, n_kv_heads=2, n_q_heads=2 * G, budget=w + 50)
+    say(f"score rows G={G} w={w} pool_mode={pool_mode}")
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 7)
+    p = util.params_from_cfg(cfg, pool_mode=pool_mode)
+    s = gk.graphkv_score(p, Kd, Qd).cpu().numpy()
+    ref = oracle.score(K, Q, "bf16", cfg.pool_kernel, pool_mode)
+    util.assert_scores_close(s, ref)
+
+
 def test_score_peaked_logits_and_custom_scale(oracle):
     """Large logits (keys x4): the softmax must not overflow; explicit scale."""
     cfg = small_bf16_cfg(key_scale=4.0)

@@ -53,7 +53,8 @@ def test_workspace_size_and_mfma_choice(lib):
     assert not gk.graphkv_uses_mfma(good_params(impl=gk.IMPL_GENERIC))
     assert not gk.graphkv_uses_mfma(good_params(dtype=gk.FP32))
     assert not gk.graphkv_uses_mfma(good_params(head_dim=64))
-    assert not gk.graphkv_uses_mfma(good_params(window=64))   # 4 * 64 rows
+    assert gk.graphkv_uses_mfma(good_params(window=64))        # 4 * 64 = 256 rows: two parts
+    assert not gk.graphkv_uses_mfma(good_params(window=96))    # 384 rows
     # the generic path stores the logits, the MFMA path does not
     assert gk.graphkv_workspace_bytes(good_params(impl=gk.IMPL_GENERIC)) > gk.graphkv_workspace_bytes(p)
 
