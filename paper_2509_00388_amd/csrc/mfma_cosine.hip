@@ -296,6 +296,12 @@ __device__ __forceinline__ uint32_t ord_key_u(uint32_t bits)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Inverse of the map above (the bits of the float a key stands for).
+__device__ __forceinline__ uint32_t ord_key_inv(uint32_t k)
+{
+    return (k & 0x80000000u) ? (k ^ 0x80000000u) : ~k;
+}
+
 // Exact top-m of one source's candidate list by (edge desc, key index asc),
 // written in ascending key order.  One workgroup per (source, head); heads whose
 // overflow flag is set are left to the dense path.
@@ -334,9 +340,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     const uint32_t self = s_self;
     uint32_t *ek = dyn;                 // [cap] order-preserving edge keys (0 = dropped)
     uint32_t *kj = dyn + cap;           // [cap] key indices
-    uint32_t *eq = kj + cap;            // [cap] key indices of the entries equal to the threshold
-    uint32_t *eb = eq + cap;            // [cap] edge bits
-    uint64_t *win = reinterpret_cast<uint64_t *>(eb + cap);   // [m] (key index << 32 | edge bits)
+    uint64_t *win = reinterpret_cast<uint64_t *>(kj + cap);   // [m] (key index << 32 | edge bits)
     uint32_t kmin = 0xffffffffu, kmax = 0u;
     for (int r = tid; r < n; r += 256) {
         int c = 0, local = r;                 // entry r of the concatenated slices
@@ -346,7 +350,6 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
         const uint32_t k = v.y == self ? 0u : ord_key_u(v.x);
         ek[r] = k;
         kj[r] = v.y;
-        eb[r] = v.x;
         if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
     }
 #pragma unroll
@@ -405,24 +408,28 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
         remaining = shift;
     }
     const uint32_t tau = kmin + prefix;
-    // winners above the threshold; entries equal to it are ranked by key index
+    // Winners above the threshold go straight to the list (its order is fixed by the
+    // final ranking).  Entries equal to the threshold all win when exactly `need` of
+    // them exist; otherwise the `need` lowest key indices win, found by a scan that
+    // only ties at the cut ever pay for.
     for (int r = tid; r < n; r += 256) {
         const uint32_t k = ek[r];
-        if (k > tau) {
-            const int at = atomicAdd(&n_win, 1);
-            win[at] = ((uint64_t)kj[r] << 32) | eb[r];
-        } else if (k == tau && k) {
-            eq[atomicAdd(&n_eq, 1)] = kj[r];
-        }
+        if (k > tau) win[atomicAdd(&n_win, 1)] = ((uint64_t)kj[r] << 32) | ord_key_inv(k);
+        else if (k == tau && k) atomicAdd(&n_eq, 1);
     }
     __syncthreads();
     const int ne = n_eq, base = n_win;
+    __syncthreads();
     for (int r = tid; r < n; r += 256) {
-        if (ek[r] == tau && ek[r]) {
+        if (ek[r] == tau && tau) {
             const uint32_t mine = kj[r];
-            uint32_t rank = 0;
-            for (int u = 0; u < ne; ++u) rank += eq[u] < mine;
-            if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | eb[r];
+            if (ne == (int)need) {
+                win[atomicAdd(&n_win, 1)] = ((uint64_t)mine << 32) | ord_key_inv(tau);
+            } else {
+                uint32_t rank = 0;
+                for (int u = 0; u < n; ++u) rank += (ek[u] == tau) & (kj[u] < mine);
+                if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | ord_key_inv(tau);
+            }
         }
     }
     __syncthreads();
@@ -484,7 +491,7 @@ bool mfma_filter_applies(int P, int m)
     // the select kernel's LDS must hold a full list.
     if (P < 8192 || P >= (1 << 24)) return false;
     if (m > mfma_sample_cols(P) / 8) return false;
-    return (size_t)mfma_cand_cap(P, m) * 16 + (size_t)m * 8 + 8 <= 140 * 1024;
+    return (size_t)mfma_cand_cap(P, m) * 8 + (size_t)m * 8 + 8 <= 140 * 1024;
 }
 
 // Key chunks per head of the filter pass and the capacity of one (source, chunk) slice:
@@ -567,7 +574,7 @@ hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t 
 {
     const int cap = mfma_cand_cap(P, m);
     const MfmaFilterGeom g = mfma_filter_geom(Hkv, P, S, m);
-    const size_t lds = (size_t)4 * cap * 4 + (size_t)m * 8;
+    const size_t lds = (size_t)2 * cap * 4 + (size_t)m * 8;
     if (!allow_big_lds((const void *)nbr_select_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(nbr_select_kernel, dim3(S, Hkv), dim3(256), lds, st, (const uint2 *)cand,
                        cand_cnt, overflow, src, S, g.chunks, g.slice_cap, cap, m, nbr, nbr_e);

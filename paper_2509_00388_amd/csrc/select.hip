@@ -415,10 +415,11 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k, int
 hipError_t launch_topk_bound(const float *x, long ld, int n, int rows, int k, float *tau_out,
                              hipStream_t st)
 {
-    // 2 sweeps of 8 bits on rows of at most 4096 entries: the bound is within 1/65536 of the
-    // row's value range below the exact k-th largest.  Longer rows get the exact value.
+    // 2 sweeps (8-bit digits on rows of at most 4096 entries, 11-bit digits up to 32768):
+    // the bound is within 1/65536 of the row's value range below the exact k-th
+    // largest.  Rows too long for the LDS kernels get the exact value.
     return launch_any<false, int>(x, ld, n, rows, k, nullptr, 0, nullptr, 0, tau_out, 0, 0, nullptr,
-                                  1, 0, n <= 4096 ? 2 : 0, st);
+                                  1, 0, n <= 32768 ? 2 : 0, st);
 }
 
 hipError_t launch_topk_final(const float *scores, int P, int rows, const LayerPlan &plan, int w,
