@@ -227,6 +227,11 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     typename std::conditional<PLAN, LayerPlan, int>::type plan, int max_sweeps)
 {
     if constexpr (WALK) {
+        // one round trip settles the usual case of no gate being set at all
+        int any = 0;
+        for (int g = threadIdx.x; g < (rows + rows_per_gate - 1) / rows_per_gate; g += BLOCK)
+            any |= gate[g];
+        if (!__syncthreads_or(any)) return;
         for (int row = blockIdx.x; row < rows; row += gridDim.x) {
             if (gate[row / rows_per_gate] == 0) continue;
             __syncthreads();   // LDS is reused from row to row

@@ -89,67 +89,111 @@ __device__ __forceinline__ void bitonic_sort_lds(uint64_t *keys, int npad, int l
     __syncthreads();
 }
 
-// Eq. 5 for one round, S*m <= 4096.  One workgroup per head.  The (source slot,
-// node, edge) triples are sorted by (node, slot); the first triple of every node
-// multiplies that node's factors in ascending slot order -- sources are stored in
-// ascending index order, so this is Eq. 5's product with a fixed floating-point
-// order -- and the node's score is written once.  No float atomics.  Edge weights
-// and the per-node products stay in LDS, so the only dependent global accesses are
-// the final read-modify-writes of the scores, issued 8 at a time.
-__global__ __launch_bounds__(256) void decay_small_kernel(
-    float *__restrict__ scores, int P, int count, int npad, const int32_t *__restrict__ nbr,
+// Eq. 5 for one round, S*m <= 4096.  One workgroup per head, no sort and no float
+// atomics.  Every (source slot, node, edge) triple t finds its node's cell in an
+// LDS hash table (open addressing; integer compare-and-swap claims a cell).  Then
+// the triples of a node are peeled off in ascending t, one per pass: all pending
+// triples post their t with an integer min, the one that reads its own t back
+// multiplies its factor into the cell's product -- it is the cell's only writer in
+// that pass -- and retires.  Sources are stored in ascending index order, so the
+// product is Eq. 5's with a fixed floating-point order whatever the thread timing.
+// Most nodes have a single triple; the number of passes is the largest number of
+// sources that share one neighbour.  Two sets of min cells alternate so that a
+// winner can reset its cell without a third barrier per pass.
+constexpr int kDecayThreads = 512;
+constexpr int kDecayPer = 4096 / kDecayThreads;
+constexpr uint32_t kNoNode = 0xffffffffu;
+
+__global__ __launch_bounds__(kDecayThreads) void decay_hash_kernel(
+    float *__restrict__ scores, int P, int count, int table_log2, const int32_t *__restrict__ nbr,
     const float *__restrict__ nbr_e, float alpha, int signal)
 {
-    extern __shared__ uint64_t keys[];                 // (node << 32) | triple id   [npad]
-    float *ev = reinterpret_cast<float *>(keys + npad);   // edge of triple id          [npad]
-    float *hf = ev + npad;                                // product at a node's first triple
-    int32_t *hn = reinterpret_cast<int32_t *>(hf + npad); // node there, -1 elsewhere
-    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    extern __shared__ uint32_t table[];
+    const int Tn = 1 << table_log2;
+    uint32_t *cell_node = table;                               // [Tn] node of a cell
+    uint32_t *low0 = table + Tn, *low1 = table + 2 * Tn;       // [Tn] lowest pending triple, two sets
+    float *prod = reinterpret_cast<float *>(table + 3 * Tn);   // [Tn] product of the retired factors
+    const int h = blockIdx.x, tid = threadIdx.x;
     const int32_t *nb = nbr + (long)h * count;
     const float *ne = nbr_e + (long)h * count;
     float *s = scores + (long)h * P;
-    for (int t = tid; t < npad; t += 256) {
-        keys[t] = t < count ? (((uint64_t)(uint32_t)nb[t] << 32) | (uint32_t)t) : ~0ull;
-        ev[t] = t < count ? ne[t] : 0.f;
+
+    uint32_t node[kDecayPer], cell[kDecayPer];
+    float fac[kDecayPer];
+#pragma unroll
+    for (int q = 0; q < kDecayPer; ++q) {
+        const int t = q * kDecayThreads + tid;
+        node[q] = t < count ? (uint32_t)nb[t] : kNoNode;
+        fac[q] = t < count ? signal_factor(ne[t], alpha, signal) : 1.0f;
+    }
+    for (int i = tid; i < Tn; i += kDecayThreads) {
+        cell_node[i] = kNoNode;
+        low0[i] = kNoNode;
+        low1[i] = kNoNode;
+        prod[i] = 1.0f;
     }
     __syncthreads();
-    bitonic_sort_lds(keys, npad, lane, wv);
-    for (int t = tid; t < npad; t += 256) {
-        int32_t node = -1;
-        float f = 1.0f;
-        if (t < count) {
-            const uint32_t nd = (uint32_t)(keys[t] >> 32);
-            if (t == 0 || (uint32_t)(keys[t - 1] >> 32) != nd) {
-                node = (int32_t)nd;
-                for (int u = t; u < count; ++u) {
-                    const uint64_t ku = keys[u];
-                    if ((uint32_t)(ku >> 32) != nd) break;
-                    f *= signal_factor(ev[(uint32_t)ku], alpha, signal);
-                }
+#pragma unroll
+    for (int q = 0; q < kDecayPer; ++q) {
+        cell[q] = 0;
+        if (node[q] != kNoNode) {
+            uint32_t c = (node[q] * 2654435761u) >> (32 - table_log2);
+            while (true) {   // the table has at least twice as many cells as triples
+                const uint32_t prev = atomicCAS(&cell_node[c], kNoNode, node[q]);
+                if (prev == kNoNode || prev == node[q]) break;
+                c = (c + 1) & (Tn - 1);
+            }
+            cell[q] = c;
+        }
+    }
+    __syncthreads();
+    for (int pass = 0;; ++pass) {
+        uint32_t *low = (pass & 1) ? low1 : low0;
+#pragma unroll
+        for (int q = 0; q < kDecayPer; ++q)
+            if (node[q] != kNoNode) atomicMin(&low[cell[q]], (uint32_t)(q * kDecayThreads + tid));
+        __syncthreads();
+        int left = 0;
+#pragma unroll
+        for (int q = 0; q < kDecayPer; ++q) {
+            if (node[q] == kNoNode) continue;
+            if (low[cell[q]] == (uint32_t)(q * kDecayThreads + tid)) {
+                prod[cell[q]] *= fac[q];
+                node[q] = kNoNode;
+            } else {
+                left = 1;
             }
         }
-        hn[t] = node;
-        hf[t] = f;
+        // every compare above is done before a winner resets its cell below; the set
+        // is next used two passes on, behind the barriers of the pass in between
+        const int more = __syncthreads_or(left);
+#pragma unroll
+        for (int q = 0; q < kDecayPer; ++q)
+            if (node[q] == kNoNode && low[cell[q]] == (uint32_t)(q * kDecayThreads + tid))
+                low[cell[q]] = kNoNode;
+        if (!more) break;
     }
     __syncthreads();
-    for (int base = 0; base < npad; base += 256 * 8) {
-        int32_t nd[8];
-        float sv[8];
+    for (int base = 0; base < Tn; base += kDecayThreads * 4) {
+        uint32_t nd[4];
+        float sv[4];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int t = base + q * 256 + tid;
-            nd[q] = t < npad ? hn[t] : -1;
+        for (int q = 0; q < 4; ++q) {
+            const int i = base + q * kDecayThreads + tid;
+            nd[q] = i < Tn ? cell_node[i] : kNoNode;
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) sv[q] = nd[q] >= 0 ? s[nd[q]] : 0.f;
+        for (int q = 0; q < 4; ++q) sv[q] = nd[q] != kNoNode ? s[nd[q]] : 0.f;
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            if (nd[q] >= 0) s[nd[q]] = signal == 2 ? -INFINITY : sv[q] * hf[base + q * 256 + tid];
+        for (int q = 0; q < 4; ++q)
+            if (nd[q] != kNoNode)
+                s[nd[q]] = signal == 2 ? -INFINITY : sv[q] * prod[base + q * kDecayThreads + tid];
     }
 }
 
-// Same as decay_small_kernel for 4096 < S*m <= 16384: only the sort keys fit in LDS
-// (128 KiB), edge weights are fetched from global memory.
+// 4096 < S*m <= 16384: the triples are sorted by (node, slot) in LDS (128 KiB of
+// keys); the first triple of every node multiplies that node's factors in ascending
+// slot order and writes the node's score once.  Edge weights come from global memory.
 __global__ __launch_bounds__(256) void decay_sorted_kernel(
     float *__restrict__ scores, int P, int count, int npad, const int32_t *__restrict__ nbr,
     const float *__restrict__ nbr_e, float alpha, int signal)
@@ -272,17 +316,19 @@ hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32
     const long count = (long)S * m;
     long npad = 512;
     while (npad < count) npad <<= 1;
-    if (npad <= 4096) {
-        static bool small_opt_in = false;
-        const size_t lds = (size_t)npad * 20;
-        if (lds > 65536 && !small_opt_in) {
-            if (hipFuncSetAttribute((const void *)decay_small_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 4096 * 20) != hipSuccess)
+    if (count <= 4096) {
+        int table_log2 = 10;
+        while ((1L << table_log2) < 2 * count) ++table_log2;
+        const size_t lds = ((size_t)16) << table_log2;
+        static bool hash_opt_in = false;
+        if (lds > 65536 && !hash_opt_in) {
+            if (hipFuncSetAttribute((const void *)decay_hash_kernel,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 16) != hipSuccess)
                 return hipGetLastError();
-            small_opt_in = true;
+            hash_opt_in = true;
         }
-        hipLaunchKernelGGL(decay_small_kernel, dim3(Hkv), dim3(256), lds, st, scores, P, (int)count,
-                           (int)npad, nbr, nbr_e, alpha, signal);
+        hipLaunchKernelGGL(decay_hash_kernel, dim3(Hkv), dim3(kDecayThreads), lds, st, scores, P,
+                           (int)count, table_log2, nbr, nbr_e, alpha, signal);
     } else if (npad <= 16384) {
         static bool lds_opt_in = false;   // 128 KiB of dynamic LDS needs a one-time opt-in
         if (npad * 8 > 65536 && !lds_opt_in) {
