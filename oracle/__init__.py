@@ -104,9 +104,21 @@ def cosine_row(Kc, dtype: str, window: int, h: int, i: int) -> np.ndarray:
 def propagate(Kc, dtype: str, window: int, s: np.ndarray, S: int, m: int, T: int,
               alpha: float = 1.0, reselect: int = 1, signal: int = 0,
               forced_src: Optional[np.ndarray] = None, debug: bool = False):
-    """Returns the refined scores (a new float64 array); with debug=True also a
-    dict with src [T,H,S], nbr [T,H,S,m], e [T,H,S,m], gap_src [T,H], gap_nbr [T,H,S]."""
-    _check_storage(Kc, dtype)
+    """Key-to-key edges (Eq. 1).  Returns the refined scores (a new float64 array); with
+    debug=True also a dict with src [T,H,S], nbr [T,H,S,m], e [T,H,S,m], gap_src [T,H],
+    gap_nbr [T,H,S]."""
+    return propagate_edges(Kc, Kc, dtype, window, s, S, m, T, alpha, reselect, signal,
+                           forced_src, debug)
+
+
+def propagate_edges(A, Bm, dtype: str, window: int, s: np.ndarray, S: int, m: int, T: int,
+                    alpha: float = 1.0, reselect: int = 1, signal: int = 0,
+                    forced_src: Optional[np.ndarray] = None, debug: bool = False):
+    """Edges e_ij = cos(A[h,i,:], Bm[h,j,:]): the source's feature from A, the other
+    node's from Bm (the Discussion's other pairings).  Same returns as propagate."""
+    _check_storage(A, dtype); _check_storage(Bm, dtype)
+    assert A.shape == Bm.shape
+    Kc = A
     Hkv, N, d = Kc.shape
     P = N - window
     s = np.array(s, dtype=np.float64, order="C", copy=True)
@@ -120,14 +132,14 @@ def propagate(Kc, dtype: str, window: int, s: np.ndarray, S: int, m: int, T: int
     if forced_src is not None:
         forced_src = np.ascontiguousarray(forced_src, dtype=np.int32)
         assert forced_src.shape == (T, Hkv, S)
-    rc = lib().gkv_oracle_propagate(
-        _p(Kc), _i(_DT[dtype]), _i(Hkv), _i(d), _i(N), _i(window), _i(S), _i(m), _i(T),
+    rc = lib().gkv_oracle_propagate_edges(
+        _p(A), _p(Bm), _i(_DT[dtype]), _i(Hkv), _i(d), _i(N), _i(window), _i(S), _i(m), _i(T),
         _d(alpha), _i(reselect), _i(signal), _p(s), _p(forced_src),
         _p(dbg["src"]) if dbg else _p(None), _p(dbg["nbr"]) if dbg else _p(None),
         _p(dbg["e"]) if dbg else _p(None), _p(dbg["gap_src"]) if dbg else _p(None),
         _p(dbg["gap_nbr"]) if dbg else _p(None))
     if rc:
-        raise ValueError("gkv_oracle_propagate rejected the arguments")
+        raise ValueError("gkv_oracle_propagate_edges rejected the arguments")
     if debug:
         for k in dbg:
             dbg[k] = dbg[k][:T]
@@ -163,9 +175,10 @@ def gather(Kc, Vc, dtype: str, idx: np.ndarray):
 
 def compress(Kc, Vc, Qw, dtype: str, pool_kernel: int, budget: int, S: int, m: int, T: int,
              alpha: float = 1.0, reselect: int = 1, signal: int = 0, pool_mode: int = 0,
-             scale: float = 0.0):
+             scale: float = 0.0, edge_mode: int = 0):
     """The whole pass for one layer.  Returns a dict: Kout, Vout, idx, scores
-    (s^(T), float64), s0 (float64), min_gap (source cut, neighbour cut, final cut)."""
+    (s^(T), float64), s0 (float64), min_gap (source cut, neighbour cut, final cut).
+    edge_mode: 0 key-key edges, 1 key-value, 2 value-value."""
     _check_storage(Kc, dtype); _check_storage(Vc, dtype); _check_storage(Qw, dtype)
     Hkv, N, d = Kc.shape
     Hq, w, _ = Qw.shape
@@ -179,7 +192,7 @@ def compress(Kc, Vc, Qw, dtype: str, pool_kernel: int, budget: int, S: int, m: i
     rc = lib().gkv_oracle_compress(
         _p(Kc), _p(Vc), _p(Qw), _i(_DT[dtype]), _i(Hkv), _i(Hq), _i(d), _i(N), _i(w),
         _i(pool_kernel), _i(pool_mode), _d(scale), _i(budget), _i(S), _i(m), _i(T), _d(alpha),
-        _i(reselect), _i(signal), _p(Kout), _p(Vout), _p(idx), _p(sc), _p(s0), _p(mg))
+        _i(reselect), _i(signal), _i(edge_mode), _p(Kout), _p(Vout), _p(idx), _p(sc), _p(s0), _p(mg))
     if rc:
         raise ValueError("gkv_oracle_compress rejected the arguments")
     return dict(Kout=Kout, Vout=Vout, idx=idx, scores=sc, s0=s0, min_gap=mg)

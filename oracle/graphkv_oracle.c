@@ -57,6 +57,15 @@
  *       signal 1 multiplies by (1 + alpha*e), signal 2 sets neighbours to -inf.
  *   R13 Source lists and neighbour lists are reported in ascending index order
  *       (their order carries no meaning in the paper).
+ *   R14 The Discussion ("Exploration of similarity for Graph Edge") also tries
+ *       query-to-key, query-to-query, key-to-value and value-to-value
+ *       similarities as edges, without formulas.  Reading: e_ij = cosine of
+ *       (row i of a first tensor, row j of a second tensor), the first tensor
+ *       giving the source's feature and the second the other node's; key-to-key
+ *       is first = second = keys.  edge_mode of the whole-pass function:
+ *       0 key-key, 1 key-value, 2 value-value (pairings with queries need the
+ *       prefix tokens' queries, which the pass does not receive; the two-tensor
+ *       propagate takes any pair).
  *
  * Arithmetic: every product, sum, exp, sqrt and division is done in double on
  * the exact values of the stored fp32/bf16 inputs.  No blocking, no fusion.
@@ -230,22 +239,25 @@ int gkv_oracle_score_knorm(const void *Kc, int dtype, int32_t Hkv, int32_t d,
 
 /* ------------------------------------------------------- stages II, III --- */
 
-/* Eq. 1 for one source i of head h against every prefix node; e[i] itself is
- * left at 0 and must be skipped by the caller.  Reading R11 for zero norms. */
-void gkv_oracle_cosine_row(const void *Kc, int dtype, int32_t d, int32_t N,
-                           int32_t P, int32_t h, int32_t i, double *e_out)
+/* Eq. 1 for one source i of head h against every prefix node, with the feature of
+ * the source taken from A and the feature of the other node from Bm (both
+ * [Hkv,N,d]; reading R14: A = Bm = keys is the paper's main definition, the
+ * Discussion's other pairings pass other tensors).  e[i] itself is left at 0 and
+ * must be skipped by the caller.  Reading R11 for zero norms. */
+void gkv_oracle_cosine_row2(const void *A, const void *Bm, int dtype, int32_t d, int32_t N,
+                            int32_t P, int32_t h, int32_t i, double *e_out)
 {
     double ni = 0.0;
     for (int32_t c = 0; c < d; ++c) {
-        double v = load_elem(Kc, dtype, ((size_t)h * N + i) * d + c);
+        double v = load_elem(A, dtype, ((size_t)h * N + i) * d + c);
         ni += v * v;
     }
     ni = sqrt(ni);
     for (int32_t j = 0; j < P; ++j) {
         double dot = 0.0, nj = 0.0;
         for (int32_t c = 0; c < d; ++c) {
-            double a = load_elem(Kc, dtype, ((size_t)h * N + i) * d + c);
-            double b = load_elem(Kc, dtype, ((size_t)h * N + j) * d + c);
+            double a = load_elem(A, dtype, ((size_t)h * N + i) * d + c);
+            double b = load_elem(Bm, dtype, ((size_t)h * N + j) * d + c);
             dot += a * b;
             nj += b * b;
         }
@@ -253,6 +265,12 @@ void gkv_oracle_cosine_row(const void *Kc, int dtype, int32_t d, int32_t N,
         e_out[j] = (ni == 0.0 || nj == 0.0) ? 0.0 : dot / (ni * nj);
     }
     e_out[i] = 0.0;
+}
+
+void gkv_oracle_cosine_row(const void *Kc, int dtype, int32_t d, int32_t N,
+                           int32_t P, int32_t h, int32_t i, double *e_out)
+{
+    gkv_oracle_cosine_row2(Kc, Kc, dtype, d, N, P, h, i, e_out);
 }
 
 /*
@@ -263,13 +281,15 @@ void gkv_oracle_cosine_row(const void *Kc, int dtype, int32_t d, int32_t N,
  *     what was picked, ascending index order (R13), and the edge weights.
  *   gap_src [T,Hkv], gap_nbr [T,Hkv,S] (optional): relative gaps at the cuts.
  * signal: 0 decay (Eq. 5), 1 enhanced, 2 evicted (R12).
+ * A, Bm: the tensors whose rows enter Eq. 1 for the source and for the other
+ *   node (R14).
  */
-int gkv_oracle_propagate(const void *Kc, int dtype, int32_t Hkv, int32_t d,
-                         int32_t N, int32_t w, int32_t S, int32_t m, int32_t T,
-                         double alpha, int32_t reselect, int32_t signal,
-                         double *s, const int32_t *forced_src,
-                         int32_t *dbg_src, int32_t *dbg_nbr, double *dbg_e,
-                         double *gap_src, double *gap_nbr)
+int gkv_oracle_propagate_edges(const void *A, const void *Bm, int dtype, int32_t Hkv, int32_t d,
+                               int32_t N, int32_t w, int32_t S, int32_t m, int32_t T,
+                               double alpha, int32_t reselect, int32_t signal,
+                               double *s, const int32_t *forced_src,
+                               int32_t *dbg_src, int32_t *dbg_nbr, double *dbg_e,
+                               double *gap_src, double *gap_nbr)
 {
     const int32_t P = N - w;
     if (Hkv < 1 || d < 1 || P < 1 || T < 0) return -1;
@@ -299,7 +319,7 @@ int gkv_oracle_propagate(const void *Kc, int dtype, int32_t Hkv, int32_t d,
                 /* Eq. 1 + Eq. 3: edges of each source and its m nearest nodes */
                 for (int32_t a = 0; a < S; ++a) {
                     double gn = INFINITY;
-                    gkv_oracle_cosine_row(Kc, dtype, d, N, P, h, src[a], erow);
+                    gkv_oracle_cosine_row2(A, Bm, dtype, d, N, P, h, src[a], erow);
                     gkv_oracle_topk(erow, P, m, src[a], nbr + (size_t)a * m, &gn);
                     for (int32_t u = 0; u < m; ++u)
                         ev[(size_t)a * m + u] = erow[nbr[(size_t)a * m + u]];
@@ -333,6 +353,18 @@ int gkv_oracle_propagate(const void *Kc, int dtype, int32_t Hkv, int32_t d,
         free(src); free(nbr); free(ev); free(erow); free(f); free(hit);
     }
     return 0;
+}
+
+/* Key-to-key edges: the paper's main definition (Eq. 1). */
+int gkv_oracle_propagate(const void *Kc, int dtype, int32_t Hkv, int32_t d,
+                         int32_t N, int32_t w, int32_t S, int32_t m, int32_t T,
+                         double alpha, int32_t reselect, int32_t signal,
+                         double *s, const int32_t *forced_src,
+                         int32_t *dbg_src, int32_t *dbg_nbr, double *dbg_e,
+                         double *gap_src, double *gap_nbr)
+{
+    return gkv_oracle_propagate_edges(Kc, Kc, dtype, Hkv, d, N, w, S, m, T, alpha, reselect, signal,
+                                      s, forced_src, dbg_src, dbg_nbr, dbg_e, gap_src, gap_nbr);
 }
 
 /* ------------------------------------------------------------ stage IV --- */
@@ -382,7 +414,7 @@ int gkv_oracle_compress(const void *Kc, const void *Vc, const void *Qw, int dtyp
                         int32_t Hkv, int32_t Hq, int32_t d, int32_t N, int32_t w,
                         int32_t pool_kernel, int32_t pool_mode, double scale,
                         int32_t B, int32_t S, int32_t m, int32_t T, double alpha,
-                        int32_t reselect, int32_t signal,
+                        int32_t reselect, int32_t signal, int32_t edge_mode,
                         void *Kout, void *Vout, int32_t *idx,
                         double *scores_out, double *s0_out, double *min_gap)
 {
@@ -395,8 +427,9 @@ int gkv_oracle_compress(const void *Kc, const void *Vc, const void *Qw, int dtyp
     int rc = gkv_oracle_score(Kc, Qw, dtype, Hkv, Hq, d, N, w, pool_kernel, pool_mode, scale, s, NULL);
     if (rc == 0 && s0_out) memcpy(s0_out, s, (size_t)Hkv * P * sizeof(double));
     if (rc == 0 && T > 0)
-        rc = gkv_oracle_propagate(Kc, dtype, Hkv, d, N, w, S, m, T, alpha, reselect, signal,
-                                  s, NULL, NULL, NULL, NULL, gs, gn);
+        rc = gkv_oracle_propagate_edges(edge_mode == 2 ? Vc : Kc, edge_mode == 0 ? Kc : Vc, dtype,
+                                        Hkv, d, N, w, S, m, T, alpha, reselect, signal,
+                                        s, NULL, NULL, NULL, NULL, gs, gn);
     if (rc == 0) rc = gkv_oracle_select(s, Hkv, N, w, B, idx, gf);
     if (rc == 0) rc = gkv_oracle_gather(Kc, Vc, dtype, Hkv, d, N, B, idx, Kout, Vout);
     if (rc == 0 && scores_out) memcpy(scores_out, s, (size_t)Hkv * P * sizeof(double));

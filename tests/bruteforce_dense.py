@@ -14,23 +14,26 @@ def stable_topk(x, k):
     return [int(i) for i in order[:k]]
 
 
-def dense_cosine(K):
-    """Eq. 1 for every pair."""
+def dense_cosine(K, other=None):
+    """Eq. 1 for every pair: E[i, j] = cos(K[i], other[j]); other = K if not given."""
     K = np.asarray(K, dtype=np.float64)
-    nrm = np.sqrt((K * K).sum(axis=1))
-    E = np.zeros((K.shape[0], K.shape[0]))
+    other = K if other is None else np.asarray(other, dtype=np.float64)
+    na = np.sqrt((K * K).sum(axis=1))
+    nb = np.sqrt((other * other).sum(axis=1))
+    E = np.zeros((K.shape[0], other.shape[0]))
     for i in range(K.shape[0]):
-        for j in range(K.shape[0]):
-            if nrm[i] > 0 and nrm[j] > 0:
-                E[i, j] = float(K[i] @ K[j]) / (nrm[i] * nrm[j])
+        for j in range(other.shape[0]):
+            if na[i] > 0 and nb[j] > 0:
+                E[i, j] = float(K[i] @ other[j]) / (na[i] * nb[j])
     return E
 
 
-def propagate_dense(K, s, S, m, T, alpha=1.0, reselect=1, signal=0):
-    """K [P,d] float64 (prefix keys of one head), s [P].  Returns s^(T)."""
+def propagate_dense(K, s, S, m, T, alpha=1.0, reselect=1, signal=0, other=None):
+    """K [P,d] float64 (prefix keys of one head), s [P].  Returns s^(T).  With `other`
+    [P,d] the edge from source i to node j is cos(K[i], other[j])."""
     s = np.array(s, dtype=np.float64)
     P = s.size
-    E = dense_cosine(K)
+    E = dense_cosine(K, other)
     nbrs = None
     for t in range(T):
         if t == 0 or reselect:

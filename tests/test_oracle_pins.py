@@ -346,6 +346,85 @@ def test_compress_is_the_staged_pipeline(oracle):
     assert out["min_gap"][2] == gap.min()
 
 
+# ---- edges between two different tensors (Discussion, "Exploration of similarity
+# ---- for Graph Edge": key-to-value, value-to-value, query-to-key ...) --------------
+
+@pytest.mark.parametrize("reselect", [0, 1])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_two_tensor_edges_equal_dense_bruteforce(oracle, reselect, dtype):
+    """e_ij = cos(A_i, B_j) on the full P x P graph, literal set semantics, tiny P."""
+    cfg = tiny_cfg(dtype=dtype, n_tokens=48, window=6)
+    K, V, _ = synth.make_layer(cfg, 2)
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    for (S, m, T, alpha) in [(4, 3, 1, 1.0), (5, 6, 3, 0.6), (42, 2, 2, 0.9)]:
+        s = oracle.propagate_edges(K, V, dtype, cfg.window, s0, S, m, T, alpha, reselect)
+        for h in range(cfg.n_kv_heads):
+            ref = bf.propagate_dense(f64(K[h], dtype)[:cfg.n_prefix], s0[h], S, m, T, alpha,
+                                     reselect, 0, other=f64(V[h], dtype)[:cfg.n_prefix])
+            np.testing.assert_allclose(s[h], ref, rtol=1e-12, atol=0)
+    # the pairing is not symmetric: swapping the tensors changes the result
+    a = oracle.propagate_edges(K, V, dtype, cfg.window, s0, 4, 3, 1)
+    b = oracle.propagate_edges(V, K, dtype, cfg.window, s0, 4, 3, 1)
+    assert not np.allclose(a, b)
+
+
+def test_two_tensor_edges_special_cases(oracle):
+    cfg = tiny_cfg(dtype="fp32")
+    K, V, _ = synth.make_layer(cfg, 4)
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    # both tensors the keys: Eq. 1 itself, bit for bit
+    assert np.array_equal(oracle.propagate_edges(K, K, "fp32", cfg.window, s0, 4, 3, 2, 0.7),
+                          oracle.propagate(K, "fp32", cfg.window, s0, 4, 3, 2, 0.7))
+    # value-to-value edges are key-to-key edges of a cache whose keys are the values
+    assert np.array_equal(oracle.propagate_edges(V, V, "fp32", cfg.window, s0, 4, 3, 2, 0.7),
+                          oracle.propagate(V, "fp32", cfg.window, s0, 4, 3, 2, 0.7))
+    # a cosine ignores the length of either vector: scale rows of both tensors independently
+    rng = np.random.default_rng(3)
+    ca = (2.0 ** rng.integers(-3, 4, size=K.shape[:2])).astype(np.float32)[..., None]
+    cb = (2.0 ** rng.integers(-3, 4, size=K.shape[:2])).astype(np.float32)[..., None]
+    ref = oracle.propagate_edges(K, V, "fp32", cfg.window, s0, 4, 3, 2, 0.7)
+    assert np.array_equal(oracle.propagate_edges(K * ca, V * cb, "fp32", cfg.window, s0, 4, 3, 2, 0.7), ref)
+    # second tensor = first tensor with negated rows: every edge flips sign, so a source's
+    # neighbours under (K, -K) with the enhanced signal (1 + e') see the factor (1 - e) of
+    # the nodes that are *least* similar under (K, K)
+    e_kk = oracle.cosine_row(K, "fp32", cfg.window, 0, 5)
+    dbg = oracle.propagate_edges(K, -K, "fp32", cfg.window, s0, 4, 3, 1, forced_src=None, debug=True)[1]
+    i = int(dbg["src"][0, 0, 0])
+    e_i = oracle.cosine_row(K, "fp32", cfg.window, 0, i)
+    np.testing.assert_allclose(dbg["e"][0, 0, 0], -e_i[dbg["nbr"][0, 0, 0]], rtol=1e-15)
+    others = np.delete(np.arange(cfg.n_prefix), i)
+    lowest = others[np.argsort(e_i[others], kind="stable")[:3]]
+    assert sorted(lowest.tolist()) == dbg["nbr"][0, 0, 0].tolist()
+    assert e_kk.shape == (cfg.n_prefix,)
+
+
+def test_hand_worked_two_tensor_example(oracle):
+    """d = 2, P = 4, source 0 (highest score), m = 1, alpha = 1.  A rows: a0 = (1,0);
+    B rows: b1 = (0,1) -> e = 0, b2 = (3,4) -> e = 0.6, b3 = (1,1) -> e = 1/sqrt 2.
+    Node 3 is the neighbour, s3 <- s3 (1 - 1/sqrt 2).  With A = B = A the neighbour of
+    a0 = (1,0) among a1 = (2,0), a2 = (0,1), a3 = (1,1) is node 1 (e = 1), s1 <- 0."""
+    A = np.array([[[1, 0], [2, 0], [0, 1], [1, 1], [1, 0]]], np.float32)      # last row: window
+    Bm = np.array([[[5, 5], [0, 1], [3, 4], [1, 1], [1, 0]]], np.float32)
+    s0 = np.array([[1.0, 0.5, 0.4, 0.3]])
+    s = oracle.propagate_edges(A, Bm, "fp32", 1, s0, 1, 1, 1, 1.0)
+    np.testing.assert_allclose(s[0], [1.0, 0.5, 0.4, 0.3 * (1 - 1 / np.sqrt(2))], rtol=1e-15)
+    s = oracle.propagate_edges(A, A, "fp32", 1, s0, 1, 1, 1, 1.0)
+    np.testing.assert_allclose(s[0], [1.0, 0.0, 0.4, 0.3], atol=1e-16)
+
+
+def test_compress_edge_modes(oracle):
+    """Whole pass with key-value / value-value edges = the staged pipeline with those tensors."""
+    cfg = tiny_cfg(dtype="bf16")
+    K, V, Q = synth.make_layer(cfg, 6)
+    s0 = oracle.score(K, Q, "bf16", cfg.pool_kernel)
+    for mode, (A, Bm) in {0: (K, K), 1: (K, V), 2: (V, V)}.items():
+        out = oracle.compress(K, V, Q, "bf16", cfg.pool_kernel, cfg.budget, 4, 3, 2, alpha=0.9,
+                              edge_mode=mode)
+        sT = oracle.propagate_edges(A, Bm, "bf16", cfg.window, s0, 4, 3, 2, 0.9)
+        idx, _ = oracle.select(sT, cfg.n_tokens, cfg.window, cfg.budget)
+        assert np.array_equal(out["scores"], sT) and np.array_equal(out["idx"], idx)
+
+
 def test_propagation_reduces_similarity_of_top_tokens(oracle):
     """Statistical smoke, not a gate on exact numbers: on clustered keys the mean
     pairwise cosine among the 10 best tokens drops after propagation (the
