@@ -58,6 +58,13 @@ enum { GRAPHKV_SIGNAL_DECAY = 0, GRAPHKV_SIGNAL_ENHANCED = 1, GRAPHKV_SIGNAL_EVI
  * w a multiple of 32 with max pooling) and the scalar kernels otherwise; GENERIC
  * forces the scalar kernels (same results up to fp32 rounding order). */
 enum { GRAPHKV_IMPL_AUTO = 0, GRAPHKV_IMPL_GENERIC = 1 };
+/* Which tensors the edges of the whole-pass calls are cosines of (Discussion,
+ * "Exploration of similarity for Graph Edge"): e_ij = cos(x_i, y_j) with x the
+ * source's row and y the other node's row.  KK is Eq. 1 (keys, keys); KV takes the
+ * source's key and the other node's value; VV values on both sides.  Pairings
+ * with queries need the prefix tokens' queries, which these calls do not
+ * receive: graphkv_propagate_edges takes any two tensors. */
+enum { GRAPHKV_EDGES_KK = 0, GRAPHKV_EDGES_KV = 1, GRAPHKV_EDGES_VV = 2 };
 
 typedef struct graphkv_params {
     int32_t n_kv_heads;    /* H_kv >= 1                                              */
@@ -80,6 +87,7 @@ typedef struct graphkv_params {
     float   softmax_scale; /* 0 selects 1/sqrt(d)                                    */
     int32_t signal;        /* GRAPHKV_SIGNAL_*                                       */
     int32_t impl;          /* GRAPHKV_IMPL_*                                         */
+    int32_t edges;         /* GRAPHKV_EDGES_* (compress calls only)                  */
 } graphkv_params;
 
 /* Bytes of scratch any of the calls below needs for these params (0 if the
@@ -132,6 +140,19 @@ int32_t graphkv_propagate(const graphkv_params *p, const void *Kc, float *scores
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The same rounds with edges e_ij = cosine of row i of Ac and row j of Bc: the
+ * source's feature comes from the first tensor, the other node's from the second
+ * (Discussion, "Exploration of similarity for Graph Edge": query-to-key,
+ * query-to-query, key-to-value, value-to-value similarities as decay signals; the
+ * paper gives no formula, this is the reading taken).  Ac = Bc = keys is
+ * graphkv_propagate.
+ *   Ac, Bc  [H_kv, N, d]  in  of type p->dtype; everything else as above
+ */
+int32_t graphkv_propagate_edges(const graphkv_params *p, const void *Ac, const void *Bc,
+                                float *scores, int32_t *dbg_src, int32_t *dbg_nbr, float *dbg_e,
+                                void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Stage IV, selection ("Decay Signal Propagation", closing paragraph: the k_l
  * tokens with the highest refined score are kept).  idx[h, 0..B-w) = the B - w
  * best prefix tokens in ascending order (ties to the lowest index), followed by
@@ -150,7 +171,7 @@ int32_t graphkv_select(const graphkv_params *p, const float *scores, int32_t *id
  *   Kout, Vout [H_kv, B, d]  out  rows idx[h, t] of Kc / Vc, byte copies
  *   idx        [H_kv, B]     out  int32
  *   scores_out [H_kv, P]     out, optional (NULL): refined scores s^(T), fp32
- * B = N gives the identity copy.
+ * B = N gives the identity copy.  p->edges picks the tensors behind the edges.
  */
 int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc,
                          const void *Qw, void *Kout, void *Vout, int32_t *idx,

@@ -33,6 +33,7 @@ def lib() -> ctypes.CDLL:
                      "gkv_oracle_select", "gkv_oracle_gather", "gkv_oracle_compress"):
             getattr(_lib, name).restype = ctypes.c_int
         _lib.gkv_oracle_cosine_row.restype = None
+        _lib.gkv_oracle_cosine_row2.restype = None
     return _lib
 
 
@@ -92,12 +93,17 @@ def score_knorm(Kc, dtype: str, window: int) -> np.ndarray:
     return s
 
 
-def cosine_row(Kc, dtype: str, window: int, h: int, i: int) -> np.ndarray:
+def cosine_row(Kc, dtype: str, window: int, h: int, i: int, other=None) -> np.ndarray:
+    """Edges of source i of head h to every prefix node (Eq. 1); with `other` the
+    other node's row is taken from that tensor instead of Kc."""
     _check_storage(Kc, dtype)
+    other = Kc if other is None else other
+    _check_storage(other, dtype)
     Hkv, N, d = Kc.shape
     P = N - window
     e = np.empty(P, dtype=np.float64)
-    lib().gkv_oracle_cosine_row(_p(Kc), _i(_DT[dtype]), _i(d), _i(N), _i(P), _i(h), _i(i), _p(e))
+    lib().gkv_oracle_cosine_row2(_p(Kc), _p(other), _i(_DT[dtype]), _i(d), _i(N), _i(P), _i(h), _i(i),
+                                 _p(e))
     return e
 
 

@@ -21,11 +21,12 @@ FP32, BF16 = 0, 1
 POOL_AVG, POOL_MAX = 0, 1
 SIGNAL_DECAY, SIGNAL_ENHANCED, SIGNAL_EVICTED = 0, 1, 2
 IMPL_AUTO, IMPL_GENERIC = 0, 1
+EDGES_KK, EDGES_KV, EDGES_VV = 0, 1, 2
 
 EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "graphkv_propagate",
            "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma",
            "graphkv_profile_begin", "graphkv_profile_end", "graphkv_kernel_name",
-           "graphkv_workspace_bytes_batched", "graphkv_compress_batched")
+           "graphkv_workspace_bytes_batched", "graphkv_compress_batched", "graphkv_propagate_edges")
 N_KERNELS = 20
 
 
@@ -42,6 +43,7 @@ class _CParams(ctypes.Structure):
         ("n_sources", ctypes.c_int32), ("n_neighbors", ctypes.c_int32), ("rounds", ctypes.c_int32),
         ("decay", ctypes.c_float), ("reselect", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float), ("signal", ctypes.c_int32), ("impl", ctypes.c_int32),
+        ("edges", ctypes.c_int32),
     ]
 
 
@@ -65,6 +67,7 @@ class Params:
     softmax_scale: float = 0.0
     signal: int = SIGNAL_DECAY
     impl: int = IMPL_AUTO
+    edges: int = EDGES_KK
 
     @property
     def n_prefix(self) -> int:
@@ -102,6 +105,8 @@ def load_library() -> ctypes.CDLL:
     lib.graphkv_score_knorm.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.graphkv_propagate.restype = i32
     lib.graphkv_propagate.argtypes = [pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.graphkv_propagate_edges.restype = i32
+    lib.graphkv_propagate_edges.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.graphkv_select.restype = i32
     lib.graphkv_select.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.graphkv_compress.restype = i32
@@ -187,6 +192,16 @@ def graphkv_propagate(p: Params, Kc, scores, dbg_src=None, dbg_nbr=None, dbg_e=N
     _check(load_library().graphkv_propagate(ctypes.byref(cp), _ptr(Kc), _ptr(scores), _ptr(dbg_src),
                                             _ptr(dbg_nbr), _ptr(dbg_e), _ptr(ws), ws.numel(),
                                             _stream()))
+    return scores
+
+
+def graphkv_propagate_edges(p: Params, Ac, Bc, scores, dbg_src=None, dbg_nbr=None, dbg_e=None, ws=None):
+    """The same rounds with edges cos(Ac[h, i], Bc[h, j]) (source's row from Ac)."""
+    ws = alloc_workspace(p, Ac.device) if ws is None else ws
+    cp = p.c()
+    _check(load_library().graphkv_propagate_edges(ctypes.byref(cp), _ptr(Ac), _ptr(Bc), _ptr(scores),
+                                                  _ptr(dbg_src), _ptr(dbg_nbr), _ptr(dbg_e), _ptr(ws),
+                                                  ws.numel(), _stream()))
     return scores
 
 

@@ -58,6 +58,7 @@ bool base_ok(const graphkv_params *p)
     if (p->impl != GRAPHKV_IMPL_AUTO && p->impl != GRAPHKV_IMPL_GENERIC) return false;
     if (p->rounds < 0) return false;
     if (p->signal < 0 || p->signal > 2) return false;
+    if (p->edges < GRAPHKV_EDGES_KK || p->edges > GRAPHKV_EDGES_VV) return false;
     if (!(p->decay >= 0.f && p->decay <= 1.f)) return false;
     if (p->reselect != 0 && p->reselect != 1) return false;
     if (p->rounds > 0) {
@@ -218,8 +219,9 @@ bool propagation_is_noop(const graphkv_params *p)
     return p->rounds == 0 || (p->decay == 0.f && p->signal != GRAPHKV_SIGNAL_EVICTED);
 }
 
-int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W, const void *Kc,
-                      float *scores, int32_t *dbg_src, int32_t *dbg_nbr, float *dbg_e, void *ws,
+// Ac: tensor of the sources' rows, Kc: tensor of the other nodes' rows (Eq. 1: both the keys).
+int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W, const void *Ac,
+                      const void *Kc, float *scores, int32_t *dbg_src, int32_t *dbg_nbr, float *dbg_e, void *ws,
                       hipStream_t st)
 {
     if (propagation_is_noop(p)) return GRAPHKV_OK;
@@ -247,26 +249,26 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                 void *cand = at<char>(ws, W.cand);
                 const int ps = mfma_sample_cols(D.P);
                 GKV_LAUNCH(GRAPHKV_K_COSINE_SAMPLE,
-                           launch_mfma_cosine_sample(Kc, D.H, D.N, D.P, D.S, src, Es, ovf, st));
+                           launch_mfma_cosine_sample(Ac, Kc, D.H, D.N, D.P, D.S, src, Es, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_TOPK_BOUND,
                            launch_topk_bound(Es, ps, ps, D.H * D.S, D.m, tau, st));
                 GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
-                           launch_mfma_cosine_filter(Kc, D.H, D.N, D.P, D.S, D.m, src, tau, cand, cnt,
+                           launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, tau, cand, cnt,
                                                      ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
                            launch_nbr_select(cand, cnt, ovf, src, D.H, D.P, D.S, D.m, nbr, ev, st));
                 // heads whose lists overflowed are redone through the dense block
-                GKV_LAUNCH(GRAPHKV_K_REDO_COSINE, launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, ovf, st));
+                GKV_LAUNCH(GRAPHKV_K_REDO_COSINE, launch_mfma_cosine(Ac, Kc, D.H, D.N, D.P, D.S, src, E, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_REDO_TOPK,
                            launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, nullptr, 0, 0,
                                             ovf, D.S, st));
             } else {
                 // Eq. 1: edges from every source to every node
                 if (D.mfma_cosine)
-                    GKV_LAUNCH(GRAPHKV_K_COSINE, launch_mfma_cosine(Kc, D.H, D.N, D.P, D.S, src, E, nullptr, st));
+                    GKV_LAUNCH(GRAPHKV_K_COSINE, launch_mfma_cosine(Ac, Kc, D.H, D.N, D.P, D.S, src, E, nullptr, st));
                 else
                     GKV_LAUNCH(GRAPHKV_K_GENERIC_COSINE,
-                               launch_generic_cosine(Kc, p->dtype, D.H, D.d, D.N, D.P, D.S, src, E, st));
+                               launch_generic_cosine(Ac, Kc, p->dtype, D.H, D.d, D.N, D.P, D.S, src, E, st));
                 // Eq. 3: neighbourhoods
                 GKV_LAUNCH(GRAPHKV_K_TOPK_NEIGHBORS,
                            launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, nullptr, 0, 0,
@@ -319,7 +321,10 @@ int32_t run_compress(const graphkv_params *p, int n_layers, const int32_t *budge
     const LayerPlan plan = make_plan(p, n_layers, budgets, &max_budget);
     float *scores = scores_out ? scores_out : at<float>(ws, W.scores);
     if (int32_t rc = run_score(p, D, W, Kc, Qw, scores, ws, st)) return rc;
-    if (int32_t rc = run_propagate(p, D, W, Kc, scores, nullptr, nullptr, nullptr, ws, st)) return rc;
+    const void *edge_src = p->edges == GRAPHKV_EDGES_VV ? Vc : Kc;
+    const void *edge_nbr = p->edges == GRAPHKV_EDGES_KK ? Kc : Vc;
+    if (int32_t rc = run_propagate(p, D, W, edge_src, edge_nbr, scores, nullptr, nullptr, nullptr, ws, st))
+        return rc;
     if (int32_t rc = run_select(D, plan, scores, idx, st)) return rc;
     GKV_LAUNCH(GRAPHKV_K_GATHER, launch_gather(Kc, Vc, idx, D.H, D.N, plan, max_budget,
                                                (int)(D.d * D.esize), Kout, Vout, st));
@@ -373,19 +378,26 @@ int32_t graphkv_score_knorm(const graphkv_params *p, const void *Kc, float *scor
     return GRAPHKV_OK;
 }
 
-int32_t graphkv_propagate(const graphkv_params *p, const void *Kc, float *scores, int32_t *dbg_src,
-                          int32_t *dbg_nbr, float *dbg_e, void *ws, size_t ws_bytes, void *stream)
+int32_t graphkv_propagate_edges(const graphkv_params *p, const void *Ac, const void *Bc, float *scores,
+                                int32_t *dbg_src, int32_t *dbg_nbr, float *dbg_e, void *ws,
+                                size_t ws_bytes, void *stream)
 {
     if (!base_ok(p)) return GRAPHKV_EINVAL;
-    if (!aligned16(Kc) || !aligned4(scores)) return GRAPHKV_EINVAL;
+    if (!aligned16(Ac) || !aligned16(Bc) || !aligned4(scores)) return GRAPHKV_EINVAL;
     if ((dbg_src && !aligned4(dbg_src)) || (dbg_nbr && !aligned4(dbg_nbr)) ||
         (dbg_e && !aligned4(dbg_e)))
         return GRAPHKV_EINVAL;
     const Dims D = dims_of(p);
     const Workspace W = carve(p, D);
     if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
-    return run_propagate(p, D, W, Kc, scores, dbg_src, dbg_nbr, dbg_e, ws,
+    return run_propagate(p, D, W, Ac, Bc, scores, dbg_src, dbg_nbr, dbg_e, ws,
                          (hipStream_t)stream);
+}
+
+int32_t graphkv_propagate(const graphkv_params *p, const void *Kc, float *scores, int32_t *dbg_src,
+                          int32_t *dbg_nbr, float *dbg_e, void *ws, size_t ws_bytes, void *stream)
+{
+    return graphkv_propagate_edges(p, Kc, Kc, scores, dbg_src, dbg_nbr, dbg_e, ws, ws_bytes, stream);
 }
 
 int32_t graphkv_select(const graphkv_params *p, const float *scores, int32_t *idx, void *ws,

@@ -83,18 +83,18 @@ __global__ __launch_bounds__(256) void generic_votes_kernel(
 // -inf so that it can never be its own neighbour (Eq. 3: j != i).
 template <typename T>
 __global__ __launch_bounds__(256) void generic_cosine_kernel(
-    const T *__restrict__ Kc, int d, int N, int P, int S, const int32_t *__restrict__ src,
-    float *__restrict__ E)
+    const T *__restrict__ Ac, const T *__restrict__ Kc, int d, int N, int P, int S,
+    const int32_t *__restrict__ src, float *__restrict__ E)
 {
     __shared__ float s_f32[512];
     const int a = blockIdx.y, h = blockIdx.z;
     const int i = src[h * S + a];
-    const T *kh = Kc + (long)h * N * d;
+    const T *kh = Kc + (long)h * N * d, *ah = Ac + (long)h * N * d;   // source rows come from Ac
     float part = 0.f;
     for (int c = threadIdx.x; c < d; c += 256) {
         float t;
-        if constexpr (sizeof(T) == 4) t = kh[(long)i * d + c];
-        else t = bf16_to_f32(kh[(long)i * d + c]);
+        if constexpr (sizeof(T) == 4) t = ah[(long)i * d + c];
+        else t = bf16_to_f32(ah[(long)i * d + c]);
         s_f32[c] = t;
     }
     __syncthreads();
@@ -154,16 +154,16 @@ hipError_t launch_generic_votes(const float *logits, const float *row_max, const
     return hipGetLastError();
 }
 
-hipError_t launch_generic_cosine(const void *Kc, int dtype, int Hkv, int d, int N, int P, int S,
+hipError_t launch_generic_cosine(const void *Ac, const void *Kc, int dtype, int Hkv, int d, int N, int P, int S,
                                  const int32_t *src, float *E, hipStream_t st)
 {
     dim3 grid((P + 255) / 256, S, Hkv);
     if (dtype == 0)
-        hipLaunchKernelGGL(generic_cosine_kernel<float>, grid, dim3(256), 0, st, (const float *)Kc,
-                           d, N, P, S, src, E);
+        hipLaunchKernelGGL(generic_cosine_kernel<float>, grid, dim3(256), 0, st, (const float *)Ac,
+                           (const float *)Kc, d, N, P, S, src, E);
     else
         hipLaunchKernelGGL(generic_cosine_kernel<uint16_t>, grid, dim3(256), 0, st,
-                           (const uint16_t *)Kc, d, N, P, S, src, E);
+                           (const uint16_t *)Ac, (const uint16_t *)Kc, d, N, P, S, src, E);
     return hipGetLastError();
 }
 

@@ -34,8 +34,9 @@ hipError_t launch_generic_logits(const void *Kc, const void *Qw, int dtype, int 
 // votes [Hq, P]: softmax weights summed over the window rows.
 hipError_t launch_generic_votes(const float *logits, const float *row_max, const float *row_sum,
                                 int Hq, int N, int w, float *votes, hipStream_t st);
-// E [Hkv, S, P] cosine of source src[h,a] against every prefix key; self = -inf.
-hipError_t launch_generic_cosine(const void *Kc, int dtype, int Hkv, int d, int N, int P, int S,
+// E [Hkv, S, P] cosine of row src[h,a] of Ac against every prefix row of Kc; self = -inf.
+// (Eq. 1: Ac = Kc = keys; other pairings of tensors give the Discussion's other edges.)
+hipError_t launch_generic_cosine(const void *Ac, const void *Kc, int dtype, int Hkv, int d, int N, int P, int S,
                                  const int32_t *src, float *E, hipStream_t st);
 // scores[h,j] = -||k_j||
 hipError_t launch_knorm(const void *Kc, int dtype, int Hkv, int d, int N, int P, float *scores,
@@ -77,7 +78,7 @@ hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int 
                                   hipStream_t st);
 // E [Hkv, S, P] from bf16 keys (same contract as launch_generic_cosine); heads with
 // gate[h] == 0 are skipped when gate != nullptr.
-hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
+hipError_t launch_mfma_cosine(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
                               float *E, const int32_t *gate, hipStream_t st);
 // Neighbourhoods without the dense block (see mfma_cosine.hip):
 bool mfma_filter_applies(int P, int m);
@@ -90,12 +91,12 @@ struct MfmaFilterGeom {
 };
 MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m);
 // E_sample [Hkv, S, sample_cols] on every (P / sample_cols)-th key; clears overflow [Hkv].
-hipError_t launch_mfma_cosine_sample(const void *Kc, int Hkv, int N, int P, int S,
+hipError_t launch_mfma_cosine_sample(const void *Ac, const void *Kc, int Hkv, int N, int P, int S,
                                      const int32_t *src, float *E_sample, int32_t *overflow,
                                      hipStream_t st);
 // Streams all keys; edges that reach tau[h, a] go to cand [Hkv, S, chunks, slice_cap] x 8
 // bytes, their number per slice to cand_cnt [Hkv, S, chunks].
-hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int S, int m,
+hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
                                      const int32_t *src, const float *tau, void *cand,
                                      int32_t *cand_cnt, int32_t *overflow, hipStream_t st);
 // Exact top-m over each source's slices -> nbr / nbr_e [Hkv, S, m]; skips heads with

@@ -71,15 +71,17 @@ struct FilterArgs {
 // e = (dot * 1/|k_j|) * 1/|k_i| in both, so the sample pass and the filter pass
 // produce the same bits.
 
+// Sources are rows of Ac, the streamed rows are rows of Kc (both [Hkv, N, 128]); for
+// Eq. 1 both are the keys, the other pairings of the paper's Discussion pass two tensors.
 // This wave's 32 source rows -> MFMA operand registers (slots beyond S repeat the
 // last source); 1/|k_i| and the source index of the 64 rows of the group go to LDS.
-__device__ __forceinline__ void load_sources(const uint16_t *Kh, const int32_t *src_h, int S,
+__device__ __forceinline__ void load_sources(const uint16_t *Ah, const int32_t *src_h, int S,
                                              int s_base, int grp, int stream, int l32, int hh,
                                              bf16x8 (&q)[kSteps], float *inv_s, int32_t *idx_s)
 {
     const int slot = min(s_base + kBlk * grp + l32, S - 1);
     const int32_t i = src_h[slot];
-    const uint16_t *p = Kh + (long)i * kD + 8 * hh;
+    const uint16_t *p = Ah + (long)i * kD + 8 * hh;
 #pragma unroll
     for (int s = 0; s < kSteps; ++s) q[s] = load8(p + 16 * s);
     float sq = half_row_sumsq(q);
@@ -94,7 +96,7 @@ __device__ __forceinline__ void load_sources(const uint16_t *Kh, const int32_t *
 // every key), -inf where the key is the source itself.  If fa.overflow is set, the first
 // workgroup of a head also clears the head's overflow flag for the filter pass that follows.
 __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
-    const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride, int S,
+    const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride, int S,
     const int32_t *__restrict__ src, int chunk_cols, float *__restrict__ E, FilterArgs fa,
     const int32_t *__restrict__ gate)
 {
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
     if (fa.overflow && chunk == 0 && blockIdx.z == 0 && tid == 0) fa.overflow[h] = 0;
 
     bf16x8 q[kSteps];
-    load_sources(Kh, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
+    load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
     __syncthreads();
     float inv_src[16];
 #pragma unroll
@@ -168,8 +170,8 @@ constexpr int kStageCap = 1024;    // staged rows per workgroup
 constexpr int kStagePitch = 80;    // bytes per staged row: 16 dots, |k|^2, key + lane bits, hit bits
 
 __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
-    const uint16_t *__restrict__ Kc, int N, int n_cols, int S, const int32_t *__restrict__ src,
-    int chunk_cols, FilterArgs fa)
+    const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int S,
+    const int32_t *__restrict__ src, int chunk_cols, FilterArgs fa)
 {
     __shared__ float inv_s[kRows], lo_s[kRows], det_s[kRows];
     __shared__ int32_t idx_s[kRows];
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     if (c0 >= n_cols) return;
 
     bf16x8 q[kSteps];
-    load_sources(Kh, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
+    load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
     if (tid == 0) { stage_n = 0; lost = 0; }
     if (tid < kRows) row_pos[tid] = 0;
     __syncthreads();
@@ -516,7 +518,7 @@ MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m)
     return g;
 }
 
-hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
+hipError_t launch_mfma_cosine(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,
                               float *E, const int32_t *gate, hipStream_t st)
 {
     const int sgroups = (S + kRows - 1) / kRows;
@@ -525,11 +527,11 @@ hipError_t launch_mfma_cosine(const void *Kc, int Hkv, int N, int P, int S, cons
     FilterArgs fa{};
     if (!allow_big_lds((const void *)cosine_dense_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(cosine_dense_kernel, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
-                       st, (const uint16_t *)Kc, N, P, 1, S, src, ck, E, fa, gate);
+                       st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, 1, S, src, ck, E, fa, gate);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_cosine_sample(const void *Kc, int Hkv, int N, int P, int S,
+hipError_t launch_mfma_cosine_sample(const void *Ac, const void *Kc, int Hkv, int N, int P, int S,
                                      const int32_t *src, float *E_sample, int32_t *overflow,
                                      hipStream_t st)
 {
@@ -541,12 +543,12 @@ hipError_t launch_mfma_cosine_sample(const void *Kc, int Hkv, int N, int P, int 
     fa.overflow = overflow;
     if (!allow_big_lds((const void *)cosine_dense_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(cosine_dense_kernel, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
-                       st, (const uint16_t *)Kc, N, ps, stride, S, src, ck, E_sample, fa,
+                       st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, ps, stride, S, src, ck, E_sample, fa,
                        (const int32_t *)nullptr);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int S, int m,
+hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
                                      const int32_t *src, const float *tau, void *cand,
                                      int32_t *cand_cnt, int32_t *overflow, hipStream_t st)
 {
@@ -563,7 +565,7 @@ hipError_t launch_mfma_cosine_filter(const void *Kc, int Hkv, int N, int P, int 
     FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, flush_every};
     if (!allow_big_lds((const void *)cosine_filter_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(cosine_filter_kernel, dim3(g.chunks, Hkv, sgroups), dim3(kThreads),
-                       2 * kTileBytes + kStageCap * kStagePitch, st, (const uint16_t *)Kc, N, P, S, src,
+                       2 * kTileBytes + kStageCap * kStagePitch, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, src,
                        g.chunk_cols, fa);
     return hipGetLastError();
 }

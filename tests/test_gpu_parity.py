@@ -277,6 +277,81 @@ def test_filtered_neighbourhoods_overflow_falls_back(oracle):
     assert np.array_equal(nbr[0, 0, a], want) and (np.abs(ev[0, 0, a] - 1.0) < 1e-6).all()
 
 
+# ---- edges between two tensors (Discussion: key-value, value-value, ... edges) ----
+
+def structured_second_tensor(K, V, dtype):
+    """A second tensor that keeps some of the keys' cluster structure (plain random
+    values give cosines without any gap at the cuts)."""
+    mix = synth.storage_to_f64(K, dtype) + 0.7 * synth.storage_to_f64(V, dtype)
+    if dtype == "bf16":
+        return synth.f32_to_bf16_bits(mix.astype(np.float32))
+    return mix.astype(np.float32)
+
+
+@pytest.mark.parametrize("case", ["c1", "bf16-dense", "bf16-filter", "bf16-generic"])
+def test_two_tensor_edges_staged(oracle, case):
+    say(f"two-tensor edges staged {case}")
+    impl = gk.IMPL_GENERIC if case == "bf16-generic" else gk.IMPL_AUTO
+    if case == "c1":
+        cfg = synth.CONFIGS["c1"]
+    elif case == "bf16-filter":
+        cfg = small_bf16_cfg(n_tokens=10007, n_sources=40, n_neighbors=12)
+    else:
+        cfg = small_bf16_cfg()
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 3)
+    W = structured_second_tensor(K, V, cfg.dtype)
+    Wd = gk.to_device(W, gk.BF16 if cfg.dtype == "bf16" else gk.FP32)
+    s0 = synth.random_scores(cfg)
+    p = util.params_from_cfg(cfg, rounds=1, impl=impl)
+    H, S, m = p.n_kv_heads, p.n_sources, p.n_neighbors
+    for name, (A, Ad, B_, Bd) in {"key-other": (K, Kd, W, Wd), "other-key": (W, Wd, K, Kd),
+                                  "other-other": (W, Wd, W, Wd), "key-value": (K, Kd, V, Vd)}.items():
+        s = torch.from_numpy(s0.copy()).cuda()
+        src = torch.full((1, H, S), -1, dtype=torch.int32, device="cuda")
+        nbr = torch.full((1, H, S, m), -1, dtype=torch.int32, device="cuda")
+        ev = torch.full((1, H, S, m), float("nan"), dtype=torch.float32, device="cuda")
+        gk.graphkv_propagate_edges(p, Ad, Bd, s, src, nbr, ev)
+        flips = util.check_round_staged(oracle, A, cfg.dtype, cfg.window, s0, s.cpu().numpy(),
+                                        src[0].cpu().numpy(), nbr[0].cpu().numpy(), ev[0].cpu().numpy(),
+                                        S, m, 1.0, other=B_)
+        say(f"  {name}: neighbour lists differing from the oracle's (near-ties): {flips}")
+    # both tensors the keys: the very same launches as graphkv_propagate
+    a = torch.from_numpy(s0.copy()).cuda(); b = torch.from_numpy(s0.copy()).cuda()
+    gk.graphkv_propagate_edges(p, Kd, Kd, a); gk.graphkv_propagate(p, Kd, b)
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("edges", [gk.EDGES_KV, gk.EDGES_VV])
+@pytest.mark.parametrize("impl", IMPLS)
+def test_compress_edge_modes(oracle, impl, edges):
+    """Whole pass with key-value / value-value edges against the oracle's."""
+    say(f"compress edges={edges} impl={impl}")
+    cfg = small_bf16_cfg()
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 8)
+    V2 = structured_second_tensor(K, V, "bf16")
+    V2d = gk.to_device(V2, gk.BF16)
+    p = util.params_from_cfg(cfg, 8, impl=impl, rounds=2, edges=edges)
+    out, sc = run_compress(p, (Kd, V2d, Qd))
+    ref = oracle.compress(K, V2, Q, "bf16", p.pool_kernel, p.budget, p.n_sources, p.n_neighbors, 2,
+                          edge_mode=edges)
+    diffs = util.compare_end_to_end(out, ref, K, V2, cfg.window)
+    if diffs:
+        say(f"  retained sets differ on heads {diffs}; oracle's smallest gaps {ref['min_gap']}")
+        assert ref["min_gap"].min() < util.REL_TOL
+    else:
+        util.assert_scores_close(sc, ref["scores"], "refined scores")
+    # the pairing matters: key-key edges give another result on this input
+    out_kk, _ = run_compress(util.params_from_cfg(cfg, 8, impl=impl, rounds=2), (Kd, V2d, Qd))
+    assert not np.array_equal(out_kk[2], out[2])
+
+
+def test_invalid_edges_value_is_rejected():
+    cfg = small_bf16_cfg()
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 8)
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_compress(util.params_from_cfg(cfg, 8, edges=3), Kd, Vd, Qd)
+
+
 # ----------------------------------------------------------- whole pass ---
 
 def run_compress(p, dev, want_scores=True):

@@ -45,7 +45,7 @@ def assert_scores_close(gpu, ref, what="scores"):
 
 
 def check_round_staged(orc, K_np, dtype_name, window, s_in, s_out, src, nbr, ev, S, m, alpha,
-                       signal=0):
+                       signal=0, other=None):
     """One propagation round of the GPU (inputs s_in, outputs s_out, src [H,S],
     nbr/ev [H,S,m]) against the oracle, stage by stage:
       - sources: bit-exact from the same fp32 scores;
@@ -55,6 +55,7 @@ def check_round_staged(orc, K_np, dtype_name, window, s_in, s_out, src, nbr, ev,
         chosen edge is worse than an unchosen one by more than the tolerance;
       - update: s_out equals s_in times the product of the factors built from
         the GPU's own (nbr, e), untouched nodes bit-identical.
+    With `other`, edges are cos(K_np[h, i], other[h, j]) (two-tensor edges).
     Returns the number of neighbour lists that differ from the oracle's pick."""
     H, P = s_in.shape
     flips = 0
@@ -65,7 +66,7 @@ def check_round_staged(orc, K_np, dtype_name, window, s_in, s_out, src, nbr, ev,
         hit = np.zeros(P, bool)
         for a in range(S):
             i = int(src[h, a])
-            e_ref = orc.cosine_row(K_np, dtype_name, window, h, i)
+            e_ref = orc.cosine_row(K_np, dtype_name, window, h, i, other=other)
             lst = nbr[h, a]
             assert (np.diff(lst) > 0).all() and lst.min() >= 0 and lst.max() < P and i not in lst
             np.testing.assert_allclose(ev[h, a], e_ref[lst], rtol=0, atol=REL_TOL)
