@@ -61,7 +61,7 @@ struct FilterArgs {
     int32_t *cand_cnt;     // [Hkv, S, chunks] entries in each slice
     int32_t *overflow;     // [Hkv]
     int slice_cap;
-    int flush_every;       // tiles between two flushes of the LDS staging area
+    int drain_every;       // tiles between two scheduled drains of the rings
 };
 
 // Both kernels below: a workgroup has 4 key streams (wave & 3) and 2 source row
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
             }
         }
     };
-    GKV_TILE_PIPELINE(kThreads, Kh, c0, n_cols - 1, key_stride, ntile, multiply_tile, (void)0);
+    GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, key_stride, ntile, multiply_tile, (void)0);
 }
 
 // Filter pass over all keys.  A lane holds, per key block, the 16 dots of its key
@@ -158,16 +158,26 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
 // bounds (dot >= bound_i * |k_j|, bounds a hair lowered so that rounding can never
 // lose an edge) with 16 fused multiply-adds and a max tree; the few lanes that
 // have a hit park their 16 dots, the key's squared norm and the key index in an
-// LDS staging area.  Every `flush_every` tiles, and at the end, the workgroup turns
-// the staged rows into exact edges (the dense kernel's formula, bit for bit),
-// keeps those that reach the bound and appends them to its own slice of each
-// source's global candidate list (one slice per key chunk, so no workgroup ever
-// waits for another: positions come from LDS counters).  The source's own column
-// may be among them: the exact select drops it.  The flush schedule is fixed by
-// the host from the expected hit rate; if the staging area or a slice overflows
-// anyway, the head's overflow flag is raised and the head is redone densely.
-constexpr int kStageCap = 1024;    // staged rows per workgroup
-constexpr int kStagePitch = 80;    // bytes per staged row: 16 dots, |k|^2, key + lane bits, hit bits
+// LDS ring.  Every half-wave has a ring of its own and positions are a prefix
+// count over the hit lanes, so parking needs no atomic and waits for nothing.
+// Every few tiles (a schedule the host derives from the expected hit rate, so
+// that most of a half-wave's 32 lanes get a row) all waves drain their rings at
+// the same time -- a drain is a chain of LDS round trips, and a wave that drains
+// alone would keep the other seven waiting at the tile barrier.  A half-wave
+// drains its own ring, so the 16 sources of a parked row are the draining lane's
+// own 16 sources and their 1/|k_i| and bounds sit in registers: the dots become
+// exact edges (the dense kernel's formula, bit for bit), and those that reach the
+// bound are appended to the workgroup's own slice of each source's global
+// candidate list (one slice per key chunk, so no workgroup ever waits for
+// another: positions come from LDS counters).  A ring holds 64 rows and a wave
+// drains on its own whenever a half has more than 32 waiting, so a tile's 32
+// rows at most always fit.  The source's own column may be among the candidates:
+// the exact select drops it.  If a slice (or the short LDS list that takes a row's
+// hits beyond its fourth) overflows, the head's overflow flag is raised and the
+// head is redone densely.
+constexpr int kRingRows = 64;      // rows per half-wave ring
+constexpr int kStagePitch = 80;    // bytes per parked row: 16 dots, |k|^2, key (72, padded)
+constexpr int kLaterCap = 256;     // LDS list of the hits beyond a row's fourth
 
 __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int S,
@@ -175,8 +185,10 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
 {
     __shared__ float inv_s[kRows], lo_s[kRows], det_s[kRows];
     __shared__ int32_t idx_s[kRows];
-    __shared__ int32_t stage_n, lost, row_pos[kRows];   // row_pos: entries written to each source's slice
-    extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the staging area
+    __shared__ int32_t row_pos[kRows];   // entries written to each source's slice
+    __shared__ uint4 later[kLaterCap];   // (edge bits, key, source row): hits beyond a row's fourth
+    __shared__ int32_t n_later;
+    extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the rings
     unsigned char *kt = smem;
     unsigned char *stage_mem = smem + 2 * kTileBytes;
 
@@ -189,8 +201,8 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
 
     bf16x8 q[kSteps];
     load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
-    if (tid == 0) { stage_n = 0; lost = 0; }
     if (tid < kRows) row_pos[tid] = 0;
+    if (tid == 0) n_later = 0;
     __syncthreads();
     if (tid < kRows) {
         // lo: what an exact edge must reach to be listed; det: the still lower bound of the
@@ -205,41 +217,82 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
         det_s[tid] = slot >= S ? INFINITY : (inv > 0.f ? lo2 / inv : (lo2 <= 0.f ? -INFINITY : INFINITY));
     }
     __syncthreads();
-    float det[16];
+    // this lane's 16 sources: row acc_row(i, hh) of row group grp
+    float det[16], inv16[16], lo16[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) det[i] = det_s[kBlk * grp + acc_row(i, hh)];
+    for (int i = 0; i < 16; ++i) {
+        det[i] = det_s[kBlk * grp + acc_row(i, hh)];
+        inv16[i] = inv_s[kBlk * grp + acc_row(i, hh)];
+        lo16[i] = lo_s[kBlk * grp + acc_row(i, hh)];
+    }
 
-    // Staged rows -> exact edges -> this workgroup's slices of the candidate lists.  Called
-    // by all threads; one thread per staged row walks the row's hit bits.
+    unsigned char *ring = stage_mem + (2 * wv + hh) * (kRingRows * kStagePitch);
+    const uint64_t half_before = (hh ? 0xffffffff00000000ull : 0x00000000ffffffffull) & ((1ull << lane) - 1ull);
     uint2 *slice0 = fa.cand + (((long)h * S + s_base) * gridDim.x + chunk) * fa.slice_cap;
     const long slice_row_stride = (long)gridDim.x * fa.slice_cap;
-    auto flush = [&]() {
-        const int n_stage = stage_n;
-        const int n = n_stage < kStageCap ? n_stage : kStageCap;
-        if (n_stage > kStageCap && tid == 0) lost = 1;
-        for (int r = tid; r < n; r += kThreads) {
-            const unsigned char *row_mem = stage_mem + r * kStagePitch;
-            const float *vals = reinterpret_cast<const float *>(row_mem);
-            const float sq = vals[16];
-            const float inv_k = inv_norm(sq);   // the dense kernel's formula
-            const uint32_t meta = *reinterpret_cast<const uint32_t *>(row_mem + 68);
-            const int rgrp = kBlk * ((meta >> 25) & 1), rhh = (meta >> 24) & 1;
-            uint32_t hits = *reinterpret_cast<const uint32_t *>(row_mem + 72);
+    // rows ever parked / ever drained by the lower and the upper half-wave (same in every lane)
+    int tail0 = 0, tail1 = 0, head0 = 0, head1 = 0;
+
+    // Each half-wave turns up to 32 waiting rows of its ring into list entries, one per lane.
+    // No loop in here holds a global store: after such a loop the compiler can no longer
+    // count the memory operations in flight and would make the next LDS store of a key tile
+    // wait for every outstanding prefetch.  A row's first four hits are stored by straight-
+    // line code; the rare further ones go to an LDS list that is emptied after the last tile.
+    auto drain = [&]() {
+        const int n0 = min(tail0 - head0, kBlk), n1 = min(tail1 - head1, kBlk);
+        if (l32 < (hh ? n1 : n0)) {
+            const unsigned char *row_mem = ring + (((hh ? head1 : head0) + l32) & (kRingRows - 1)) * kStagePitch;
+            const float4 *vals = reinterpret_cast<const float4 *>(row_mem);
+            const float2 extra = *reinterpret_cast<const float2 *>(row_mem + 64);   // |k|^2, key
+            const float inv_k = inv_norm(extra.x);   // the dense kernel's formula
+            const uint32_t key = __float_as_uint(extra.y);
+            // Nearly every parked row holds a single hit: its edge is picked up on the way
+            // through the 16 tests.
+            uint32_t hits = 0;
+            float e_first = 0.f;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float4 dv = vals[v];
+                const float d4[4] = {dv.x, dv.y, dv.z, dv.w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = 4 * v + u;
+                    const float e = (d4[u] * inv_k) * inv16[i];
+                    const bool in = e >= lo16[i];
+                    e_first = (in && hits == 0) ? e : e_first;
+                    hits |= (in ? 1u : 0u) << i;
+                }
+            }
+            long off[4];
+            float ev[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                off[k] = -1;
+                ev[k] = 0.f;
+                if (hits) {
+                    const int i = __ffs(hits) - 1;
+                    hits &= hits - 1;
+                    const int row = kBlk * grp + acc_row(i, hh);
+                    ev[k] = k == 0 ? e_first
+                                   : (reinterpret_cast<const float *>(row_mem)[i] * inv_k) * inv_s[row];
+                    const int at = atomicAdd(&row_pos[row], 1);
+                    if (at < fa.slice_cap) off[k] = row * slice_row_stride + at;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (off[k] >= 0) slice0[off[k]] = make_uint2(__float_as_uint(ev[k]), key);
             while (hits) {
                 const int i = __ffs(hits) - 1;
                 hits &= hits - 1;
-                const int row = rgrp + acc_row(i, rhh);
-                const float e = (vals[i] * inv_k) * inv_s[row];
-                if (e >= lo_s[row]) {
-                    const int at = atomicAdd(&row_pos[row], 1);
-                    if (at < fa.slice_cap)
-                        slice0[row * slice_row_stride + at] = make_uint2(__float_as_uint(e), meta & 0xffffffu);
-                }
+                const int row = kBlk * grp + acc_row(i, hh);
+                const float e = (reinterpret_cast<const float *>(row_mem)[i] * inv_k) * inv_s[row];
+                const int at = atomicAdd(&n_later, 1);
+                if (at < kLaterCap) later[at] = make_uint4(__float_as_uint(e), key, (uint32_t)row, 0u);
             }
         }
-        __syncthreads();
-        if (tid == 0) stage_n = 0;
-        __syncthreads();
+        head0 += n0;
+        head1 += n1;
     };
 
     const int ntile = (c1 - c0 + kTileKeys - 1) / kTileKeys;
@@ -263,31 +316,45 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
 #pragma unroll
         for (int i = 1; i < 16; ++i) best = fmaxf(best, d[i]);
         const int key = c0 + kTileKeys * t + kBlk * stream + l32;
-        if (best >= 0.f && key < c1) {
-            uint32_t hits = 0;
+        const bool hit = best >= 0.f && key < c1;
+        const uint64_t hit_lanes = __ballot(hit);
+        if (hit) {
+            const int at = (hh ? tail1 : tail0) + (int)__popcll(hit_lanes & half_before);
+            unsigned char *row_mem = ring + (at & (kRingRows - 1)) * kStagePitch;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) hits |= (d[i] >= 0.f ? 1u : 0u) << i;
-            const int at = atomicAdd(&stage_n, 1);
-            if (at < kStageCap) {
-                unsigned char *row_mem = stage_mem + at * kStagePitch;
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    *reinterpret_cast<float4 *>(row_mem + 16 * v) =
-                        make_float4(acc[4 * v], acc[4 * v + 1], acc[4 * v + 2], acc[4 * v + 3]);
-                *reinterpret_cast<float4 *>(row_mem + 64) =
-                    make_float4(sq, __uint_as_float((uint32_t)key | ((uint32_t)hh << 24) | ((uint32_t)grp << 25)),
-                                __uint_as_float(hits), 0.f);
-            }
+            for (int v = 0; v < 4; ++v)
+                *reinterpret_cast<float4 *>(row_mem + 16 * v) =
+                    make_float4(acc[4 * v], acc[4 * v + 1], acc[4 * v + 2], acc[4 * v + 3]);
+            *reinterpret_cast<float2 *>(row_mem + 64) = make_float2(sq, __int_as_float(key));
         }
+        tail0 += (int)__popcll(hit_lanes & 0x00000000ffffffffull);
+        tail1 += (int)__popcll(hit_lanes >> 32);
+        // a ring must take the next tile's 32 rows at most (at most 64 wait: one pass suffices)
+        if (tail0 - head0 > kRingRows - kBlk || tail1 - head1 > kRingRows - kBlk) drain();
     };
-    const int fe = fa.flush_every;
-    GKV_TILE_PIPELINE(kThreads, Kh, c0, n_cols - 1, 1, ntile, multiply_tile,
-                      if ((tile_done % fe) == 0) flush());
-    flush();
+    const int de = fa.drain_every;   // even
+    // A scheduled drain empties the rings: two passes of 32 rows per half-wave at most.  It
+    // runs after an odd number of tiles only, i.e. in the first half of the unrolled tile
+    // loop: the wait in front of the LDS store that follows there leaves the younger memory
+    // operations alone, the one at the top of the loop waits for everything in flight --
+    // the drain's own stores included, a round trip to memory on the tile's critical path.
+    GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, 1, ntile, multiply_tile,
+                      if ((tile_done & 1) && tile_done % de == de - 1) { drain(); drain(); });
+    drain();
+    drain();
+    __syncthreads();
+    // hits beyond a row's fourth
+    const int nl = n_later < kLaterCap ? n_later : kLaterCap;
+    for (int x = tid; x < nl; x += kThreads) {
+        const uint4 r = later[x];
+        const int at = atomicAdd(&row_pos[r.z], 1);
+        if (at < fa.slice_cap) slice0[(long)r.z * slice_row_stride + at] = make_uint2(r.x, r.y);
+    }
+    __syncthreads();      // every candidate is counted
     if (tid < kRows && s_base + tid < S) {
         const int c = row_pos[tid];
         fa.cand_cnt[((long)h * S + s_base + tid) * gridDim.x + chunk] = c < fa.slice_cap ? c : fa.slice_cap;
-        if (c > fa.slice_cap || lost) fa.overflow[h] = 1;
+        if (c > fa.slice_cap || n_later > kLaterCap) fa.overflow[h] = 1;
     }
 }
 
@@ -555,17 +622,17 @@ hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, in
     const int sgroups = (S + kRows - 1) / kRows;
     const int stride = P / mfma_sample_cols(P);
     const MfmaFilterGeom g = mfma_filter_geom(Hkv, P, S, m);
-    // Expected staged rows per tile: 512 lanes x P(a lane's 16 edges hold a hit), with a
+    // Rows a half-wave parks per tile: 32 lanes x P(a lane's 16 edges hold a hit), with a
     // per-edge hit rate of about m * stride / P (each source keeps ~m * stride candidates).
+    // Drains are scheduled for when about 30 of a half-wave's 32 lanes get a row.
     const double rate = (double)m * stride / (double)P;
-    const double per_tile = 512.0 * (1.0 - pow(1.0 - (rate < 1.0 ? rate : 1.0), 16.0));
-    int flush_every = (int)((kStageCap / 2) / (per_tile > 1.0 ? per_tile : 1.0));
-    if (flush_every < 1) flush_every = 1;
-    if (flush_every > 64) flush_every = 64;
-    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, flush_every};
+    const double per_tile = 32.0 * (1.0 - pow(1.0 - (rate < 1.0 ? rate : 1.0), 16.0));
+    int drain_every = (int)(30.0 / (per_tile > 0.45 ? per_tile : 0.45)) & ~1;   // even, see the kernel
+    if (drain_every < 2) drain_every = 2;
+    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, drain_every};
     if (!allow_big_lds((const void *)cosine_filter_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(cosine_filter_kernel, dim3(g.chunks, Hkv, sgroups), dim3(kThreads),
-                       2 * kTileBytes + kStageCap * kStagePitch, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, src,
+                       2 * kTileBytes + 2 * (kThreads / kWave) * kRingRows * kStagePitch, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, src,
                        g.chunk_cols, fa);
     return hipGetLastError();
 }

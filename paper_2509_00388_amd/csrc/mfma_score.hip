@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
             }
         }
     };
-    GKV_TILE_PIPELINE(NT, Kh, k0, N - 1, 1, ntile, multiply_tile, (void)0);
+    GKV_TILE_PIPELINE(NT, Kh, k0, k1 - 1, 1, ntile, multiply_tile, (void)0);
 
     // merge the two half-waves (same query, other key rows), then the 4 key streams
 #pragma unroll
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
             }
         }
     };
-    GKV_TILE_PIPELINE(NT, Kh, k0, P - 1, 1, ntile, multiply_tile, (void)0);
+    GKV_TILE_PIPELINE(NT, Kh, k0, k1 - 1, 1, ntile, multiply_tile, (void)0);
 }
 
 // Kernels that use more than 64 KiB of dynamic LDS need a one-time opt-in per kernel.

@@ -84,26 +84,31 @@ __device__ __forceinline__ void tile_read(const unsigned char *buf, int stream, 
 // right after each tile's barrier with `tile_done` = number of tiles finished (it
 // may contain barriers: every thread reaches it).  The loop is unrolled twice so
 // that the LDS buffer and the register set of a tile are compile-time choices.
+//
+// The prefetch loads are issued unconditionally, also past the last tile (rows are
+// clamped to `clamp_`, the last row the workgroup needs, so those loads hit one
+// cached row): the compiler can then count the loads in flight exactly and the
+// wait in front of each LDS store leaves the newer tile's loads outstanding.
+// With conditional loads it has to assume they were skipped and waits for
+// everything.
 #define GKV_TILE_PIPELINE(NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE)                 \
     do {                                                                                               \
         u32x4 stage_a[tile_pieces<NT_>()], stage_b[tile_pieces<NT_>()];                                \
         tile_load<NT_>(Kh_, first_, clamp_, stride_, tid, stage_a);                                    \
         tile_store<NT_>(kt, tid, stage_a);                                                             \
-        if (1 < ntile_) tile_load<NT_>(Kh_, first_ + kTileKeys, clamp_, stride_, tid, stage_a);        \
-        if (2 < ntile_) tile_load<NT_>(Kh_, first_ + 2 * kTileKeys, clamp_, stride_, tid, stage_b);    \
+        tile_load<NT_>(Kh_, first_ + kTileKeys, clamp_, stride_, tid, stage_a);                        \
+        tile_load<NT_>(Kh_, first_ + 2 * kTileKeys, clamp_, stride_, tid, stage_b);                    \
         __syncthreads();                                                                               \
         for (int t_ = 0; t_ < ntile_; t_ += 2) {                                                       \
             body(kt, t_);                                                                              \
-            if (t_ + 1 < ntile_) tile_store<NT_>(kt + kTileBytes, tid, stage_a);                       \
-            if (t_ + 3 < ntile_)                                                                       \
-                tile_load<NT_>(Kh_, first_ + kTileKeys * (t_ + 3), clamp_, stride_, tid, stage_a);     \
+            tile_store<NT_>(kt + kTileBytes, tid, stage_a);                                            \
+            tile_load<NT_>(Kh_, first_ + kTileKeys * (t_ + 3), clamp_, stride_, tid, stage_a);         \
             __syncthreads();                                                                           \
             { const int tile_done = t_ + 1; (void)tile_done; AFTER_TILE; }                             \
             if (t_ + 1 >= ntile_) break;                                                               \
             body(kt + kTileBytes, t_ + 1);                                                             \
-            if (t_ + 2 < ntile_) tile_store<NT_>(kt, tid, stage_b);                                    \
-            if (t_ + 4 < ntile_)                                                                       \
-                tile_load<NT_>(Kh_, first_ + kTileKeys * (t_ + 4), clamp_, stride_, tid, stage_b);     \
+            tile_store<NT_>(kt, tid, stage_b);                                                         \
+            tile_load<NT_>(Kh_, first_ + kTileKeys * (t_ + 4), clamp_, stride_, tid, stage_b);         \
             __syncthreads();                                                                           \
             { const int tile_done = t_ + 2; (void)tile_done; AFTER_TILE; }                             \
         }                                                                                              \
