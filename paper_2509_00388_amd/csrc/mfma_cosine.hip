@@ -296,6 +296,7 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     };
 
     const int ntile = (c1 - c0 + kTileKeys - 1) / kTileKeys;
+    const int de = fa.drain_every;
     auto multiply_tile = [&](const unsigned char *buf, int t) {
         bf16x8 kc[kSteps];
         tile_read(buf, stream, l32, hh, kc);
@@ -329,17 +330,16 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
         }
         tail0 += (int)__popcll(hit_lanes & 0x00000000ffffffffull);
         tail1 += (int)__popcll(hit_lanes >> 32);
-        // a ring must take the next tile's 32 rows at most (at most 64 wait: one pass suffices)
-        if (tail0 - head0 > kRingRows - kBlk || tail1 - head1 > kRingRows - kBlk) drain();
+        // A scheduled drain empties the rings: two passes of 32 rows per half-wave at most.
+        // It sits here, in front of the tile's prefetch loads: the drain's stores are then
+        // older than those loads, and the wait in front of the next LDS store of a key tile
+        // -- a count of memory operations still in flight -- lets the loads stay in flight.
+        // Otherwise a ring must at least be able to take the next tile's 32 rows (at most 64
+        // wait: one pass suffices).
+        if (t % de == de - 1) { drain(); drain(); }
+        else if (tail0 - head0 > kRingRows - kBlk || tail1 - head1 > kRingRows - kBlk) drain();
     };
-    const int de = fa.drain_every;   // even
-    // A scheduled drain empties the rings: two passes of 32 rows per half-wave at most.  It
-    // runs after an odd number of tiles only, i.e. in the first half of the unrolled tile
-    // loop: the wait in front of the LDS store that follows there leaves the younger memory
-    // operations alone, the one at the top of the loop waits for everything in flight --
-    // the drain's own stores included, a round trip to memory on the tile's critical path.
-    GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, 1, ntile, multiply_tile,
-                      if ((tile_done & 1) && tile_done % de == de - 1) { drain(); drain(); });
+    GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, 1, ntile, multiply_tile, (void)0);
     drain();
     drain();
     __syncthreads();
@@ -627,8 +627,8 @@ hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, in
     // Drains are scheduled for when about 30 of a half-wave's 32 lanes get a row.
     const double rate = (double)m * stride / (double)P;
     const double per_tile = 32.0 * (1.0 - pow(1.0 - (rate < 1.0 ? rate : 1.0), 16.0));
-    int drain_every = (int)(30.0 / (per_tile > 0.45 ? per_tile : 0.45)) & ~1;   // even, see the kernel
-    if (drain_every < 2) drain_every = 2;
+    int drain_every = (int)(30.0 / (per_tile > 0.45 ? per_tile : 0.45));
+    if (drain_every < 1) drain_every = 1;
     FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, drain_every};
     if (!allow_big_lds((const void *)cosine_filter_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(cosine_filter_kernel, dim3(g.chunks, Hkv, sgroups), dim3(kThreads),
