@@ -68,7 +68,7 @@ def algorithmic_bytes(cfg, B):
         "topk_sources": H * P * 4 + H * S * 4,
         "cosine": H * P * d * e + H * S * d * e,
         "cosine_filter": H * P * d * e + H * S * d * e,
-        "cosine_sample": H * (P // 16) * d * e + H * S * d * e,
+        "cosine_bound": H * (P // 16) * d * e + H * S * d * e,
         "topk_neighbors": H * S * m * 8,
         "decay": 2 * H * S * m * 8,
         "topk_final": H * P * 4 + H * B * 4,

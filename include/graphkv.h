@@ -218,7 +218,7 @@ enum {
     GRAPHKV_K_SCORE_STATS = 0, GRAPHKV_K_SCORE_VOTES, GRAPHKV_K_POOL, GRAPHKV_K_TOPK_SOURCES,
     GRAPHKV_K_COSINE, GRAPHKV_K_TOPK_NEIGHBORS, GRAPHKV_K_DECAY, GRAPHKV_K_TOPK_FINAL,
     GRAPHKV_K_GATHER, GRAPHKV_K_GENERIC_LOGITS, GRAPHKV_K_GENERIC_VOTES, GRAPHKV_K_GENERIC_COSINE,
-    GRAPHKV_K_KNORM, GRAPHKV_K_COPY, GRAPHKV_K_COSINE_SAMPLE, GRAPHKV_K_TOPK_BOUND,
+    GRAPHKV_K_KNORM, GRAPHKV_K_COPY, GRAPHKV_K_COSINE_BOUND,
     GRAPHKV_K_COSINE_FILTER, GRAPHKV_K_NBR_SELECT, GRAPHKV_K_REDO_COSINE, GRAPHKV_K_REDO_TOPK,
     GRAPHKV_N_KERNELS
 };

@@ -24,7 +24,7 @@ struct Dims {
 // Workspace: a bump allocation of every scratch array any entry point may need.
 struct Workspace {
     size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, part;
-    size_t E_sample, tau, cand, cand_cnt, overflow, total;
+    size_t tau, cand, cand_cnt, overflow, total;
 };
 
 // The MFMA kernels cover bf16 keys with d = 128.  Scoring additionally needs the
@@ -124,7 +124,6 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.nbr_e = take((size_t)D.H * D.S * D.m * 4);
     W.scores = take((size_t)D.H * D.P * 4);
     W.part = take(D.mfma_score ? mfma_score_plan(D.H, D.G * D.w, D.N).part_bytes : 0);
-    W.E_sample = take(D.filter ? (size_t)D.H * D.S * mfma_sample_cols(D.P) * 4 : 0);
     W.tau = take((size_t)D.H * D.S * 4);
     const MfmaFilterGeom fg = D.filter ? mfma_filter_geom(D.H, D.P, D.S, D.m) : MfmaFilterGeom{0, 0, 0};
     W.cand = take((size_t)D.H * D.S * fg.chunks * fg.slice_cap * 8);
@@ -167,7 +166,7 @@ Profiler g_prof;
 const char *const kKernelNames[GRAPHKV_N_KERNELS] = {
     "score_stats", "score_votes", "pool_group", "topk_sources", "cosine", "topk_neighbors",
     "decay", "topk_final", "gather", "generic_logits", "generic_votes", "generic_cosine",
-    "knorm", "copy", "cosine_sample", "topk_bound", "cosine_filter", "nbr_select",
+    "knorm", "copy", "cosine_bound", "cosine_filter", "nbr_select",
     "redo_cosine", "redo_topk"};
 
 #define GKV_LAUNCH(id, expr)                                              \
@@ -244,14 +243,11 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
             if (D.filter) {
                 // Eq. 1 + Eq. 3 in one streaming pass over the keys: a bound on each source's
                 // m-th largest edge from a strided sample, then only edges above it are kept.
-                float *Es = at<float>(ws, W.E_sample), *tau = at<float>(ws, W.tau);
+                float *tau = at<float>(ws, W.tau);
                 int32_t *cnt = at<int32_t>(ws, W.cand_cnt), *ovf = at<int32_t>(ws, W.overflow);
                 void *cand = at<char>(ws, W.cand);
-                const int ps = mfma_sample_cols(D.P);
-                GKV_LAUNCH(GRAPHKV_K_COSINE_SAMPLE,
-                           launch_mfma_cosine_sample(Ac, Kc, D.H, D.N, D.P, D.S, src, Es, ovf, st));
-                GKV_LAUNCH(GRAPHKV_K_TOPK_BOUND,
-                           launch_topk_bound(Es, ps, ps, D.H * D.S, D.m, tau, st));
+                GKV_LAUNCH(GRAPHKV_K_COSINE_BOUND,
+                           launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, tau, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
                            launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, tau, cand, cnt,
                                                      ovf, st));

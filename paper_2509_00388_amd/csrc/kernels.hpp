@@ -21,11 +21,6 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k,
                             float *tau_out, int append_from, int append_count,
                             const int32_t *gate, int rows_per_gate, hipStream_t st);
 
-// A lower bound of each row's k-th largest value (exact up to a sliver of the row's value
-// range): enough for the candidate filter, cheaper than the exact selection.
-hipError_t launch_topk_bound(const float *x, long ld, int n, int rows, int k, float *tau_out,
-                             hipStream_t st);
-
 // ---- scalar kernels for any dtype / shape (generic.hip) ----------------------
 // logits [Hq*w, N] (fp32, scaled), then per-row max and sum of exp.
 hipError_t launch_generic_logits(const void *Kc, const void *Qw, int dtype, int Hkv, int Hq, int d,
@@ -90,10 +85,10 @@ struct MfmaFilterGeom {
     int slice_cap;    // entries per (source, chunk) slice
 };
 MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m);
-// E_sample [Hkv, S, sample_cols] on every (P / sample_cols)-th key; clears overflow [Hkv].
-hipError_t launch_mfma_cosine_sample(const void *Ac, const void *Kc, int Hkv, int N, int P, int S,
-                                     const int32_t *src, float *E_sample, int32_t *overflow,
-                                     hipStream_t st);
+// tau [Hkv, S]: a lower bound of each source's m-th largest edge, from the edges to every
+// (P / sample_cols)-th key (within 1/256 of the m-th largest sampled edge); clears overflow [Hkv].
+hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
+                                    const int32_t *src, float *tau, int32_t *overflow, hipStream_t st);
 // Streams all keys; edges that reach tau[h, a] go to cand [Hkv, S, chunks, slice_cap] x 8
 // bytes, their number per slice to cand_cnt [Hkv, S, chunks].
 hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,

@@ -153,6 +153,110 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
     GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, key_stride, ntile, multiply_tile, (void)0);
 }
 
+// Bound pass: a lower bound of every source's m-th largest edge, from the edges to a
+// strided sample of the keys (column c = key c * key_stride) -- a subset's m-th
+// largest can only be smaller than the whole row's.  One workgroup takes the whole
+// sample of a (head, source group): the edges never leave the registers, they are
+// counted into a 512-bin histogram over [-1, 1] per source in LDS (16-bit counters,
+// two to a word), and the bound is the lower edge of the bin in which the count
+// from the top reaches m: at most 1/256 below the m-th largest sampled edge.  (An
+// edge a rounding error below a bin edge may be counted into the bin above; the
+// filter pass lowers every bound by far more than that.)  The source's own column
+// is left out (Eq. 3: j != i).  Also clears the head's overflow flag for the filter
+// pass that follows.
+constexpr int kBoundBins = 512;
+
+__global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
+    const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride,
+    int S, const int32_t *__restrict__ src, int m, float *__restrict__ tau, int32_t *__restrict__ overflow)
+{
+    __shared__ float inv_s[kRows];
+    __shared__ int32_t idx_s[kRows];
+    extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the histograms
+    unsigned char *kt = smem;
+    uint32_t *hist = reinterpret_cast<uint32_t *>(smem + 2 * kTileBytes);   // [kRows][kBoundBins / 2]
+
+    const int h = blockIdx.y, s_base = blockIdx.z * kRows;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
+    const int stream = wv & 3, grp = wv >> 2;
+    const uint16_t *Kh = Kc + (long)h * N * kD;
+    if (blockIdx.z == 0 && tid == 0) overflow[h] = 0;
+
+    bf16x8 q[kSteps];
+    load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
+    for (int u = tid; u < kRows * (kBoundBins / 2); u += kThreads) hist[u] = 0;
+    __syncthreads();
+    float inv_src[16];
+    int32_t self[16];   // the source's own key; -1 for rows past S: those count nothing
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = kBlk * grp + acc_row(i, hh);
+        inv_src[i] = inv_s[row];
+        self[i] = s_base + row < S ? idx_s[row] : -1;
+    }
+
+    const int ntile = (n_cols + kTileKeys - 1) / kTileKeys;
+    auto multiply_tile = [&](const unsigned char *buf, int t) {
+        bf16x8 kc[kSteps];
+        tile_read(buf, stream, l32, hh, kc);
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s)   // rows = sources, columns = keys
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[s], kc[s], acc, 0, 0, 0);
+
+        float sq = half_row_sumsq(kc);
+        sq += __shfl_xor(sq, 32, kWave);
+        const float inv_k = inv_norm(sq);
+        const int col = kTileKeys * t + kBlk * stream + l32;
+        const int key = col * key_stride;
+        if (col < n_cols) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (self[i] >= 0 && key != self[i]) {
+                    const float e = (acc[i] * inv_k) * inv_src[i];   // the dense kernel's formula
+                    int b = (int)((e + 1.0f) * (0.5f * kBoundBins));
+                    b = b < 0 ? 0 : (b > kBoundBins - 1 ? kBoundBins - 1 : b);
+                    atomicAdd(&hist[(kBlk * grp + acc_row(i, hh)) * (kBoundBins / 2) + (b >> 1)],
+                              (b & 1) ? 65536u : 1u);
+                }
+            }
+        }
+    };
+    GKV_TILE_PIPELINE(kThreads, Kh, 0, n_cols - 1, key_stride, ntile, multiply_tile, (void)0);
+    __syncthreads();
+
+    // Wave w scans the histograms of rows 8w .. 8w+7 from the top; lane L holds bins 8L .. 8L+7.
+    for (int r = 0; r < kRows / (kThreads / kWave); ++r) {
+        const int row = wv * (kRows / (kThreads / kWave)) + r;
+        const uint4 w4 = *reinterpret_cast<const uint4 *>(&hist[row * (kBoundBins / 2) + 4 * lane]);
+        const uint32_t c[8] = {w4.x & 0xffffu, w4.x >> 16, w4.y & 0xffffu, w4.y >> 16,
+                               w4.z & 0xffffu, w4.z >> 16, w4.w & 0xffffu, w4.w >> 16};
+        uint32_t mine = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) mine += c[k];
+        uint32_t from_top = mine;   // count in this lane's bins and all higher ones
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t v = __shfl_down(from_top, o, kWave);
+            if (lane + o < 64) from_top += v;
+        }
+        const uint32_t above = from_top - mine;
+        if (above < (uint32_t)m && from_top >= (uint32_t)m && s_base + row < S) {
+            uint32_t cum = above;
+            int k = 7;
+            for (; k > 0; --k) {
+                if (cum + c[k] >= (uint32_t)m) break;
+                cum += c[k];
+            }
+            tau[(long)h * S + s_base + row] = (float)(8 * lane + k) * (2.0f / kBoundBins) - 1.0f;
+        }
+        if (lane == 0 && from_top < (uint32_t)m && s_base + row < S)
+            tau[(long)h * S + s_base + row] = -INFINITY;   // fewer than m sampled edges: no bound
+    }
+}
+
 // Filter pass over all keys.  A lane holds, per key block, the 16 dots of its key
 // with 16 of the wave's sources.  It tests them all at once against the sources'
 // bounds (dot >= bound_i * |k_j|, bounds a hair lowered so that rounding can never
@@ -172,12 +276,12 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
 // another: positions come from LDS counters).  A ring holds 64 rows and a wave
 // drains on its own whenever a half has more than 32 waiting, so a tile's 32
 // rows at most always fit.  The source's own column may be among the candidates:
-// the exact select drops it.  If a slice (or the short LDS list that takes a row's
-// hits beyond its fourth) overflows, the head's overflow flag is raised and the
-// head is redone densely.
+// the exact select drops it.  If a slice (or one of the short LDS lists that take
+// a row's hits beyond its fourth) overflows, the head's overflow flag is raised and
+// the head is redone densely.
 constexpr int kRingRows = 64;      // rows per half-wave ring
 constexpr int kStagePitch = 80;    // bytes per parked row: 16 dots, |k|^2, key (72, padded)
-constexpr int kLaterCap = 256;     // LDS list of the hits beyond a row's fourth
+constexpr int kLaterCap = 128;     // entries of each of the two LDS lists of hits beyond a row's fourth
 
 __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int S,
@@ -186,8 +290,10 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     __shared__ float inv_s[kRows], lo_s[kRows], det_s[kRows];
     __shared__ int32_t idx_s[kRows];
     __shared__ int32_t row_pos[kRows];   // entries written to each source's slice
-    __shared__ uint4 later[kLaterCap];   // (edge bits, key, source row): hits beyond a row's fourth
-    __shared__ int32_t n_later;
+    // (edge bits, key, source row) of the hits beyond a row's fourth: one list for even and one
+    // for odd tiles, each emptied right after the barrier that ends its tile
+    __shared__ uint4 later[2][kLaterCap];
+    __shared__ int32_t n_later[2], later_lost;   // entries ever listed (never reset)
     extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the rings
     unsigned char *kt = smem;
     unsigned char *stage_mem = smem + 2 * kTileBytes;
@@ -202,7 +308,8 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     bf16x8 q[kSteps];
     load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
     if (tid < kRows) row_pos[tid] = 0;
-    if (tid == 0) n_later = 0;
+    if (tid < 2) n_later[tid] = 0;
+    if (tid == 0) later_lost = 0;
     __syncthreads();
     if (tid < kRows) {
         // lo: what an exact edge must reach to be listed; det: the still lower bound of the
@@ -237,8 +344,9 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     // No loop in here holds a global store: after such a loop the compiler can no longer
     // count the memory operations in flight and would make the next LDS store of a key tile
     // wait for every outstanding prefetch.  A row's first four hits are stored by straight-
-    // line code; the rare further ones go to an LDS list that is emptied after the last tile.
-    auto drain = [&]() {
+    // line code; further ones (keys that are close to many sources at once) go to the LDS
+    // list of the current tile's parity.
+    auto drain = [&](int par) {
         const int n0 = min(tail0 - head0, kBlk), n1 = min(tail1 - head1, kBlk);
         if (l32 < (hh ? n1 : n0)) {
             const unsigned char *row_mem = ring + (((hh ? head1 : head0) + l32) & (kRingRows - 1)) * kStagePitch;
@@ -287,8 +395,8 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
                 hits &= hits - 1;
                 const int row = kBlk * grp + acc_row(i, hh);
                 const float e = (reinterpret_cast<const float *>(row_mem)[i] * inv_k) * inv_s[row];
-                const int at = atomicAdd(&n_later, 1);
-                if (at < kLaterCap) later[at] = make_uint4(__float_as_uint(e), key, (uint32_t)row, 0u);
+                const int at = atomicAdd(&n_later[par], 1);
+                later[par][at & (kLaterCap - 1)] = make_uint4(__float_as_uint(e), key, (uint32_t)row, 0u);
             }
         }
         head0 += n0;
@@ -336,25 +444,34 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
         // -- a count of memory operations still in flight -- lets the loads stay in flight.
         // Otherwise a ring must at least be able to take the next tile's 32 rows (at most 64
         // wait: one pass suffices).
-        if (t % de == de - 1) { drain(); drain(); }
-        else if (tail0 - head0 > kRingRows - kBlk || tail1 - head1 > kRingRows - kBlk) drain();
+        if (t % de == de - 1) { drain(t & 1); drain(t & 1); }
+        else if (tail0 - head0 > kRingRows - kBlk || tail1 - head1 > kRingRows - kBlk) drain(t & 1);
     };
-    GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, 1, ntile, multiply_tile, (void)0);
-    drain();
-    drain();
+    // Entries listed during the tile that just ended are final behind its barrier, and the next
+    // tile lists into the other list: one thread per entry stores them.  A list holds
+    // kLaterCap entries; more than that in one tile and the head is redone densely.
+    int later_seen[2] = {0, 0};
+    auto store_later = [&](int par) {
+        const int n = n_later[par];
+        const int x = later_seen[par] + tid;
+        if (n - later_seen[par] > kLaterCap && tid == 0) later_lost = 1;
+        later_seen[par] = n;
+        if (x < n) {
+            const uint4 r = later[par][x & (kLaterCap - 1)];
+            const int at = atomicAdd(&row_pos[r.z], 1);
+            if (at < fa.slice_cap) slice0[(long)r.z * slice_row_stride + at] = make_uint2(r.x, r.y);
+        }
+    };
+    GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, 1, ntile, multiply_tile, store_later((tile_done - 1) & 1));
+    drain(ntile & 1);
+    drain(ntile & 1);
     __syncthreads();
-    // hits beyond a row's fourth
-    const int nl = n_later < kLaterCap ? n_later : kLaterCap;
-    for (int x = tid; x < nl; x += kThreads) {
-        const uint4 r = later[x];
-        const int at = atomicAdd(&row_pos[r.z], 1);
-        if (at < fa.slice_cap) slice0[(long)r.z * slice_row_stride + at] = make_uint2(r.x, r.y);
-    }
+    store_later(ntile & 1);
     __syncthreads();      // every candidate is counted
     if (tid < kRows && s_base + tid < S) {
         const int c = row_pos[tid];
         fa.cand_cnt[((long)h * S + s_base + tid) * gridDim.x + chunk] = c < fa.slice_cap ? c : fa.slice_cap;
-        if (c > fa.slice_cap || n_later > kLaterCap) fa.overflow[h] = 1;
+        if (c > fa.slice_cap || later_lost) fa.overflow[h] = 1;
     }
 }
 
@@ -598,20 +715,15 @@ hipError_t launch_mfma_cosine(const void *Ac, const void *Kc, int Hkv, int N, in
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_cosine_sample(const void *Ac, const void *Kc, int Hkv, int N, int P, int S,
-                                     const int32_t *src, float *E_sample, int32_t *overflow,
-                                     hipStream_t st)
+hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
+                                    const int32_t *src, float *tau, int32_t *overflow, hipStream_t st)
 {
     const int ps = mfma_sample_cols(P), stride = P / ps;
     const int sgroups = (S + kRows - 1) / kRows;
-    const int ck = chunk_cols_for(Hkv, sgroups, ps);
-    const int chunks = (ps + ck - 1) / ck;
-    FilterArgs fa{};
-    fa.overflow = overflow;
-    if (!allow_big_lds((const void *)cosine_dense_kernel)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_dense_kernel, dim3(chunks, Hkv, sgroups), dim3(kThreads), 2 * kTileBytes,
-                       st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, ps, stride, S, src, ck, E_sample, fa,
-                       (const int32_t *)nullptr);
+    if (!allow_big_lds((const void *)cosine_bound_kernel)) return hipGetLastError();
+    hipLaunchKernelGGL(cosine_bound_kernel, dim3(1, Hkv, sgroups), dim3(kThreads),
+                       2 * kTileBytes + kRows * (kBoundBins / 2) * 4, st, (const uint16_t *)Ac,
+                       (const uint16_t *)Kc, N, ps, stride, S, src, m, tau, overflow);
     return hipGetLastError();
 }
 

@@ -83,15 +83,13 @@ __device__ __forceinline__ void find_bin(const uint32_t *hist, uint32_t need, in
 // therefore (i, wave, lane), and the emit sweep counts per (i, wave) cell with
 // ballots and scans the cells once.
 // DIG = bits per radix sweep (11 for long rows, 8 for short ones: fewer bins to clear
-// and scan).  max_sweeps > 0 stops after that many sweeps: tau_out then receives a
-// value at most (row range) / 2^(DIG * max_sweeps) below the k-th largest -- a valid,
-// slightly loose lower bound (idx_out must be nullptr in that case).
+// and scan).
 template <int BLOCK, bool PLAN, int DIG>
 __device__ __forceinline__ void topk_row_lds(
     int row, const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out,
     long idx_ld, float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out,
     int append_from, int append_count,
-    const typename std::conditional<PLAN, LayerPlan, int>::type &plan, int max_sweeps)
+    const typename std::conditional<PLAN, LayerPlan, int>::type &plan)
 {
     constexpr int NW = BLOCK / kWave;
     constexpr int NBINS = 1 << DIG;
@@ -143,8 +141,7 @@ __device__ __forceinline__ void topk_row_lds(
     const uint32_t range = kmax - kmin;
     int remaining = range ? 32 - __clz(range) : 0;
     uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
-    int sweeps = 0;
-    while (remaining > 0 && (max_sweeps <= 0 || sweeps < max_sweeps)) {
+    while (remaining > 0) {
         const int bits = remaining < DIG ? remaining : DIG;
         const int shift = remaining - bits;
         const uint32_t dmask = (1u << bits) - 1u;
@@ -162,9 +159,7 @@ __device__ __forceinline__ void topk_row_lds(
         mask |= dmask << shift;
         need = s_need;
         remaining = shift;
-        ++sweeps;
     }
-    // If sweeps were cut short the unresolved low bits are 0: the lower edge of the bin.
     const uint32_t tau = kmin + prefix;   // key of the k-th largest entry; take `need` entries equal to it
     if (tau_out && tid == 0) tau_out[row] = key_to_float(tau);
     if (!out) return;
@@ -224,7 +219,7 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     const float *__restrict__ x, long ld, int n, int rows, int k, int32_t *__restrict__ idx_out,
     long idx_ld, float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out,
     int append_from, int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
-    typename std::conditional<PLAN, LayerPlan, int>::type plan, int max_sweeps)
+    typename std::conditional<PLAN, LayerPlan, int>::type plan)
 {
     if constexpr (WALK) {
         // one round trip settles the usual case of no gate being set at all
@@ -236,11 +231,11 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
             if (gate[row / rows_per_gate] == 0) continue;
             __syncthreads();   // LDS is reused from row to row
             topk_row_lds<BLOCK, PLAN, DIG>(row, x, ld, n, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                                           append_from, append_count, plan, max_sweeps);
+                                           append_from, append_count, plan);
         }
     } else {
         topk_row_lds<BLOCK, PLAN, DIG>(blockIdx.x, x, ld, n, k, idx_out, idx_ld, val_out, val_ld,
-                                       tau_out, append_from, append_count, plan, max_sweeps);
+                                       tau_out, append_from, append_count, plan);
     }
 }
 
@@ -363,7 +358,7 @@ template <int BLOCK, bool PLAN, int DIG, typename PlanArg>
 static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
                              long idx_ld, float *val_out, long val_ld, float *tau_out,
                              int append_from, int append_count, const int32_t *gate,
-                             int rows_per_gate, PlanArg plan, int max_sweeps, hipStream_t st)
+                             int rows_per_gate, PlanArg plan, hipStream_t st)
 {
     const int items = (n + BLOCK - 1) / BLOCK;
     const size_t lds = ((size_t)items * BLOCK + 2 * (size_t)items * (BLOCK / kWave)) * 4;
@@ -379,11 +374,11 @@ static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, in
     if (gate)
         hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN, DIG, true>), dim3(rows > 1024 ? 1024 : rows),
                            dim3(BLOCK), lds, st, x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld,
-                           tau_out, append_from, append_count, gate, rows_per_gate, plan, max_sweeps);
+                           tau_out, append_from, append_count, gate, rows_per_gate, plan);
     else
         hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN, DIG, false>), dim3(rows), dim3(BLOCK), lds,
                            st, x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from,
-                           append_count, gate, rows_per_gate, plan, max_sweeps);
+                           append_count, gate, rows_per_gate, plan);
     return hipGetLastError();
 }
 
@@ -391,17 +386,15 @@ template <bool PLAN, typename PlanArg>
 static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
                              long idx_ld, float *val_out, long val_ld, float *tau_out,
                              int append_from, int append_count, const int32_t *gate,
-                             int rows_per_gate, PlanArg plan, int max_sweeps, hipStream_t st)
+                             int rows_per_gate, PlanArg plan, hipStream_t st)
 {
     if (rows <= 0) return hipSuccess;
     if (n <= 4096)
         return launch_lds<256, PLAN, 8>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                                        append_from, append_count, gate, rows_per_gate, plan,
-                                        max_sweeps, st);
+                                        append_from, append_count, gate, rows_per_gate, plan, st);
     if (n <= 32768)
         return launch_lds<1024, PLAN, 11>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                                          append_from, append_count, gate, rows_per_gate, plan,
-                                          max_sweeps, st);
+                                          append_from, append_count, gate, rows_per_gate, plan, st);
     hipLaunchKernelGGL((topk_rows_stream_kernel<1024, PLAN>), dim3(rows), dim3(1024), 0, st, x, ld, n,
                        k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
                        rows_per_gate, plan);
@@ -414,24 +407,14 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k, int
                             int rows_per_gate, hipStream_t st)
 {
     return launch_any<false, int>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
-                                  append_from, append_count, gate, rows_per_gate, 0, 0, st);
-}
-
-hipError_t launch_topk_bound(const float *x, long ld, int n, int rows, int k, float *tau_out,
-                             hipStream_t st)
-{
-    // 2 sweeps (8-bit digits on rows of at most 4096 entries, 11-bit digits up to 32768):
-    // the bound is within 1/65536 of the row's value range below the exact k-th
-    // largest.  Rows too long for the LDS kernels get the exact value.
-    return launch_any<false, int>(x, ld, n, rows, k, nullptr, 0, nullptr, 0, tau_out, 0, 0, nullptr,
-                                  1, 0, n <= 32768 ? 2 : 0, st);
+                                  append_from, append_count, gate, rows_per_gate, 0, st);
 }
 
 hipError_t launch_topk_final(const float *scores, int P, int rows, const LayerPlan &plan, int w,
                              int32_t *idx, hipStream_t st)
 {
     return launch_any<true, LayerPlan>(scores, P, P, rows, 0, idx, 0, nullptr, 0, nullptr, P, w,
-                                       nullptr, 1, plan, 0, st);
+                                       nullptr, 1, plan, st);
 }
 
 }  // namespace gkv

@@ -256,6 +256,29 @@ def test_filtered_neighbourhoods_staged(oracle, S, m):
     assert np.count_nonzero((nbr != nbr_g).any(axis=-1)) <= 2 + flips
 
 
+def test_filtered_neighbourhoods_keys_close_to_many_sources(oracle):
+    """A tight cluster that holds 12 of the sources: each of its keys is a candidate of all
+    12 at once, far more hits per key than the filter pass stores in line."""
+    cfg = small_bf16_cfg(n_tokens=11000, n_sources=24, n_neighbors=16, n_kv_heads=2, n_q_heads=8)
+    (K, V, Q), _ = util.device_layer(cfg, 2)
+    P = cfg.n_prefix
+    rng = np.random.default_rng(17)
+    members = rng.choice(P, size=90, replace=False)
+    centre = synth.bf16_bits_to_f32(K[1, members[0]]).astype(np.float64)
+    noisy = centre[None, :] * (1.0 + 0.02 * rng.standard_normal((90, cfg.head_dim)))
+    K[1, members] = synth.f32_to_bf16_bits(noisy.astype(np.float32))
+    Kd = gk.to_device(K, gk.BF16)
+    s0 = synth.random_scores(cfg)
+    s0[1, members[:12]] = 40.0 + np.arange(12)          # 12 cluster members become sources
+    p = util.params_from_cfg(cfg, rounds=1)
+    s1, src, nbr, ev = run_propagate(p, Kd, s0)
+    assert set(members[:12].tolist()) <= set(src[0, 1].tolist())
+    flips = util.check_round_staged(oracle, K, "bf16", cfg.window, s0, s1, src[0], nbr[0], ev[0], 24, 16, 1.0)
+    say(f"  neighbour lists differing from the oracle's (near-ties): {flips}")
+    a = src[0, 1].tolist().index(int(members[0]))
+    assert set(nbr[0, 1, a].tolist()) <= set(members.tolist())   # its neighbours are cluster members
+
+
 def test_filtered_neighbourhoods_overflow_falls_back(oracle):
     """Masses of exactly equal edges defeat any bound: those heads must be redone
     through the dense block and still give the exact lowest-index answer."""
