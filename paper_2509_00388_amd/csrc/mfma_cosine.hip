@@ -62,6 +62,7 @@ struct FilterArgs {
     int32_t *overflow;     // [Hkv]
     int slice_cap;
     int drain_every;       // tiles between two scheduled drains of the rings
+    int sgroups;           // groups of 64 sources
 };
 
 // Both kernels below: a workgroup has 4 key streams (wave & 3) and 2 source row
@@ -176,11 +177,11 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
     unsigned char *kt = smem;
     uint32_t *hist = reinterpret_cast<uint32_t *>(smem + 2 * kTileBytes);   // [kRows][kBoundBins / 2]
 
-    const int h = blockIdx.y, s_base = blockIdx.z * kRows;
+    const int h = blockIdx.y, s_base = blockIdx.x * kRows;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, grp = wv >> 2;
     const uint16_t *Kh = Kc + (long)h * N * kD;
-    if (blockIdx.z == 0 && tid == 0) overflow[h] = 0;
+    if (blockIdx.x == 0 && tid == 0) overflow[h] = 0;
 
     bf16x8 q[kSteps];
     load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
@@ -298,7 +299,11 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     unsigned char *kt = smem;
     unsigned char *stage_mem = smem + 2 * kTileBytes;
 
-    const int h = blockIdx.y, chunk = blockIdx.x, s_base = blockIdx.z * kRows;
+    // The source groups of a key chunk sit next to each other in the grid: their workgroups run
+    // at about the same time, and the keys the first one pulls from HBM are still in the
+    // memory-side cache when the others ask for them.
+    const int n_chunks = gridDim.x / fa.sgroups;
+    const int h = blockIdx.y, chunk = blockIdx.x / fa.sgroups, s_base = (blockIdx.x % fa.sgroups) * kRows;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, grp = wv >> 2;
     const uint16_t *Kh = Kc + (long)h * N * kD;
@@ -335,8 +340,8 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
 
     unsigned char *ring = stage_mem + (2 * wv + hh) * (kRingRows * kStagePitch);
     const uint64_t half_before = (hh ? 0xffffffff00000000ull : 0x00000000ffffffffull) & ((1ull << lane) - 1ull);
-    uint2 *slice0 = fa.cand + (((long)h * S + s_base) * gridDim.x + chunk) * fa.slice_cap;
-    const long slice_row_stride = (long)gridDim.x * fa.slice_cap;
+    uint2 *slice0 = fa.cand + (((long)h * S + s_base) * n_chunks + chunk) * fa.slice_cap;
+    const long slice_row_stride = (long)n_chunks * fa.slice_cap;
     // rows ever parked / ever drained by the lower and the upper half-wave (same in every lane)
     int tail0 = 0, tail1 = 0, head0 = 0, head1 = 0;
 
@@ -470,7 +475,7 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     __syncthreads();      // every candidate is counted
     if (tid < kRows && s_base + tid < S) {
         const int c = row_pos[tid];
-        fa.cand_cnt[((long)h * S + s_base + tid) * gridDim.x + chunk] = c < fa.slice_cap ? c : fa.slice_cap;
+        fa.cand_cnt[((long)h * S + s_base + tid) * n_chunks + chunk] = c < fa.slice_cap ? c : fa.slice_cap;
         if (c > fa.slice_cap || later_lost) fa.overflow[h] = 1;
     }
 }
@@ -721,7 +726,7 @@ hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int
     const int ps = mfma_sample_cols(P), stride = P / ps;
     const int sgroups = (S + kRows - 1) / kRows;
     if (!allow_big_lds((const void *)cosine_bound_kernel)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_bound_kernel, dim3(1, Hkv, sgroups), dim3(kThreads),
+    hipLaunchKernelGGL(cosine_bound_kernel, dim3(sgroups, Hkv), dim3(kThreads),
                        2 * kTileBytes + kRows * (kBoundBins / 2) * 4, st, (const uint16_t *)Ac,
                        (const uint16_t *)Kc, N, ps, stride, S, src, m, tau, overflow);
     return hipGetLastError();
@@ -741,9 +746,9 @@ hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, in
     const double per_tile = 32.0 * (1.0 - pow(1.0 - (rate < 1.0 ? rate : 1.0), 16.0));
     int drain_every = (int)(30.0 / (per_tile > 0.45 ? per_tile : 0.45));
     if (drain_every < 1) drain_every = 1;
-    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, drain_every};
+    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, drain_every, sgroups};
     if (!allow_big_lds((const void *)cosine_filter_kernel)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_filter_kernel, dim3(g.chunks, Hkv, sgroups), dim3(kThreads),
+    hipLaunchKernelGGL(cosine_filter_kernel, dim3(g.chunks * sgroups, Hkv), dim3(kThreads),
                        2 * kTileBytes + 2 * (kThreads / kWave) * kRingRows * kStagePitch, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, src,
                        g.chunk_cols, fa);
     return hipGetLastError();

@@ -58,12 +58,16 @@ __device__ __forceinline__ void load_queries(const uint16_t *Qb, int l32, int hh
 template <int NB, int SPLIT>
 __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w,
-    int chunk_keys, float c, float *__restrict__ part, int R_total, int row_base)
+    int chunk_keys, float c, float *__restrict__ part, int R_total, int row_base, int nparts)
 {
     constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
     __shared__ float sm[4][R], sz[4][R];
-    const int h = blockIdx.y, chunk = blockIdx.x, nchunks = gridDim.x;
+    // nparts > 1: equal parts of 128 rows share one launch, the parts of a key chunk next to
+    // each other in the grid, so that the keys one part pulls from HBM are still in the
+    // memory-side cache when the next part asks for them
+    const int h = blockIdx.y, chunk = blockIdx.x / nparts, nchunks = gridDim.x / nparts;
+    row_base += 128 * (blockIdx.x % nparts);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, row0 = (wv >> 2) * NBW * kBlk;   // first query row of this wave
 
@@ -162,12 +166,14 @@ template <int NB, int SPLIT, bool PERQ>
 __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w, int G,
     int chunk_keys, float c, const float *__restrict__ part, int part_chunks,
-    float *__restrict__ votes, int R_total, int row_base, int vote_rows, int vote_row_base)
+    float *__restrict__ votes, int R_total, int row_base, int vote_rows, int vote_row_base, int nparts)
 {
     constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
     __shared__ float bias_s[R];
-    const int h = blockIdx.y, chunk = blockIdx.x;
+    const int h = blockIdx.y, chunk = blockIdx.x / nparts;
+    row_base += 128 * (blockIdx.x % nparts);
+    vote_row_base += SPLIT * (blockIdx.x % nparts);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, grp = wv >> 2, row0 = grp * NBW * kBlk;
 
@@ -309,14 +315,16 @@ hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int 
     const int ck = chunk_keys_for(Hkv, N);
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
-    dim3 grid(plan.chunks, Hkv);
+    // equal parts of 128 rows go into one launch (see the kernel), other splits one launch per part
+    const int merged = (R > 128 && R % 128 == 0) ? R / 128 : 1;
+    dim3 grid(plan.chunks * merged, Hkv);
 #define GKV_STATS(NB, SP)                                                                          \
     do {                                                                                           \
         if (!allow_big_lds((const void *)score_stats_kernel<NB, SP>)) return hipGetLastError();    \
         hipLaunchKernelGGL((score_stats_kernel<NB, SP>), grid, dim3(256 * SP), 2 * kTileBytes, st, \
-                           K, Q, N, P, w, ck, c, part, R, row_base);                               \
+                           K, Q, N, P, w, ck, c, part, R, row_base, merged);                       \
     } while (0)
-    for (int pt = 0; 128 * pt < R; ++pt) {
+    for (int pt = 0; 128 * pt < R; pt += merged) {
         const int row_base = 128 * pt;
         switch (part_rows(R, pt) / 32) {
             case 1: GKV_STATS(1, 1); break;
@@ -334,18 +342,19 @@ hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int 
 template <int NB, int SPLIT>
 static void launch_votes_nb(dim3 grid, const uint16_t *K, const uint16_t *Q, int N, int P, int w, int G,
                             int ck, float c, const float *part, int chunks, int per_q, float *votes,
-                            int R_total, int row_base, int vote_rows, int vote_row_base, hipStream_t st)
+                            int R_total, int row_base, int vote_rows, int vote_row_base, int nparts,
+                            hipStream_t st)
 {
     if (per_q) {
         if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, true>)) return;
         hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, true>), grid, dim3(256 * SPLIT),
                            2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
-                           row_base, vote_rows, vote_row_base);
+                           row_base, vote_rows, vote_row_base, nparts);
     } else {
         if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, false>)) return;
         hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, false>), grid, dim3(256 * SPLIT),
                            2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
-                           row_base, vote_rows, vote_row_base);
+                           row_base, vote_rows, vote_row_base, nparts);
     }
 }
 
@@ -358,13 +367,14 @@ hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int 
     const int ck = chunk_keys_for(Hkv, N);
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
-    dim3 grid(plan.chunks, Hkv);
+    const int merged = (R > 128 && R % 128 == 0) ? R / 128 : 1;   // as in the statistics pass
+    dim3 grid(plan.chunks * merged, Hkv);
     const int vote_rows = mfma_score_vote_rows(G, w, per_qhead_votes);
     int vote_row_base = 0;
 #define GKV_VOTES(NB, SP)                                                                             \
     launch_votes_nb<NB, SP>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, R, \
-                            row_base, vote_rows, vote_row_base, st)
-    for (int pt = 0; 128 * pt < R; ++pt) {
+                            row_base, vote_rows, vote_row_base, merged, st)
+    for (int pt = 0; 128 * pt < R; pt += merged) {
         const int row_base = 128 * pt, rows = part_rows(R, pt);
         const int split = part_split(rows, w, per_qhead_votes);
         switch (rows / 32) {
