@@ -439,6 +439,33 @@ def test_compress_variants(oracle, impl, kw):
         assert (out[2] == np.arange(1500)).all()
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_compress_random_shapes(oracle, seed):
+    """Randomly drawn shapes and parameters (both kernel families, both neighbourhood routes,
+    ragged sizes), whole pass against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    big = seed % 4 == 3                                  # every fourth case takes the filter route
+    G = int(rng.choice([1, 2, 4]))
+    w = int(rng.choice([32, 64])) if rng.random() < 0.7 else int(rng.integers(3, 40))
+    Hkv = int(rng.integers(1, 4))
+    N = int(rng.integers(8200 + w, 12000)) if big else int(rng.integers(w + 40, 3000))
+    P = N - w
+    S = int(rng.integers(1, min(P, 150) + 1))
+    m = int(rng.integers(1, min(P - 1, 60) + 1))
+    B = int(rng.integers(w + 1, N + 1))
+    kw = dict(n_tokens=N, window=w, n_kv_heads=Hkv, n_q_heads=Hkv * G, budget=B, n_sources=S,
+              n_neighbors=m, rounds=int(rng.integers(0, 4)), pool_kernel=int(rng.choice([1, 3, 7])),
+              pool_mode=int(rng.integers(0, 2)), reselect=int(rng.integers(0, 2)),
+              decay=float(rng.choice([1.0, 0.5])), signal=int(rng.choice([0, 0, 1, 2])))
+    cfg = small_bf16_cfg(**{k: v for k, v in kw.items() if k in ("n_tokens", "window", "n_kv_heads",
+                                                                  "n_q_heads", "budget", "n_sources",
+                                                                  "n_neighbors", "pool_kernel")})
+    extra = {k: kw[k] for k in ("rounds", "pool_mode", "reselect", "decay", "signal")}
+    impl = gk.IMPL_AUTO if seed % 3 else gk.IMPL_GENERIC
+    say(f"random shape seed={seed} impl={impl} {kw}")
+    end_to_end(oracle, cfg, seed, impl, **extra)
+
+
 def test_generic_and_mfma_agree():
     cfg = small_bf16_cfg()
     host, dev = util.device_layer(cfg, 9)

@@ -37,7 +37,7 @@ def assert_scores_close(gpu, ref, what="scores"):
     assert np.array_equal(np.isfinite(gpu), finite), f"{what}: infinities differ"
     assert np.array_equal(gpu[~finite], ref[~finite]), f"{what}: infinities differ"
     scale = np.abs(ref[finite]).max() if finite.any() else 0.0
-    err = np.abs(gpu - ref)[finite]
+    err = np.abs(gpu[finite] - ref[finite])
     bound = REL_TOL * np.abs(ref[finite]) + 1e-9 * scale
     bad = err > bound
     assert not bad.any(), (f"{what}: {bad.sum()} of {bad.size} beyond tolerance, worst rel err "
