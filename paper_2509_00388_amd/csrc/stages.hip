@@ -37,26 +37,29 @@ __global__ __launch_bounds__(256) void pool_group_kernel(const float *__restrict
 // coalesced load per row and thread) and the sum is pooled once out of an LDS tile
 // with a halo.  Same value as pooling each row and adding, up to fp32 rounding order.
 constexpr int kPoolHalo = 16;
+constexpr int kPoolTile = 2048;   // outputs per workgroup: 8 per thread, enough loads in flight per CU
 __global__ __launch_bounds__(256) void pool_avg_kernel(const float *__restrict__ votes, int Gv, int P,
                                                        int pool_kernel, float div,
                                                        float *__restrict__ scores)
 {
-    __shared__ float tile[256 + 2 * kPoolHalo];
-    const int h = blockIdx.y, j0 = blockIdx.x * 256, tid = threadIdx.x;
+    __shared__ float tile[kPoolTile + 2 * kPoolHalo];
+    const int h = blockIdx.y, j0 = blockIdx.x * kPoolTile, tid = threadIdx.x;
     const int half = (pool_kernel - 1) / 2;
-    for (int u = tid; u < 256 + 2 * kPoolHalo; u += 256) {
+    for (int u = tid; u < kPoolTile + 2 * kPoolHalo; u += 256) {
         const int j = j0 - kPoolHalo + u;
         float v = 0.f;                               // zero padding outside the row
-        if (j >= 0 && j < P && u >= kPoolHalo - half && u < 256 + kPoolHalo + half)
+        if (j >= 0 && j < P && u >= kPoolHalo - half && u < kPoolTile + kPoolHalo + half)
             for (int g = 0; g < Gv; ++g) v += votes[((long)h * Gv + g) * P + j];
         tile[u] = v;
     }
     __syncthreads();
-    const int j = j0 + tid;
-    if (j >= P) return;
-    float acc = 0.f;
-    for (int t = -half; t <= half; ++t) acc += tile[kPoolHalo + tid + t];
-    scores[(long)h * P + j] = acc / (float)pool_kernel / div;
+    for (int o = tid; o < kPoolTile; o += 256) {
+        const int j = j0 + o;
+        if (j >= P) break;
+        float acc = 0.f;
+        for (int t = -half; t <= half; ++t) acc += tile[kPoolHalo + o + t];
+        scores[(long)h * P + j] = acc / (float)pool_kernel / div;
+    }
 }
 
 __device__ __forceinline__ float signal_factor(float e, float alpha, int signal)
@@ -302,7 +305,7 @@ hipError_t launch_pool_group(const float *votes, int Hkv, int Gv, int P, int poo
                              int pool_mode, float div, float *scores, hipStream_t st)
 {
     if (pool_mode == 0 && pool_kernel <= 2 * kPoolHalo + 1)
-        hipLaunchKernelGGL(pool_avg_kernel, dim3((P + 255) / 256, Hkv), dim3(256), 0, st, votes, Gv, P,
+        hipLaunchKernelGGL(pool_avg_kernel, dim3((P + kPoolTile - 1) / kPoolTile, Hkv), dim3(256), 0, st, votes, Gv, P,
                            pool_kernel, div, scores);
     else
         hipLaunchKernelGGL(pool_group_kernel, dim3((P + 255) / 256, Hkv), dim3(256), 0, st, votes, Gv,
