@@ -12,9 +12,10 @@ JSON line.
                    time; every layer and KV head of the model is processed)
   roofline         for the kernel that takes the most time: algorithmic bytes
                    per launch / average launch duration, measured with HIP
-                   events on the launch stream during extra profiled steps that
-                   follow the timed region (event records would perturb the
-                   whole-step time if they were inside it)
+                   events on the launch stream over a repetition of the timed
+                   steps right after them (two event records around each of a
+                   step's ~25 launches add 4-5 % to the step time, so they
+                   stay out of the steps that `value` is computed from)
   cpu_baseline     the CPU oracle, unchanged, on a bounded sample of the same
                    layers, extrapolated to the full model
 """
@@ -90,7 +91,9 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--layers", type=int, default=0, help="use only the first LAYERS layers (debug)")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--profile-steps", type=int, default=-1,
+                    help="steps repeated with per-kernel HIP events after the timed ones "
+                         "(default: as many as --steps; 0: none)")
     ap.add_argument("--mode", default="batched", choices=["batched", "per-layer"],
                     help="batched: graphkv_compress_batched over the model's contiguous cache; "
                          "per-layer: one graphkv_compress call per layer")
@@ -196,18 +199,20 @@ def main():
     copy_gbps = 2 * Kall.numel() * Kall.element_size() * 5 / (time.perf_counter() - tcp) / 1e9
     del scratch
 
-    # ---- per-kernel durations (HIP events on the launch stream), after the timed region ----
+    # ---- per-kernel durations: the timed steps once more, every kernel bracketed by two HIP
+    # events on the launch stream ----
     kernels = {}
     roofline = None
-    if args.profile_steps > 0:
+    profile_steps = args.steps if args.profile_steps < 0 else args.profile_steps
+    if profile_steps > 0:
         gk.graphkv_profile_begin()
-        for _ in range(args.profile_steps):
+        for _ in range(profile_steps):
             step()
         prof = gk.graphkv_profile_end()
         torch.cuda.synchronize()
         alg = [algorithmic_bytes(cfg, p.budget) for p in params]
         for name, (ms, cnt) in prof.items():
-            per_step = cnt / args.profile_steps
+            per_step = cnt / profile_steps
             avg_us = ms * 1e3 / cnt
             layers_per_launch = min(group, L) if args.mode == "batched" else 1
             bytes_per_launch = float(np.mean([a.get(name, 0) for a in alg])) * layers_per_launch
@@ -227,7 +232,7 @@ def main():
             "unit": "GB/s", "frac": round(kernels[dom]["alg_GBps"] / HBM_PEAK_GBS, 4),
             "traffic": traffic, "avg_launch_us": kernels[dom]["avg_us"],
             "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"],
-            "measured_over": f"{args.profile_steps} profiled steps after the timed region",
+            "measured_over": f"{profile_steps} steps with per-kernel events, right after the timed ones",
         }
 
     # whole-pass view against the streaming model (2 + T passes over K, plus the gather)
