@@ -239,6 +239,129 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
     }
 }
 
+// ---- small k out of a long row ------------------------------------------------
+// For k far below the row length (the source nodes: 64 of 32736) the keys need not
+// go through LDS at all.  Every thread keeps its 32 keys in registers.  A bound
+// comes almost for free: split the 1024 threads into G >= k groups; the smallest
+// of the G group maxima is reached by G different entries, so the k-th largest key
+// is at least that.  Only the few hundred keys that reach the bound take part in
+// the radix select (the same sweeps as above, fed from registers: a compare per key
+// and an LDS atomic for the few that pass), and the emit sweep is the one above.
+constexpr int kSmallK = 256;       // largest k this path takes
+
+__global__ __launch_bounds__(1024) void topk_rows_smallk_kernel(
+    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld)
+{
+    constexpr int BLOCK = 1024, ITEMS = 32, NW = BLOCK / kWave, DIG = 11, NBINS = 1 << DIG;
+    __shared__ uint32_t hist[NBINS];
+    __shared__ uint32_t s_bin, s_need, s_grp[kSmallK], s_bound, s_wmax[NW], s_max;
+    __shared__ uint32_t cg[ITEMS * NW], ce[ITEMS * NW];
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float *xr = x + (long)row * ld;
+    int32_t *out = idx_out + (long)row * idx_ld;
+
+    uint32_t key[ITEMS];
+    uint32_t best = 0;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int j = i * BLOCK + tid;
+        key[i] = j < n ? ord_key(xr[j]) : 0u;          // 0 is below the key of every number
+        best = max(best, key[i]);
+    }
+    // G groups of consecutive threads (G a power of two, k <= G <= 256, so a group is 4 to 64
+    // lanes of one wave): group maxima, their minimum = the bound; the row maximum on the way.
+    int G = 16;
+    while (G < k) G <<= 1;
+    const int gs = BLOCK / G;
+    uint32_t gmax = best;
+    for (int o = 1; o < gs; o <<= 1) gmax = max(gmax, (uint32_t)__shfl_xor((int)gmax, o, kWave));
+    if ((tid & (gs - 1)) == 0) s_grp[tid / gs] = gmax;
+    uint32_t wmax = best;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) wmax = max(wmax, (uint32_t)__shfl_xor((int)wmax, o, kWave));
+    if (lane == 0) s_wmax[wv] = wmax;
+    __syncthreads();
+    if (wv == 0) {
+        uint32_t mn = 0xffffffffu, mx = 0u;
+        for (int g = lane; g < G; g += kWave) mn = min(mn, s_grp[g]);
+        if (lane < NW) mx = s_wmax[lane];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            mn = min(mn, (uint32_t)__shfl_xor((int)mn, o, kWave));
+            mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, kWave));
+        }
+        if (lane == 0) { s_bound = mn; s_max = mx; }
+    }
+    __syncthreads();
+    const uint32_t kmin = s_bound, kmax = s_max;
+
+    // radix select on (key - bound) among the keys that reach the bound
+    const uint32_t range = kmax - kmin;
+    int remaining = range ? 32 - __clz(range) : 0;
+    uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
+    while (remaining > 0) {
+        const int bits = remaining < DIG ? remaining : DIG;
+        const int shift = remaining - bits;
+        const uint32_t dmask = (1u << bits) - 1u;
+        for (int b = tid; b < NBINS; b += BLOCK) hist[b] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const uint32_t rel = key[i] - kmin;
+            if (key[i] >= kmin && (rel & mask) == prefix) atomicAdd(&hist[(rel >> shift) & dmask], 1u);
+        }
+        __syncthreads();
+        if (wv == 0) find_bin<NBINS / 64>(hist, need, lane, &s_bin, &s_need);
+        __syncthreads();
+        prefix |= s_bin << shift;
+        mask |= dmask << shift;
+        need = s_need;
+        remaining = shift;
+    }
+    const uint32_t tau = kmin + prefix;   // key of the k-th largest entry; take `need` entries equal to it
+
+    // emit in index order: entries above tau and the first `need` entries equal to it
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const uint32_t ng = __popcll(__ballot(key[i] > tau));
+        const uint32_t ne = __popcll(__ballot(key[i] == tau));
+        if (lane == 0) { cg[i * NW + wv] = ng; ce[i * NW + wv] = ne; }
+    }
+    __syncthreads();
+    if (wv == 0) {   // exclusive scan of the cells in index order; lane L owns a contiguous run
+        constexpr int per = ITEMS * NW / 64;
+        const int c0 = lane * per;
+        uint32_t sg = 0, se = 0;
+#pragma unroll
+        for (int c = 0; c < per; ++c) { sg += cg[c0 + c]; se += ce[c0 + c]; }
+        uint32_t ig = sg, ie = se;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t a = __shfl_up(ig, o, kWave), b = __shfl_up(ie, o, kWave);
+            if (lane >= o) { ig += a; ie += b; }
+        }
+        uint32_t bg = ig - sg, be = ie - se;
+#pragma unroll
+        for (int c = 0; c < per; ++c) {
+            const uint32_t tg = cg[c0 + c], te = ce[c0 + c];
+            cg[c0 + c] = bg; ce[c0 + c] = be;
+            bg += tg; be += te;
+        }
+    }
+    __syncthreads();
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const bool g = key[i] > tau, e = key[i] == tau;   // keys of entries past n are 0 < tau
+        const uint64_t mg = __ballot(g), me = __ballot(e);
+        if (g || e) {
+            const uint32_t g_before = cg[i * NW + wv] + __popcll(mg & lt_mask);
+            const uint32_t e_before = ce[i * NW + wv] + __popcll(me & lt_mask);
+            if (g || e_before < need) out[g_before + min(e_before, need)] = i * BLOCK + tid;
+        }
+    }
+}
+
 // ---- rows of any length: every sweep re-reads the row ------------------------
 template <int BLOCK, bool PLAN>
 __global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
@@ -392,6 +515,14 @@ static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, in
     if (n <= 4096)
         return launch_lds<256, PLAN, 8>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
                                         append_from, append_count, gate, rows_per_gate, plan, st);
+    if constexpr (!PLAN) {
+        if (n > 4096 && n <= 32768 && k <= kSmallK && idx_out && !val_out && !tau_out && append_count == 0 &&
+            !gate) {
+            hipLaunchKernelGGL(topk_rows_smallk_kernel, dim3(rows), dim3(1024), 0, st, x, ld, n, k, idx_out,
+                               idx_ld);
+            return hipGetLastError();
+        }
+    }
     if (n <= 32768)
         return launch_lds<1024, PLAN, 11>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
                                           append_from, append_count, gate, rows_per_gate, plan, st);
