@@ -37,7 +37,9 @@ __global__ __launch_bounds__(256) void pool_group_kernel(const float *__restrict
 // coalesced load per row and thread) and the sum is pooled once out of an LDS tile
 // with a halo.  Same value as pooling each row and adding, up to fp32 rounding order.
 constexpr int kPoolHalo = 16;
-constexpr int kPoolTile = 2048;   // outputs per workgroup: 8 per thread, enough loads in flight per CU
+// kPoolTile outputs per workgroup: 2048 (8 per thread, enough loads in flight per CU) when
+// there are many heads, 256 when the grid would otherwise not fill the chip.
+template <int kPoolTile>
 __global__ __launch_bounds__(256) void pool_avg_kernel(const float *__restrict__ votes, int Gv, int P,
                                                        int pool_kernel, float div,
                                                        float *__restrict__ scores)
@@ -304,12 +306,17 @@ __global__ __launch_bounds__(256) void copy_kernel(const T *__restrict__ src, T 
 hipError_t launch_pool_group(const float *votes, int Hkv, int Gv, int P, int pool_kernel,
                              int pool_mode, float div, float *scores, hipStream_t st)
 {
-    if (pool_mode == 0 && pool_kernel <= 2 * kPoolHalo + 1)
-        hipLaunchKernelGGL(pool_avg_kernel, dim3((P + kPoolTile - 1) / kPoolTile, Hkv), dim3(256), 0, st, votes, Gv, P,
-                           pool_kernel, div, scores);
-    else
+    if (pool_mode == 0 && pool_kernel <= 2 * kPoolHalo + 1) {
+        if ((long)((P + 2047) / 2048) * Hkv >= 1024)
+            hipLaunchKernelGGL(pool_avg_kernel<2048>, dim3((P + 2047) / 2048, Hkv), dim3(256), 0, st, votes,
+                               Gv, P, pool_kernel, div, scores);
+        else
+            hipLaunchKernelGGL(pool_avg_kernel<256>, dim3((P + 255) / 256, Hkv), dim3(256), 0, st, votes,
+                               Gv, P, pool_kernel, div, scores);
+    } else {
         hipLaunchKernelGGL(pool_group_kernel, dim3((P + 255) / 256, Hkv), dim3(256), 0, st, votes, Gv,
                            P, pool_kernel, pool_mode, div, scores);
+    }
     return hipGetLastError();
 }
 
