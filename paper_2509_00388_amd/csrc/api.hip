@@ -24,7 +24,7 @@ struct Dims {
 // Workspace: a bump allocation of every scratch array any entry point may need.
 struct Workspace {
     size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, part;
-    size_t tau, cand, cand_cnt, overflow, total;
+    size_t bound_hist, tau, cand, cand_cnt, overflow, total;
 };
 
 // The MFMA kernels cover bf16 keys with d = 128.  Scoring additionally needs the
@@ -125,6 +125,7 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.scores = take((size_t)D.H * D.P * 4);
     W.part = take(D.mfma_score ? mfma_score_plan(D.H, D.G * D.w, D.N).part_bytes : 0);
     W.tau = take((size_t)D.H * D.S * 4);
+    W.bound_hist = take(D.filter ? mfma_bound_scratch_bytes(D.H, D.P, D.S) : 0);
     const MfmaFilterGeom fg = D.filter ? mfma_filter_geom(D.H, D.P, D.S, D.m) : MfmaFilterGeom{0, 0, 0};
     W.cand = take((size_t)D.H * D.S * fg.chunks * fg.slice_cap * 8);
     W.cand_cnt = take((size_t)D.H * D.S * fg.chunks * 4);
@@ -247,7 +248,8 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                 int32_t *cnt = at<int32_t>(ws, W.cand_cnt), *ovf = at<int32_t>(ws, W.overflow);
                 void *cand = at<char>(ws, W.cand);
                 GKV_LAUNCH(GRAPHKV_K_COSINE_BOUND,
-                           launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, tau, ovf, st));
+                           launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src,
+                                                    at<char>(ws, W.bound_hist), tau, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
                            launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, tau, cand, cnt,
                                                      ovf, st));

@@ -87,8 +87,10 @@ struct MfmaFilterGeom {
 MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m);
 // tau [Hkv, S]: a lower bound of each source's m-th largest edge, from the edges to every
 // (P / sample_cols)-th key (within 1/256 of the m-th largest sampled edge); clears overflow [Hkv].
+size_t mfma_bound_scratch_bytes(int Hkv, int P, int S);   // per-chunk histograms (0 if one chunk)
 hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                    const int32_t *src, float *tau, int32_t *overflow, hipStream_t st);
+                                    const int32_t *src, void *hist_part, float *tau, int32_t *overflow,
+                                    hipStream_t st);
 // Streams all keys; edges that reach tau[h, a] go to cand [Hkv, S, chunks, slice_cap] x 8
 // bytes, their number per slice to cand_cnt [Hkv, S, chunks].
 hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,

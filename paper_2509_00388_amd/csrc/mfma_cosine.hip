@@ -167,9 +167,38 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
 // pass that follows.
 constexpr int kBoundBins = 512;
 
+// One wave, one source: lane L holds the packed counters of bins 8L .. 8L+7 in w4.  Finds
+// the bin in which the count from the top reaches m and writes its lower edge.
+__device__ __forceinline__ void bound_from_histogram(const uint4 w4, int m, int lane, float *tau_row)
+{
+    const uint32_t c[8] = {w4.x & 0xffffu, w4.x >> 16, w4.y & 0xffffu, w4.y >> 16,
+                           w4.z & 0xffffu, w4.z >> 16, w4.w & 0xffffu, w4.w >> 16};
+    uint32_t mine = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) mine += c[k];
+    uint32_t from_top = mine;   // count in this lane's bins and all higher ones
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_down(from_top, o, kWave);
+        if (lane + o < 64) from_top += v;
+    }
+    const uint32_t above = from_top - mine;
+    if (above < (uint32_t)m && from_top >= (uint32_t)m) {
+        uint32_t cum = above;
+        int k = 7;
+        for (; k > 0; --k) {
+            if (cum + c[k] >= (uint32_t)m) break;
+            cum += c[k];
+        }
+        *tau_row = (float)(8 * lane + k) * (2.0f / kBoundBins) - 1.0f;
+    }
+    if (lane == 0 && from_top < (uint32_t)m) *tau_row = -INFINITY;   // fewer than m sampled edges: no bound
+}
+
 __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
     const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride,
-    int S, const int32_t *__restrict__ src, int m, float *__restrict__ tau, int32_t *__restrict__ overflow)
+    int S, const int32_t *__restrict__ src, int m, int chunk_cols, uint32_t *__restrict__ hist_part,
+    float *__restrict__ tau, int32_t *__restrict__ overflow)
 {
     __shared__ float inv_s[kRows];
     __shared__ int32_t idx_s[kRows];
@@ -177,11 +206,14 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
     unsigned char *kt = smem;
     uint32_t *hist = reinterpret_cast<uint32_t *>(smem + 2 * kTileBytes);   // [kRows][kBoundBins / 2]
 
-    const int h = blockIdx.y, s_base = blockIdx.x * kRows;
+    // with few heads the sample is cut into chunks (blockIdx.z) whose histograms are added up
+    // by bound_merge_kernel: otherwise a handful of workgroups would walk the sample alone
+    const int h = blockIdx.y, s_base = blockIdx.x * kRows, chunk = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, grp = wv >> 2;
     const uint16_t *Kh = Kc + (long)h * N * kD;
-    if (blockIdx.x == 0 && tid == 0) overflow[h] = 0;
+    const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
+    if (blockIdx.x == 0 && chunk == 0 && tid == 0) overflow[h] = 0;
 
     bf16x8 q[kSteps];
     load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
@@ -196,7 +228,7 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
         self[i] = s_base + row < S ? idx_s[row] : -1;
     }
 
-    const int ntile = (n_cols + kTileKeys - 1) / kTileKeys;
+    const int ntile = c1 > c0 ? (c1 - c0 + kTileKeys - 1) / kTileKeys : 0;
     auto multiply_tile = [&](const unsigned char *buf, int t) {
         bf16x8 kc[kSteps];
         tile_read(buf, stream, l32, hh, kc);
@@ -210,9 +242,9 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
         float sq = half_row_sumsq(kc);
         sq += __shfl_xor(sq, 32, kWave);
         const float inv_k = inv_norm(sq);
-        const int col = kTileKeys * t + kBlk * stream + l32;
+        const int col = c0 + kTileKeys * t + kBlk * stream + l32;
         const int key = col * key_stride;
-        if (col < n_cols) {
+        if (col < c1) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 if (self[i] >= 0 && key != self[i]) {
@@ -225,37 +257,42 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
             }
         }
     };
-    GKV_TILE_PIPELINE(kThreads, Kh, 0, n_cols - 1, key_stride, ntile, multiply_tile, (void)0);
+    if (ntile > 0) GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, key_stride, ntile, multiply_tile, (void)0);
     __syncthreads();
 
+    if (gridDim.z > 1) {   // this chunk's counts go to global memory
+        uint4 *out = reinterpret_cast<uint4 *>(
+            hist_part + ((((long)h * gridDim.x + blockIdx.x) * gridDim.z + chunk) * kRows) * (kBoundBins / 2));
+        const uint4 *in = reinterpret_cast<const uint4 *>(hist);
+        for (int u = tid; u < kRows * (kBoundBins / 2) / 4; u += kThreads) out[u] = in[u];
+        return;
+    }
     // Wave w scans the histograms of rows 8w .. 8w+7 from the top; lane L holds bins 8L .. 8L+7.
     for (int r = 0; r < kRows / (kThreads / kWave); ++r) {
         const int row = wv * (kRows / (kThreads / kWave)) + r;
         const uint4 w4 = *reinterpret_cast<const uint4 *>(&hist[row * (kBoundBins / 2) + 4 * lane]);
-        const uint32_t c[8] = {w4.x & 0xffffu, w4.x >> 16, w4.y & 0xffffu, w4.y >> 16,
-                               w4.z & 0xffffu, w4.z >> 16, w4.w & 0xffffu, w4.w >> 16};
-        uint32_t mine = 0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) mine += c[k];
-        uint32_t from_top = mine;   // count in this lane's bins and all higher ones
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t v = __shfl_down(from_top, o, kWave);
-            if (lane + o < 64) from_top += v;
-        }
-        const uint32_t above = from_top - mine;
-        if (above < (uint32_t)m && from_top >= (uint32_t)m && s_base + row < S) {
-            uint32_t cum = above;
-            int k = 7;
-            for (; k > 0; --k) {
-                if (cum + c[k] >= (uint32_t)m) break;
-                cum += c[k];
-            }
-            tau[(long)h * S + s_base + row] = (float)(8 * lane + k) * (2.0f / kBoundBins) - 1.0f;
-        }
-        if (lane == 0 && from_top < (uint32_t)m && s_base + row < S)
-            tau[(long)h * S + s_base + row] = -INFINITY;   // fewer than m sampled edges: no bound
+        if (s_base + row < S) bound_from_histogram(w4, m, lane, &tau[(long)h * S + s_base + row]);
     }
+}
+
+// Adds up the histograms of the sample's chunks (16-bit counters, two to a word: a bin's
+// total is at most the sample size, which stays below 65536) and takes the bound.  One
+// wave per source.
+__global__ __launch_bounds__(256) void bound_merge_kernel(const uint32_t *__restrict__ hist_part,
+                                                          int chunks, int sgroups, int S, int m,
+                                                          float *__restrict__ tau)
+{
+    const int lane = threadIdx.x & 63;
+    const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), h = blockIdx.y;
+    if (slot >= S) return;
+    const int sg = slot / kRows, row = slot % kRows;
+    uint4 w4 = make_uint4(0, 0, 0, 0);
+    for (int c = 0; c < chunks; ++c) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(
+            hist_part + ((((long)h * sgroups + sg) * chunks + c) * kRows + row) * (kBoundBins / 2) + 4 * lane);
+        w4.x += v.x; w4.y += v.y; w4.z += v.z; w4.w += v.w;
+    }
+    bound_from_histogram(w4, m, lane, &tau[(long)h * S + slot]);
 }
 
 // Filter pass over all keys.  A lane holds, per key block, the 16 dots of its key
@@ -720,15 +757,39 @@ hipError_t launch_mfma_cosine(const void *Ac, const void *Kc, int Hkv, int N, in
     return hipGetLastError();
 }
 
+// Chunks of the sample per (head, source group): 1 when the heads alone give 128 workgroups or
+// more, else enough for about 256 workgroups, at least two key tiles each.
+int mfma_bound_chunks(int Hkv, int P, int S)
+{
+    const int ps = mfma_sample_cols(P), sgroups = (S + kRows - 1) / kRows;
+    if (Hkv * sgroups >= 128) return 1;
+    int chunks = 256 / (Hkv * sgroups);
+    if (chunks > ps / (2 * kTileKeys)) chunks = ps / (2 * kTileKeys);
+    return chunks < 1 ? 1 : chunks;
+}
+
+size_t mfma_bound_scratch_bytes(int Hkv, int P, int S)
+{
+    const int chunks = mfma_bound_chunks(Hkv, P, S), sgroups = (S + kRows - 1) / kRows;
+    return chunks > 1 ? (size_t)Hkv * sgroups * chunks * kRows * (kBoundBins / 2) * 4 : 0;
+}
+
 hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                    const int32_t *src, float *tau, int32_t *overflow, hipStream_t st)
+                                    const int32_t *src, void *hist_part, float *tau, int32_t *overflow,
+                                    hipStream_t st)
 {
     const int ps = mfma_sample_cols(P), stride = P / ps;
     const int sgroups = (S + kRows - 1) / kRows;
+    const int chunks = mfma_bound_chunks(Hkv, P, S);
+    const int chunk_cols = (((ps + chunks - 1) / chunks + kTileKeys - 1) / kTileKeys) * kTileKeys;
     if (!allow_big_lds((const void *)cosine_bound_kernel)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_bound_kernel, dim3(sgroups, Hkv), dim3(kThreads),
+    hipLaunchKernelGGL(cosine_bound_kernel, dim3(sgroups, Hkv, chunks), dim3(kThreads),
                        2 * kTileBytes + kRows * (kBoundBins / 2) * 4, st, (const uint16_t *)Ac,
-                       (const uint16_t *)Kc, N, ps, stride, S, src, m, tau, overflow);
+                       (const uint16_t *)Kc, N, ps, stride, S, src, m, chunk_cols, (uint32_t *)hist_part, tau,
+                       overflow);
+    if (chunks > 1)
+        hipLaunchKernelGGL(bound_merge_kernel, dim3((S + 3) / 4, Hkv), dim3(256), 0, st,
+                           (const uint32_t *)hist_part, chunks, sgroups, S, m, tau);
     return hipGetLastError();
 }
 
