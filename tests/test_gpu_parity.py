@@ -237,7 +237,7 @@ def test_propagate_degenerate(oracle, impl):
 
 # ---------------------------------- neighbourhoods without the dense block ---
 
-@pytest.mark.parametrize("S,m", [(40, 20), (64, 32), (130, 7)])
+@pytest.mark.parametrize("S,m", [(40, 20), (64, 32), (130, 7), (1, 1), (256, 256)])
 def test_filtered_neighbourhoods_staged(oracle, S, m):
     """P >= 8192 on the MFMA path takes the sampled-bound + filter route; source
     counts that do not fill the 64-row groups, ragged key tail."""
