@@ -196,8 +196,15 @@ int32_t run_score(const graphkv_params *p, const Dims &D, const Workspace &W, co
         const int per_q = p->pool_mode == GRAPHKV_POOL_MAX;
         GKV_LAUNCH(GRAPHKV_K_SCORE_STATS, launch_mfma_score_stats(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale,
                                                                   at<float>(ws, W.part), st));
+        if (mfma_score_fuses_pool(D.G, D.w, per_q, p->pool_kernel)) {
+            // average pooling and the mean over the group happen inside pass B
+            GKV_LAUNCH(GRAPHKV_K_SCORE_VOTES,
+                       launch_mfma_score_votes(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale, per_q, p->pool_kernel,
+                                               at<float>(ws, W.part), scores, st));
+            return GRAPHKV_OK;
+        }
         GKV_LAUNCH(GRAPHKV_K_SCORE_VOTES,
-                   launch_mfma_score_votes(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale, per_q,
+                   launch_mfma_score_votes(Kc, Qw, D.H, D.Hq, D.N, D.w, D.scale, per_q, 0,
                                            at<float>(ws, W.part), votes, st));
         GKV_LAUNCH(GRAPHKV_K_POOL,
                    launch_pool_group(votes, D.H, mfma_score_vote_rows(D.G, D.w, per_q), D.P, p->pool_kernel,

@@ -68,9 +68,13 @@ MfmaScorePlan mfma_score_plan(int Hkv, int rows, int N);
 int mfma_score_vote_rows(int G, int w, int per_qhead_votes);
 hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
                                   float scale, float *part, hipStream_t st);
+// fused_pool_kernel > 0 (only if mfma_score_fuses_pool()): average pooling with that kernel
+// size and the mean over the query heads are done in the same kernel; `votes` is then the
+// score array [Hkv, P] and no pooling kernel follows.
+bool mfma_score_fuses_pool(int G, int w, int per_qhead_votes, int pool_kernel);
 hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
-                                  float scale, int per_qhead_votes, const float *part, float *votes,
-                                  hipStream_t st);
+                                  float scale, int per_qhead_votes, int fused_pool_kernel,
+                                  const float *part, float *votes, hipStream_t st);
 // E [Hkv, S, P] from bf16 keys (same contract as launch_generic_cosine); heads with
 // gate[h] == 0 are skipped when gate != nullptr.
 hipError_t launch_mfma_cosine(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, const int32_t *src,

@@ -162,11 +162,18 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
 // Heads with more than 128 stacked query rows are handled in parts of at most 128
 // rows (row_base .. row_base + R of R_total), one launch per part: the keys are then
 // streamed once per part.
+//
+// pool_half >= 0 (average pooling, one part): the votes never leave the workgroup.  Each row
+// group keeps the votes of the workgroup's keys in LDS, the workgroup also multiplies the
+// pool_half keys on either side of its chunk, and at the end it writes the pooled, grouped
+// scores of its chunk itself: votes[] is then the score array [Hkv, P].  The sums are
+// formed in the order of the separate pooling kernel, so the bits are the same.
 template <int NB, int SPLIT, bool PERQ>
 __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w, int G,
     int chunk_keys, float c, const float *__restrict__ part, int part_chunks,
-    float *__restrict__ votes, int R_total, int row_base, int vote_rows, int vote_row_base, int nparts)
+    float *__restrict__ votes, int R_total, int row_base, int vote_rows, int vote_row_base, int nparts,
+    int pool_half)
 {
     constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
@@ -179,6 +186,13 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
 
     const int k0 = chunk * chunk_keys, k1 = min(P, k0 + chunk_keys);
     if (k0 >= P) return;
+    const bool fused = !PERQ && pool_half >= 0;
+    const int first = fused ? max(0, k0 - pool_half) : k0;      // keys this workgroup multiplies
+    const int kend = fused ? min(P, k1 + pool_half) : k1;
+    const int span = chunk_keys + 2 * pool_half;
+    float *vs = reinterpret_cast<float *>(kt + 2 * kTileBytes);   // [SPLIT][span], slot 0 = key k0 - pool_half
+    if (fused)
+        for (int u = tid; u < SPLIT * span; u += NT) vs[u] = 0.f;   // zero padding outside the row
 
     if (tid < R) {   // row statistics of the whole head: merge the chunks of pass A
         float mm = -INFINITY, zz = 0.f;
@@ -199,7 +213,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
         for (int i = 0; i < 16; ++i) bias[b][i] = bias_s[row0 + kBlk * b + acc_row(i, hh)];
 
     const uint16_t *Kh = Kc + (long)h * N * kD;
-    const int ntile = (k1 - k0 + kTileKeys - 1) / kTileKeys;
+    const int ntile = (kend - first + kTileKeys - 1) / kTileKeys;
     const int bpq = PERQ ? w / kBlk : 1;   // MFMA row blocks per query head
 
     auto multiply_tile = [&](const unsigned char *buf, int t) {
@@ -225,13 +239,16 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
             for (int i = 0; i < 16; ++i) s += fast_exp2(fmaf(acc[b][i], c, -bias[b][i]));
             pb[b] = s;
         }
-        const int key = k0 + kTileKeys * t + kBlk * stream + l32;
+        const int key = first + kTileKeys * t + kBlk * stream + l32;
         if constexpr (!PERQ) {
             float p = pb[0];
 #pragma unroll
             for (int b = 1; b < NBW; ++b) p += pb[b];
             p += __shfl_xor(p, 32, kWave);
-            if (hh == 0 && key < k1) votes[((long)h * vote_rows + vote_row_base + grp) * P + key] = p;
+            if (hh == 0 && key < kend) {
+                if (fused) vs[grp * span + key - (k0 - pool_half)] = p;
+                else votes[((long)h * vote_rows + vote_row_base + grp) * P + key] = p;
+            }
         } else {
             const int g0 = (row_base / kBlk + grp * NBW) / bpq;   // first query head of this row group
 #pragma unroll
@@ -240,12 +257,26 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
 #pragma unroll
                 for (int b = 0; b < NBW; ++b) p += (b / bpq == g) ? pb[b] : 0.f;
                 p += __shfl_xor(p, 32, kWave);
-                if (g0 + g < G && g * bpq < NBW && hh == 0 && key < k1)
+                if (g0 + g < G && g * bpq < NBW && hh == 0 && key < kend)
                     votes[((long)h * G + g0 + g) * P + key] = p;
             }
         }
     };
-    GKV_TILE_PIPELINE(NT, Kh, k0, k1 - 1, 1, ntile, multiply_tile, (void)0);
+    GKV_TILE_PIPELINE(NT, Kh, first, kend - 1, 1, ntile, multiply_tile, (void)0);
+    if (fused) {
+        __syncthreads();
+        const float taps = (float)(2 * pool_half + 1), div = (float)G;
+        for (int o = tid; o < k1 - k0; o += NT) {
+            float acc = 0.f;
+            for (int t = 0; t <= 2 * pool_half; ++t) {
+                float v = 0.f;
+#pragma unroll
+                for (int g = 0; g < SPLIT; ++g) v += vs[g * span + o + t];
+                acc += v;
+            }
+            votes[(long)h * P + k0 + o] = acc / taps / div;
+        }
+    }
 }
 
 // Kernels that use more than 64 KiB of dynamic LDS need a one-time opt-in per kernel.
@@ -343,28 +374,38 @@ template <int NB, int SPLIT>
 static void launch_votes_nb(dim3 grid, const uint16_t *K, const uint16_t *Q, int N, int P, int w, int G,
                             int ck, float c, const float *part, int chunks, int per_q, float *votes,
                             int R_total, int row_base, int vote_rows, int vote_row_base, int nparts,
-                            hipStream_t st)
+                            int pool_half, hipStream_t st)
 {
+    const size_t lds = 2 * kTileBytes + (pool_half >= 0 ? (size_t)SPLIT * (ck + 2 * pool_half) * 4 : 0);
     if (per_q) {
         if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, true>)) return;
         hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, true>), grid, dim3(256 * SPLIT),
-                           2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
-                           row_base, vote_rows, vote_row_base, nparts);
+                           lds, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
+                           row_base, vote_rows, vote_row_base, nparts, pool_half);
     } else {
         if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, false>)) return;
         hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, false>), grid, dim3(256 * SPLIT),
-                           2 * kTileBytes, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
-                           row_base, vote_rows, vote_row_base, nparts);
+                           lds, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
+                           row_base, vote_rows, vote_row_base, nparts, pool_half);
     }
 }
 
+bool mfma_score_fuses_pool(int G, int w, int per_qhead_votes, int pool_kernel)
+{
+    return !per_qhead_votes && G * w <= 128 && pool_kernel <= 33;
+}
+
 hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
-                                  float scale, int per_qhead_votes, const float *part, float *votes,
-                                  hipStream_t st)
+                                  float scale, int per_qhead_votes, int fused_pool_kernel,
+                                  const float *part, float *votes, hipStream_t st)
 {
     const int G = Hq / Hkv, R = G * w, P = N - w;
     const MfmaScorePlan plan = mfma_score_plan(Hkv, R, N);
-    const int ck = chunk_keys_for(Hkv, N);
+    // fused pooling: a workgroup also multiplies pool_half keys on either side of its chunk; the
+    // P prefix keys are spread evenly over as many chunks as pass A has, so that the number of
+    // workgroups (and, when w covers the extra keys, the number of tiles) stays the same
+    const int pool_half = fused_pool_kernel > 0 ? (fused_pool_kernel - 1) / 2 : -1;
+    const int ck = pool_half >= 0 ? (P + plan.chunks - 1) / plan.chunks : chunk_keys_for(Hkv, N);
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
     const int merged = (R > 128 && R % 128 == 0) ? R / 128 : 1;   // as in the statistics pass
@@ -373,7 +414,7 @@ hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int 
     int vote_row_base = 0;
 #define GKV_VOTES(NB, SP)                                                                             \
     launch_votes_nb<NB, SP>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, R, \
-                            row_base, vote_rows, vote_row_base, merged, st)
+                            row_base, vote_rows, vote_row_base, merged, pool_half, st)
     for (int pt = 0; 128 * pt < R; pt += merged) {
         const int row_base = 128 * pt, rows = part_rows(R, pt);
         const int split = part_split(rows, w, per_qhead_votes);
