@@ -241,18 +241,19 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
 
 // ---- small k out of a long row ------------------------------------------------
 // For k far below the row length (the source nodes: 64 of 32736) the keys need not
-// go through LDS at all.  Every thread keeps its 32 keys in registers.  A bound
-// comes almost for free: split the 1024 threads into G >= k groups; the smallest
+// go through LDS at all.  Every thread keeps its keys (32 with 1024 threads; 512
+// threads measured slower) in registers.  A bound comes almost for free: split the threads into G >= k groups; the smallest
 // of the G group maxima is reached by G different entries, so the k-th largest key
 // is at least that.  Only the few hundred keys that reach the bound take part in
 // the radix select (the same sweeps as above, fed from registers: a compare per key
 // and an LDS atomic for the few that pass), and the emit sweep is the one above.
 constexpr int kSmallK = 256;       // largest k this path takes
 
-__global__ __launch_bounds__(1024) void topk_rows_smallk_kernel(
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void topk_rows_smallk_kernel(
     const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld)
 {
-    constexpr int BLOCK = 1024, ITEMS = 32, NW = BLOCK / kWave, DIG = 11, NBINS = 1 << DIG;
+    constexpr int ITEMS = 32768 / BLOCK, NW = BLOCK / kWave, DIG = 11, NBINS = 1 << DIG;
     __shared__ uint32_t hist[NBINS];
     __shared__ uint32_t s_bin, s_need, s_grp[kSmallK], s_bound, s_wmax[NW], s_max;
     __shared__ uint32_t cg[ITEMS * NW], ce[ITEMS * NW];
@@ -518,8 +519,8 @@ static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, in
     if constexpr (!PLAN) {
         if (n > 4096 && n <= 32768 && k <= kSmallK && idx_out && !val_out && !tau_out && append_count == 0 &&
             !gate) {
-            hipLaunchKernelGGL(topk_rows_smallk_kernel, dim3(rows), dim3(1024), 0, st, x, ld, n, k, idx_out,
-                               idx_ld);
+            hipLaunchKernelGGL(topk_rows_smallk_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, k,
+                               idx_out, idx_ld);
             return hipGetLastError();
         }
     }
