@@ -27,7 +27,7 @@ EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "g
            "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma",
            "graphkv_profile_begin", "graphkv_profile_end", "graphkv_kernel_name",
            "graphkv_workspace_bytes_batched", "graphkv_compress_batched", "graphkv_propagate_edges")
-N_KERNELS = 19
+N_KERNELS = 20
 
 
 class GraphKVError(RuntimeError):

@@ -24,7 +24,9 @@ struct Dims {
 // Workspace: a bump allocation of every scratch array any entry point may need.
 struct Workspace {
     size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, part;
-    size_t bound_hist, tau, cand, cand_cnt, overflow, total;
+    size_t bound_hist, tau, cand, cand_cnt, overflow;
+    size_t src_b, nbr_b, nbr_e_b, reuse_code, new_src, new_pos, n_new;   // lists kept from one round to the next
+    size_t total;
 };
 
 // The MFMA kernels cover bf16 keys with d = 128.  Scoring additionally needs the
@@ -130,6 +132,14 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.cand = take((size_t)D.H * D.S * fg.chunks * fg.slice_cap * 8);
     W.cand_cnt = take((size_t)D.H * D.S * fg.chunks * 4);
     W.overflow = take((size_t)D.H * 4);
+    const bool keep = D.filter && D.T > 1 && p->reselect && source_reuse_applies(D.S);
+    W.src_b = take(keep ? (size_t)D.H * D.S * 4 : 0);
+    W.nbr_b = take(keep ? (size_t)D.H * D.S * D.m * 4 : 0);
+    W.nbr_e_b = take(keep ? (size_t)D.H * D.S * D.m * 4 : 0);
+    W.reuse_code = take(keep ? (size_t)D.H * D.S * 4 : 0);
+    W.new_src = take(keep ? (size_t)D.H * D.S * 4 : 0);
+    W.new_pos = take(keep ? (size_t)D.H * D.S * 4 : 0);
+    W.n_new = take(keep ? (size_t)D.H * 4 : 0);
     W.total = off;
     return W;
 }
@@ -168,7 +178,7 @@ const char *const kKernelNames[GRAPHKV_N_KERNELS] = {
     "score_stats", "score_votes", "pool_group", "topk_sources", "cosine", "topk_neighbors",
     "decay", "topk_final", "gather", "generic_logits", "generic_votes", "generic_cosine",
     "knorm", "copy", "cosine_bound", "cosine_filter", "nbr_select",
-    "redo_cosine", "redo_topk"};
+    "redo_cosine", "redo_topk", "match_sources"};
 
 #define GKV_LAUNCH(id, expr)                                              \
     do {                                                                  \
@@ -237,10 +247,22 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
     int32_t *src0 = dbg_src ? dbg_src : at<int32_t>(ws, W.src);
     int32_t *nbr0 = dbg_nbr ? dbg_nbr : at<int32_t>(ws, W.nbr);
     float *e0 = dbg_e ? dbg_e : at<float>(ws, W.nbr_e);
+    // The neighbourhood of a source depends on the keys alone (Eq. 1, Eq. 3), not on the
+    // scores: a source that comes back in the next round keeps its list, and the bound,
+    // filter and select passes of that round only take the sources that are new.  The lists
+    // of two consecutive rounds live in two buffers that take turns.
+    const bool keep = D.filter && D.T > 1 && p->reselect && source_reuse_applies(D.S);
+    const int32_t *prev_src = nullptr, *prev_nbr = nullptr;
+    const float *prev_e = nullptr;
     for (int t = 0; t < D.T; ++t) {
         int32_t *src = src0, *nbr = nbr0;
         float *ev = e0;
         if (t == 0 || p->reselect) {
+            if (keep && (t & 1)) {
+                src = at<int32_t>(ws, W.src_b);
+                nbr = at<int32_t>(ws, W.nbr_b);
+                ev = at<float>(ws, W.nbr_e_b);
+            }
             if (dbg_src) src = dbg_src + t * n_src;
             if (dbg_nbr) nbr = dbg_nbr + t * n_nbr;
             if (dbg_e) ev = dbg_e + t * n_nbr;
@@ -254,14 +276,27 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                 float *tau = at<float>(ws, W.tau);
                 int32_t *cnt = at<int32_t>(ws, W.cand_cnt), *ovf = at<int32_t>(ws, W.overflow);
                 void *cand = at<char>(ws, W.cand);
+                const int32_t *fsrc = src, *n_new = nullptr;
+                SourceReuse ru{};
+                if (keep && prev_src) {
+                    int32_t *code = at<int32_t>(ws, W.reuse_code), *new_src = at<int32_t>(ws, W.new_src);
+                    int32_t *new_pos = at<int32_t>(ws, W.new_pos), *cnt_new = at<int32_t>(ws, W.n_new);
+                    GKV_LAUNCH(GRAPHKV_K_MATCH_SOURCES,
+                               launch_match_sources(prev_src, src, D.H, D.S, D.m, prev_nbr, prev_e, code, new_src,
+                                                    new_pos, cnt_new, nbr, ev, st));
+                    ru = SourceReuse{cnt_new, code, new_pos};
+                    fsrc = new_src;
+                    n_new = cnt_new;
+                }
                 GKV_LAUNCH(GRAPHKV_K_COSINE_BOUND,
-                           launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src,
+                           launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.S, D.m, fsrc, n_new,
                                                     at<char>(ws, W.bound_hist), tau, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
-                           launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, tau, cand, cnt,
-                                                     ovf, st));
+                           launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.S, D.m, fsrc, n_new, tau, cand,
+                                                     cnt, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
-                           launch_nbr_select(cand, cnt, ovf, src, D.H, D.P, D.S, D.m, nbr, ev, st));
+                           launch_nbr_select(cand, cnt, ovf, fsrc, D.H, D.P, D.S, D.m, ru.code ? &ru : nullptr,
+                                             nbr, ev, st));
                 // heads whose lists overflowed are redone through the dense block
                 GKV_LAUNCH(GRAPHKV_K_REDO_COSINE, launch_mfma_cosine(Ac, Kc, D.H, D.N, D.P, D.S, src, E, ovf, st));
                 GKV_LAUNCH(GRAPHKV_K_REDO_TOPK,
@@ -286,6 +321,9 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
         }
         // Eq. 5: one round of the signal
         GKV_LAUNCH(GRAPHKV_K_DECAY, launch_decay(scores, D.H, D.P, D.S, D.m, nbr, ev, p->decay, p->signal, st));
+        prev_src = src;
+        prev_nbr = nbr;
+        prev_e = ev;
     }
     return GRAPHKV_OK;
 }

@@ -92,18 +92,35 @@ MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m);
 // tau [Hkv, S]: a lower bound of each source's m-th largest edge, from the edges to every
 // (P / sample_cols)-th key (within 1/256 of the m-th largest sampled edge); clears overflow [Hkv].
 size_t mfma_bound_scratch_bytes(int Hkv, int P, int S);   // per-chunk histograms (0 if one chunk)
+// n_src (bound and filter pass): null, or [Hkv] rows of each head's source list in use; the
+// arrays keep their pitch of S rows.
 hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                    const int32_t *src, void *hist_part, float *tau, int32_t *overflow,
-                                    hipStream_t st);
+                                    const int32_t *src, const int32_t *n_src, void *hist_part, float *tau,
+                                    int32_t *overflow, hipStream_t st);
 // Streams all keys; edges that reach tau[h, a] go to cand [Hkv, S, chunks, slice_cap] x 8
 // bytes, their number per slice to cand_cnt [Hkv, S, chunks].
 hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                     const int32_t *src, const float *tau, void *cand,
+                                     const int32_t *src, const int32_t *n_src, const float *tau, void *cand,
                                      int32_t *cand_cnt, int32_t *overflow, hipStream_t st);
 // Exact top-m over each source's slices -> nbr / nbr_e [Hkv, S, m]; skips heads with
 // overflow[h], and raises overflow[h] itself if a source has more candidates than it can take.
+// Neighbour lists kept from the previous round: Eq. 1 and Eq. 3 depend on the keys alone, so
+// a source that was one in the previous round has the same neighbourhood.
+struct SourceReuse {
+    const int32_t *n_new;      // [Hkv] sources that were none in the previous round
+    const int32_t *code;       // [Hkv, S] per source: its slot in the previous round, or -1 - r (r-th new one)
+    const int32_t *new_pos;    // [Hkv, S] slot of the r-th new source in this round's list
+};
+bool source_reuse_applies(int S);
+// prev, cur [Hkv, S] ascending -> code, new_pos as above, new_src [Hkv, S] (the new sources in
+// order, n_new[h] of them); copies the lists of the sources that stay from prev_nbr / prev_e
+// [Hkv, S, m] to their slots in nbr / nbr_e.
+hipError_t launch_match_sources(const int32_t *prev, const int32_t *cur, int Hkv, int S, int m,
+                                const int32_t *prev_nbr, const float *prev_e, int32_t *code, int32_t *new_src,
+                                int32_t *new_pos, int32_t *n_new, int32_t *nbr, float *nbr_e, hipStream_t st);
+// reuse: null, or the candidate rows are those of the new sources (src = new_src).
 hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t *overflow,
-                             const int32_t *src, int Hkv, int P, int S, int m, int32_t *nbr,
-                             float *nbr_e, hipStream_t st);
+                             const int32_t *src, int Hkv, int P, int S, int m, const SourceReuse *reuse,
+                             int32_t *nbr, float *nbr_e, hipStream_t st);
 
 }  // namespace gkv

@@ -56,6 +56,7 @@ __device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
 }
 
 struct FilterArgs {
+    const int32_t *n_src;  // [Hkv] rows of the head's source list in use; null: all S
     const float *tau;      // [Hkv, S] lower bound of each source's m-th largest edge
     uint2 *cand;           // [Hkv, S, chunks, slice_cap] (edge bits, key index): one slice per key chunk
     int32_t *cand_cnt;     // [Hkv, S, chunks] entries in each slice
@@ -197,8 +198,8 @@ __device__ __forceinline__ void bound_from_histogram(const uint4 w4, int m, int 
 
 __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
     const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride,
-    int S, const int32_t *__restrict__ src, int m, int chunk_cols, uint32_t *__restrict__ hist_part,
-    float *__restrict__ tau, int32_t *__restrict__ overflow)
+    int S, const int32_t *__restrict__ src, const int32_t *__restrict__ n_src, int m, int chunk_cols,
+    uint32_t *__restrict__ hist_part, float *__restrict__ tau, int32_t *__restrict__ overflow)
 {
     __shared__ float inv_s[kRows];
     __shared__ int32_t idx_s[kRows];
@@ -214,9 +215,12 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
     const uint16_t *Kh = Kc + (long)h * N * kD;
     const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
     if (blockIdx.x == 0 && chunk == 0 && tid == 0) overflow[h] = 0;
+    // rows of this head's source list in use (the arrays keep their pitch of S rows)
+    const int Sh = n_src ? n_src[h] : S;
+    if (s_base >= Sh) return;
 
     bf16x8 q[kSteps];
-    load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
+    load_sources(Ac + (long)h * N * kD, src + (long)h * S, Sh, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
     for (int u = tid; u < kRows * (kBoundBins / 2); u += kThreads) hist[u] = 0;
     __syncthreads();
     float inv_src[16];
@@ -225,7 +229,7 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
     for (int i = 0; i < 16; ++i) {
         const int row = kBlk * grp + acc_row(i, hh);
         inv_src[i] = inv_s[row];
-        self[i] = s_base + row < S ? idx_s[row] : -1;
+        self[i] = s_base + row < Sh ? idx_s[row] : -1;
     }
 
     const int ntile = c1 > c0 ? (c1 - c0 + kTileKeys - 1) / kTileKeys : 0;
@@ -271,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
     for (int r = 0; r < kRows / (kThreads / kWave); ++r) {
         const int row = wv * (kRows / (kThreads / kWave)) + r;
         const uint4 w4 = *reinterpret_cast<const uint4 *>(&hist[row * (kBoundBins / 2) + 4 * lane]);
-        if (s_base + row < S) bound_from_histogram(w4, m, lane, &tau[(long)h * S + s_base + row]);
+        if (s_base + row < Sh) bound_from_histogram(w4, m, lane, &tau[(long)h * S + s_base + row]);
     }
 }
 
@@ -279,12 +283,13 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
 // total is at most the sample size, which stays below 65536) and takes the bound.  One
 // wave per source.
 __global__ __launch_bounds__(256) void bound_merge_kernel(const uint32_t *__restrict__ hist_part,
-                                                          int chunks, int sgroups, int S, int m,
+                                                          int chunks, int sgroups, int S,
+                                                          const int32_t *__restrict__ n_src, int m,
                                                           float *__restrict__ tau)
 {
     const int lane = threadIdx.x & 63;
     const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), h = blockIdx.y;
-    if (slot >= S) return;
+    if (slot >= (n_src ? n_src[h] : S)) return;
     const int sg = slot / kRows, row = slot % kRows;
     uint4 w4 = make_uint4(0, 0, 0, 0);
     for (int c = 0; c < chunks; ++c) {
@@ -346,24 +351,26 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     const uint16_t *Kh = Kc + (long)h * N * kD;
     const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
     if (c0 >= n_cols) return;
+    const int Sh = fa.n_src ? fa.n_src[h] : S;   // the arrays keep their pitch of S rows
+    if (s_base >= Sh) return;
 
     bf16x8 q[kSteps];
-    load_sources(Ac + (long)h * N * kD, src + (long)h * S, S, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
+    load_sources(Ac + (long)h * N * kD, src + (long)h * S, Sh, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
     if (tid < kRows) row_pos[tid] = 0;
     if (tid < 2) n_later[tid] = 0;
     if (tid == 0) later_lost = 0;
     __syncthreads();
     if (tid < kRows) {
         // lo: what an exact edge must reach to be listed; det: the still lower bound of the
-        // in-loop test, expressed for dot / |k_j| (i.e. divided by 1/|k_i|).  Rows past S
-        // and impossible bounds never hit; a zero source (all edges 0) hits everywhere.
+        // in-loop test, expressed for dot / |k_j| (i.e. divided by 1/|k_i|).  Rows past the
+        // last source and impossible bounds never hit; a zero source (all edges 0) hits everywhere.
         const int slot = s_base + tid;
-        const float t = fa.tau[(long)h * S + min(slot, S - 1)];
+        const float t = fa.tau[(long)h * S + min(slot, Sh - 1)];
         const float slack = 4e-6f + 1e-5f * fabsf(t);
         const float inv = inv_s[tid];
         const float lo = t - slack, lo2 = t - 2.f * slack;
-        lo_s[tid] = slot < S ? lo : INFINITY;
-        det_s[tid] = slot >= S ? INFINITY : (inv > 0.f ? lo2 / inv : (lo2 <= 0.f ? -INFINITY : INFINITY));
+        lo_s[tid] = slot < Sh ? lo : INFINITY;
+        det_s[tid] = slot >= Sh ? INFINITY : (inv > 0.f ? lo2 / inv : (lo2 <= 0.f ? -INFINITY : INFINITY));
     }
     __syncthreads();
     // this lane's 16 sources: row acc_row(i, hh) of row group grp
@@ -446,8 +453,14 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     };
 
     const int ntile = (c1 - c0 + kTileKeys - 1) / kTileKeys;
-    const int de = fa.drain_every;
+    // The host's schedule is for lanes whose 16 rows are all sources; with fewer (a short
+    // list fills the rows in order, four to a lane at a time) the rings fill that much slower.
+    const int lane_rows = min(16, 4 * ((min(Sh - s_base, kBlk) + 7) / 8));
+    const int de = fa.drain_every * 16 / lane_rows;
+    // a row group without sources only helps to move the key tiles
+    const bool idle = s_base + kBlk * grp >= Sh;
     auto multiply_tile = [&](const unsigned char *buf, int t) {
+        if (idle) return;
         bf16x8 kc[kSteps];
         tile_read(buf, stream, l32, hh, kc);
         f32x16 acc;
@@ -510,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     __syncthreads();
     store_later(ntile & 1);
     __syncthreads();      // every candidate is counted
-    if (tid < kRows && s_base + tid < S) {
+    if (tid < kRows && s_base + tid < Sh) {
         const int c = row_pos[tid];
         fa.cand_cnt[((long)h * S + s_base + tid) * n_chunks + chunk] = c < fa.slice_cap ? c : fa.slice_cap;
         if (c > fa.slice_cap || later_lost) fa.overflow[h] = 1;
@@ -531,142 +544,438 @@ __device__ __forceinline__ uint32_t ord_key_inv(uint32_t k)
 }
 
 // Exact top-m of one source's candidate list by (edge desc, key index asc),
-// written in ascending key order.  One workgroup per (source, head); heads whose
-// overflow flag is set are left to the dense path.
+// written in ascending key order.  The workgroups of a head share its sources in
+// turn (a workgroup's next list is asked for while it works on the current one);
+// heads whose overflow flag is set are left to the dense path.
 //
 // The m-th largest edge value is found by a radix select over the order-
 // preserving keys of the (short) list, as in the row top-k; entries above it are
 // in, and of the entries equal to it the `need` lowest key indices are in.  The
 // winners' output position is their rank by key index among themselves.
+//
+// With `ru` (lists kept from the previous round) the candidate rows are those of the
+// sources that are new in this round, in their order, and row x is written to the slot
+// that source has in this round's list.
 __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict__ cand,
                                                          const int32_t *__restrict__ cand_cnt,
                                                          int32_t *__restrict__ overflow,
                                                          const int32_t *__restrict__ src, int S,
                                                          int chunks, int slice_cap, int cap, int m,
-                                                         int32_t *__restrict__ nbr,
+                                                         SourceReuse ru, int32_t *__restrict__ nbr,
                                                          float *__restrict__ nbr_e)
 {
     extern __shared__ uint32_t dyn[];
     __shared__ uint32_t hist[256];   // 8-bit digits: the lists are short
     __shared__ uint32_t s_bin, s_need, s_min[4], s_max[4];
     __shared__ int32_t n_win, n_eq;
-    const int a = blockIdx.x, h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const long row = (long)h * S + a;
-    // slice sizes, the overflow flag and the source index: independent loads, one round trip
-    __shared__ int32_t cnt_s[256], s_ovf;
+    __shared__ int32_t cnt_s[256], s_pos;
     __shared__ uint32_t s_self;
-    for (int c = tid; c < chunks; c += 256) cnt_s[c] = cand_cnt[row * chunks + c];
-    if (tid == 0) { s_ovf = overflow[h]; s_self = (uint32_t)src[row]; n_win = 0; n_eq = 0; }
-    __syncthreads();
-    if (s_ovf) return;
-    int n = 0;
-    for (int c = 0; c < chunks; ++c) n += cnt_s[c];
-    if (n > cap) {          // more candidates than the select can hold: redo the head densely
-        if (tid == 0) overflow[h] = 1;
-        return;
-    }
-    const uint32_t self = s_self;
+    const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int n_rows = ru.code ? ru.n_new[h] : S;
+    if (overflow[h]) return;
     uint32_t *ek = dyn;                 // [cap] order-preserving edge keys (0 = dropped)
     uint32_t *kj = dyn + cap;           // [cap] key indices
     uint64_t *win = reinterpret_cast<uint64_t *>(kj + cap);   // [m] (key index << 32 | edge bits)
-    uint32_t kmin = 0xffffffffu, kmax = 0u;
-    for (int r = tid; r < n; r += 256) {
-        int c = 0, local = r;                 // entry r of the concatenated slices
-        while (local >= cnt_s[c]) { local -= cnt_s[c]; ++c; }
-        const uint2 v = cand[(row * chunks + c) * (long)slice_cap + local];
-        // the source's own column is no neighbour (Eq. 3: j != i): key 0 sorts below every edge
-        const uint32_t k = v.y == self ? 0u : ord_key_u(v.x);
-        ek[r] = k;
-        kj[r] = v.y;
-        if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
-        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
-    }
-    if (lane == 0) { s_min[wv] = kmin; s_max[wv] = kmax; }
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < 4; ++u) { kmin = min(kmin, s_min[u]); kmax = max(kmax, s_max[u]); }
 
-    const uint32_t range = kmax - kmin;
-    int remaining = (kmax >= kmin && range) ? 32 - __clz(range) : 0;
-    uint32_t prefix = 0, mask = 0, need = (uint32_t)m;
-    while (remaining > 0) {
-        const int bits = remaining < 8 ? remaining : 8;
-        const int shift = remaining - bits;
-        const uint32_t dmask = (1u << bits) - 1u;
-        hist[tid] = 0;
+    // slice sizes (thread c: chunk c), source index and output slot of a row: independent loads
+    auto ask = [&](int x, int32_t &cnt_r, int32_t &self_r, int32_t &pos_r) {
+        const long row = (long)h * S + x;
+        cnt_r = tid < chunks ? cand_cnt[row * chunks + tid] : 0;
+        if (tid == 0) {
+            self_r = src[row];
+            pos_r = ru.code ? ru.new_pos[row] : x;
+        }
+    };
+    int32_t cnt_r = 0, self_r = 0, pos_r = 0;
+    if ((int)blockIdx.x < n_rows) ask(blockIdx.x, cnt_r, self_r, pos_r);
+
+    for (int x = blockIdx.x; x < n_rows; x += gridDim.x) {
+        const long row = (long)h * S + x;
+        cnt_s[tid] = cnt_r;
+        if (tid == 0) { s_self = (uint32_t)self_r; s_pos = pos_r; n_win = 0; n_eq = 0; }
         __syncthreads();
+        if (x + (int)gridDim.x < n_rows) ask(x + gridDim.x, cnt_r, self_r, pos_r);
+        int n = 0;
+        for (int c = 0; c < chunks; ++c) n += cnt_s[c];
+        if (n > cap) {          // more candidates than the select can hold: redo the head densely
+            if (tid == 0) overflow[h] = 1;
+            return;
+        }
+        const uint32_t self = s_self;
+        const long out_row = (long)h * S + s_pos;
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        for (int r = tid; r < n; r += 256) {
+            int c = 0, local = r;                 // entry r of the concatenated slices
+            while (local >= cnt_s[c]) { local -= cnt_s[c]; ++c; }
+            const uint2 v = cand[(row * chunks + c) * (long)slice_cap + local];
+            // the source's own column is no neighbour (Eq. 3: j != i): key 0 sorts below every edge
+            const uint32_t k = v.y == self ? 0u : ord_key_u(v.x);
+            ek[r] = k;
+            kj[r] = v.y;
+            if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+        }
+        if (lane == 0) { s_min[wv] = kmin; s_max[wv] = kmax; }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { kmin = min(kmin, s_min[u]); kmax = max(kmax, s_max[u]); }
+
+        const uint32_t range = kmax - kmin;
+        int remaining = (kmax >= kmin && range) ? 32 - __clz(range) : 0;
+        uint32_t prefix = 0, mask = 0, need = (uint32_t)m;
+        while (remaining > 0) {
+            const int bits = remaining < 8 ? remaining : 8;
+            const int shift = remaining - bits;
+            const uint32_t dmask = (1u << bits) - 1u;
+            hist[tid] = 0;
+            __syncthreads();
+            for (int r = tid; r < n; r += 256) {
+                const uint32_t k = ek[r];
+                if (k) {
+                    const uint32_t rel = k - kmin;
+                    if ((rel & mask) == prefix) atomicAdd(&hist[(rel >> shift) & dmask], 1u);
+                }
+            }
+            __syncthreads();
+            if (wv == 0) {   // bin where the count of larger-or-equal digits reaches `need`
+                uint32_t tsum = 0;
+                for (int b = 0; b < 4; ++b) tsum += hist[4 * lane + b];
+                uint32_t incl = tsum;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t v = __shfl_down(incl, o, kWave);
+                    if (lane + o < 64) incl += v;
+                }
+                const uint32_t excl = incl - tsum;
+                if (excl < need && need <= incl) {
+                    uint32_t cum = excl;
+                    int b = 3;
+                    for (; b > 0; --b) {
+                        const uint32_t cb = hist[4 * lane + b];
+                        if (cum + cb >= need) break;
+                        cum += cb;
+                    }
+                    s_bin = 4 * lane + b;
+                    s_need = need - cum;
+                }
+            }
+            __syncthreads();
+            prefix |= s_bin << shift;
+            mask |= dmask << shift;
+            need = s_need;
+            remaining = shift;
+        }
+        const uint32_t tau = kmin + prefix;
+        // Winners above the threshold go straight to the list (its order is fixed by the
+        // final ranking).  Entries equal to the threshold all win when exactly `need` of
+        // them exist; otherwise the `need` lowest key indices win, found by a scan that
+        // only ties at the cut ever pay for.
         for (int r = tid; r < n; r += 256) {
             const uint32_t k = ek[r];
-            if (k) {
-                const uint32_t rel = k - kmin;
-                if ((rel & mask) == prefix) atomicAdd(&hist[(rel >> shift) & dmask], 1u);
-            }
+            if (k > tau) win[atomicAdd(&n_win, 1)] = ((uint64_t)kj[r] << 32) | ord_key_inv(k);
+            else if (k == tau && k) atomicAdd(&n_eq, 1);
         }
         __syncthreads();
-        if (wv == 0) {   // bin where the count of larger-or-equal digits reaches `need`
-            uint32_t tsum = 0;
-            for (int b = 0; b < 4; ++b) tsum += hist[4 * lane + b];
-            uint32_t incl = tsum;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t v = __shfl_down(incl, o, kWave);
-                if (lane + o < 64) incl += v;
-            }
-            const uint32_t excl = incl - tsum;
-            if (excl < need && need <= incl) {
-                uint32_t cum = excl;
-                int b = 3;
-                for (; b > 0; --b) {
-                    const uint32_t cb = hist[4 * lane + b];
-                    if (cum + cb >= need) break;
-                    cum += cb;
+        const int ne = n_eq, base = n_win;
+        __syncthreads();
+        for (int r = tid; r < n; r += 256) {
+            if (ek[r] == tau && tau) {
+                const uint32_t mine = kj[r];
+                if (ne == (int)need) {
+                    win[atomicAdd(&n_win, 1)] = ((uint64_t)mine << 32) | ord_key_inv(tau);
+                } else {
+                    uint32_t rank = 0;
+                    for (int u = 0; u < n; ++u) rank += (ek[u] == tau) & (kj[u] < mine);
+                    if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | ord_key_inv(tau);
                 }
-                s_bin = 4 * lane + b;
-                s_need = need - cum;
             }
         }
         __syncthreads();
-        prefix |= s_bin << shift;
-        mask |= dmask << shift;
-        need = s_need;
-        remaining = shift;
+        for (int r = tid; r < m; r += 256) {
+            const uint64_t mine = win[r];
+            int pos = 0;
+            for (int u = 0; u < m; ++u) pos += win[u] < mine;
+            nbr[out_row * m + pos] = (int32_t)(mine >> 32);
+            nbr_e[out_row * m + pos] = __uint_as_float((uint32_t)mine);
+        }
+        __syncthreads();   // the lists in LDS are free for the next row
     }
-    const uint32_t tau = kmin + prefix;
-    // Winners above the threshold go straight to the list (its order is fixed by the
-    // final ranking).  Entries equal to the threshold all win when exactly `need` of
-    // them exist; otherwise the `need` lowest key indices win, found by a scan that
-    // only ties at the cut ever pay for.
-    for (int r = tid; r < n; r += 256) {
-        const uint32_t k = ek[r];
-        if (k > tau) win[atomicAdd(&n_win, 1)] = ((uint64_t)kj[r] << 32) | ord_key_inv(k);
-        else if (k == tau && k) atomicAdd(&n_eq, 1);
-    }
-    __syncthreads();
-    const int ne = n_eq, base = n_win;
-    __syncthreads();
-    for (int r = tid; r < n; r += 256) {
-        if (ek[r] == tau && tau) {
-            const uint32_t mine = kj[r];
-            if (ne == (int)need) {
-                win[atomicAdd(&n_win, 1)] = ((uint64_t)mine << 32) | ord_key_inv(tau);
-            } else {
-                uint32_t rank = 0;
-                for (int u = 0; u < n; ++u) rank += (ek[u] == tau) & (kj[u] < mine);
-                if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | ord_key_inv(tau);
-            }
+}
+
+// The m-th largest of the keys in the first NIT registers of every lane (unused registers
+// hold 0, below every key), all between kmin and kmax: built bit by bit from the top; the
+// count of the keys that reach a trial value is one wave vote per register.  Straight-line
+// code for a given NIT: branches between the votes would cost more than the votes.
+template <int NIT, int R>
+__device__ __forceinline__ uint32_t mth_largest_key(const uint32_t (&E)[R], uint32_t kmin, uint32_t kmax, int m)
+{
+    static_assert(NIT <= R, "");
+    uint32_t tau = kmin;
+    if (kmax > kmin) {
+        for (int b = 31 - __clz(kmax - kmin); b >= 0; --b) {
+            const uint32_t trial = tau + (1u << b);   // bits below b of tau - kmin are still 0
+            int reach = 0;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) reach += (int)__popcll(__ballot(E[it] >= trial));
+            if (trial > tau && reach >= m) tau = trial;   // (a trial that wrapped around is beyond every key)
         }
     }
+    return tau;
+}
+
+// The same select for short lists, one wave per source and no workgroup barrier: a lane
+// keeps the keys of up to R candidates in registers, so that a compute unit works on
+// several times as many sources at once as with a workgroup per source -- the select is
+// a chain of memory and LDS round trips, and only the number of chains in flight hides
+// them.  Everything that reaches the m-th largest key goes to a small LDS list per wave
+// (m entries and room for 64 more that are tied at the cut); only then are the key
+// indices of the listed entries fetched, the tied entries with the lowest key indices are
+// kept, and the winners are ranked by key index.  Lists longer than 64 R, with fewer than
+// m entries, or with more ties at the cut than the list has room for, raise the head's
+// overflow flag (the head is then redone densely).
+constexpr int kTieRoom = 64;
+
+template <int R>
+__global__ __launch_bounds__(256) void nbr_select_wave_kernel(const uint2 *__restrict__ cand,
+                                                              const int32_t *__restrict__ cand_cnt,
+                                                              int32_t *__restrict__ overflow,
+                                                              const int32_t *__restrict__ src, int S,
+                                                              int chunks, int slice_cap, int m,
+                                                              SourceReuse ru, int32_t *__restrict__ nbr,
+                                                              float *__restrict__ nbr_e)
+{
+    static_assert(R == 16 || R == 32, "register groups of 16");
+    extern __shared__ __align__(8) uint32_t dyn[];   // per wave: [64] slice starts, [m + kTieRoom] list (64 bit)
+    const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);   // (scalar: so are the row and its addresses)
+    const int n_rows = ru.code ? ru.n_new[h] : S;
+    if (overflow[h]) return;
+    const int list_cap = m + kTieRoom;
+    uint32_t *start_s = dyn + wv * (64 + 2 * list_cap);
+    uint64_t *win = reinterpret_cast<uint64_t *>(start_s + 64);
+    const uint64_t below = (1ull << lane) - 1ull;
+
+    for (int x = blockIdx.x * 4 + wv; x < n_rows; x += gridDim.x * 4) {
+        const long row = (long)h * S + x;
+        const uint2 *slices = cand + row * chunks * (long)slice_cap;
+        // slice sizes -> where each slice starts in the concatenated list
+        const int cnt = lane < chunks ? cand_cnt[row * chunks + lane] : 0;
+        const uint32_t self = (uint32_t)src[row];
+        const long out_row = (long)h * S + (ru.code ? ru.new_pos[row] : x);
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += v;
+        }
+        // (values every lane holds alike are moved to scalar registers: the code below then
+        // branches as a wave instead of masking lanes)
+        const int n = __builtin_amdgcn_readfirstlane(__shfl(incl, 63, kWave));
+        if (n > 64 * R || n < m) {   // too long for the lanes (or short of m): redo the head densely
+            if (lane == 0) overflow[h] = 1;
+            return;
+        }
+        start_s[lane] = (uint32_t)(incl - cnt);
+        __builtin_amdgcn_wave_barrier();
+        const int n_it = (n + 63) >> 6;
+
+        // Register it of lane L holds entry 64 it + L: first where it sits in the row's slices,
+        // then its order-preserving edge key (0 = no entry / dropped).  The slice starts are the
+        // same for every lane: a scalar walk over the slices, the last slice that starts at or
+        // before the entry wins.  The loads of 16 registers leave together.
+        uint32_t E[R];
+        // (the lane number as a value the compiler cannot see through: otherwise it keeps
+        // "64 it + lane" for every register in a register of its own across the whole loop)
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+#pragma unroll
+        for (int it = 0; it < R; ++it) E[it] = (uint32_t)(ln + it * 64);
+        for (int c = 1; c < chunks; ++c) {
+            const int s_c = __builtin_amdgcn_readlane(incl - cnt, c);
+            const int shift = c * slice_cap - s_c;
+#pragma unroll
+            for (int it = 0; it < R; ++it)
+                if ((it & ~15) < n_it) E[it] = ln >= s_c - it * 64 ? (uint32_t)(ln + (it * 64 + shift)) : E[it];
+        }
+#pragma unroll
+        for (int it = 0; it < R; ++it) E[it] = ln < n - it * 64 ? E[it] : 0u;   // past the end: any valid entry
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        bool dropped = false;   // this lane held the source's own column
+#pragma unroll
+        for (int g = 0; g < R; g += 16) {
+            if (g < n_it) {
+                uint2 v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    v[u] = *reinterpret_cast<const uint2 *>(reinterpret_cast<const char *>(slices) + E[g + u] * 8u);
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    // the source's own column is no neighbour (Eq. 3: j != i): key 0 sorts below every edge
+                    const bool present = ln < n - (g + u) * 64, own = present && v[u].y == self;
+                    const uint32_t k = (present && !own) ? ord_key_u(v[u].x) : 0u;
+                    dropped |= own;
+                    E[g + u] = k;
+                    if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 16; ++u) E[g + u] = 0u;
+            }
+        }
+        const int valid = n - (int)__popcll(__ballot(dropped));
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+        }
+        kmin = (uint32_t)__builtin_amdgcn_readfirstlane((int)kmin);
+        kmax = (uint32_t)__builtin_amdgcn_readfirstlane((int)kmax);
+        if (valid < m) {
+            if (lane == 0) overflow[h] = 1;
+            return;
+        }
+
+        uint32_t tau;
+        if (n_it <= 4) tau = mth_largest_key<4>(E, kmin, kmax, m);
+        else if (n_it <= 8) tau = mth_largest_key<8>(E, kmin, kmax, m);
+        else if (n_it <= 12) tau = mth_largest_key<12>(E, kmin, kmax, m);
+        else if (n_it <= 16) tau = mth_largest_key<16>(E, kmin, kmax, m);
+        else if (n_it <= 24) tau = mth_largest_key<(R > 24 ? 24 : R)>(E, kmin, kmax, m);
+        else tau = mth_largest_key<R>(E, kmin, kmax, m);
+
+        // everything that reaches tau -> LDS list as (entry number, key), any order
+        int listed = 0;
+#pragma unroll
+        for (int it = 0; it < R; ++it)
+            if ((it & ~3) < n_it) {
+                const bool in = E[it] >= tau;
+                const uint64_t votes = __ballot(in);
+                const int at = listed + (int)__popcll(votes & below);
+                if (in && at < list_cap) win[at] = ((uint64_t)(uint32_t)(ln + it * 64) << 32) | E[it];
+                listed += (int)__popcll(votes);
+            }
+        if (listed > list_cap) {   // too many exactly equal edges at the cut
+            if (lane == 0) overflow[h] = 1;
+            return;
+        }
+        __builtin_amdgcn_wave_barrier();
+        // the key indices of the listed entries: (key index, edge bits) from here on
+        for (int r = lane; r < listed; r += 64) {
+            const uint64_t w = win[r];
+            const int e = (int)(w >> 32);
+            int lo = 0, hi = chunks - 1;    // last slice that starts at or before entry e
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if ((int)start_s[mid] <= e) lo = mid; else hi = mid - 1;
+            }
+            const uint32_t j = slices[lo * slice_cap + (e - (int)start_s[lo])].y;
+            win[r] = ((uint64_t)j << 32) | ord_key_inv((uint32_t)w);
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (listed > m) {
+            // Of the entries equal to tau only those with the lowest key indices stay: one that
+            // `keep` or more tied entries precede is dropped (a dropped entry sorts behind all).
+            const uint32_t tau_bits = ord_key_inv(tau);
+            int n_tied = 0;
+            for (int u = 0; u < listed; ++u) n_tied += (uint32_t)win[u] == tau_bits;
+            const int keep = m - (listed - n_tied);
+            for (int r0 = 0; r0 < listed; r0 += 64) {
+                const int r = r0 + lane;
+                const uint64_t mine = r < listed ? win[r] : 0ull;
+                int before = 0;
+                if (r < listed && (uint32_t)mine == tau_bits)
+                    for (int u = 0; u < listed; ++u) {
+                        const uint64_t w = win[u];
+                        before += (uint32_t)w == tau_bits && w < mine;
+                    }
+                __builtin_amdgcn_wave_barrier();
+                if (before >= keep) win[r] = ~0ull;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        // each winner's rank by key index is its place in the output
+        for (int r = lane; r < listed; r += 64) {
+            const uint64_t mine = win[r];
+            if (mine != ~0ull) {
+                int pos = 0;
+                for (int u = 0; u < listed; ++u) pos += win[u] < mine;
+                nbr[out_row * m + pos] = (int32_t)(mine >> 32);
+                nbr_e[out_row * m + pos] = __uint_as_float((uint32_t)mine);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+// Which sources of this round (cur [Hkv, S], ascending) were sources in the previous round
+// (prev, ascending): code[h, a] = slot in prev, or -1 - r for the r-th source that was not;
+// those go, in order, to new_src[h, 0 .. n_new[h]), new_pos[h, r] = a.  The lists of the
+// sources that were there (prev_nbr, prev_e [Hkv, S, m]) are copied to their slots of this
+// round (nbr, nbr_e).  One workgroup per head.
+__global__ __launch_bounds__(256) void match_sources_kernel(const int32_t *__restrict__ prev,
+                                                            const int32_t *__restrict__ cur, int S,
+                                                            int32_t *__restrict__ code,
+                                                            int32_t *__restrict__ new_src,
+                                                            int32_t *__restrict__ new_pos,
+                                                            int32_t *__restrict__ n_new, int m,
+                                                            const int32_t *__restrict__ prev_nbr,
+                                                            const float *__restrict__ prev_e,
+                                                            int32_t *__restrict__ nbr,
+                                                            float *__restrict__ nbr_e)
+{
+    extern __shared__ int32_t prev_s[];   // [S] previous sources, then [S] this round's codes
+    int32_t *code_s = prev_s + S;
+    __shared__ int32_t wave_new[4];
+    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const long row0 = (long)h * S;
+    for (int b = tid; b < S; b += 256) prev_s[b] = prev[row0 + b];
     __syncthreads();
-    for (int r = tid; r < m; r += 256) {
-        const uint64_t mine = win[r];
-        int pos = 0;
-        for (int u = 0; u < m; ++u) pos += win[u] < mine;
-        nbr[row * m + pos] = (int32_t)(mine >> 32);
-        nbr_e[row * m + pos] = __uint_as_float((uint32_t)mine);
+    int base = 0;
+    for (int a0 = 0; a0 < S; a0 += 256) {
+        const int a = a0 + tid;
+        int i = 0, found = -1;
+        if (a < S) {
+            i = cur[row0 + a];
+            int lo = 0, hi = S;   // first slot of prev that holds i or more
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (prev_s[mid] < i) lo = mid + 1; else hi = mid;
+            }
+            if (lo < S && prev_s[lo] == i) found = lo;
+        }
+        const bool is_new = a < S && found < 0;
+        const uint64_t mask = __ballot(is_new);
+        if (lane == 0) wave_new[wv] = (int32_t)__popcll(mask);
+        __syncthreads();
+        int before = base, total = 0;
+        for (int u = 0; u < 4; ++u) {
+            if (u < wv) before += wave_new[u];
+            total += wave_new[u];
+        }
+        if (is_new) {
+            const int r = before + (int)__popcll(mask & ((1ull << lane) - 1ull));
+            new_src[row0 + r] = i;
+            new_pos[row0 + r] = a;
+            code[row0 + a] = code_s[a] = -1 - r;
+        } else if (a < S) {
+            code[row0 + a] = code_s[a] = found;
+        }
+        base += total;
+        __syncthreads();
+    }
+    if (tid == 0) n_new[h] = base;
+    // the lists that stay: the neighbourhood of a source does not depend on the scores
+    for (long u = tid; u < (long)S * m; u += 256) {
+        const int a = (int)(u / m), r = (int)(u % m);
+        const int from = code_s[a];
+        if (from >= 0) {
+            nbr[(row0 + a) * m + r] = prev_nbr[(row0 + from) * m + r];
+            nbr_e[(row0 + a) * m + r] = prev_e[(row0 + from) * m + r];
+        }
     }
 }
 
@@ -775,8 +1084,8 @@ size_t mfma_bound_scratch_bytes(int Hkv, int P, int S)
 }
 
 hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                    const int32_t *src, void *hist_part, float *tau, int32_t *overflow,
-                                    hipStream_t st)
+                                    const int32_t *src, const int32_t *n_src, void *hist_part, float *tau,
+                                    int32_t *overflow, hipStream_t st)
 {
     const int ps = mfma_sample_cols(P), stride = P / ps;
     const int sgroups = (S + kRows - 1) / kRows;
@@ -785,16 +1094,16 @@ hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int
     if (!allow_big_lds((const void *)cosine_bound_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(cosine_bound_kernel, dim3(sgroups, Hkv, chunks), dim3(kThreads),
                        2 * kTileBytes + kRows * (kBoundBins / 2) * 4, st, (const uint16_t *)Ac,
-                       (const uint16_t *)Kc, N, ps, stride, S, src, m, chunk_cols, (uint32_t *)hist_part, tau,
-                       overflow);
+                       (const uint16_t *)Kc, N, ps, stride, S, src, n_src, m, chunk_cols, (uint32_t *)hist_part,
+                       tau, overflow);
     if (chunks > 1)
         hipLaunchKernelGGL(bound_merge_kernel, dim3((S + 3) / 4, Hkv), dim3(256), 0, st,
-                           (const uint32_t *)hist_part, chunks, sgroups, S, m, tau);
+                           (const uint32_t *)hist_part, chunks, sgroups, S, n_src, m, tau);
     return hipGetLastError();
 }
 
 hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                     const int32_t *src, const float *tau, void *cand,
+                                     const int32_t *src, const int32_t *n_src, const float *tau, void *cand,
                                      int32_t *cand_cnt, int32_t *overflow, hipStream_t st)
 {
     const int sgroups = (S + kRows - 1) / kRows;
@@ -807,7 +1116,7 @@ hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, in
     const double per_tile = 32.0 * (1.0 - pow(1.0 - (rate < 1.0 ? rate : 1.0), 16.0));
     int drain_every = (int)(30.0 / (per_tile > 0.45 ? per_tile : 0.45));
     if (drain_every < 1) drain_every = 1;
-    FilterArgs fa{tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, drain_every, sgroups};
+    FilterArgs fa{n_src, tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, drain_every, sgroups};
     if (!allow_big_lds((const void *)cosine_filter_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(cosine_filter_kernel, dim3(g.chunks * sgroups, Hkv), dim3(kThreads),
                        2 * kTileBytes + 2 * (kThreads / kWave) * kRingRows * kStagePitch, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, src,
@@ -815,16 +1124,44 @@ hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, in
     return hipGetLastError();
 }
 
+bool source_reuse_applies(int S) { return S <= 4096; }   // the previous list and the codes sit in LDS
+
+hipError_t launch_match_sources(const int32_t *prev, const int32_t *cur, int Hkv, int S, int m,
+                                const int32_t *prev_nbr, const float *prev_e, int32_t *code, int32_t *new_src,
+                                int32_t *new_pos, int32_t *n_new, int32_t *nbr, float *nbr_e, hipStream_t st)
+{
+    hipLaunchKernelGGL(match_sources_kernel, dim3(Hkv), dim3(256), (size_t)S * 8, st, prev, cur, S, code,
+                       new_src, new_pos, n_new, m, prev_nbr, prev_e, nbr, nbr_e);
+    return hipGetLastError();
+}
+
 hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t *overflow,
-                             const int32_t *src, int Hkv, int P, int S, int m, int32_t *nbr,
-                             float *nbr_e, hipStream_t st)
+                             const int32_t *src, int Hkv, int P, int S, int m, const SourceReuse *reuse,
+                             int32_t *nbr, float *nbr_e, hipStream_t st)
 {
     const int cap = mfma_cand_cap(P, m);
     const MfmaFilterGeom g = mfma_filter_geom(Hkv, P, S, m);
+    const SourceReuse ru = reuse ? *reuse : SourceReuse{};
+    // Every source has a list (first round, or nothing kept) and the lists are short: a wave
+    // per source.  That kernel is long straight-line code, which only pays when there are
+    // many lists to go through; the few new sources of a later round take the other one.
+    if (!reuse && cap <= 64 * 32 && g.chunks <= 64) {
+        int per_head = 8192 / Hkv < 1 ? 1 : 8192 / Hkv;   // four sources per workgroup
+        const int wgs = per_head > (S + 3) / 4 ? (S + 3) / 4 : per_head;
+        const size_t lds = (size_t)4 * (64 + 2 * (m + kTieRoom)) * 4;
+        auto *kernel = cap <= 64 * 16 ? nbr_select_wave_kernel<16> : nbr_select_wave_kernel<32>;
+        hipLaunchKernelGGL(kernel, dim3(wgs, Hkv), dim3(256), lds, st, (const uint2 *)cand, cand_cnt, overflow,
+                           src, S, g.chunks, g.slice_cap, m, ru, nbr, nbr_e);
+        return hipGetLastError();
+    }
+    // The workgroups of a head share its sources in turn: few workgroups when only the new
+    // sources of a round have lists (most would find nothing to do), many otherwise.
+    int per_head = (reuse ? 3072 : 16384) / Hkv;
+    per_head = per_head < 1 ? 1 : (per_head > S ? S : per_head);
     const size_t lds = (size_t)2 * cap * 4 + (size_t)m * 8;
     if (!allow_big_lds((const void *)nbr_select_kernel)) return hipGetLastError();
-    hipLaunchKernelGGL(nbr_select_kernel, dim3(S, Hkv), dim3(256), lds, st, (const uint2 *)cand,
-                       cand_cnt, overflow, src, S, g.chunks, g.slice_cap, cap, m, nbr, nbr_e);
+    hipLaunchKernelGGL(nbr_select_kernel, dim3(per_head, Hkv), dim3(256), lds, st, (const uint2 *)cand,
+                       cand_cnt, overflow, src, S, g.chunks, g.slice_cap, cap, m, ru, nbr, nbr_e);
     return hipGetLastError();
 }
 

@@ -279,6 +279,35 @@ def test_filtered_neighbourhoods_keys_close_to_many_sources(oracle):
     assert set(nbr[0, 1, a].tolist()) <= set(members.tolist())   # its neighbours are cluster members
 
 
+@pytest.mark.parametrize("n_copies", [5, 100])
+def test_filtered_neighbourhoods_ties_at_the_cut(oracle, n_copies):
+    """Exact copies of a source's weakest neighbour tie with it at the cut: the lowest key
+    indices win (a few ties are settled among the listed candidates, a hundred send the head
+    through the dense block)."""
+    cfg = small_bf16_cfg(n_tokens=10007, n_sources=40, n_neighbors=20, n_kv_heads=2, n_q_heads=8)
+    (K, V, Q), _ = util.device_layer(cfg, 9)
+    P, S, m = cfg.n_prefix, 40, 20
+    s0 = synth.random_scores(cfg)
+    src0, _ = oracle.topk(s0[0].astype(np.float64), S)
+    i = int(src0[0])
+    e0 = oracle.cosine_row(K, "bf16", cfg.window, 0, i)
+    top, _ = oracle.topk(e0, m, skip=i)
+    weakest = int(top[np.argmin(e0[top])])
+    rng = np.random.default_rng(23)
+    free = np.setdiff1d(np.arange(P), np.concatenate([src0, top]))
+    spots = rng.choice(free, size=n_copies, replace=False)
+    K[0, spots] = K[0, weakest]
+    Kd = gk.to_device(K, gk.BF16)
+    p = util.params_from_cfg(cfg, rounds=1)
+    s1, src, nbr, ev = run_propagate(p, Kd, s0)
+    util.check_round_staged(oracle, K, "bf16", cfg.window, s0, s1, src[0], nbr[0], ev[0], S, m, 1.0)
+    e1 = oracle.cosine_row(K, "bf16", cfg.window, 0, i)
+    want, gap = oracle.topk(e1, m, skip=i)
+    assert gap == 0.0                                      # the cut falls among equal edges
+    assert np.array_equal(nbr[0, 0, 0], want)
+    assert min(int(spots.min()), weakest) in want and int(max(spots.max(), weakest)) not in want
+
+
 def test_filtered_neighbourhoods_overflow_falls_back(oracle):
     """Masses of exactly equal edges defeat any bound: those heads must be redone
     through the dense block and still give the exact lowest-index answer."""
@@ -298,6 +327,68 @@ def test_filtered_neighbourhoods_overflow_falls_back(oracle):
     want = np.sort(dup)[:17]
     want = want[want != src[0, 0, a]][:16]
     assert np.array_equal(nbr[0, 0, a], want) and (np.abs(ev[0, 0, a] - 1.0) < 1e-6).all()
+
+
+@pytest.mark.parametrize("S,m,alpha,signal", [(40, 20, 1.0, 0), (130, 7, 0.7, 0), (64, 32, 1e-3, 0),
+                                              (24, 16, 1.0, 2), (48, 12, 0.5, 1)])
+def test_filtered_multi_round_keeps_lists(oracle, S, m, alpha, signal):
+    """From the second round on, a source that was one in the round before keeps its
+    neighbour list and only the new sources go through the bound, filter and select
+    passes: every round must equal a one-round call on the scores of the round before
+    (which computes every list), bit for bit, and hold against the oracle stage by stage.
+    alpha = 1e-3 leaves the sources as they are (no new source in any head)."""
+    cfg = small_bf16_cfg(n_tokens=10007, n_sources=S, n_neighbors=m)
+    say(f"filtered multi-round S={S} m={m} alpha={alpha} signal={signal}")
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 6)
+    s0 = synth.random_scores(cfg)
+    T = 3
+    p = util.params_from_cfg(cfg, rounds=T, decay=alpha, signal=signal)
+    sT, src, nbr, ev = run_propagate(p, Kd, s0)
+    p1 = util.params_from_cfg(cfg, rounds=1, decay=alpha, signal=signal)
+    s = s0
+    kept = 0
+    for t in range(T):
+        s_next, src1, nbr1, ev1 = run_propagate(p1, Kd, s)
+        assert np.array_equal(src[t], src1[0]), f"round {t}: sources"
+        assert np.array_equal(nbr[t], nbr1[0]), f"round {t}: neighbour lists"
+        assert np.array_equal(ev[t], ev1[0]), f"round {t}: edge weights"
+        if t:
+            kept += sum(len(set(src[t, h].tolist()) & set(src[t - 1, h].tolist())) for h in range(cfg.n_kv_heads))
+        if t == T - 1:
+            util.check_round_staged(oracle, K, "bf16", cfg.window, s, s_next, src[t], nbr[t], ev[t], S, m,
+                                    alpha, signal)
+        s = s_next
+    say(f"  sources kept from the round before: {kept} of {(T - 1) * cfg.n_kv_heads * S}")
+    assert np.array_equal(s, sT, equal_nan=True)
+    # without the per-round outputs the lists of two rounds take turns in two buffers
+    sT2, _, _, _ = run_propagate(p, Kd, s0, debug=False)
+    assert np.array_equal(sT, sT2, equal_nan=True)
+
+
+def test_filtered_multi_round_with_overflowing_head(oracle):
+    """A head whose lists overflow is redone densely in every round; the other head
+    keeps its lists."""
+    cfg = small_bf16_cfg(n_tokens=12000, n_sources=8, n_neighbors=16, n_kv_heads=2, n_q_heads=8)
+    (K, V, Q), _ = util.device_layer(cfg, 1)
+    P = cfg.n_prefix
+    rng = np.random.default_rng(5)
+    dup = rng.choice(P, size=P // 2, replace=False)
+    K[0, dup] = K[0, dup[0]]
+    Kd = gk.to_device(K, gk.BF16)
+    s0 = synth.random_scores(cfg)
+    s0[0, dup[:4]] = 50.0
+    p = util.params_from_cfg(cfg, rounds=3, decay=0.9)
+    sT, src, nbr, ev = run_propagate(p, Kd, s0)
+    p1 = util.params_from_cfg(cfg, rounds=1, decay=0.9)
+    s = s0
+    for t in range(3):
+        s_next, src1, nbr1, ev1 = run_propagate(p1, Kd, s)
+        assert np.array_equal(src[t], src1[0]) and np.array_equal(nbr[t], nbr1[0])
+        assert np.array_equal(ev[t], ev1[0])
+        s = s_next
+    assert np.array_equal(s, sT)
+    util.check_round_staged(oracle, K, "bf16", cfg.window, s0, run_propagate(p1, Kd, s0)[0], src[0], nbr[0],
+                            ev[0], 8, 16, 0.9)
 
 
 # ---- edges between two tensors (Discussion: key-value, value-value, ... edges) ----
