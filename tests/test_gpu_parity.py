@@ -557,6 +557,17 @@ def test_compress_random_shapes(oracle, seed):
     end_to_end(oracle, cfg, seed, impl, **extra)
 
 
+@pytest.mark.parametrize("S,m,T,signal,alpha", [(64, 32, 3, 0, 1.0), (20, 9, 4, 0, 0.5), (150, 5, 2, 1, 0.5),
+                                                (33, 40, 3, 2, 1.0)])
+def test_compress_filter_route_multi_round(oracle, S, m, T, signal, alpha):
+    """Whole pass with several re-picking rounds on the sampled-bound + filter route (lists of
+    returning sources are kept, the lists of two rounds take turns in the workspace)."""
+    cfg = small_bf16_cfg(n_tokens=9000 + 7 * S, n_sources=S, n_neighbors=m, n_kv_heads=3, n_q_heads=6,
+                         budget=1500)
+    say(f"filter route, {T} rounds, S={S} m={m} signal={signal} alpha={alpha}")
+    end_to_end(oracle, cfg, 2, gk.IMPL_AUTO, rounds=T, reselect=1, signal=signal, decay=alpha)
+
+
 def test_generic_and_mfma_agree():
     cfg = small_bf16_cfg()
     host, dev = util.device_layer(cfg, 9)
