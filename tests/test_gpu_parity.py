@@ -256,6 +256,18 @@ def test_filtered_neighbourhoods_staged(oracle, S, m):
     assert np.count_nonzero((nbr != nbr_g).any(axis=-1)) <= 2 + flips
 
 
+def test_filtered_neighbourhoods_longer_lists(oracle):
+    """About 400 candidates per source (every 9th key sampled, m = 45): lists that need the
+    wave-per-source select's larger register file."""
+    cfg = small_bf16_cfg(n_tokens=20011, n_sources=70, n_neighbors=45, n_kv_heads=2, n_q_heads=8)
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 5)
+    s0 = synth.random_scores(cfg)
+    p = util.params_from_cfg(cfg, rounds=1)
+    s1, src, nbr, ev = run_propagate(p, Kd, s0)
+    flips = util.check_round_staged(oracle, K, "bf16", cfg.window, s0, s1, src[0], nbr[0], ev[0], 70, 45, 1.0)
+    say(f"  neighbour lists differing from the oracle's (near-ties): {flips}")
+
+
 def test_filtered_neighbourhoods_keys_close_to_many_sources(oracle):
     """A tight cluster that holds 12 of the sources: each of its keys is a candidate of all
     12 at once, far more hits per key than the filter pass stores in line."""
