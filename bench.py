@@ -99,7 +99,7 @@ def main():
                          "per-layer: one graphkv_compress call per layer")
     ap.add_argument("--group", type=int, default=0, help="layers per batched call (0 = all)")
     ap.add_argument("--streams", type=int, default=1,
-                    help="HIP streams the batched calls are spread over (each with its own workspace)")
+                    help="HIP streams the calls are spread over (each with its own workspace)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the eviction pass of one sequence); "
@@ -169,12 +169,27 @@ def main():
                 if st is not None:
                     cur.wait_stream(st)
     else:
-        ws = torch.empty(max(gk.graphkv_workspace_bytes(p) for p in params), dtype=torch.uint8, device=dev)
+        # the layers are independent: with --streams > 1 they go round-robin over that many
+        # streams, each with a workspace of its own
+        n_str = max(1, args.streams)
+        ws_bytes = max(gk.graphkv_workspace_bytes(p) for p in params)
+        wss = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(n_str)]
+        streams = [torch.cuda.Stream() for _ in range(n_str)] if n_str > 1 else [None]
 
         def step():
+            cur = torch.cuda.current_stream()
+            for st in streams:
+                if st is not None:
+                    st.wait_stream(cur)
             for l in range(L):
-                gk.graphkv_compress(params[l], Kall[l], Vall[l], Qall[l], Kout[row_off[l]:row_off[l + 1]],
-                                    Vout[row_off[l]:row_off[l + 1]], Iout[row_off[l]:row_off[l + 1]], None, ws)
+                st = streams[l % n_str]
+                with torch.cuda.stream(st) if st is not None else contextlib.nullcontext():
+                    gk.graphkv_compress(params[l], Kall[l], Vall[l], Qall[l], Kout[row_off[l]:row_off[l + 1]],
+                                        Vout[row_off[l]:row_off[l + 1]], Iout[row_off[l]:row_off[l + 1]], None,
+                                        wss[l % n_str])
+            for st in streams:
+                if st is not None:
+                    cur.wait_stream(st)
 
     for _ in range(args.warmup):
         step()
@@ -285,7 +300,8 @@ def main():
                                f"d={cfg.head_dim}, N={cfg.n_tokens}, w={cfg.window}, pool={cfg.pool_kernel}, "
                                f"B={cfg.budget_for_layer(0)}..{cfg.budget_for_layer(L - 1)}, S={cfg.n_sources}, "
                                f"m={cfg.n_neighbors}, T={cfg.rounds}, reselect={cfg.reselect}, alpha={cfg.decay}",
-                   "mode": args.mode + (f" (groups of {group} layers, {args.streams} stream(s))" if args.mode == "batched" else ""),
+                   "mode": args.mode + (f" (groups of {group} layers, {args.streams} stream(s))" if args.mode == "batched"
+                                        else f" ({args.streams} stream(s))"),
                    "token_head_units_per_s": round(tokens_per_s * cfg.n_layers * cfg.n_kv_heads, 1),
                    "input_generation_s": round(t_gen, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "pass_vs_streaming_model": pass_view,
