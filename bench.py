@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--group", type=int, default=0, help="layers per batched call (0 = all)")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the calls are spread over (each with its own workspace)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph after the warm-up and replay it (the library "
+                         "allocates nothing and only launches kernels on the caller's stream)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the eviction pass of one sequence); "
@@ -191,9 +194,17 @@ def main():
                 if st is not None:
                     cur.wait_stream(st)
 
-    for _ in range(args.warmup):
+    for _ in range(max(args.warmup, 1 if args.graph else 0)):
         step()
     torch.cuda.synchronize()
+    eager_step = step
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager_step()
+        step = graph.replay
+        step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -222,7 +233,7 @@ def main():
     if profile_steps > 0:
         gk.graphkv_profile_begin()
         for _ in range(profile_steps):
-            step()
+            eager_step()
         prof = gk.graphkv_profile_end()
         torch.cuda.synchronize()
         alg = [algorithmic_bytes(cfg, p.budget) for p in params]
@@ -301,7 +312,7 @@ def main():
                                f"B={cfg.budget_for_layer(0)}..{cfg.budget_for_layer(L - 1)}, S={cfg.n_sources}, "
                                f"m={cfg.n_neighbors}, T={cfg.rounds}, reselect={cfg.reselect}, alpha={cfg.decay}",
                    "mode": args.mode + (f" (groups of {group} layers, {args.streams} stream(s))" if args.mode == "batched"
-                                        else f" ({args.streams} stream(s))"),
+                                        else f" ({args.streams} stream(s))") + (", one HIP graph per step" if args.graph else ""),
                    "token_head_units_per_s": round(tokens_per_s * cfg.n_layers * cfg.n_kv_heads, 1),
                    "input_generation_s": round(t_gen, 1)},
         "roofline": roofline, "cpu_baseline": cpu, "pass_vs_streaming_model": pass_view,

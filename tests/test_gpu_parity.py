@@ -614,6 +614,43 @@ def test_non_default_stream_and_workspace_reuse(oracle):
     assert np.array_equal(idx.cpu().numpy(), ref[2]) and np.array_equal(gk.to_host_bits(Kout), ref[0])
 
 
+@pytest.mark.parametrize("route", ["dense", "filter"])
+def test_compress_replayed_from_a_hip_graph(oracle, route):
+    """The library only launches kernels on the caller's stream and allocates nothing, so a
+    call can be captured into a HIP graph.  The graph is replayed on three different inputs
+    (copied into the captured buffers), with eager calls and synchronisations in between,
+    and every replay must give the eager call's bytes."""
+    if route == "dense":
+        cfg = small_bf16_cfg()
+        kw = dict(rounds=2)
+    else:
+        cfg = small_bf16_cfg(n_tokens=9100, n_sources=40, n_neighbors=12, budget=700)
+        kw = dict(rounds=3)
+    p = util.params_from_cfg(cfg, **kw)
+    layers = [util.device_layer(cfg, l)[1] for l in (0, 1, 2)]
+    Kd, Vd, Qd = (t.clone() for t in layers[0])
+    ws = gk.alloc_workspace(p)
+    shape = (p.n_kv_heads, p.budget, p.head_dim)
+    Kout = torch.empty(shape, dtype=Kd.dtype, device="cuda")
+    Vout = torch.empty(shape, dtype=Kd.dtype, device="cuda")
+    idx = torch.empty((p.n_kv_heads, p.budget), dtype=torch.int32, device="cuda")
+    gk.graphkv_compress(p, Kd, Vd, Qd, Kout, Vout, idx, ws=ws)     # first use outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gk.graphkv_compress(p, Kd, Vd, Qd, Kout, Vout, idx, ws=ws)
+    for rep, l in enumerate((1, 2, 0, 1)):
+        say(f"graph replay {rep} ({route} route) on layer {l}")
+        want, _ = run_compress(p, layers[l], want_scores=False)     # eager, own buffers
+        for dst, src in zip((Kd, Vd, Qd), layers[l]):
+            dst.copy_(src)
+        Kout.zero_(); Vout.zero_(); idx.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(idx.cpu().numpy(), want[2]), f"replay {rep}: indices"
+        assert np.array_equal(gk.to_host_bits(Kout), want[0]) and np.array_equal(gk.to_host_bits(Vout), want[1])
+
+
 # ------------------------------------------------------------ batched call ---
 
 @pytest.mark.parametrize("impl", IMPLS)
