@@ -719,6 +719,49 @@ def test_full_size_layer(oracle, name, layer):
     assert sum(n for _, n in diffs) <= 8 * cfg.n_neighbors
 
 
+def test_full_size_batched_c3(oracle):
+    """The headline workload as the benchmark launches it: all 32 layers of c3 in one batched
+    call.  Three layers are compared with the oracle in full, and with a per-layer call bit
+    for bit; the size-independent properties are checked on every layer."""
+    cfg = synth.CONFIGS["c3"]
+    L, H, B = cfg.n_layers, cfg.n_kv_heads, cfg.budget
+    say("full-size c3, 32 layers in one batched call")
+    p = util.params_from_cfg(cfg)
+    tdt = torch.bfloat16
+    Kall = torch.empty((L, H, cfg.n_tokens, cfg.head_dim), dtype=tdt, device="cuda")
+    Vall = torch.empty_like(Kall)
+    Qall = torch.empty((L, cfg.n_q_heads, cfg.window, cfg.head_dim), dtype=tdt, device="cuda")
+    checked = (0, 13, 31)
+    host = {}
+    for l in range(L):
+        K, V, Q = synth.make_layer(cfg, l)
+        Kall[l].copy_(gk.to_device(K, gk.BF16)); Vall[l].copy_(gk.to_device(V, gk.BF16))
+        Qall[l].copy_(gk.to_device(Q, gk.BF16))
+        if l in checked:
+            host[l] = (K, V, Q)
+    Kout, Vout, idx = gk.graphkv_compress_batched(p, L, None, Kall, Vall, Qall)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy().reshape(L, H, B)
+    P = cfg.n_prefix
+    assert (np.diff(idx_h, axis=2) > 0).all() and idx_h.min() >= 0 and idx_h.max() < cfg.n_tokens
+    assert (idx_h[:, :, B - cfg.window:] == np.arange(P, cfg.n_tokens)).all()
+    Ko = gk.to_host_bits(Kout).reshape(L, H, B, cfg.head_dim)
+    Vo = gk.to_host_bits(Vout).reshape(L, H, B, cfg.head_dim)
+    for l in checked:
+        K, V, Q = host[l]
+        say(f"  layer {l} against the oracle")
+        ref = oracle.compress(K, V, Q, "bf16", p.pool_kernel, p.budget, p.n_sources, p.n_neighbors, p.rounds,
+                              alpha=p.decay, reselect=p.reselect, signal=p.signal, pool_mode=p.pool_mode,
+                              scale=p.softmax_scale)
+        diffs = util.compare_end_to_end((Ko[l], Vo[l], idx_h[l]), ref, K, V, cfg.window)
+        if diffs:
+            say(f"  layer {l}: retained sets differ on heads {diffs}; oracle min gaps {ref['min_gap']}")
+            assert ref["min_gap"].min() < util.REL_TOL
+            assert sum(n for _, n in diffs) <= 8 * cfg.n_neighbors
+        one, _ = run_compress(p, (Kall[l], Vall[l], Qall[l]), want_scores=False)
+        assert np.array_equal(one[2], idx_h[l]) and np.array_equal(one[0], Ko[l]) and np.array_equal(one[1], Vo[l])
+
+
 def test_long_context_properties(oracle):
     """c5's shape (N = 131072, w = 64, S = m = 128): too large for a full oracle
     run inside the test budget, so: stage I on sampled heads against the oracle,
