@@ -17,6 +17,10 @@
 //   3. an exact (value desc, index asc) top-m over each short list.
 // A source whose list overflows (masses of equal edges, adversarial order) sets
 // a per-head flag and that head is redone through the dense block instead.
+//
+// From the second round on only the sources that were none in the round before
+// go through these passes (a neighbourhood depends on the keys alone): the others
+// keep their lists, and the kernels take a per-head count of rows in use.
 #include "common.hpp"
 #include "kernels.hpp"
 #include "mfma_tile.hpp"
