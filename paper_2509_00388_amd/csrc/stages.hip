@@ -69,14 +69,15 @@ __device__ __forceinline__ float signal_factor(float e, float alpha, int signal)
     return signal == 1 ? fmaf(alpha, e, 1.0f) : fmaf(-alpha, e, 1.0f);
 }
 
-// Bitonic sort of npad 64-bit keys in LDS by one workgroup of 4 waves.  Wave w
-// owns pairs [w*Q, (w+1)*Q), Q = npad/8.  For compare distances j <= Q those pairs
-// touch only elements [2wQ, 2(w+1)Q), so such stages need no workgroup barrier:
-// LDS operations of one wave complete in order.  Only the 3 stages with j > Q
+// Bitonic sort of npad 64-bit keys in LDS by one workgroup of NW waves.  Wave w
+// owns pairs [w*Q, (w+1)*Q), Q = npad / (2 NW).  For compare distances j <= Q those
+// pairs touch only elements [2wQ, 2(w+1)Q), so such stages need no workgroup barrier:
+// LDS operations of one wave complete in order.  Only the stages with j > Q
 // synchronise the workgroup.
+template <int NW>
 __device__ __forceinline__ void bitonic_sort_lds(uint64_t *keys, int npad, int lane, int wv)
 {
-    const int Q = npad >> 3;
+    const int Q = npad / (2 * NW);
     for (int k = 2; k <= npad; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
             const bool wide = j > Q;
@@ -199,7 +200,8 @@ __global__ __launch_bounds__(kDecayThreads) void decay_hash_kernel(
 // 4096 < S*m <= 16384: the triples are sorted by (node, slot) in LDS (128 KiB of
 // keys); the first triple of every node multiplies that node's factors in ascending
 // slot order and writes the node's score once.  Edge weights come from global memory.
-__global__ __launch_bounds__(256) void decay_sorted_kernel(
+template <int NT>
+__global__ __launch_bounds__(NT) void decay_sorted_kernel(
     float *__restrict__ scores, int P, int count, int npad, const int32_t *__restrict__ nbr,
     const float *__restrict__ nbr_e, float alpha, int signal)
 {
@@ -208,11 +210,11 @@ __global__ __launch_bounds__(256) void decay_sorted_kernel(
     const int32_t *nb = nbr + (long)h * count;
     const float *ne = nbr_e + (long)h * count;
     float *s = scores + (long)h * P;
-    for (int t = tid; t < npad; t += 256)
+    for (int t = tid; t < npad; t += NT)
         keys[t] = t < count ? (((uint64_t)(uint32_t)nb[t] << 32) | (uint32_t)t) : ~0ull;
     __syncthreads();
-    bitonic_sort_lds(keys, npad, lane, wv);
-    for (int t = tid; t < count; t += 256) {
+    bitonic_sort_lds<NT / kWave>(keys, npad, lane, wv);
+    for (int t = tid; t < count; t += NT) {
         const uint64_t key = keys[t];
         const uint32_t node = (uint32_t)(key >> 32);
         if (t > 0 && (uint32_t)(keys[t - 1] >> 32) == node) continue;   // not the first of its node
@@ -342,13 +344,18 @@ hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32
     } else if (npad <= 16384) {
         static bool lds_opt_in = false;   // 128 KiB of dynamic LDS needs a one-time opt-in
         if (npad * 8 > 65536 && !lds_opt_in) {
-            if (hipFuncSetAttribute((const void *)decay_sorted_kernel,
+            if (hipFuncSetAttribute((const void *)decay_sorted_kernel<1024>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 8) != hipSuccess)
                 return hipGetLastError();
             lds_opt_in = true;
         }
-        hipLaunchKernelGGL(decay_sorted_kernel, dim3(Hkv), dim3(256), (size_t)npad * 8, st, scores,
-                           P, (int)count, (int)npad, nbr, nbr_e, alpha, signal);
+        // 16 waves sort 16384 keys four times as fast as 4; 8192 keys are 64 pairs a wave
+        if (npad >= 8192)
+            hipLaunchKernelGGL(decay_sorted_kernel<1024>, dim3(Hkv), dim3(1024), (size_t)npad * 8, st, scores,
+                               P, (int)count, (int)npad, nbr, nbr_e, alpha, signal);
+        else
+            hipLaunchKernelGGL(decay_sorted_kernel<256>, dim3(Hkv), dim3(256), (size_t)npad * 8, st, scores,
+                               P, (int)count, (int)npad, nbr, nbr_e, alpha, signal);
     } else {
         hipLaunchKernelGGL(decay_sequential_kernel, dim3(Hkv), dim3(1024), 0, st, scores, P, S, m,
                            nbr, nbr_e, alpha, signal);
