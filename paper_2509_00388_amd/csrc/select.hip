@@ -365,7 +365,7 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_smallk_kernel(
 
 // ---- rows of any length: every sweep re-reads the row ------------------------
 template <int BLOCK, bool PLAN>
-__global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
+__device__ __forceinline__ void topk_stream_row(
     const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
     float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
     int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
@@ -478,6 +478,155 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
     }
 }
 
+template <int BLOCK, bool PLAN>
+__global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
+    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
+    float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
+    int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
+    typename std::conditional<PLAN, LayerPlan, int>::type plan)
+{
+    topk_stream_row<BLOCK, PLAN>(x, ld, n, k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from,
+                                 append_count, gate, rows_per_gate, plan);
+}
+
+// Long rows, few winners (k <= kSmallK <= BLOCK): two reads of the row instead of five.
+// Every thread takes the maximum of the elements it owns; the k-th largest of those maxima is
+// a lower bound of the row's k-th largest element (k different elements reach it).  The second
+// read collects the few elements that reach the bound into an LDS list, and the exact select
+// (radix select over the list, ties at the cut to the lowest indices, winners ranked by index)
+// runs on that list.  A row with more than kLongCap elements at or above the bound (masses of
+// equal values) goes through the five-read algorithm instead.
+constexpr int kLongCap = 4096;
+
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
+    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld)
+{
+    constexpr int NW = BLOCK / kWave, U = 8;
+    __shared__ uint32_t lk[kLongCap], lj[kLongCap];   // keys and indices of the candidates
+    __shared__ uint32_t tmax[BLOCK];
+    __shared__ uint64_t win[kSmallK];                 // (index << 32) | key of the winners
+    __shared__ uint32_t hist8[256];
+    __shared__ uint32_t s_cnt, s_bin, s_need, s_wmax[NW], s_wmin[NW];
+    __shared__ int32_t n_win, n_eq;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float *xr = x + (long)blockIdx.x * ld;
+    int32_t *out = idx_out + (long)blockIdx.x * idx_ld;
+
+    // first read: the largest key each thread owns (0 is below the key of every number)
+    uint32_t mx = 0u;
+    for (int j0 = 0; j0 < n; j0 += BLOCK * U) {
+        float t[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * BLOCK + tid;
+            t[u] = j < n ? xr[j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (j0 + u * BLOCK + tid < n) mx = max(mx, ord_key(t[u]));
+    }
+    tmax[tid] = mx;
+    uint32_t wmax = mx, wmin = mx;   // the largest and the smallest of the maxima
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        wmax = max(wmax, (uint32_t)__shfl_xor((int)wmax, o, kWave));
+        wmin = min(wmin, (uint32_t)__shfl_xor((int)wmin, o, kWave));
+    }
+    if (lane == 0) { s_wmax[wv] = wmax; s_wmin[wv] = wmin; }
+    if (tid == 0) { s_cnt = 0; n_win = 0; n_eq = 0; }
+    __syncthreads();
+    uint32_t kmax = 0u, kmin = 0xffffffffu;
+#pragma unroll
+    for (int u = 0; u < NW; ++u) { kmax = max(kmax, s_wmax[u]); kmin = min(kmin, s_wmin[u]); }
+
+    // The want-th largest of arr[0 .. count), all keys in [lo, kmax]: radix select over key - lo,
+    // 8 bits a sweep from the top bit in which the keys can differ.  Returns the key and leaves
+    // in `left` how many entries equal to it are among the want largest.
+    auto kth_largest = [&](const uint32_t *arr, int count, uint32_t lo, int want, uint32_t &left) {
+        int remaining = kmax > lo ? 32 - __clz(kmax - lo) : 0;
+        uint32_t prefix = 0, mask = 0, need = (uint32_t)want;
+        while (remaining > 0) {
+            const int bits = remaining < 8 ? remaining : 8;
+            const int shift = remaining - bits;
+            const uint32_t dmask = (1u << bits) - 1u;
+            if (tid < 256) hist8[tid] = 0;
+            __syncthreads();
+            for (int r = tid; r < count; r += BLOCK) {
+                const uint32_t rel = arr[r] - lo;
+                if ((rel & mask) == prefix) atomicAdd(&hist8[(rel >> shift) & dmask], 1u);
+            }
+            __syncthreads();
+            if (wv == 0) find_bin<4>(hist8, need, lane, &s_bin, &s_need);
+            __syncthreads();
+            prefix |= s_bin << shift;
+            mask |= dmask << shift;
+            need = s_need;
+            remaining = shift;
+        }
+        left = need;
+        return lo + prefix;
+    };
+    uint32_t unused;
+    const uint32_t bound = kth_largest(tmax, BLOCK, kmin, k, unused);
+
+    // second read: everything that reaches the bound goes to the list
+    for (int j0 = 0; j0 < n; j0 += BLOCK * U) {
+        float t[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * BLOCK + tid;
+            t[u] = j < n ? xr[j] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * BLOCK + tid;
+            const uint32_t key = ord_key(t[u]);
+            if (j < n && key >= bound) {
+                const uint32_t at = atomicAdd(&s_cnt, 1u);
+                if (at < (uint32_t)kLongCap) { lk[at] = key; lj[at] = (uint32_t)j; }
+            }
+        }
+    }
+    __syncthreads();
+    const int cnt = (int)s_cnt;
+    if (cnt > kLongCap) {   // (the same for every thread)
+        topk_stream_row<BLOCK, false>(x, ld, n, k, idx_out, idx_ld, nullptr, 0, nullptr, 0, 0, nullptr, 1, 0);
+        return;
+    }
+
+    uint32_t need;
+    const uint32_t tau = kth_largest(lk, cnt, bound, k, need);
+    // winners above tau; of the entries equal to tau the `need` lowest indices
+    for (int r = tid; r < cnt; r += BLOCK) {
+        const uint32_t key = lk[r];
+        if (key > tau) win[atomicAdd(&n_win, 1)] = ((uint64_t)lj[r] << 32) | key;
+        else if (key == tau) atomicAdd(&n_eq, 1);
+    }
+    __syncthreads();
+    const int ne = n_eq, base = n_win;
+    __syncthreads();
+    for (int r = tid; r < cnt; r += BLOCK) {
+        if (lk[r] == tau) {
+            const uint32_t mine = lj[r];
+            if (ne == (int)need) {
+                win[atomicAdd(&n_win, 1)] = ((uint64_t)mine << 32) | tau;
+            } else {
+                uint32_t rank = 0;
+                for (int u = 0; u < cnt; ++u) rank += (lk[u] == tau) & (lj[u] < mine);
+                if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | tau;
+            }
+        }
+    }
+    __syncthreads();
+    for (int r = tid; r < k; r += BLOCK) {   // ascending index order
+        const uint64_t mine = win[r];
+        int pos = 0;
+        for (int u = 0; u < k; ++u) pos += win[u] < mine;
+        out[pos] = (int32_t)(mine >> 32);
+    }
+}
+
 template <int BLOCK, bool PLAN, int DIG, typename PlanArg>
 static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
                              long idx_ld, float *val_out, long val_ld, float *tau_out,
@@ -527,6 +676,13 @@ static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, in
     if (n <= 32768)
         return launch_lds<1024, PLAN, 11>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
                                           append_from, append_count, gate, rows_per_gate, plan, st);
+    if constexpr (!PLAN) {
+        if (k <= kSmallK && idx_out && !val_out && !tau_out && append_count == 0 && !gate) {
+            hipLaunchKernelGGL(topk_rows_long_smallk_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, k,
+                               idx_out, idx_ld);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL((topk_rows_stream_kernel<1024, PLAN>), dim3(rows), dim3(1024), 0, st, x, ld, n,
                        k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
                        rows_per_gate, plan);

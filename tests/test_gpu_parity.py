@@ -48,6 +48,30 @@ def test_select_bit_exact(oracle, P, k):
     assert np.array_equal(idx, ref)
 
 
+@pytest.mark.parametrize("P,S", [(70000, 1), (70000, 100), (131008, 128), (40001, 256)])
+def test_sources_of_long_rows_bit_exact(oracle, P, S):
+    """Source selection (Eq. 2) on rows beyond 32768 entries: a bound from per-thread maxima
+    and a short candidate list; a row of masses of equal values overflows the list and takes
+    the general algorithm."""
+    say(f"sources of long rows P={P} S={S}")
+    rng = np.random.default_rng(P + S)
+    w, H, d = 3, 3, 8
+    s = rng.standard_normal((H, P)).astype(np.float32)
+    s[1] = rng.integers(0, 6, size=P).astype(np.float32)          # heavy ties
+    s[2] = np.abs(s[2]) * 1e-6
+    s[2, rng.choice(P, size=300, replace=False)] = 2e-6           # a tie that straddles the cut for S < 300
+    K = rng.standard_normal((H, P + w, d)).astype(np.float32)
+    p = gk.Params(n_kv_heads=H, n_q_heads=H, head_dim=d, n_tokens=P + w, window=w, budget=w + 1,
+                  n_sources=S, n_neighbors=1, rounds=1, dtype=gk.FP32)
+    sd = torch.from_numpy(s.copy()).cuda()
+    src = torch.full((1, H, S), -1, dtype=torch.int32, device="cuda")
+    gk.graphkv_propagate(p, torch.from_numpy(K).cuda(), sd, src, None, None)
+    got = src.cpu().numpy()[0]
+    for h in range(H):
+        want, _ = oracle.topk(s[h].astype(np.float64), S)
+        assert np.array_equal(got[h], want), f"row {h}"
+
+
 # ------------------------------------------------------------------ score ---
 
 @pytest.mark.parametrize("impl", IMPLS)
