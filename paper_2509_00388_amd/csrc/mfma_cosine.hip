@@ -534,6 +534,8 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     }
 }
 
+constexpr int kTieRoom = 64;   // entries tied at the cut that a select lists beyond the m winners
+
 __device__ __forceinline__ uint32_t ord_key_u(uint32_t bits)
 {
     float f = __uint_as_float(bits) + 0.0f;
@@ -568,18 +570,21 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
                                                          SourceReuse ru, int32_t *__restrict__ nbr,
                                                          float *__restrict__ nbr_e)
 {
-    extern __shared__ uint32_t dyn[];
+    extern __shared__ __align__(8) uint32_t dyn[];
     __shared__ uint32_t hist[256];   // 8-bit digits: the lists are short
     __shared__ uint32_t s_bin, s_need, s_min[4], s_max[4];
-    __shared__ int32_t n_win, n_eq;
+    __shared__ int32_t n_win;
     __shared__ int32_t cnt_s[256], s_pos;
     __shared__ uint32_t s_self;
     const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int n_rows = ru.code ? ru.n_new[h] : S;
     if (overflow[h]) return;
+    // Only the edge keys of a list stay in LDS (half the footprint, twice the workgroups per
+    // compute unit); the key indices of the winners, and of entries tied at the cut, are fetched
+    // from the slices again once those are known.
     uint32_t *ek = dyn;                 // [cap] order-preserving edge keys (0 = dropped)
-    uint32_t *kj = dyn + cap;           // [cap] key indices
-    uint64_t *win = reinterpret_cast<uint64_t *>(kj + cap);   // [m] (key index << 32 | edge bits)
+    uint64_t *win = reinterpret_cast<uint64_t *>(dyn + cap + (cap & 1));   // [m + kTieRoom] winners
+    const int win_cap = m + kTieRoom;
 
     // slice sizes (thread c: chunk c), source index and output slot of a row: independent loads
     auto ask = [&](int x, int32_t &cnt_r, int32_t &self_r, int32_t &pos_r) {
@@ -596,7 +601,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     for (int x = blockIdx.x; x < n_rows; x += gridDim.x) {
         const long row = (long)h * S + x;
         cnt_s[tid] = cnt_r;
-        if (tid == 0) { s_self = (uint32_t)self_r; s_pos = pos_r; n_win = 0; n_eq = 0; }
+        if (tid == 0) { s_self = (uint32_t)self_r; s_pos = pos_r; n_win = 0; }
         __syncthreads();
         if (x + (int)gridDim.x < n_rows) ask(x + gridDim.x, cnt_r, self_r, pos_r);
         int n = 0;
@@ -615,7 +620,6 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
             // the source's own column is no neighbour (Eq. 3: j != i): key 0 sorts below every edge
             const uint32_t k = v.y == self ? 0u : ord_key_u(v.x);
             ek[r] = k;
-            kj[r] = v.y;
             if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
         }
 #pragma unroll
@@ -674,37 +678,64 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
             remaining = shift;
         }
         const uint32_t tau = kmin + prefix;
-        // Winners above the threshold go straight to the list (its order is fixed by the
-        // final ranking).  Entries equal to the threshold all win when exactly `need` of
-        // them exist; otherwise the `need` lowest key indices win, found by a scan that
-        // only ties at the cut ever pay for.
+        // Everything that reaches the threshold goes to the list as (entry number, edge bits);
+        // its order is fixed by the final ranking.  More entries equal to the threshold than
+        // the list has room for beyond m: the head is redone densely.
         for (int r = tid; r < n; r += 256) {
             const uint32_t k = ek[r];
-            if (k > tau) win[atomicAdd(&n_win, 1)] = ((uint64_t)kj[r] << 32) | ord_key_inv(k);
-            else if (k == tau && k) atomicAdd(&n_eq, 1);
-        }
-        __syncthreads();
-        const int ne = n_eq, base = n_win;
-        __syncthreads();
-        for (int r = tid; r < n; r += 256) {
-            if (ek[r] == tau && tau) {
-                const uint32_t mine = kj[r];
-                if (ne == (int)need) {
-                    win[atomicAdd(&n_win, 1)] = ((uint64_t)mine << 32) | ord_key_inv(tau);
-                } else {
-                    uint32_t rank = 0;
-                    for (int u = 0; u < n; ++u) rank += (ek[u] == tau) & (kj[u] < mine);
-                    if (rank < need) win[base + rank] = ((uint64_t)mine << 32) | ord_key_inv(tau);
-                }
+            if (k >= tau && k) {
+                const int at = atomicAdd(&n_win, 1);
+                if (at < win_cap) win[at] = ((uint64_t)(uint32_t)r << 32) | ord_key_inv(k);
             }
         }
         __syncthreads();
-        for (int r = tid; r < m; r += 256) {
+        const int listed = n_win;
+        if (listed > win_cap || listed < m) {   // (fewer than m: the list was short of candidates)
+            if (tid == 0) overflow[h] = 1;
+            return;
+        }
+        // the key indices of the listed entries: (key index, edge bits) from here on
+        for (int r = tid; r < listed; r += 256) {
+            const uint64_t w = win[r];
+            int c = 0, local = (int)(w >> 32);
+            while (local >= cnt_s[c]) { local -= cnt_s[c]; ++c; }
+            const uint32_t j = cand[(row * chunks + c) * (long)slice_cap + local].y;
+            win[r] = ((uint64_t)j << 32) | (uint32_t)w;
+        }
+        __syncthreads();
+        if (listed > m) {
+            // Of the entries equal to the threshold only those with the lowest key indices stay:
+            // one that `keep` or more tied entries precede is dropped (it then sorts behind all).
+            const uint32_t tau_bits = ord_key_inv(tau);
+            int n_tied = 0;
+            for (int u = 0; u < listed; ++u) n_tied += (uint32_t)win[u] == tau_bits;
+            const int keep = m - (listed - n_tied);
+            uint32_t drop = 0u;   // bit i: entry tid + 256 i is dropped (written once all have compared)
+            for (int r = tid, i = 0; r < listed; r += 256, ++i) {
+                const uint64_t mine = win[r];
+                if ((uint32_t)mine == tau_bits) {
+                    int before = 0;
+                    for (int u = 0; u < listed; ++u) {
+                        const uint64_t w = win[u];
+                        before += (uint32_t)w == tau_bits && w < mine;
+                    }
+                    if (before >= keep) drop |= 1u << i;
+                }
+            }
+            __syncthreads();
+            for (int r = tid, i = 0; r < listed; r += 256, ++i)
+                if ((drop >> i) & 1u) win[r] = ~0ull;
+            __syncthreads();
+        }
+        // each winner's rank by key index is its place in the output
+        for (int r = tid; r < listed; r += 256) {
             const uint64_t mine = win[r];
-            int pos = 0;
-            for (int u = 0; u < m; ++u) pos += win[u] < mine;
-            nbr[out_row * m + pos] = (int32_t)(mine >> 32);
-            nbr_e[out_row * m + pos] = __uint_as_float((uint32_t)mine);
+            if (mine != ~0ull) {
+                int pos = 0;
+                for (int u = 0; u < listed; ++u) pos += win[u] < mine;
+                nbr[out_row * m + pos] = (int32_t)(mine >> 32);
+                nbr_e[out_row * m + pos] = __uint_as_float((uint32_t)mine);
+            }
         }
         __syncthreads();   // the lists in LDS are free for the next row
     }
@@ -741,8 +772,6 @@ __device__ __forceinline__ uint32_t mth_largest_key(const uint32_t (&E)[R], uint
 // kept, and the winners are ranked by key index.  Lists longer than 64 R, with fewer than
 // m entries, or with more ties at the cut than the list has room for, raise the head's
 // overflow flag (the head is then redone densely).
-constexpr int kTieRoom = 64;
-
 template <int R>
 __global__ __launch_bounds__(256) void nbr_select_wave_kernel(const uint2 *__restrict__ cand,
                                                               const int32_t *__restrict__ cand_cnt,
@@ -1162,7 +1191,7 @@ hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t 
     // sources of a round have lists (most would find nothing to do), many otherwise.
     int per_head = (reuse ? 3072 : 16384) / Hkv;
     per_head = per_head < 1 ? 1 : (per_head > S ? S : per_head);
-    const size_t lds = (size_t)2 * cap * 4 + (size_t)m * 8;
+    const size_t lds = (size_t)(cap + (cap & 1)) * 4 + (size_t)(m + kTieRoom) * 8;
     if (!allow_big_lds((const void *)nbr_select_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(nbr_select_kernel, dim3(per_head, Hkv), dim3(256), lds, st, (const uint2 *)cand,
                        cand_cnt, overflow, src, S, g.chunks, g.slice_cap, cap, m, ru, nbr, nbr_e);

@@ -315,14 +315,15 @@ def test_filtered_neighbourhoods_keys_close_to_many_sources(oracle):
     assert set(nbr[0, 1, a].tolist()) <= set(members.tolist())   # its neighbours are cluster members
 
 
-@pytest.mark.parametrize("n_copies", [5, 100])
-def test_filtered_neighbourhoods_ties_at_the_cut(oracle, n_copies):
+@pytest.mark.parametrize("n_copies,m", [(5, 20), (100, 20), (7, 160), (90, 160)])
+def test_filtered_neighbourhoods_ties_at_the_cut(oracle, n_copies, m):
     """Exact copies of a source's weakest neighbour tie with it at the cut: the lowest key
     indices win (a few ties are settled among the listed candidates, a hundred send the head
-    through the dense block)."""
-    cfg = small_bf16_cfg(n_tokens=10007, n_sources=40, n_neighbors=20, n_kv_heads=2, n_q_heads=8)
+    through the dense block).  m = 20 takes the wave-per-source select, m = 160 (lists of up to
+    2560 candidates) the workgroup-per-source one."""
+    cfg = small_bf16_cfg(n_tokens=10007, n_sources=40, n_neighbors=m, n_kv_heads=2, n_q_heads=8)
     (K, V, Q), _ = util.device_layer(cfg, 9)
-    P, S, m = cfg.n_prefix, 40, 20
+    P, S = cfg.n_prefix, 40
     s0 = synth.random_scores(cfg)
     src0, _ = oracle.topk(s0[0].astype(np.float64), S)
     i = int(src0[0])
