@@ -366,7 +366,7 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_smallk_kernel(
 // ---- rows of any length: every sweep re-reads the row ------------------------
 template <int BLOCK, bool PLAN>
 __device__ __forceinline__ void topk_stream_row(
-    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
+    int row, const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
     float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
     int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
     typename std::conditional<PLAN, LayerPlan, int>::type plan)
@@ -377,13 +377,13 @@ __device__ __forceinline__ void topk_stream_row(
     __shared__ uint32_t s_bin, s_need;
     __shared__ uint32_t w_gt[NW], w_eq[NW];
 
-    if (gate && gate[blockIdx.x / rows_per_gate] == 0) return;
+    if (gate && gate[row / rows_per_gate] == 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const float *xr = x + (long)blockIdx.x * ld;
-    int32_t *out = idx_out ? idx_out + (long)blockIdx.x * idx_ld : nullptr;
-    float *vout = val_out ? val_out + (long)blockIdx.x * val_ld : nullptr;
+    const float *xr = x + (long)row * ld;
+    int32_t *out = idx_out ? idx_out + (long)row * idx_ld : nullptr;
+    float *vout = val_out ? val_out + (long)row * val_ld : nullptr;
     if constexpr (PLAN) {   // per-layer budget: k and the output row come from the plan
-        const int g = blockIdx.x / plan.heads_per_layer, hl = blockIdx.x % plan.heads_per_layer;
+        const int g = row / plan.heads_per_layer, hl = row % plan.heads_per_layer;
         k = plan.budget[g] - append_count;
         out = idx_out + (plan.row_off[g] + (long)hl * plan.budget[g]);
     }
@@ -420,7 +420,7 @@ __device__ __forceinline__ void topk_stream_row(
         need = s_need;
     }
     const uint32_t tau = prefix;
-    if (tau_out && tid == 0) tau_out[blockIdx.x] = key_to_float(tau);
+    if (tau_out && tid == 0) tau_out[row] = key_to_float(tau);
     if (!out) return;
 
     // Each wave owns a contiguous, 64-aligned segment of the row.
@@ -480,13 +480,23 @@ __device__ __forceinline__ void topk_stream_row(
 
 template <int BLOCK, bool PLAN>
 __global__ __launch_bounds__(BLOCK) void topk_rows_stream_kernel(
-    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
+    const float *__restrict__ x, long ld, int n, int rows, int k, int32_t *__restrict__ idx_out, long idx_ld,
     float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
     int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
     typename std::conditional<PLAN, LayerPlan, int>::type plan)
 {
-    topk_stream_row<BLOCK, PLAN>(x, ld, n, k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from,
-                                 append_count, gate, rows_per_gate, plan);
+    // (a gated launch has few workgroups that walk the rows; usually no gate is open at all)
+    if (gate) {
+        const int n_gates = (rows + rows_per_gate - 1) / rows_per_gate;
+        int open = 0;
+        for (int g = threadIdx.x; g < n_gates; g += BLOCK) open |= gate[g] != 0;
+        if (!__syncthreads_or(open)) return;
+    }
+    for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+        topk_stream_row<BLOCK, PLAN>(row, x, ld, n, k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from,
+                                     append_count, gate, rows_per_gate, plan);
+        __syncthreads();
+    }
 }
 
 // Long rows, few winners (k <= kSmallK <= BLOCK): two reads of the row instead of five.
@@ -591,7 +601,8 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
     __syncthreads();
     const int cnt = (int)s_cnt;
     if (cnt > kLongCap) {   // (the same for every thread)
-        topk_stream_row<BLOCK, false>(x, ld, n, k, idx_out, idx_ld, nullptr, 0, nullptr, 0, 0, nullptr, 1, 0);
+        topk_stream_row<BLOCK, false>(blockIdx.x, x, ld, n, k, idx_out, idx_ld, nullptr, 0, nullptr, 0, 0, nullptr,
+                                      1, 0);
         return;
     }
 
@@ -683,9 +694,9 @@ static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, in
             return hipGetLastError();
         }
     }
-    hipLaunchKernelGGL((topk_rows_stream_kernel<1024, PLAN>), dim3(rows), dim3(1024), 0, st, x, ld, n,
-                       k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from, append_count, gate,
-                       rows_per_gate, plan);
+    hipLaunchKernelGGL((topk_rows_stream_kernel<1024, PLAN>), dim3(gate && rows > 1024 ? 1024 : rows), dim3(1024),
+                       0, st, x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out, append_from,
+                       append_count, gate, rows_per_gate, plan);
     return hipGetLastError();
 }
 

@@ -345,10 +345,12 @@ def test_filtered_neighbourhoods_ties_at_the_cut(oracle, n_copies, m):
     assert min(int(spots.min()), weakest) in want and int(max(spots.max(), weakest)) not in want
 
 
-def test_filtered_neighbourhoods_overflow_falls_back(oracle):
+@pytest.mark.parametrize("n_tokens", [12000, 40000])
+def test_filtered_neighbourhoods_overflow_falls_back(oracle, n_tokens):
     """Masses of exactly equal edges defeat any bound: those heads must be redone
-    through the dense block and still give the exact lowest-index answer."""
-    cfg = small_bf16_cfg(n_tokens=12000, n_sources=8, n_neighbors=16, n_kv_heads=2, n_q_heads=8)
+    through the dense block and still give the exact lowest-index answer (edge rows beyond
+    32768 entries take the row top-k that re-reads the row)."""
+    cfg = small_bf16_cfg(n_tokens=n_tokens, n_sources=8, n_neighbors=16, n_kv_heads=2, n_q_heads=8)
     (K, V, Q), _ = util.device_layer(cfg, 1)
     P = cfg.n_prefix
     rng = np.random.default_rng(5)
