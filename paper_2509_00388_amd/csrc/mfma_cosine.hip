@@ -345,11 +345,22 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     unsigned char *kt = smem;
     unsigned char *stage_mem = smem + 2 * kTileBytes;
 
-    // The source groups of a key chunk sit next to each other in the grid: their workgroups run
-    // at about the same time, and the keys the first one pulls from HBM are still in the
-    // memory-side cache when the others ask for them.
+    // The workgroups that stream the same keys (the source groups of a key chunk) should run at
+    // about the same time on the same XCD, so that all but the first find the keys in that XCD's
+    // L2.  Workgroups go to the 8 XCDs round robin in the order of their linear number, so the
+    // groups of one (head, chunk) unit sit 8 apart: 8 units x all their groups take 8 x sgroups
+    // consecutive numbers.  (Unit counts that are no multiple of 8 keep the plain order.)
     const int n_chunks = gridDim.x / fa.sgroups;
-    const int h = blockIdx.y, chunk = blockIdx.x / fa.sgroups, s_base = (blockIdx.x % fa.sgroups) * kRows;
+    int h = blockIdx.y, chunk = blockIdx.x / fa.sgroups, s_base = (blockIdx.x % fa.sgroups) * kRows;
+    if (fa.sgroups > 1 && ((long)gridDim.y * n_chunks) % 8 == 0) {
+        const long lin = (long)blockIdx.y * gridDim.x + blockIdx.x;
+        const long grp8 = lin / (8 * fa.sgroups);
+        const int r = (int)(lin % (8 * fa.sgroups));
+        const long unit = grp8 * 8 + (r & 7);
+        h = (int)(unit / n_chunks);
+        chunk = (int)(unit % n_chunks);
+        s_base = (r >> 3) * kRows;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, grp = wv >> 2;
     const uint16_t *Kh = Kc + (long)h * N * kD;

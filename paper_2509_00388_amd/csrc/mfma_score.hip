@@ -54,6 +54,29 @@ __device__ __forceinline__ void load_queries(const uint16_t *Qb, int l32, int hh
 // 256 registers, two waves share a SIMD, and one wave's exp2 work overlaps the
 // other's MFMAs.
 
+// Which (head, chunk, part) a workgroup takes.  The parts of a key chunk stream the same keys
+// and should run at about the same time on the same XCD, so that all but the first find the
+// keys in that XCD's L2.  Workgroups go to the 8 XCDs round robin in the order of their linear
+// number, so the parts of one (head, chunk) unit sit 8 apart: 8 units x their parts take
+// 8 x nparts consecutive numbers.  (Unit counts that are no multiple of 8 keep the plain order,
+// parts next to each other.)
+__device__ __forceinline__ void unit_of_workgroup(int nparts, int &h, int &chunk, int &part)
+{
+    const int nchunks = gridDim.x / nparts;
+    h = blockIdx.y;
+    chunk = blockIdx.x / nparts;
+    part = blockIdx.x % nparts;
+    if (nparts > 1 && ((long)gridDim.y * nchunks) % 8 == 0) {
+        const long lin = (long)blockIdx.y * gridDim.x + blockIdx.x;
+        const long grp8 = lin / (8 * nparts);
+        const int r = (int)(lin % (8 * nparts));
+        const long unit = grp8 * 8 + (r & 7);
+        h = (int)(unit / nchunks);
+        chunk = (int)(unit % nchunks);
+        part = r >> 3;
+    }
+}
+
 // ---------------------------------------------------------------- pass A ---
 template <int NB, int SPLIT>
 __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
@@ -63,11 +86,11 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
     constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
     __shared__ float sm[4][R], sz[4][R];
-    // nparts > 1: equal parts of 128 rows share one launch, the parts of a key chunk next to
-    // each other in the grid, so that the keys one part pulls from HBM are still in the
-    // memory-side cache when the next part asks for them
-    const int h = blockIdx.y, chunk = blockIdx.x / nparts, nchunks = gridDim.x / nparts;
-    row_base += 128 * (blockIdx.x % nparts);
+    // nparts > 1: equal parts of 128 rows share one launch
+    int h, chunk, row_part;
+    unit_of_workgroup(nparts, h, chunk, row_part);
+    const int nchunks = gridDim.x / nparts;
+    row_base += 128 * row_part;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, row0 = (wv >> 2) * NBW * kBlk;   // first query row of this wave
 
@@ -178,9 +201,10 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
     __shared__ float bias_s[R];
-    const int h = blockIdx.y, chunk = blockIdx.x / nparts;
-    row_base += 128 * (blockIdx.x % nparts);
-    vote_row_base += SPLIT * (blockIdx.x % nparts);
+    int h, chunk, row_part;
+    unit_of_workgroup(nparts, h, chunk, row_part);
+    row_base += 128 * row_part;
+    vote_row_base += SPLIT * row_part;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, grp = wv >> 2, row0 = grp * NBW * kBlk;
 
