@@ -181,24 +181,43 @@ def gather(Kc, Vc, dtype: str, idx: np.ndarray):
 
 def compress(Kc, Vc, Qw, dtype: str, pool_kernel: int, budget: int, S: int, m: int, T: int,
              alpha: float = 1.0, reselect: int = 1, signal: int = 0, pool_mode: int = 0,
-             scale: float = 0.0, edge_mode: int = 0):
-    """The whole pass for one layer.  Returns a dict: Kout, Vout, idx, scores
-    (s^(T), float64), s0 (float64), min_gap (source cut, neighbour cut, final cut).
-    edge_mode: 0 key-key edges, 1 key-value, 2 value-value."""
-    _check_storage(Kc, dtype); _check_storage(Vc, dtype); _check_storage(Qw, dtype)
+             scale: float = 0.0, edge_mode: int = 0, scorer: int = 0, window: Optional[int] = None):
+    """The whole pass for one layer.  Returns a dict: Kout, Vout, idx, scores (s^(T),
+    float64), s0 (float64); what was picked per round, src [T,H,S] and nbr [T,H,S,m]; the
+    relative gap at every cut, gap_src [T,H], gap_nbr [T,H,S], gap_final [H]; and min_gap =
+    their minima (source cut, neighbour cut, final cut).
+    edge_mode: 0 key-key edges, 1 key-value, 2 value-value.
+    scorer: 0 observation-window attention score, 1 KNorm (Qw may then be None and
+    `window` gives w)."""
+    _check_storage(Kc, dtype); _check_storage(Vc, dtype)
     Hkv, N, d = Kc.shape
-    Hq, w, _ = Qw.shape
+    if Qw is not None:
+        _check_storage(Qw, dtype)
+        Hq, w, _ = Qw.shape
+    elif scorer == 1 and window is not None:
+        Hq, w = Hkv, int(window)          # KNorm reads no queries
+    else:
+        raise ValueError("Qw is required unless scorer=1 and window is given")
     P = N - w
+    Tn = max(T, 1)
     Kout = np.empty((Hkv, budget, d), dtype=Kc.dtype)
     Vout = np.empty((Hkv, budget, d), dtype=Vc.dtype)
     idx = np.empty((Hkv, budget), dtype=np.int32)
     sc = np.empty((Hkv, P), dtype=np.float64)
     s0 = np.empty((Hkv, P), dtype=np.float64)
-    mg = np.empty(3, dtype=np.float64)
+    src = np.zeros((Tn, Hkv, max(S, 1)), dtype=np.int32)
+    nbr = np.zeros((Tn, Hkv, max(S, 1), max(m, 1)), dtype=np.int32)
+    gs = np.full((Tn, Hkv), np.inf)
+    gn = np.full((Tn, Hkv, max(S, 1)), np.inf)
+    gf = np.full(Hkv, np.inf)
     rc = lib().gkv_oracle_compress(
-        _p(Kc), _p(Vc), _p(Qw), _i(_DT[dtype]), _i(Hkv), _i(Hq), _i(d), _i(N), _i(w),
-        _i(pool_kernel), _i(pool_mode), _d(scale), _i(budget), _i(S), _i(m), _i(T), _d(alpha),
-        _i(reselect), _i(signal), _i(edge_mode), _p(Kout), _p(Vout), _p(idx), _p(sc), _p(s0), _p(mg))
+        _p(Kc), _p(Vc), _p(Qw), _i(_DT[dtype]), _i(Hkv), _i(Hq), _i(d), _i(N),
+        _i(w), _i(pool_kernel), _i(pool_mode), _d(scale), _i(budget), _i(S), _i(m), _i(T), _d(alpha),
+        _i(reselect), _i(signal), _i(edge_mode), _i(scorer), _p(Kout), _p(Vout), _p(idx), _p(sc), _p(s0),
+        _p(src), _p(nbr), _p(gs), _p(gn), _p(gf))
     if rc:
         raise ValueError("gkv_oracle_compress rejected the arguments")
-    return dict(Kout=Kout, Vout=Vout, idx=idx, scores=sc, s0=s0, min_gap=mg)
+    src, nbr, gs, gn = src[:T], nbr[:T], gs[:T], gn[:T]
+    mg = np.array([gs.min() if T > 0 else np.inf, gn.min() if T > 0 else np.inf, gf.min()])
+    return dict(Kout=Kout, Vout=Vout, idx=idx, scores=sc, s0=s0, src=src, nbr=nbr,
+                gap_src=gs, gap_nbr=gn, gap_final=gf, min_gap=mg)

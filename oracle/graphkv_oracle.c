@@ -66,6 +66,19 @@
  *       0 key-key, 1 key-value, 2 value-value (pairings with queries need the
  *       prefix tokens' queries, which the pass does not receive; the two-tensor
  *       propagate takes any pair).
+ *   R15 KNorm as the indicator that initialises the nodes (Sparse Graph Building,
+ *       first paragraph; Baseline Methods: "L2 norm of keys"): that method keeps
+ *       the keys of small norm, so s_j = -||k_j|| (scorer 1 of the whole-pass
+ *       function; no queries are needed).
+ *   R16 Scores of either sign.  Eq. 4 / Eq. 5 are written for a non-negative
+ *       indicator; multiplied into a negative score, (1 - alpha e) would RAISE
+ *       it, against what "Decay Signal Propagation" says the signal does
+ *       (the decay "reduc[es] the scores of redundant tokens", in proportion
+ *       to the similarity).  Reading: the change of Eq. 4 is taken on the
+ *       magnitude, s_j' = s_j - alpha e_ij |s_j|, i.e. the factor of Eq. 5 is
+ *       (1 - alpha e) for s_j >= 0 and (1 + alpha e) for s_j < 0, the sign being
+ *       that of the score at the start of the round; the enhanced signal mirrors
+ *       it.  For s_j >= 0 this is Eq. 4 / Eq. 5 as printed.
  *
  * Arithmetic: every product, sum, exp, sqrt and division is done in double on
  * the exact values of the stored fp32/bf16 inputs.  No blocking, no fusion.
@@ -73,8 +86,10 @@
  * Pins (tests, CPU only): brute force on a dense P x P cosine matrix for tiny
  * P; T = 0 / alpha = 0 reducing to plain top-(B-w); closed forms for zero
  * queries; softmax re-derived with a library routine; orthogonal keys; exact
- * duplicates; scale invariance; a hand-worked 6-node example.  The choice
- * among the readings R2, R6, R7, R8 cannot be pinned by the paper:
+ * duplicates; scale invariance; a hand-worked 6-node example (also with negative
+ * scores); Eq. 4 iterated source by source on negative scores; the decay of -s
+ * mirroring the enhanced signal on s; the value of the reported cut gaps.  The
+ * choice among the readings R2, R6, R7, R8, R15, R16 cannot be pinned by the paper:
  * "parity unpinned" for those beyond agreement under the stated reading.
  */
 #include <math.h>
@@ -280,7 +295,7 @@ void gkv_oracle_cosine_row(const void *Kc, int dtype, int32_t d, int32_t N,
  *   dbg_src [T,Hkv,S], dbg_nbr [T,Hkv,S,m], dbg_e [T,Hkv,S,m] (optional):
  *     what was picked, ascending index order (R13), and the edge weights.
  *   gap_src [T,Hkv], gap_nbr [T,Hkv,S] (optional): relative gaps at the cuts.
- * signal: 0 decay (Eq. 5), 1 enhanced, 2 evicted (R12).
+ * signal: 0 decay (Eq. 5), 1 enhanced, 2 evicted (R12); negative scores: R16.
  * A, Bm: the tensors whose rows enter Eq. 1 for the source and for the other
  *   node (R14).
  */
@@ -341,8 +356,10 @@ int gkv_oracle_propagate_edges(const void *A, const void *Bm, int dtype, int32_t
                     const int32_t j = nbr[(size_t)a * m + u];
                     const double e = ev[(size_t)a * m + u];
                     hit[j] = 1;
-                    if (signal == 1) f[j] *= (1.0 + alpha * e);
-                    else             f[j] *= (1.0 - alpha * e);
+                    /* R16: the signal acts on the magnitude of the score the round
+                     * started with: decay lowers it, the enhanced signal raises it */
+                    const double dir = ((signal == 1) != (sh[j] < 0.0)) ? 1.0 : -1.0;
+                    f[j] *= (1.0 + dir * alpha * e);
                 }
             for (int32_t j = 0; j < P; ++j) {
                 if (!hit[j]) continue;
@@ -405,42 +422,40 @@ int gkv_oracle_gather(const void *Kc, const void *Vc, int dtype, int32_t Hkv,
 
 /*
  * The whole pass for one layer: stage I -> T rounds of II+III -> IV.
+ * scorer: 0 the observation-window attention score (R8), 1 KNorm (R15; Qw unused).
  * scores_out (optional) [Hkv,P] double: the refined scores s^(T).
  * s0_out (optional) [Hkv,P] double: the initial scores.
- * min_gap (optional) [3]: the smallest relative gap met at the source cut, the
- * neighbour cut and the final cut over all heads and rounds.
+ * What was picked and how close every cut was (all optional):
+ *   src_out [T,Hkv,S], nbr_out [T,Hkv,S,m]: sources and neighbour lists per round;
+ *   gap_src [T,Hkv], gap_nbr [T,Hkv,S], gap_final [Hkv]: the relative gap between
+ *   the last entry kept and the first one dropped at the source cut, at each
+ *   source's neighbour cut and at the final cut (see gkv_oracle_topk).
  */
 int gkv_oracle_compress(const void *Kc, const void *Vc, const void *Qw, int dtype,
                         int32_t Hkv, int32_t Hq, int32_t d, int32_t N, int32_t w,
                         int32_t pool_kernel, int32_t pool_mode, double scale,
                         int32_t B, int32_t S, int32_t m, int32_t T, double alpha,
-                        int32_t reselect, int32_t signal, int32_t edge_mode,
+                        int32_t reselect, int32_t signal, int32_t edge_mode, int32_t scorer,
                         void *Kout, void *Vout, int32_t *idx,
-                        double *scores_out, double *s0_out, double *min_gap)
+                        double *scores_out, double *s0_out,
+                        int32_t *src_out, int32_t *nbr_out,
+                        double *gap_src, double *gap_nbr, double *gap_final)
 {
     const int32_t P = N - w;
     if (P < 1 || B <= w || B > N) return -1;
+    if (scorer != 0 && scorer != 1) return -1;
     double *s = (double *)malloc((size_t)Hkv * P * sizeof(double));
-    double *gs = (double *)malloc((size_t)(T > 0 ? T : 1) * Hkv * sizeof(double));
-    double *gn = (double *)malloc((size_t)(T > 0 ? T : 1) * Hkv * (S > 0 ? S : 1) * sizeof(double));
-    double *gf = (double *)malloc((size_t)Hkv * sizeof(double));
-    int rc = gkv_oracle_score(Kc, Qw, dtype, Hkv, Hq, d, N, w, pool_kernel, pool_mode, scale, s, NULL);
+    int rc = scorer == 1
+        ? gkv_oracle_score_knorm(Kc, dtype, Hkv, d, N, w, s)
+        : gkv_oracle_score(Kc, Qw, dtype, Hkv, Hq, d, N, w, pool_kernel, pool_mode, scale, s, NULL);
     if (rc == 0 && s0_out) memcpy(s0_out, s, (size_t)Hkv * P * sizeof(double));
     if (rc == 0 && T > 0)
         rc = gkv_oracle_propagate_edges(edge_mode == 2 ? Vc : Kc, edge_mode == 0 ? Kc : Vc, dtype,
                                         Hkv, d, N, w, S, m, T, alpha, reselect, signal,
-                                        s, NULL, NULL, NULL, NULL, gs, gn);
-    if (rc == 0) rc = gkv_oracle_select(s, Hkv, N, w, B, idx, gf);
+                                        s, NULL, src_out, nbr_out, NULL, gap_src, gap_nbr);
+    if (rc == 0) rc = gkv_oracle_select(s, Hkv, N, w, B, idx, gap_final);
     if (rc == 0) rc = gkv_oracle_gather(Kc, Vc, dtype, Hkv, d, N, B, idx, Kout, Vout);
     if (rc == 0 && scores_out) memcpy(scores_out, s, (size_t)Hkv * P * sizeof(double));
-    if (rc == 0 && min_gap) {
-        min_gap[0] = min_gap[1] = min_gap[2] = INFINITY;
-        if (T > 0) {
-            for (size_t i = 0; i < (size_t)T * Hkv; ++i) if (gs[i] < min_gap[0]) min_gap[0] = gs[i];
-            for (size_t i = 0; i < (size_t)T * Hkv * S; ++i) if (gn[i] < min_gap[1]) min_gap[1] = gn[i];
-        }
-        for (int32_t h = 0; h < Hkv; ++h) if (gf[h] < min_gap[2]) min_gap[2] = gf[h];
-    }
-    free(s); free(gs); free(gn); free(gf);
+    free(s);
     return rc;
 }

@@ -51,10 +51,14 @@ def propagate_dense(K, s, S, m, T, alpha=1.0, reselect=1, signal=0, other=None):
             if signal == 2:
                 new[j] = -np.inf
                 continue
-            f = 1.0
-            for i in hit:                                             # Eq. 5
-                f *= (1.0 + alpha * E[i, j]) if signal == 1 else (1.0 - alpha * E[i, j])
-            new[j] = s[j] * f
+            # Eq. 4, one source after the other: the change is alpha * e_ij times the size of the
+            # score, taken away by the decay signal and added by the enhanced one.  For a score
+            # that is not negative this is Eq. 5's product of (1 - alpha e_ij).
+            v = s[j]
+            for i in hit:
+                step = alpha * E[i, j] * abs(v)
+                v = v + step if signal == 1 else v - step
+            new[j] = v
         s = new
     return s
 

@@ -56,6 +56,36 @@ def test_topk_matches_stable_argsort(oracle):
         assert idx.tolist() == sorted(bf.stable_topk(x, k))
 
 
+def test_topk_reports_the_relative_gap_at_the_cut(oracle):
+    """The gap every excused index mismatch rests on: (last kept - first dropped) / |last kept|."""
+    _, gap = oracle.topk(np.array([4.0, 3.0, 2.0, 1.0]), 2)
+    assert gap == pytest.approx(1.0 / 3.0, rel=1e-15)             # (3 - 2) / 3
+    _, gap = oracle.topk(np.array([1.0, 4.0, 2.0, 3.0]), 2)        # order of the entries is irrelevant
+    assert gap == pytest.approx(1.0 / 3.0, rel=1e-15)
+    _, gap = oracle.topk(np.array([10.0, 9.99]), 1)
+    assert gap == pytest.approx(0.001, rel=1e-12)
+    # a negative last-kept value: the gap stays positive, relative to its magnitude
+    idx, gap = oracle.topk(np.array([-1.0, -4.0, -2.0, -8.0]), 2)
+    assert idx.tolist() == [0, 2] and gap == pytest.approx(1.0, rel=1e-15)     # (-2 - -4) / 2
+    _, gap = oracle.topk(np.array([5.0, -1.0, -3.0]), 2)
+    assert gap == pytest.approx(2.0, rel=1e-15)                    # (-1 - -3) / 1
+    # the skipped index takes no part in the cut
+    _, gap = oracle.topk(np.array([9.0, 4.0, 3.0, 2.0]), 1, skip=0)
+    assert gap == pytest.approx(0.25, rel=1e-15)                   # (4 - 3) / 4
+    # the gaps a propagation reports are these very numbers
+    cfg = tiny_cfg(dtype="bf16")
+    K, V, Q = synth.make_layer(cfg, 3)
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    _, dbg = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 1, debug=True)
+    for h in range(cfg.n_kv_heads):
+        srt = np.sort(s0[h])[::-1]
+        assert dbg["gap_src"][0, h] == pytest.approx((srt[3] - srt[4]) / srt[3], rel=1e-14)
+        for a, i in enumerate(dbg["src"][0, h]):
+            e = np.delete(oracle.cosine_row(K, "bf16", cfg.window, h, int(i)), int(i))
+            srt = np.sort(e)[::-1]
+            assert dbg["gap_nbr"][0, h, a] == pytest.approx((srt[2] - srt[3]) / abs(srt[2]), rel=1e-13)
+
+
 # ---------------------------------------------------------------- stage I ---
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
@@ -166,8 +196,8 @@ def test_hand_worked_example(oracle):
     K = np.concatenate([keys, np.ones((1, 2), np.float32)])[None]      # one window token
     rows = [l.split() for l in open(os.path.join(GOLD, "hand_worked_6node.txt"))
             if l.strip() and not l.startswith("#")]
-    assert len(rows) == 3
-    for r in rows:
+    assert len(rows) == 4
+    for r in rows[:3]:
         S, m = int(r[1]), int(r[2])
         want = np.array([float(x) for x in r[3:9]])
         keep = [int(x) for x in r[9:12]]
@@ -175,6 +205,15 @@ def test_hand_worked_example(oracle):
         np.testing.assert_allclose(s[0], want, rtol=0, atol=1e-12)
         idx, _ = oracle.select(s, 7, 1, 4)
         assert idx[0].tolist() == keep + [6]
+    # negative scores: the decay takes alpha * e * |s| away (the factor is 1 + e)
+    r = rows[3]
+    assert r[0] == "neg"
+    sneg = np.array([[-1.0, -0.1, -0.8, -0.5, -0.45, -0.7]])
+    s, dbg = oracle.propagate(K, "fp32", 1, sneg, int(r[1]), int(r[2]), 1, alpha=1.0, debug=True)
+    assert dbg["src"][0, 0].tolist() == [1] and dbg["nbr"][0, 0, 0].tolist() == [2, 5]
+    np.testing.assert_allclose(s[0], [float(x) for x in r[3:9]], rtol=0, atol=1e-12)
+    idx, _ = oracle.select(s, 7, 1, 5)
+    assert idx[0].tolist() == [int(x) for x in r[9:13]] + [6]
     # the edge weights themselves (case iii: e01 = 0.8, e15 = 1.0)
     s, dbg = oracle.propagate(K, "fp32", 1, s0, 2, 1, 1, debug=True)
     assert dbg["src"][0, 0].tolist() == [0, 1]
@@ -210,6 +249,42 @@ def test_bruteforce_with_ties(oracle):
         s = oracle.propagate(K, "fp32", 2, s0, S, m, T, 0.5, 1, 0)
         ref = bf.propagate_dense(keys.astype(np.float64), s0[0], S, m, T, 0.5, 1, 0)
         np.testing.assert_allclose(s[0], ref, rtol=1e-12)
+
+
+@pytest.mark.parametrize("signal", [0, 1, 2])
+@pytest.mark.parametrize("sign", ["negative", "mixed"])
+def test_negative_scores_equal_iterated_eq4(oracle, signal, sign):
+    """Scores below zero (an indicator such as minus the key norm): Eq. 4 applied source by
+    source on the magnitude of the score, on the dense graph."""
+    cfg = tiny_cfg(dtype="bf16", n_tokens=48, window=6)
+    K, _, _ = synth.make_layer(cfg, 7)
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    if sign == "negative":
+        s0 = -s0
+    else:
+        s0 = s0 - np.median(s0)
+    for (S, m, T, alpha, reselect) in [(4, 3, 1, 1.0, 1), (5, 6, 3, 0.6, 1), (6, 9, 2, 0.9, 0)]:
+        s = oracle.propagate(K, "bf16", cfg.window, s0, S, m, T, alpha, reselect, signal)
+        for h in range(cfg.n_kv_heads):
+            ref = bf.propagate_dense(f64(K[h], "bf16")[:cfg.n_prefix], s0[h], S, m, T, alpha,
+                                     reselect, signal)
+            np.testing.assert_allclose(s[h], ref, rtol=1e-12, atol=0)
+
+
+def test_decay_of_negated_scores_mirrors_the_enhanced_signal(oracle):
+    """With the sources held fixed, decaying -s is the mirror image of enhancing s: both
+    move a node by alpha * e * |s| away from zero.  And with all edges positive no negative
+    score rises under the decay (the property the reading of negative scores is there for)."""
+    cfg = tiny_cfg(dtype="fp32", n_kv_heads=1, n_q_heads=1)
+    K, _, _ = synth.make_layer(cfg, 4)
+    K = np.abs(K)                                             # all cosines >= 0
+    s0 = synth.random_scores(cfg).astype(np.float64)
+    src = np.sort(np.random.default_rng(5).choice(cfg.n_prefix, size=(2, 1, 4), replace=False), axis=2)
+    src = src.astype(np.int32)
+    up = oracle.propagate(K, "fp32", cfg.window, s0, 4, 3, 2, 0.7, signal=1, forced_src=src)
+    down = oracle.propagate(K, "fp32", cfg.window, -s0, 4, 3, 2, 0.7, signal=0, forced_src=src)
+    assert np.array_equal(down, -up)
+    assert (down <= -s0).all() and np.count_nonzero(down != -s0) > 0
 
 
 def test_fixed_graph_closed_form_and_T1_equivalence(oracle):
@@ -338,12 +413,39 @@ def test_compress_is_the_staged_pipeline(oracle):
     K, V, Q = synth.make_layer(cfg, 6)
     out = oracle.compress(K, V, Q, "bf16", cfg.pool_kernel, cfg.budget, 4, 3, 2, alpha=0.9)
     s0 = oracle.score(K, Q, "bf16", cfg.pool_kernel)
-    sT = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 2, 0.9)
+    sT, dbg = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 2, 0.9, debug=True)
     idx, gap = oracle.select(sT, cfg.n_tokens, cfg.window, cfg.budget)
     Ko, Vo = oracle.gather(K, V, "bf16", idx)
     assert np.array_equal(out["scores"], sT) and np.array_equal(out["idx"], idx)
     assert np.array_equal(out["Kout"], Ko) and np.array_equal(out["Vout"], Vo)
-    assert out["min_gap"][2] == gap.min()
+    # what was picked and the gap at every cut are those of the stages
+    assert np.array_equal(out["src"], dbg["src"]) and np.array_equal(out["nbr"], dbg["nbr"])
+    assert np.array_equal(out["gap_src"], dbg["gap_src"]) and np.array_equal(out["gap_nbr"], dbg["gap_nbr"])
+    assert np.array_equal(out["gap_final"], gap)
+    assert out["min_gap"].tolist() == [dbg["gap_src"].min(), dbg["gap_nbr"].min(), gap.min()]
+
+
+@pytest.mark.parametrize("signal", [0, 2])
+def test_compress_with_knorm_scorer_is_the_staged_pipeline(oracle, signal):
+    """Key-norm indicator (Baseline Methods) -> propagation -> selection -> gather; the
+    queries take no part."""
+    cfg = tiny_cfg(dtype="bf16")
+    K, V, Q = synth.make_layer(cfg, 6)
+    out = oracle.compress(K, V, None, "bf16", cfg.pool_kernel, cfg.budget, 4, 3, 2, alpha=0.9,
+                          signal=signal, scorer=1, window=cfg.window)
+    s0 = oracle.score_knorm(K, "bf16", cfg.window)
+    assert (s0 < 0).all() and np.array_equal(out["s0"], s0)
+    sT = oracle.propagate(K, "bf16", cfg.window, s0, 4, 3, 2, 0.9, signal=signal)
+    idx, gap = oracle.select(sT, cfg.n_tokens, cfg.window, cfg.budget)
+    assert np.array_equal(out["scores"], sT) and np.array_equal(out["idx"], idx)
+    assert np.array_equal(out["Kout"], oracle.gather(K, V, "bf16", idx)[0])
+    same = oracle.compress(K, V, Q, "bf16", cfg.pool_kernel, cfg.budget, 4, 3, 2, alpha=0.9,
+                           signal=signal, scorer=1)
+    assert np.array_equal(same["idx"], idx)
+    # the lowest key norms are the sources of the first round (Eq. 2 on this indicator)
+    norms = np.linalg.norm(f64(K, "bf16")[:, :cfg.n_prefix], axis=2)
+    for h in range(cfg.n_kv_heads):
+        assert out["src"][0, h].tolist() == sorted(np.argsort(norms[h], kind="stable")[:4].tolist())
 
 
 # ---- edges between two different tensors (Discussion, "Exploration of similarity
