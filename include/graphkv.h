@@ -10,8 +10,11 @@
  *   - All tensor pointers are DEVICE pointers, contiguous, row-major with the
  *     head dimension innermost, 16-byte aligned.  The params struct and the
  *     returned strings live on the HOST.
- *   - The caller owns every buffer.  The library allocates nothing, keeps no
- *     state between calls, never synchronises and never copies to the host.
+ *   - The caller owns every buffer.  The library allocates nothing, never
+ *     synchronises and never copies to the host.  It keeps no state between calls
+ *     except which kernels have had their one-time opt-in to large shared memory
+ *     (process-wide, guarded by a mutex: first calls may come from several host
+ *     threads) and the measurement aid at the end of this header.
  *     All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream).  Inputs are read-only unless stated otherwise.
  *   - `ws` is scratch memory of at least graphkv_workspace_bytes(params) bytes,
@@ -65,6 +68,10 @@ enum { GRAPHKV_IMPL_AUTO = 0, GRAPHKV_IMPL_GENERIC = 1 };
  * with queries need the prefix tokens' queries, which these calls do not
  * receive: graphkv_propagate_edges takes any two tensors. */
 enum { GRAPHKV_EDGES_KK = 0, GRAPHKV_EDGES_KV = 1, GRAPHKV_EDGES_VV = 2 };
+/* Indicator that initialises the node scores in the whole-pass calls ("Sparse Graph
+ * Building", first paragraph: attention-based scores or KNorm): ATTENTION is
+ * graphkv_score, KNORM is graphkv_score_knorm (the queries are not read). */
+enum { GRAPHKV_SCORER_ATTENTION = 0, GRAPHKV_SCORER_KNORM = 1 };
 
 typedef struct graphkv_params {
     int32_t n_kv_heads;    /* H_kv >= 1                                              */
@@ -88,6 +95,7 @@ typedef struct graphkv_params {
     int32_t signal;        /* GRAPHKV_SIGNAL_*                                       */
     int32_t impl;          /* GRAPHKV_IMPL_*                                         */
     int32_t edges;         /* GRAPHKV_EDGES_* (compress calls only)                  */
+    int32_t scorer;        /* GRAPHKV_SCORER_* (compress calls only)                 */
 } graphkv_params;
 
 /* Bytes of scratch any of the calls below needs for these params (0 if the
@@ -113,7 +121,8 @@ int32_t graphkv_score(const graphkv_params *p, const void *Kc, const void *Qw,
 /*
  * KNorm-style initial score, another indicator the paper plugs GraphKV into
  * (Baseline Methods: "L2 norm of keys"): scores[h, j] = -||k_j||, so that the
- * low-norm keys that method keeps rank highest.
+ * low-norm keys that method keeps rank highest.  The scores are negative: see
+ * graphkv_propagate for what the signal does to them.
  */
 int32_t graphkv_score_knorm(const graphkv_params *p, const void *Kc, float *scores,
                             void *ws, size_t ws_bytes, void *stream);
@@ -128,6 +137,12 @@ int32_t graphkv_score_knorm(const graphkv_params *p, const void *Kc, float *scor
  * in ascending source index (Eq. 4, Eq. 5, Alg. 2).  Ties in either top-k go
  * to the lowest index; a zero-norm key has e = 0.  rounds = 0, or decay = 0
  * with a multiplicative signal, leaves scores untouched.
+ * Scores of either sign: Eq. 4 / Eq. 5 are written for a non-negative indicator.
+ * The signal acts on the magnitude of the score a round starts with, s_j' = s_j -
+ * alpha e_ij |s_j| (Eq. 4), so that the decay lowers a negative score too, as
+ * "Decay Signal Propagation" says it should (it reduces the scores of redundant
+ * tokens); the factor of Eq. 5 is then (1 + alpha e_ij) for s_j < 0.  The enhanced
+ * signal mirrors this.
  *   Kc      [H_kv, N, d]       in
  *   scores  [H_kv, P]          in/out  fp32
  *   dbg_src [T, H_kv, S]       out, optional (NULL): sources, ascending
@@ -171,7 +186,9 @@ int32_t graphkv_select(const graphkv_params *p, const float *scores, int32_t *id
  *   Kout, Vout [H_kv, B, d]  out  rows idx[h, t] of Kc / Vc, byte copies
  *   idx        [H_kv, B]     out  int32
  *   scores_out [H_kv, P]     out, optional (NULL): refined scores s^(T), fp32
- * B = N gives the identity copy.  p->edges picks the tensors behind the edges.
+ * B = N gives the identity copy.  p->edges picks the tensors behind the edges,
+ * p->scorer the indicator of stage I (with GRAPHKV_SCORER_KNORM Qw is not read and
+ * may be NULL, and n_q_heads, pool_* and softmax_scale are ignored).
  */
 int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc,
                          const void *Qw, void *Kout, void *Vout, int32_t *idx,
@@ -208,8 +225,8 @@ const char *graphkv_strerror(int32_t code);
  * Measurement aid (not part of the method): per-kernel timing with HIP events.
  * Between graphkv_profile_begin() and graphkv_profile_end() every kernel the
  * library launches is bracketed by two events on the caller's stream (the event
- * pool is created on first use and kept; this is the one piece of process-wide
- * state, and it is not thread-safe).  graphkv_profile_end() waits for the
+ * pool is created on first use and kept; process-wide: one recording at a time,
+ * begin and end from one host thread).  graphkv_profile_end() waits for the
  * recorded events and adds up, per kernel id, the elapsed milliseconds into
  * ms[GRAPHKV_N_KERNELS] and the number of launches into launches[...] (HOST
  * arrays, either may be NULL).

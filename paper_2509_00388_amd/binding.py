@@ -22,6 +22,7 @@ POOL_AVG, POOL_MAX = 0, 1
 SIGNAL_DECAY, SIGNAL_ENHANCED, SIGNAL_EVICTED = 0, 1, 2
 IMPL_AUTO, IMPL_GENERIC = 0, 1
 EDGES_KK, EDGES_KV, EDGES_VV = 0, 1, 2
+SCORER_ATTENTION, SCORER_KNORM = 0, 1
 
 EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "graphkv_propagate",
            "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma",
@@ -43,7 +44,7 @@ class _CParams(ctypes.Structure):
         ("n_sources", ctypes.c_int32), ("n_neighbors", ctypes.c_int32), ("rounds", ctypes.c_int32),
         ("decay", ctypes.c_float), ("reselect", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float), ("signal", ctypes.c_int32), ("impl", ctypes.c_int32),
-        ("edges", ctypes.c_int32),
+        ("edges", ctypes.c_int32), ("scorer", ctypes.c_int32),
     ]
 
 
@@ -68,6 +69,7 @@ class Params:
     signal: int = SIGNAL_DECAY
     impl: int = IMPL_AUTO
     edges: int = EDGES_KK
+    scorer: int = SCORER_ATTENTION
 
     @property
     def n_prefix(self) -> int:
@@ -136,11 +138,21 @@ def _check(rc: int):
         raise GraphKVError(f"graphkv error {rc}: {graphkv_strerror(rc)}")
 
 
-def _ptr(t: Optional[torch.Tensor]):
+def _arg(t: Optional[torch.Tensor], name: str, dtype, numel: int, optional: bool = False):
+    """Device address of a tensor argument after checking what the library itself cannot see:
+    that it lives on the GPU, is contiguous, has the element type the call expects and holds at
+    least `numel` elements (a short or mistyped buffer would make the kernels read or write out
+    of bounds)."""
     if t is None:
-        return None
-    if not t.is_cuda or not t.is_contiguous():
-        raise GraphKVError("tensors must be contiguous device tensors")
+        if optional:
+            return None
+        raise GraphKVError(f"{name} is required")
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+        raise GraphKVError(f"{name} must be a contiguous device tensor")
+    if t.dtype != dtype:
+        raise GraphKVError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if t.numel() < numel:
+        raise GraphKVError(f"{name} holds {t.numel()} elements, the call needs {numel}")
     return t.data_ptr()
 
 
@@ -165,14 +177,40 @@ def alloc_workspace(p: Params, device="cuda") -> torch.Tensor:
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
+def _ws(p: Params, ws, device, n_layers: int = 0):
+    """(address, bytes) of the workspace: the caller's, or a fresh one of the right size."""
+    need = graphkv_workspace_bytes_batched(p, n_layers) if n_layers else graphkv_workspace_bytes(p)
+    if need == 0:
+        raise GraphKVError("invalid params: workspace size is 0")
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+    return _arg(ws, "ws", torch.uint8, need), ws.numel(), ws
+
+
+def _kv_numel(p: Params, layers: int = 1) -> int:
+    return layers * p.n_kv_heads * p.n_tokens * p.head_dim
+
+
+def _q_numel(p: Params, layers: int = 1) -> int:
+    return layers * p.n_q_heads * p.window * p.head_dim
+
+
+def _dbg_args(p: Params, dbg_src, dbg_nbr, dbg_e):
+    T, n_src = max(p.rounds, 0), p.n_kv_heads * p.n_sources
+    return (_arg(dbg_src, "dbg_src", torch.int32, T * n_src, optional=True),
+            _arg(dbg_nbr, "dbg_nbr", torch.int32, T * n_src * p.n_neighbors, optional=True),
+            _arg(dbg_e, "dbg_e", torch.float32, T * n_src * p.n_neighbors, optional=True))
+
+
 def graphkv_score(p: Params, Kc, Qw, scores=None, ws=None):
     """scores [H_kv, P] fp32 (allocated if None).  Stage I."""
     if scores is None:
         scores = torch.empty((p.n_kv_heads, p.n_prefix), dtype=torch.float32, device=Kc.device)
-    ws = alloc_workspace(p, Kc.device) if ws is None else ws
+    wp, wn, ws = _ws(p, ws, Kc.device)
     cp = p.c()
-    _check(load_library().graphkv_score(ctypes.byref(cp), _ptr(Kc), _ptr(Qw), _ptr(scores),
-                                        _ptr(ws), ws.numel(), _stream()))
+    _check(load_library().graphkv_score(
+        ctypes.byref(cp), _arg(Kc, "Kc", p.torch_dtype, _kv_numel(p)), _arg(Qw, "Qw", p.torch_dtype, _q_numel(p)),
+        _arg(scores, "scores", torch.float32, p.n_kv_heads * p.n_prefix), wp, wn, _stream()))
     return scores
 
 
@@ -180,28 +218,32 @@ def graphkv_score_knorm(p: Params, Kc, scores=None, ws=None):
     if scores is None:
         scores = torch.empty((p.n_kv_heads, p.n_prefix), dtype=torch.float32, device=Kc.device)
     cp = p.c()
-    _check(load_library().graphkv_score_knorm(ctypes.byref(cp), _ptr(Kc), _ptr(scores),
-                                              _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
+    _check(load_library().graphkv_score_knorm(
+        ctypes.byref(cp), _arg(Kc, "Kc", p.torch_dtype, _kv_numel(p)),
+        _arg(scores, "scores", torch.float32, p.n_kv_heads * p.n_prefix),
+        _arg(ws, "ws", torch.uint8, 0, optional=True), ws.numel() if ws is not None else 0, _stream()))
     return scores
 
 
 def graphkv_propagate(p: Params, Kc, scores, dbg_src=None, dbg_nbr=None, dbg_e=None, ws=None):
     """Refines `scores` [H_kv, P] fp32 in place.  Stages II and III."""
-    ws = alloc_workspace(p, Kc.device) if ws is None else ws
+    wp, wn, ws = _ws(p, ws, Kc.device)
     cp = p.c()
-    _check(load_library().graphkv_propagate(ctypes.byref(cp), _ptr(Kc), _ptr(scores), _ptr(dbg_src),
-                                            _ptr(dbg_nbr), _ptr(dbg_e), _ptr(ws), ws.numel(),
-                                            _stream()))
+    _check(load_library().graphkv_propagate(
+        ctypes.byref(cp), _arg(Kc, "Kc", p.torch_dtype, _kv_numel(p)),
+        _arg(scores, "scores", torch.float32, p.n_kv_heads * p.n_prefix),
+        *_dbg_args(p, dbg_src, dbg_nbr, dbg_e), wp, wn, _stream()))
     return scores
 
 
 def graphkv_propagate_edges(p: Params, Ac, Bc, scores, dbg_src=None, dbg_nbr=None, dbg_e=None, ws=None):
     """The same rounds with edges cos(Ac[h, i], Bc[h, j]) (source's row from Ac)."""
-    ws = alloc_workspace(p, Ac.device) if ws is None else ws
+    wp, wn, ws = _ws(p, ws, Ac.device)
     cp = p.c()
-    _check(load_library().graphkv_propagate_edges(ctypes.byref(cp), _ptr(Ac), _ptr(Bc), _ptr(scores),
-                                                  _ptr(dbg_src), _ptr(dbg_nbr), _ptr(dbg_e), _ptr(ws),
-                                                  ws.numel(), _stream()))
+    _check(load_library().graphkv_propagate_edges(
+        ctypes.byref(cp), _arg(Ac, "Ac", p.torch_dtype, _kv_numel(p)), _arg(Bc, "Bc", p.torch_dtype, _kv_numel(p)),
+        _arg(scores, "scores", torch.float32, p.n_kv_heads * p.n_prefix),
+        *_dbg_args(p, dbg_src, dbg_nbr, dbg_e), wp, wn, _stream()))
     return scores
 
 
@@ -210,13 +252,16 @@ def graphkv_select(p: Params, scores, idx=None, ws=None):
     if idx is None:
         idx = torch.empty((p.n_kv_heads, p.budget), dtype=torch.int32, device=scores.device)
     cp = p.c()
-    _check(load_library().graphkv_select(ctypes.byref(cp), _ptr(scores), _ptr(idx), _ptr(ws),
-                                         ws.numel() if ws is not None else 0, _stream()))
+    _check(load_library().graphkv_select(
+        ctypes.byref(cp), _arg(scores, "scores", torch.float32, p.n_kv_heads * p.n_prefix),
+        _arg(idx, "idx", torch.int32, p.n_kv_heads * max(p.budget, 0)),
+        _arg(ws, "ws", torch.uint8, 0, optional=True), ws.numel() if ws is not None else 0, _stream()))
     return idx
 
 
 def graphkv_compress(p: Params, Kc, Vc, Qw, Kout=None, Vout=None, idx=None, scores_out=None, ws=None):
-    """The whole pass for one layer.  Returns (Kout, Vout, idx)."""
+    """The whole pass for one layer.  Returns (Kout, Vout, idx).  Qw may be None with
+    scorer = SCORER_KNORM."""
     dev = Kc.device
     shape = (p.n_kv_heads, p.budget, p.head_dim)
     if Kout is None:
@@ -225,11 +270,17 @@ def graphkv_compress(p: Params, Kc, Vc, Qw, Kout=None, Vout=None, idx=None, scor
         Vout = torch.empty(shape, dtype=Vc.dtype, device=dev)
     if idx is None:
         idx = torch.empty((p.n_kv_heads, p.budget), dtype=torch.int32, device=dev)
-    ws = alloc_workspace(p, dev) if ws is None else ws
+    wp, wn, ws = _ws(p, ws, dev)
     cp = p.c()
-    _check(load_library().graphkv_compress(ctypes.byref(cp), _ptr(Kc), _ptr(Vc), _ptr(Qw), _ptr(Kout),
-                                           _ptr(Vout), _ptr(idx), _ptr(scores_out), _ptr(ws),
-                                           ws.numel(), _stream()))
+    n_out = p.n_kv_heads * max(p.budget, 0)
+    knorm = p.scorer == SCORER_KNORM
+    _check(load_library().graphkv_compress(
+        ctypes.byref(cp), _arg(Kc, "Kc", p.torch_dtype, _kv_numel(p)), _arg(Vc, "Vc", p.torch_dtype, _kv_numel(p)),
+        _arg(Qw, "Qw", p.torch_dtype, 0 if knorm else _q_numel(p), optional=knorm),
+        _arg(Kout, "Kout", p.torch_dtype, n_out * p.head_dim), _arg(Vout, "Vout", p.torch_dtype, n_out * p.head_dim),
+        _arg(idx, "idx", torch.int32, n_out),
+        _arg(scores_out, "scores_out", torch.float32, p.n_kv_heads * p.n_prefix, optional=True),
+        wp, wn, _stream()))
     return Kout, Vout, idx
 
 
@@ -245,22 +296,28 @@ def graphkv_compress_batched(p: Params, n_layers: int, budgets, Kc, Vc, Qw, Kout
     packed layer after layer: Kout, Vout [sum_l H_kv * B_l, d], idx [sum_l H_kv * B_l].
     Returns (Kout, Vout, idx)."""
     dev = Kc.device
-    bl = list(budgets) if budgets is not None else [p.budget] * n_layers
-    assert len(bl) == n_layers
-    rows = p.n_kv_heads * sum(bl)
+    bl = [int(b) for b in budgets] if budgets is not None else [p.budget] * n_layers
+    if len(bl) != n_layers or n_layers < 1:
+        raise GraphKVError("one budget per layer is required")
+    rows = p.n_kv_heads * sum(max(b, 0) for b in bl)
     if Kout is None:
         Kout = torch.empty((rows, p.head_dim), dtype=Kc.dtype, device=dev)
     if Vout is None:
         Vout = torch.empty((rows, p.head_dim), dtype=Vc.dtype, device=dev)
     if idx is None:
         idx = torch.empty((rows,), dtype=torch.int32, device=dev)
-    if ws is None:
-        ws = torch.empty(graphkv_workspace_bytes_batched(p, n_layers), dtype=torch.uint8, device=dev)
+    wp, wn, ws = _ws(p, ws, dev, n_layers)
     cp = p.c()
     carr = (ctypes.c_int32 * n_layers)(*bl) if budgets is not None else None
-    _check(load_library().graphkv_compress_batched(ctypes.byref(cp), n_layers, carr, _ptr(Kc), _ptr(Vc),
-                                                   _ptr(Qw), _ptr(Kout), _ptr(Vout), _ptr(idx),
-                                                   _ptr(scores_out), _ptr(ws), ws.numel(), _stream()))
+    knorm = p.scorer == SCORER_KNORM
+    _check(load_library().graphkv_compress_batched(
+        ctypes.byref(cp), n_layers, carr,
+        _arg(Kc, "Kc", p.torch_dtype, _kv_numel(p, n_layers)), _arg(Vc, "Vc", p.torch_dtype, _kv_numel(p, n_layers)),
+        _arg(Qw, "Qw", p.torch_dtype, 0 if knorm else _q_numel(p, n_layers), optional=knorm),
+        _arg(Kout, "Kout", p.torch_dtype, rows * p.head_dim), _arg(Vout, "Vout", p.torch_dtype, rows * p.head_dim),
+        _arg(idx, "idx", torch.int32, rows),
+        _arg(scores_out, "scores_out", torch.float32, n_layers * p.n_kv_heads * p.n_prefix, optional=True),
+        wp, wn, _stream()))
     return Kout, Vout, idx
 
 

@@ -4,6 +4,8 @@
 #include "kernels.hpp"
 
 #include <math.h>
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 namespace {
@@ -61,6 +63,7 @@ bool base_ok(const graphkv_params *p)
     if (p->rounds < 0) return false;
     if (p->signal < 0 || p->signal > 2) return false;
     if (p->edges < GRAPHKV_EDGES_KK || p->edges > GRAPHKV_EDGES_VV) return false;
+    if (p->scorer != GRAPHKV_SCORER_ATTENTION && p->scorer != GRAPHKV_SCORER_KNORM) return false;
     if (!(p->decay >= 0.f && p->decay <= 1.f)) return false;
     if (p->reselect != 0 && p->reselect != 1) return false;
     if (p->rounds > 0) {
@@ -115,7 +118,8 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes > 0 ? bytes : 1); return o; };
     const size_t rows = (size_t)D.Hq * D.w;
-    const bool scoring = p->n_q_heads >= p->n_kv_heads && p->pool_kernel >= 1;
+    const bool scoring = p->scorer == GRAPHKV_SCORER_ATTENTION && p->n_q_heads >= p->n_kv_heads &&
+                         p->pool_kernel >= 1;
     W.logits = take(!D.mfma_score && scoring ? rows * D.N * 4 : 0);
     W.row_max = take(rows * 4);
     W.row_sum = take(rows * 4);
@@ -155,10 +159,12 @@ int32_t check_ws(const Workspace &W, const void *ws, size_t ws_bytes)
 
 // ---- optional per-kernel timing (graphkv_profile_begin / _end) ----------------
 // While profiling is on, every kernel launch is bracketed by two HIP events on
-// the caller's stream.  Process-wide and not thread-safe: a measurement aid.
+// the caller's stream.  Process-wide (one recording at a time, whichever host thread
+// launches); the records are guarded by a mutex.
 struct ProfRec { int id; hipEvent_t e0, e1; };
 struct Profiler {
-    bool on = false;
+    std::atomic<bool> on{false};
+    std::mutex mu;
     std::vector<hipEvent_t> pool;
     size_t used = 0;
     std::vector<ProfRec> recs;
@@ -183,13 +189,16 @@ const char *const kKernelNames[GRAPHKV_N_KERNELS] = {
 #define GKV_LAUNCH(id, expr)                                              \
     do {                                                                  \
         hipEvent_t e0_ = nullptr, e1_ = nullptr;                          \
-        if (g_prof.on) {                                                  \
+        const bool prof_ = g_prof.on.load(std::memory_order_relaxed);     \
+        if (prof_) {                                                      \
+            std::lock_guard<std::mutex> lock_(g_prof.mu);                 \
             e0_ = g_prof.next();                                          \
             e1_ = g_prof.next();                                          \
             if (e0_ && e1_) (void)hipEventRecord(e0_, st);                \
         }                                                                 \
         const hipError_t err_ = (expr);                                   \
-        if (g_prof.on && e0_ && e1_) {                                    \
+        if (prof_ && e0_ && e1_) {                                        \
+            std::lock_guard<std::mutex> lock_(g_prof.mu);                 \
             (void)hipEventRecord(e1_, st);                                \
             g_prof.recs.push_back({(id), e0_, e1_});                      \
         }                                                                 \
@@ -363,7 +372,10 @@ int32_t run_compress(const graphkv_params *p, int n_layers, const int32_t *budge
     int max_budget = 0;
     const LayerPlan plan = make_plan(p, n_layers, budgets, &max_budget);
     float *scores = scores_out ? scores_out : at<float>(ws, W.scores);
-    if (int32_t rc = run_score(p, D, W, Kc, Qw, scores, ws, st)) return rc;
+    if (p->scorer == GRAPHKV_SCORER_KNORM)
+        GKV_LAUNCH(GRAPHKV_K_KNORM, launch_knorm(Kc, p->dtype, D.H, D.d, D.N, D.P, scores, st));
+    else if (int32_t rc = run_score(p, D, W, Kc, Qw, scores, ws, st))
+        return rc;
     const void *edge_src = p->edges == GRAPHKV_EDGES_VV ? Vc : Kc;
     const void *edge_nbr = p->edges == GRAPHKV_EDGES_KK ? Kc : Vc;
     if (int32_t rc = run_propagate(p, D, W, edge_src, edge_nbr, scores, nullptr, nullptr, nullptr, ws, st))
@@ -474,9 +486,11 @@ int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, cons
                                  void *Vout, int32_t *idx, float *scores_out, void *ws,
                                  size_t ws_bytes, void *stream)
 {
-    if (!base_ok(p) || !score_ok(p) || n_layers < 1) return GRAPHKV_EINVAL;
+    if (!base_ok(p) || n_layers < 1) return GRAPHKV_EINVAL;
+    const bool knorm = p->scorer == GRAPHKV_SCORER_KNORM;   // reads no queries: Qw may be NULL
+    if (!knorm && !score_ok(p)) return GRAPHKV_EINVAL;
     if (!budgets_ok(p, n_layers, budgets)) return GRAPHKV_EINVAL;
-    if (!aligned16(Kc) || !aligned16(Vc) || !aligned16(Qw) || !aligned16(Kout) ||
+    if (!aligned16(Kc) || !aligned16(Vc) || (!knorm && !aligned16(Qw)) || !aligned16(Kout) ||
         !aligned16(Vout) || !aligned4(idx))
         return GRAPHKV_EINVAL;
     if (scores_out && !aligned4(scores_out)) return GRAPHKV_EINVAL;
@@ -495,7 +509,7 @@ int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, cons
         const int32_t *bl = budgets ? budgets + l0 : nullptr;
         const int32_t rc = run_compress(
             p, nl, bl, (const char *)Kc + l0 * kv_layer, (const char *)Vc + l0 * kv_layer,
-            (const char *)Qw + l0 * q_layer, (char *)Kout + out_rows * p->head_dim * esize,
+            Qw ? (const char *)Qw + l0 * q_layer : nullptr, (char *)Kout + out_rows * p->head_dim * esize,
             (char *)Vout + out_rows * p->head_dim * esize, idx + out_rows,
             scores_out ? scores_out + l0 * s_layer : nullptr, ws, st);
         if (rc) return rc;
@@ -506,6 +520,7 @@ int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, cons
 
 int32_t graphkv_profile_begin(void)
 {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
     g_prof.used = 0;
     g_prof.recs.clear();
     g_prof.on = true;
@@ -515,6 +530,7 @@ int32_t graphkv_profile_begin(void)
 int32_t graphkv_profile_end(double *ms, int64_t *launches)
 {
     g_prof.on = false;
+    std::lock_guard<std::mutex> lock(g_prof.mu);
     for (int i = 0; i < GRAPHKV_N_KERNELS; ++i) {
         if (ms) ms[i] = 0.0;
         if (launches) launches[i] = 0;

@@ -8,6 +8,12 @@
 
 namespace gkv {
 
+// Kernels that use more than 64 KiB of dynamic LDS need a one-time opt-in per kernel and
+// device.  Which (device, kernel) pairs have it is the library's only state besides the
+// measurement aid; it is process-wide and guarded by a mutex, so first calls may come from
+// several host threads at once.  Returns false if the opt-in failed.
+bool allow_big_lds(const void *kernel, int bytes = 160 * 1024 - 8192);
+
 // ---- selection (select.hip) -------------------------------------------------
 // For each of `rows` rows of x (row r starts at x + r*ld, n entries): the k
 // entries that come first by (value descending, index ascending), written in

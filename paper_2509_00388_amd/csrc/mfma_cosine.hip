@@ -26,7 +26,6 @@
 #include "mfma_tile.hpp"
 
 #include <math.h>
-#include <unordered_set>
 
 namespace gkv {
 
@@ -1021,18 +1020,6 @@ __global__ __launch_bounds__(256) void match_sources_kernel(const int32_t *__res
             nbr_e[(row0 + a) * m + r] = prev_e[(row0 + from) * m + r];
         }
     }
-}
-
-// Kernels that use more than 64 KiB of dynamic LDS need a one-time opt-in per kernel.
-bool allow_big_lds(const void *kernel)
-{
-    static std::unordered_set<const void *> done;   // host-side, filled on first use of each kernel
-    if (done.count(kernel)) return true;
-    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 8192) !=
-        hipSuccess)
-        return false;
-    done.insert(kernel);
-    return true;
 }
 
 // Columns per workgroup: about 1024 workgroups in flight over all heads and source

@@ -20,7 +20,6 @@
 #include "kernels.hpp"
 #include "mfma_tile.hpp"
 
-#include <unordered_set>
 
 namespace gkv {
 
@@ -301,18 +300,6 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
             votes[(long)h * P + k0 + o] = acc / taps / div;
         }
     }
-}
-
-// Kernels that use more than 64 KiB of dynamic LDS need a one-time opt-in per kernel.
-bool allow_big_lds(const void *kernel)
-{
-    static std::unordered_set<const void *> done;   // host-side, filled on first use of each kernel
-    if (done.count(kernel)) return true;
-    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 8192) !=
-        hipSuccess)
-        return false;
-    done.insert(kernel);
-    return true;
 }
 
 // Keys per workgroup: about 1024 workgroups in flight over all heads, but at least

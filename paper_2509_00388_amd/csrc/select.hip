@@ -646,15 +646,10 @@ static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, in
 {
     const int items = (n + BLOCK - 1) / BLOCK;
     const size_t lds = ((size_t)items * BLOCK + 2 * (size_t)items * (BLOCK / kWave)) * 4;
-    static bool opt_in = false;   // more than 64 KiB of dynamic LDS needs a one-time opt-in
-    if (lds > 65536 && !opt_in) {
-        if (hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK, PLAN, DIG, false>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess ||
-            hipFuncSetAttribute((const void *)topk_rows_lds_kernel<BLOCK, PLAN, DIG, true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 140 * 1024) != hipSuccess)
-            return hipGetLastError();
-        opt_in = true;
-    }
+    if (lds > 65536 &&    // more than 64 KiB of dynamic LDS needs a one-time opt-in
+        (!allow_big_lds((const void *)topk_rows_lds_kernel<BLOCK, PLAN, DIG, false>, 140 * 1024) ||
+         !allow_big_lds((const void *)topk_rows_lds_kernel<BLOCK, PLAN, DIG, true>, 140 * 1024)))
+        return hipGetLastError();
     if (gate)
         hipLaunchKernelGGL((topk_rows_lds_kernel<BLOCK, PLAN, DIG, true>), dim3(rows > 1024 ? 1024 : rows),
                            dim3(BLOCK), lds, st, x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld,

@@ -3,7 +3,25 @@
 #include "common.hpp"
 #include "kernels.hpp"
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 namespace gkv {
+
+bool allow_big_lds(const void *kernel, int bytes)
+{
+    static std::mutex mu;
+    static std::set<std::pair<int, const void *>> done;   // (device, kernel) pairs that are opted in
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({dev, kernel})) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        return false;
+    done.insert({dev, kernel});
+    return true;
+}
 
 // scores[h, j] = (1/div) * sum_g pool(votes[h*Gv + g, j-half .. j+half]).
 // Average pooling pads with zeros and divides by the kernel size; max pooling
@@ -64,9 +82,13 @@ __global__ __launch_bounds__(256) void pool_avg_kernel(const float *__restrict__
     }
 }
 
-__device__ __forceinline__ float signal_factor(float e, float alpha, int signal)
+// Factor of one edge (Eq. 4 / Eq. 5).  The signal acts on the magnitude of the score the
+// round started with: the decay takes alpha * e * |s| away, the enhanced signal adds it, so
+// for a negative score (an indicator such as minus the key norm) the signs swap and the
+// decay still lowers the score.  For s >= 0 this is (1 - alpha e) as printed.
+__device__ __forceinline__ float signal_factor(float e, float alpha, int signal, bool negative)
 {
-    return signal == 1 ? fmaf(alpha, e, 1.0f) : fmaf(-alpha, e, 1.0f);
+    return ((signal == 1) != negative) ? fmaf(alpha, e, 1.0f) : fmaf(-alpha, e, 1.0f);
 }
 
 // Bitonic sort of npad 64-bit keys in LDS by one workgroup of NW waves.  Wave w
@@ -130,7 +152,14 @@ __global__ __launch_bounds__(kDecayThreads) void decay_hash_kernel(
     for (int q = 0; q < kDecayPer; ++q) {
         const int t = q * kDecayThreads + tid;
         node[q] = t < count ? (uint32_t)nb[t] : kNoNode;
-        fac[q] = t < count ? signal_factor(ne[t], alpha, signal) : 1.0f;
+        fac[q] = t < count ? ne[t] : 0.f;
+    }
+    // the sign of each node's score decides the direction of its factors; these loads are in
+    // flight while the table is set up
+#pragma unroll
+    for (int q = 0; q < kDecayPer; ++q) {
+        const float sj = node[q] != kNoNode ? s[node[q]] : 0.f;
+        fac[q] = node[q] != kNoNode ? signal_factor(fac[q], alpha, signal, sj < 0.f) : 1.0f;
     }
     for (int i = tid; i < Tn; i += kDecayThreads) {
         cell_node[i] = kNoNode;
@@ -219,13 +248,14 @@ __global__ __launch_bounds__(NT) void decay_sorted_kernel(
         const uint32_t node = (uint32_t)(key >> 32);
         if (t > 0 && (uint32_t)(keys[t - 1] >> 32) == node) continue;   // not the first of its node
         if (signal == 2) { s[node] = -INFINITY; continue; }
+        const float sj = s[node];
         float f = 1.0f;
         for (int u = t; u < count; ++u) {
             const uint64_t ku = keys[u];
             if ((uint32_t)(ku >> 32) != node) break;
-            f *= signal_factor(ne[(uint32_t)ku], alpha, signal);
+            f *= signal_factor(ne[(uint32_t)ku], alpha, signal, sj < 0.f);
         }
-        s[node] *= f;
+        s[node] = sj * f;
     }
 }
 
@@ -259,17 +289,19 @@ __global__ __launch_bounds__(1024) void decay_sequential_kernel(
         }
         if (!first) continue;
         if (signal == 2) { s[j] = -INFINITY; continue; }
-        float f = signal_factor(ne[t], alpha, signal);
+        const float sj = s[j];
+        const bool neg = sj < 0.f;
+        float f = signal_factor(ne[t], alpha, signal, neg);
         for (int b = a + 1; b < S; ++b) {
             int lo = 0, hi = m - 1;
             while (lo <= hi) {
                 const int mid = (lo + hi) >> 1;
                 const int32_t v = nb[(long)b * m + mid];
-                if (v == j) { f *= signal_factor(ne[(long)b * m + mid], alpha, signal); break; }
+                if (v == j) { f *= signal_factor(ne[(long)b * m + mid], alpha, signal, neg); break; }
                 if (v < j) lo = mid + 1; else hi = mid - 1;
             }
         }
-        s[j] *= f;
+        s[j] = sj * f;
     }
 }
 
@@ -332,23 +364,13 @@ hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32
         int table_log2 = 10;
         while ((1L << table_log2) < 2 * count) ++table_log2;
         const size_t lds = ((size_t)16) << table_log2;
-        static bool hash_opt_in = false;
-        if (lds > 65536 && !hash_opt_in) {
-            if (hipFuncSetAttribute((const void *)decay_hash_kernel,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 16) != hipSuccess)
-                return hipGetLastError();
-            hash_opt_in = true;
-        }
+        if (lds > 65536 && !allow_big_lds((const void *)decay_hash_kernel, 8192 * 16)) return hipGetLastError();
         hipLaunchKernelGGL(decay_hash_kernel, dim3(Hkv), dim3(kDecayThreads), lds, st, scores, P,
                            (int)count, table_log2, nbr, nbr_e, alpha, signal);
     } else if (npad <= 16384) {
-        static bool lds_opt_in = false;   // 128 KiB of dynamic LDS needs a one-time opt-in
-        if (npad * 8 > 65536 && !lds_opt_in) {
-            if (hipFuncSetAttribute((const void *)decay_sorted_kernel<1024>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 8) != hipSuccess)
-                return hipGetLastError();
-            lds_opt_in = true;
-        }
+        // 128 KiB of dynamic LDS
+        if (npad * 8 > 65536 && !allow_big_lds((const void *)decay_sorted_kernel<1024>, 16384 * 8))
+            return hipGetLastError();
         // 16 waves sort 16384 keys four times as fast as 4; 8192 keys are 64 pairs a wave
         if (npad >= 8192)
             hipLaunchKernelGGL(decay_sorted_kernel<1024>, dim3(Hkv), dim3(1024), (size_t)npad * 8, st, scores,

@@ -17,3 +17,16 @@ def oracle():
     import oracle as orc
     orc.lib()
     return orc
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Lists the heads whose retained set differed from the oracle's at a near-tie and was
+    accepted (layer, head, the cut that differed first, the oracle's gap there)."""
+    try:
+        from tests import util
+    except Exception:
+        return
+    if util.EXCUSED:
+        terminalreporter.write_line(f"index mismatches accepted at near-ties: {len(util.EXCUSED)}")
+        for case in util.EXCUSED:
+            terminalreporter.write_line(f"  {case}")

@@ -1,8 +1,11 @@
 """GPU parity tests: the HIP path, called through the C ABI, against the CPU
 oracle on the same seeded inputs.  Integer results (retained indices, sources,
-gathered bytes) must match bit for bit; scores within 2e-3 relative.  Where a
-retained set differs, the oracle's own gap at one of the three cuts must be
-below that tolerance, and the case is printed."""
+gathered bytes) must match bit for bit; scores within 2e-3 relative.  Where the
+retained set of a head differs, the first cut of THAT head at which the GPU's
+picks leave the oracle's must be one where the oracle's own relative gap is
+below that tolerance, everything after it must be a valid run on the GPU's own
+upstream values (tests/util.py: judge_layer), and the case is recorded in
+util.EXCUSED, which the terminal summary lists."""
 import numpy as np
 import pytest
 import torch
@@ -48,11 +51,14 @@ def test_select_bit_exact(oracle, P, k):
     assert np.array_equal(idx, ref)
 
 
-@pytest.mark.parametrize("P,S", [(70000, 1), (70000, 100), (131008, 128), (40001, 256)])
+@pytest.mark.parametrize("P,S", [(70000, 1), (70000, 100), (131008, 128), (40001, 256),
+                                 (4097, 64), (10000, 64), (32736, 64), (32736, 96), (32768, 256), (5000, 1)])
 def test_sources_of_long_rows_bit_exact(oracle, P, S):
-    """Source selection (Eq. 2) on rows beyond 32768 entries: a bound from per-thread maxima
-    and a short candidate list; a row of masses of equal values overflows the list and takes
-    the general algorithm."""
+    """Source selection (Eq. 2) with few winners out of a long row.  Rows of 4097 to 32768
+    entries (the benchmark's: 32736) keep the keys in registers; rows beyond 32768 entries take
+    a bound from per-thread maxima and a short candidate list.  Row 1 is masses of equal values
+    (overflows every short list, takes the general algorithm), row 2 has a 300-way tie that
+    straddles the cut."""
     say(f"sources of long rows P={P} S={S}")
     rng = np.random.default_rng(P + S)
     w, H, d = 3, 3, 8
@@ -219,12 +225,20 @@ def test_propagate_multi_round(oracle, impl, reselect):
         s1, _, _, _ = run_propagate(p1, Kd, s0)
         f = s1.astype(np.float64) / s0
         np.testing.assert_allclose(sT, s0 * f ** T, rtol=1e-5)
-    ref = oracle.propagate(K, "bf16", cfg.window, s0.astype(np.float64), cfg.n_sources,
-                           cfg.n_neighbors, T, 0.8, reselect)
-    close = np.isclose(sT, ref, rtol=util.REL_TOL, atol=0)
-    say(f"  multi-round reselect={reselect}: {np.count_nonzero(~close)} of {close.size} scores "
-        "outside tolerance of the chained oracle (near-tie cascades)")
-    assert np.count_nonzero(~close) <= 4 * cfg.n_neighbors
+    # against the oracle's own T rounds: a head whose picks equal the oracle's in every round has
+    # all its scores within tolerance; a head may leave the oracle's picks only at a cut whose
+    # gap (the oracle's) is below the tolerance, and is then judged by the staged checks above
+    ref, dbg = oracle.propagate(K, "bf16", cfg.window, s0.astype(np.float64), cfg.n_sources,
+                                cfg.n_neighbors, T, 0.8, reselect, debug=True)
+    for h in range(cfg.n_kv_heads):
+        first = util.first_divergence(dict(src=dbg["src"], nbr=dbg["nbr"], gap_src=dbg["gap_src"],
+                                           gap_nbr=dbg["gap_nbr"], gap_final=np.full(cfg.n_kv_heads, np.inf)),
+                                      dict(src=list(src), nbr=list(nbr)), h)
+        if first[0] == "final":          # no cut differed
+            util.assert_scores_close(sT[h], ref[h], f"head {h}: scores after {T} rounds")
+        else:
+            say(f"  multi-round reselect={reselect} head {h}: picks leave the oracle's at {first}")
+            assert first[3] < util.REL_TOL, f"head {h}: picks differ at a cut that is no near-tie: {first}"
 
 
 @pytest.mark.parametrize("impl", IMPLS)
@@ -485,14 +499,9 @@ def test_compress_edge_modes(oracle, impl, edges):
     V2d = gk.to_device(V2, gk.BF16)
     p = util.params_from_cfg(cfg, 8, impl=impl, rounds=2, edges=edges)
     out, sc = run_compress(p, (Kd, V2d, Qd))
-    ref = oracle.compress(K, V2, Q, "bf16", p.pool_kernel, p.budget, p.n_sources, p.n_neighbors, 2,
-                          edge_mode=edges)
-    diffs = util.compare_end_to_end(out, ref, K, V2, cfg.window)
-    if diffs:
-        say(f"  retained sets differ on heads {diffs}; oracle's smallest gaps {ref['min_gap']}")
-        assert ref["min_gap"].min() < util.REL_TOL
-    else:
-        util.assert_scores_close(sc, ref["scores"], "refined scores")
+    ref = oracle_compress(oracle, (K, V2, Q), p, "bf16")
+    util.compare_end_to_end(out, ref, K, V2, cfg.window)
+    util.judge_layer(oracle, p, (K, V2, Q), (Kd, V2d, Qd), ref, out[2], sc, layer=8, excused=util.EXCUSED)
     # the pairing matters: key-key edges give another result on this input
     out_kk, _ = run_compress(util.params_from_cfg(cfg, 8, impl=impl, rounds=2), (Kd, V2d, Qd))
     assert not np.array_equal(out_kk[2], out[2])
@@ -510,9 +519,18 @@ def test_invalid_edges_value_is_rejected():
 def run_compress(p, dev, want_scores=True):
     Kd, Vd, Qd = dev
     sc = torch.empty((p.n_kv_heads, p.n_prefix), dtype=torch.float32, device="cuda") if want_scores else None
-    Kout, Vout, idx = gk.graphkv_compress(p, Kd, Vd, Qd, scores_out=sc)
+    Kout, Vout, idx = gk.graphkv_compress(p, Kd, Vd, Qd if p.scorer == gk.SCORER_ATTENTION else None,
+                                          scores_out=sc)
     torch.cuda.synchronize()
     return (gk.to_host_bits(Kout), gk.to_host_bits(Vout), idx.cpu().numpy()), (sc.cpu().numpy() if want_scores else None)
+
+
+def oracle_compress(oracle, host, p, dtype, budget=None):
+    K, V, Q = host
+    return oracle.compress(K, V, Q if p.scorer == gk.SCORER_ATTENTION else None, dtype, p.pool_kernel,
+                           p.budget if budget is None else budget, p.n_sources, p.n_neighbors, p.rounds,
+                           alpha=p.decay, reselect=p.reselect, signal=p.signal, pool_mode=p.pool_mode,
+                           scale=p.softmax_scale, edge_mode=p.edges, scorer=p.scorer, window=p.window)
 
 
 def end_to_end(oracle, cfg, layer, impl, **kw):
@@ -520,21 +538,15 @@ def end_to_end(oracle, cfg, layer, impl, **kw):
     K, V, Q = host
     p = util.params_from_cfg(cfg, layer, impl=impl, **kw)
     out, sc = run_compress(p, dev)
-    ref = oracle.compress(K, V, Q, cfg.dtype, p.pool_kernel, p.budget, p.n_sources, p.n_neighbors,
-                          p.rounds, alpha=p.decay, reselect=p.reselect, signal=p.signal,
-                          pool_mode=p.pool_mode, scale=p.softmax_scale)
-    diffs = util.compare_end_to_end(out, ref, K, V, cfg.window)
-    gaps = ref["min_gap"]
+    ref = oracle_compress(oracle, host, p, cfg.dtype)
+    util.compare_end_to_end(out, ref, K, V, cfg.window)
+    diffs = util.judge_layer(oracle, p, host, dev, ref, out[2], sc, layer=layer, excused=util.EXCUSED)
     if diffs:
-        say(f"  {cfg.name} layer {layer} impl {impl}: retained sets differ on heads {diffs}; oracle's "
-            f"smallest relative gaps (source cut, neighbour cut, final cut) = {gaps}")
-        assert gaps.min() < util.REL_TOL, "retained set differs although no cut is a near-tie"
-    else:
-        util.assert_scores_close(sc, ref["scores"], "refined scores")
+        say(f"  {cfg.name} layer {layer} impl {impl}: retained sets differ on heads {diffs}: {util.EXCUSED[-len(diffs):]}")
     # without the optional score output the result is the same
     out2, _ = run_compress(p, dev, want_scores=False)
     assert all(np.array_equal(a, b) for a, b in zip(out, out2))
-    return diffs, gaps, (out, sc, ref)
+    return diffs, ref["min_gap"], (out, sc, ref)
 
 
 @pytest.mark.parametrize("impl", IMPLS)
@@ -733,10 +745,10 @@ def test_batched_more_layers_than_one_group(oracle):
     row = 0
     for l in range(L):
         (K, V, Q) = layers[pick[l]][0]
-        ref = oracle.compress(K, V, Q, "bf16", cfg.pool_kernel, budgets[l], cfg.n_sources, cfg.n_neighbors, cfg.rounds)
-        got = idx[row:row + budgets[l]]
-        if not np.array_equal(got, ref["idx"][0]):
-            assert ref["min_gap"].min() < util.REL_TOL
+        pl = util.params_from_cfg(cfg, budget=budgets[l])
+        ref = oracle_compress(oracle, (K, V, Q), pl, "bf16")
+        got = idx[row:row + budgets[l]].reshape(1, budgets[l])
+        util.judge_layer(oracle, pl, (K, V, Q), layers[pick[l]][1], ref, got, layer=l, excused=util.EXCUSED)
         row += budgets[l]
 
 
@@ -750,7 +762,6 @@ def test_full_size_layer(oracle, name, layer):
     say(f"full-size {name} layer {layer} budget {cfg.budget_for_layer(layer)}")
     diffs, gaps, _ = end_to_end(oracle, cfg, layer, gk.IMPL_AUTO)
     say(f"  heads with a differing retained set: {diffs}; oracle min gaps {gaps}")
-    assert sum(n for _, n in diffs) <= 8 * cfg.n_neighbors
 
 
 def test_full_size_batched_c3(oracle):
@@ -784,31 +795,153 @@ def test_full_size_batched_c3(oracle):
     for l in checked:
         K, V, Q = host[l]
         say(f"  layer {l} against the oracle")
-        ref = oracle.compress(K, V, Q, "bf16", p.pool_kernel, p.budget, p.n_sources, p.n_neighbors, p.rounds,
-                              alpha=p.decay, reselect=p.reselect, signal=p.signal, pool_mode=p.pool_mode,
-                              scale=p.softmax_scale)
-        diffs = util.compare_end_to_end((Ko[l], Vo[l], idx_h[l]), ref, K, V, cfg.window)
+        ref = oracle_compress(oracle, host[l], p, "bf16")
+        util.compare_end_to_end((Ko[l], Vo[l], idx_h[l]), ref, K, V, cfg.window)
+        diffs = util.judge_layer(oracle, p, host[l], (Kall[l], Vall[l], Qall[l]), ref, idx_h[l], layer=l,
+                                 excused=util.EXCUSED)
         if diffs:
-            say(f"  layer {l}: retained sets differ on heads {diffs}; oracle min gaps {ref['min_gap']}")
-            assert ref["min_gap"].min() < util.REL_TOL
-            assert sum(n for _, n in diffs) <= 8 * cfg.n_neighbors
+            say(f"  layer {l}: retained sets differ on heads {diffs}: {util.EXCUSED[-len(diffs):]}")
         one, _ = run_compress(p, (Kall[l], Vall[l], Qall[l]), want_scores=False)
         assert np.array_equal(one[2], idx_h[l]) and np.array_equal(one[0], Ko[l]) and np.array_equal(one[1], Vo[l])
 
 
-def test_long_context_properties(oracle):
-    """c5's shape (N = 131072, w = 64, S = m = 128): too large for a full oracle
-    run inside the test budget, so: stage I on sampled heads against the oracle,
-    one propagation round staged on one head, and the size-independent
-    invariants on the whole output."""
-    cfg = synth.scaled(synth.CONFIGS["c5"], n_kv_heads=2, n_q_heads=8)
-    say("long context c5 (2 of 8 heads)")
+def long_context_head():
+    """One KV head (4 query heads) of the long-context workload: N = 131072, w = 64 (256
+    stacked query rows), S = m = 128, 10 % near-duplicate keys."""
+    cfg = synth.scaled(synth.CONFIGS["c5"], n_kv_heads=1, n_q_heads=4)
     host, dev = util.device_layer(cfg, 0)
+    return cfg, host, dev
+
+
+def test_long_context_round_staged(oracle):
+    """One propagation round at the long-context shape on one head, stage by stage against the
+    oracle: the sources out of a row of 131008 scores, the filter route over 131008 keys with
+    128 sources (two source groups), candidate lists of thousands of entries (a workgroup per
+    source), the sort-based update for 16384 edges."""
+    cfg, (K, V, Q), (Kd, Vd, Qd) = long_context_head()
+    say("long context: one staged round on one head")
+    p = util.params_from_cfg(cfg, rounds=1)
+    s0 = gk.graphkv_score(p, Kd, Qd).cpu().numpy()
+    s1, src, nbr, ev = run_propagate(p, Kd, s0)
+    flips = util.check_round_staged(oracle, K, "bf16", cfg.window, s0, s1, src[0], nbr[0], ev[0],
+                                    cfg.n_sources, cfg.n_neighbors, 1.0)
+    say(f"  neighbour lists differing from the oracle's (near-ties): {flips}")
+    # a second round on those scores keeps the lists of the returning sources
+    p2 = util.params_from_cfg(cfg, rounds=2)
+    s2, src2, nbr2, ev2 = run_propagate(p2, Kd, s0)
+    assert np.array_equal(src2[0], src[0]) and np.array_equal(nbr2[0], nbr[0]) and np.array_equal(ev2[0], ev[0])
+    s2b, src1b, nbr1b, ev1b = run_propagate(p, Kd, s1)
+    assert np.array_equal(src2[1], src1b[0]) and np.array_equal(nbr2[1], nbr1b[0]) and np.array_equal(s2, s2b)
+
+
+def test_long_context_whole_pass(oracle):
+    """The whole pass at the long-context shape on one head against the oracle's: 256 stacked
+    query rows, T = 3 rounds, the final selection of 4032 out of 131008 scores."""
+    cfg, host, dev = long_context_head()
     K, V, Q = host
+    say("long context: whole pass on one head")
     p = util.params_from_cfg(cfg)
-    s0 = gk.graphkv_score(p, dev[0], dev[2]).cpu().numpy()
-    ref = oracle.score(K[:1].copy(), Q[:4].copy(), "bf16", cfg.pool_kernel)
-    util.assert_scores_close(s0[:1], ref)
     out, sc = run_compress(p, dev)
-    util.compare_end_to_end(out, dict(idx=out[2]), K, V, cfg.window)
-    assert out[2].shape == (2, cfg.budget)
+    say("  oracle ...")
+    ref = oracle_compress(oracle, host, p, "bf16")
+    util.assert_scores_close(gk.graphkv_score(p, dev[0], dev[2]).cpu().numpy(), ref["s0"], "initial scores")
+    util.compare_end_to_end(out, ref, K, V, cfg.window)
+    diffs = util.judge_layer(oracle, p, host, dev, ref, out[2], sc, excused=util.EXCUSED)
+    say(f"  heads with a differing retained set: {diffs}; oracle min gaps {ref['min_gap']}")
+    assert out[2].shape == (1, cfg.budget)
+
+
+# ------------------------------------------ key-norm indicator (negative scores) ---
+
+@pytest.mark.parametrize("impl", IMPLS)
+@pytest.mark.parametrize("signal,alpha", [(0, 1.0), (0, 0.6), (1, 0.5), (2, 1.0)])
+def test_propagate_negative_scores_staged(oracle, impl, signal, alpha):
+    """One round on negative scores (minus the key norm, and a mixed-sign array): the decay
+    takes alpha * e * |s| away from a score of either sign."""
+    cfg = small_bf16_cfg()
+    say(f"negative scores staged impl={impl} signal={signal} alpha={alpha}")
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 0)
+    p = util.params_from_cfg(cfg, impl=impl, rounds=1, decay=alpha, signal=signal)
+    s_knorm = gk.graphkv_score_knorm(p, Kd).cpu().numpy()
+    assert (s_knorm < 0).all()
+    mixed = synth.random_scores(cfg) - np.float32(0.5)
+    for s0 in (s_knorm, mixed):
+        s1, src, nbr, ev = run_propagate(p, Kd, s0)
+        flips = util.check_round_staged(oracle, K, cfg.dtype, cfg.window, s0, s1, src[0], nbr[0], ev[0],
+                                        cfg.n_sources, cfg.n_neighbors, alpha, signal)
+        if signal == 0:
+            # nodes that only positive edges reach: the decay lowers their score whatever its sign
+            reached, some_nonpos = np.zeros(s0.shape, bool), np.zeros(s0.shape, bool)
+            for h in range(s0.shape[0]):
+                reached[h, nbr[0, h].ravel()] = True
+                some_nonpos[h, nbr[0, h].ravel()[ev[0, h].ravel() <= 0]] = True
+            down = reached & ~some_nonpos
+            assert down.any() and (s1[down] < s0[down]).all()
+        if flips == 0:      # same picks as the oracle: its refined scores are the reference
+            ref = oracle.propagate(K, "bf16", cfg.window, s0.astype(np.float64), cfg.n_sources,
+                                   cfg.n_neighbors, 1, alpha, 1, signal)
+            util.assert_scores_close(s1, ref, "refined scores")
+
+
+@pytest.mark.parametrize("case", ["dense-auto", "dense-generic", "filter", "c1-fp32"])
+def test_compress_knorm_scorer(oracle, case):
+    """Key-norm indicator -> propagation -> selection -> gather in one call, against the
+    oracle's whole pass with the same switch; the queries are not read (none are passed)."""
+    say(f"compress with the key-norm scorer: {case}")
+    impl = gk.IMPL_GENERIC if case == "dense-generic" else gk.IMPL_AUTO
+    if case == "filter":
+        cfg = small_bf16_cfg(n_tokens=9500, n_sources=48, n_neighbors=20, n_kv_heads=3, n_q_heads=6, budget=1200)
+        kw = dict(rounds=3)
+    elif case == "c1-fp32":
+        cfg, kw = synth.CONFIGS["c1"], dict(rounds=2)
+    else:
+        cfg, kw = small_bf16_cfg(), dict(rounds=2)
+    end_to_end(oracle, cfg, 4, impl, scorer=gk.SCORER_KNORM, **kw)
+    # no propagation: plain selection of the lowest key norms
+    diffs, _, (out, sc, ref) = end_to_end(oracle, cfg, 4, impl, scorer=gk.SCORER_KNORM, rounds=0)
+    K = util.device_layer(cfg, 4)[0][0]
+    norms = np.linalg.norm(synth.storage_to_f64(K, cfg.dtype)[:, :cfg.n_prefix], axis=2)
+    if not diffs:
+        keep = cfg.budget - cfg.window
+        for h in range(cfg.n_kv_heads):
+            assert np.array_equal(out[2][h, :keep], np.sort(np.argsort(norms[h], kind="stable")[:keep]))
+
+
+def test_batched_knorm_equals_per_layer(oracle):
+    L = 3
+    cfg = small_bf16_cfg(rounds=2)
+    layers = [util.device_layer(cfg, l) for l in range(L)]
+    p = util.params_from_cfg(cfg, scorer=gk.SCORER_KNORM)
+    Kall = torch.stack([d[1][0] for d in layers]).contiguous()
+    Vall = torch.stack([d[1][1] for d in layers]).contiguous()
+    Ko, Vo, idx = gk.graphkv_compress_batched(p, L, None, Kall, Vall, None)
+    idx = idx.cpu().numpy().reshape(L, p.n_kv_heads, p.budget)
+    for l in range(L):
+        one, _ = run_compress(p, layers[l][1], want_scores=False)
+        assert np.array_equal(one[2], idx[l])
+
+
+# ------------------------------------------------------ argument checks ---
+
+def test_binding_rejects_mistyped_and_short_buffers():
+    """The binding checks what the C ABI cannot see: element type and size of every tensor."""
+    cfg = small_bf16_cfg()
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 0)
+    p = util.params_from_cfg(cfg)
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_compress(p, Kd.float(), Vd, Qd)                       # wrong element type
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_compress(p, Kd[:, :-1].contiguous(), Vd, Qd)          # a row short
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_compress(p, Kd, Vd, Qd, idx=torch.empty((p.n_kv_heads, p.budget), dtype=torch.int64, device="cuda"))
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_compress(p, Kd, Vd, Qd, ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_compress(p, Kd, Vd, None)                             # attention scorer needs queries
+    s = torch.zeros((p.n_kv_heads, p.n_prefix), dtype=torch.float32, device="cuda")
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_propagate(p, Kd, s, dbg_src=torch.empty(3, dtype=torch.int32, device="cuda"))
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_select(p, s.double())
+    with pytest.raises(gk.GraphKVError):
+        gk.graphkv_score(p, Kd.cpu(), Qd)
