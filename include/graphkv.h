@@ -47,7 +47,8 @@ enum {
     GRAPHKV_OK = 0,
     GRAPHKV_EINVAL = -1,      /* a constraint listed below is violated, or a required pointer is NULL/misaligned */
     GRAPHKV_EWORKSPACE = -2,  /* ws is NULL, misaligned or smaller than graphkv_workspace_bytes() */
-    GRAPHKV_EHIP = -3         /* a kernel launch failed */
+    GRAPHKV_EHIP = -3,        /* a kernel launch failed */
+    GRAPHKV_ESCRATCH = -4     /* graphkv_compress_static: the params need more scratch than its built-in buffer holds */
 };
 
 enum { GRAPHKV_FP32 = 0, GRAPHKV_BF16 = 1 };
@@ -217,6 +218,26 @@ int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, cons
                                  const void *Kc, const void *Vc, const void *Qw, void *Kout,
                                  void *Vout, int32_t *idx, float *scores_out, void *ws,
                                  size_t ws_bytes, void *stream);
+
+/*
+ * graphkv_compress for callers that cannot allocate device memory or size a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  Same arguments and results as graphkv_compress, without
+ * `ws`: the scratch memory is a buffer of GRAPHKV_STATIC_SCRATCH_BYTES that
+ * belongs to the library's code object (every GPU the library runs on holds its
+ * own copy until the process ends).  The call allocates and frees nothing.
+ *   - params whose graphkv_workspace_bytes() exceeds GRAPHKV_STATIC_SCRATCH_BYTES
+ *     are rejected with GRAPHKV_ESCRATCH before anything is enqueued;
+ *   - every call on a GPU uses that GPU's one buffer: calls that overlap in time on
+ *     one GPU (two streams, two host threads) race -- serialise them, or use
+ *     graphkv_compress with a workspace each;
+ *   - the first call on a device resolves the buffer's address and opts kernels in
+ *     to large shared memory: make it outside a graph capture.
+ */
+#define GRAPHKV_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int32_t graphkv_compress_static(const graphkv_params *p, const void *Kc, const void *Vc,
+                                const void *Qw, void *Kout, void *Vout, int32_t *idx,
+                                float *scores_out, void *stream);
 
 /* Host string for a return code (static storage). */
 const char *graphkv_strerror(int32_t code);

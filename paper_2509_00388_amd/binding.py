@@ -27,7 +27,9 @@ SCORER_ATTENTION, SCORER_KNORM = 0, 1
 EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "graphkv_propagate",
            "graphkv_select", "graphkv_compress", "graphkv_strerror", "graphkv_uses_mfma",
            "graphkv_profile_begin", "graphkv_profile_end", "graphkv_kernel_name",
-           "graphkv_workspace_bytes_batched", "graphkv_compress_batched", "graphkv_propagate_edges")
+           "graphkv_workspace_bytes_batched", "graphkv_compress_batched", "graphkv_propagate_edges",
+           "graphkv_compress_static")
+STATIC_SCRATCH_BYTES = 64 << 20
 N_KERNELS = 20
 
 
@@ -113,6 +115,8 @@ def load_library() -> ctypes.CDLL:
     lib.graphkv_select.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.graphkv_compress.restype = i32
     lib.graphkv_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.graphkv_compress_static.restype = i32
+    lib.graphkv_compress_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.graphkv_workspace_bytes_batched.restype = sz
     lib.graphkv_workspace_bytes_batched.argtypes = [pp, i32]
     lib.graphkv_compress_batched.restype = i32
@@ -281,6 +285,21 @@ def graphkv_compress(p: Params, Kc, Vc, Qw, Kout=None, Vout=None, idx=None, scor
         _arg(idx, "idx", torch.int32, n_out),
         _arg(scores_out, "scores_out", torch.float32, p.n_kv_heads * p.n_prefix, optional=True),
         wp, wn, _stream()))
+    return Kout, Vout, idx
+
+
+def graphkv_compress_static(p: Params, Kc, Vc, Qw, Kout, Vout, idx, scores_out=None):
+    """graphkv_compress on the library's built-in scratch buffer: no workspace, nothing is
+    allocated here or in the library (the caller passes every output)."""
+    cp = p.c()
+    n_out = p.n_kv_heads * max(p.budget, 0)
+    knorm = p.scorer == SCORER_KNORM
+    _check(load_library().graphkv_compress_static(
+        ctypes.byref(cp), _arg(Kc, "Kc", p.torch_dtype, _kv_numel(p)), _arg(Vc, "Vc", p.torch_dtype, _kv_numel(p)),
+        _arg(Qw, "Qw", p.torch_dtype, 0 if knorm else _q_numel(p), optional=knorm),
+        _arg(Kout, "Kout", p.torch_dtype, n_out * p.head_dim), _arg(Vout, "Vout", p.torch_dtype, n_out * p.head_dim),
+        _arg(idx, "idx", torch.int32, n_out),
+        _arg(scores_out, "scores_out", torch.float32, p.n_kv_heads * p.n_prefix, optional=True), _stream()))
     return Kout, Vout, idx
 
 

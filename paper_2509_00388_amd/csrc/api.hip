@@ -12,6 +12,32 @@ namespace {
 
 using namespace gkv;
 
+// Scratch memory of graphkv_compress_static: device memory that belongs to the library's code
+// object, so that callers which cannot allocate (HIP graph capture, serving loops) need no
+// workspace.  Each GPU the library runs on holds its own copy at its own address until the
+// process ends; `scratch` itself is only a host-side stand-in for those addresses.
+constexpr size_t kStaticScratchBytes = GRAPHKV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, once resolved
+
+// The address of the current device's copy of `scratch` (resolved on the first call on that
+// device); nullptr if it cannot be had.
+void *static_scratch()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
 
@@ -473,6 +499,21 @@ int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc
                                     ws_bytes, stream);
 }
 
+int32_t graphkv_compress_static(const graphkv_params *p, const void *Kc, const void *Vc, const void *Qw,
+                                void *Kout, void *Vout, int32_t *idx, float *scores_out, void *stream)
+{
+    const size_t need = graphkv_workspace_bytes(p);   // 0: invalid params
+    if (need == 0) return GRAPHKV_EINVAL;
+    if (need > kStaticScratchBytes) return GRAPHKV_ESCRATCH;
+    // (the pointer checks of the call below come before the address is resolved)
+    if (!aligned16(Kc) || !aligned16(Vc) || !aligned16(Kout) || !aligned16(Vout) || !aligned4(idx))
+        return GRAPHKV_EINVAL;
+    void *ws = static_scratch();
+    if (!ws) return GRAPHKV_EHIP;
+    return graphkv_compress_batched(p, 1, nullptr, Kc, Vc, Qw, Kout, Vout, idx, scores_out, ws,
+                                    kStaticScratchBytes, stream);
+}
+
 size_t graphkv_workspace_bytes_batched(const graphkv_params *p, int32_t n_layers)
 {
     if (!base_ok(p) || n_layers < 1) return 0;
@@ -562,6 +603,7 @@ const char *graphkv_strerror(int32_t code)
         case GRAPHKV_EINVAL: return "invalid argument (a graphkv_params constraint is violated or a pointer is NULL/misaligned)";
         case GRAPHKV_EWORKSPACE: return "workspace is NULL, misaligned or smaller than graphkv_workspace_bytes()";
         case GRAPHKV_EHIP: return "a HIP kernel launch failed";
+        case GRAPHKV_ESCRATCH: return "the problem needs more scratch memory than graphkv_compress_static's built-in buffer holds (use graphkv_compress with a workspace)";
         default: return "unknown graphkv error code";
     }
 }

@@ -93,6 +93,23 @@ def test_null_misaligned_and_small_workspace(lib):
     assert gk.graphkv_strerror(-3) and gk.graphkv_strerror(-99)
 
 
+def test_static_scratch_entry_checks_on_the_host(lib):
+    """graphkv_compress_static: invalid params and problems beyond its built-in buffer are turned
+    down before anything touches a GPU."""
+    fake = ctypes.c_void_p(0x10000)
+    big = good_params(n_tokens=131072, window=64, budget=4096, n_sources=128, n_neighbors=128, rounds=3).c()
+    assert lib.graphkv_workspace_bytes(ctypes.byref(big)) > gk.STATIC_SCRATCH_BYTES
+    assert lib.graphkv_compress_static(ctypes.byref(big), fake, fake, fake, fake, fake, fake, None, None) == -4
+    assert "scratch" in gk.graphkv_strerror(-4)
+    bad = good_params(head_dim=100).c()
+    assert lib.graphkv_compress_static(ctypes.byref(bad), fake, fake, fake, fake, fake, fake, None, None) == -1
+    ok = good_params().c()
+    assert lib.graphkv_workspace_bytes(ctypes.byref(ok)) <= gk.STATIC_SCRATCH_BYTES
+    assert lib.graphkv_compress_static(ctypes.byref(ok), None, fake, fake, fake, fake, fake, None, None) == -1
+    header = open(os.path.join(ROOT, "include", "graphkv.h")).read()
+    assert re.search(r"#define GRAPHKV_STATIC_SCRATCH_BYTES \(\(size_t\)64 << 20\)", header)
+
+
 def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(gk, "_lib", None)
     monkeypatch.setattr(gk, "LIB_PATH", "/nonexistent/libgraphkv.so")
