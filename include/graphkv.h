@@ -210,8 +210,9 @@ int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc
  *   idx        packed the same way, [H_kv, B_l] per layer
  *   scores_out [n_layers, H_kv, P] or NULL
  *   ws         graphkv_workspace_bytes_batched(p, n_layers) bytes
- * Layers are processed in groups of at most 64.  Results are identical to
- * n_layers per-layer calls.
+ * Layers are processed in groups: at most 64 layers, fewer while the scratch
+ * memory of a group would exceed 1.5 GiB (long prompts).  Results are identical
+ * to n_layers per-layer calls.
  */
 size_t graphkv_workspace_bytes_batched(const graphkv_params *p, int32_t n_layers);
 int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, const int32_t *budgets,
@@ -257,7 +258,7 @@ enum {
     GRAPHKV_K_COSINE, GRAPHKV_K_TOPK_NEIGHBORS, GRAPHKV_K_DECAY, GRAPHKV_K_TOPK_FINAL,
     GRAPHKV_K_GATHER, GRAPHKV_K_GENERIC_LOGITS, GRAPHKV_K_GENERIC_VOTES, GRAPHKV_K_GENERIC_COSINE,
     GRAPHKV_K_KNORM, GRAPHKV_K_COPY, GRAPHKV_K_COSINE_BOUND,
-    GRAPHKV_K_COSINE_FILTER, GRAPHKV_K_NBR_SELECT, GRAPHKV_K_REDO_COSINE, GRAPHKV_K_REDO_TOPK,
+    GRAPHKV_K_COSINE_FILTER, GRAPHKV_K_NBR_SELECT, GRAPHKV_K_REDO_ROWS,
     GRAPHKV_K_MATCH_SOURCES, GRAPHKV_N_KERNELS
 };
 int32_t graphkv_profile_begin(void);

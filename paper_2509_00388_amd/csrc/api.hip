@@ -150,7 +150,9 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.row_max = take(rows * 4);
     W.row_sum = take(rows * 4);
     W.votes = take((size_t)D.Hq * D.P * 4);
-    W.E = take((size_t)D.H * D.S * D.P * 4);
+    // the dense edge block [heads, S, P] of the routes that materialise it; on the filter route
+    // only the scratch rows of the workgroups that redo overflowed heads
+    W.E = take(D.filter ? redo_rows_scratch_bytes(D.H, D.S, D.P) : (size_t)D.H * D.S * D.P * 4);
     W.src = take((size_t)D.H * D.S * 4);
     W.nbr = take((size_t)D.H * D.S * D.m * 4);
     W.nbr_e = take((size_t)D.H * D.S * D.m * 4);
@@ -210,7 +212,7 @@ const char *const kKernelNames[GRAPHKV_N_KERNELS] = {
     "score_stats", "score_votes", "pool_group", "topk_sources", "cosine", "topk_neighbors",
     "decay", "topk_final", "gather", "generic_logits", "generic_votes", "generic_cosine",
     "knorm", "copy", "cosine_bound", "cosine_filter", "nbr_select",
-    "redo_cosine", "redo_topk", "match_sources"};
+    "redo_rows", "match_sources"};
 
 #define GKV_LAUNCH(id, expr)                                              \
     do {                                                                  \
@@ -332,11 +334,9 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                 GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
                            launch_nbr_select(cand, cnt, ovf, fsrc, D.H, D.P, D.S, D.m, ru.code ? &ru : nullptr,
                                              nbr, ev, st));
-                // heads whose lists overflowed are redone through the dense block
-                GKV_LAUNCH(GRAPHKV_K_REDO_COSINE, launch_mfma_cosine(Ac, Kc, D.H, D.N, D.P, D.S, src, E, ovf, st));
-                GKV_LAUNCH(GRAPHKV_K_REDO_TOPK,
-                           launch_topk_rows(E, D.P, D.P, D.H * D.S, D.m, nbr, D.m, ev, D.m, nullptr, 0, 0,
-                                            ovf, D.S, st));
+                // heads whose lists overflowed are redone row by row, exactly
+                GKV_LAUNCH(GRAPHKV_K_REDO_ROWS,
+                           launch_redo_rows(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, ovf, E, nbr, ev, st));
             } else {
                 // Eq. 1: edges from every source to every node
                 if (D.mfma_cosine)
@@ -410,6 +410,18 @@ int32_t run_compress(const graphkv_params *p, int n_layers, const int32_t *budge
     GKV_LAUNCH(GRAPHKV_K_GATHER, launch_gather(Kc, Vc, idx, D.H, D.N, plan, max_budget,
                                                (int)(D.d * D.esize), Kout, Vout, st));
     return GRAPHKV_OK;
+}
+
+// Layers that go through the kernels together: at most kMaxLayers and 65535 heads, and fewer
+// while the scratch memory of a group would exceed 1.5 GiB (long prompts: the candidate lists
+// and vote rows grow with the number of heads in flight).
+constexpr size_t kGroupScratchCap = (size_t)1536 << 20;
+int group_layers(const graphkv_params *p, int n_layers)
+{
+    int g = n_layers < kMaxLayers ? n_layers : kMaxLayers;
+    while (g > 1 && ((long)p->n_kv_heads * g > 65535 || carve(p, dims_of(p, g)).total > kGroupScratchCap))
+        g = (g + 1) / 2;
+    return g;
 }
 
 bool budgets_ok(const graphkv_params *p, int n_layers, const int32_t *budgets)
@@ -517,9 +529,7 @@ int32_t graphkv_compress_static(const graphkv_params *p, const void *Kc, const v
 size_t graphkv_workspace_bytes_batched(const graphkv_params *p, int32_t n_layers)
 {
     if (!base_ok(p) || n_layers < 1) return 0;
-    const int group = n_layers < kMaxLayers ? n_layers : kMaxLayers;
-    if ((long)p->n_kv_heads * group > 65535) return 0;
-    return carve(p, dims_of(p, group)).total;
+    return carve(p, dims_of(p, group_layers(p, n_layers))).total;
 }
 
 int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, const int32_t *budgets,
@@ -535,8 +545,7 @@ int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, cons
         !aligned16(Vout) || !aligned4(idx))
         return GRAPHKV_EINVAL;
     if (scores_out && !aligned4(scores_out)) return GRAPHKV_EINVAL;
-    const int group = n_layers < kMaxLayers ? n_layers : kMaxLayers;
-    if ((long)p->n_kv_heads * group > 65535) return GRAPHKV_EINVAL;
+    const int group = group_layers(p, n_layers);
     const Workspace W = carve(p, dims_of(p, group));
     if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
     hipStream_t st = (hipStream_t)stream;

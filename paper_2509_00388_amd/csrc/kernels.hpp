@@ -27,6 +27,14 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k,
                             float *tau_out, int append_from, int append_count,
                             const int32_t *gate, int rows_per_gate, hipStream_t st);
 
+// Neighbourhoods of the heads whose overflow flag is set (filter route, bf16, d = 128): a fixed
+// number of workgroups walk the (head, source) rows of those heads, each computing one row of
+// edges into its own scratch row (rows: redo_rows_scratch_bytes()) and taking the exact top-m.
+size_t redo_rows_scratch_bytes(int heads, int S, int P);
+hipError_t launch_redo_rows(const void *Ac, const void *Kc, int heads, int N, int P, int S, int m,
+                            const int32_t *src, const int32_t *overflow, float *rows, int32_t *nbr,
+                            float *nbr_e, hipStream_t st);
+
 // ---- scalar kernels for any dtype / shape (generic.hip) ----------------------
 // logits [Hq*w, N] (fp32, scaled), then per-row max and sum of exp.
 hipError_t launch_generic_logits(const void *Kc, const void *Qw, int dtype, int Hkv, int Hq, int d,

@@ -638,6 +638,65 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
     }
 }
 
+// ---- neighbourhoods of heads whose candidate lists overflowed ------------------------
+// The filter route (mfma_cosine.hip) gives up on a head when a candidate list cannot hold what
+// reaches the bound (masses of equal edges, an adversarial key order) and raises the head's
+// flag.  Such heads are rare, so they are not worth an [heads, S, P] edge block in memory: a
+// fixed number of workgroups walk the (head, source) rows of the flagged heads, and each row's
+// edges (Eq. 1, scalar fused multiply-adds over the bf16 rows, d = 128) go to the workgroup's
+// own scratch row of P floats, out of which the exact top-m (Eq. 3) is taken by the row
+// kernels above.  A launch that finds no flag set returns after one round trip.
+constexpr int kRedoBlock = 1024;
+constexpr int kRedoDim = 128;
+
+__global__ __launch_bounds__(kRedoBlock) void redo_rows_kernel(
+    const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int P, int S, int m, int heads,
+    const int32_t *__restrict__ src, const int32_t *__restrict__ overflow, float *__restrict__ rows,
+    int32_t *__restrict__ nbr, float *__restrict__ nbr_e)
+{
+    __shared__ float s_f32[kRedoDim];
+    const int tid = threadIdx.x;
+    int open = 0;
+    for (int g = tid; g < heads; g += kRedoBlock) open |= overflow[g] != 0;
+    if (!__syncthreads_or(open)) return;
+    float *erow = rows + (long)blockIdx.x * P;
+    for (long item = blockIdx.x; item < (long)heads * S; item += gridDim.x) {
+        const int h = (int)(item / S);
+        if (overflow[h] == 0) continue;           // (the same for every thread)
+        const int32_t i = src[item];
+        const uint16_t *ah = Ac + (long)h * N * kRedoDim, *kh = Kc + (long)h * N * kRedoDim;
+        __syncthreads();                          // the previous row's LDS and scratch row are free
+        if (tid < kRedoDim) s_f32[tid] = bf16_to_f32(ah[(long)i * kRedoDim + tid]);
+        __syncthreads();
+        float sq_i = 0.f;                         // |x_i|^2 in a fixed order, the same in every thread
+        for (int c = 0; c < kRedoDim; ++c) sq_i = fmaf(s_f32[c], s_f32[c], sq_i);
+        const float inv_i = sq_i == 0.f ? 0.f : __builtin_amdgcn_rsqf(sq_i);
+        for (int j = tid; j < P; j += kRedoBlock) {
+            const uint4 *kv = reinterpret_cast<const uint4 *>(kh + (long)j * kRedoDim);
+            float dot = 0.f, sq = 0.f;
+#pragma unroll 4
+            for (int c = 0; c < kRedoDim / 8; ++c) {
+                float t[8];
+                Elem<uint16_t>::unpack(kv[c], t);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    dot = fmaf(s_f32[c * 8 + u], t[u], dot);
+                    sq = fmaf(t[u], t[u], sq);
+                }
+            }
+            const float inv_k = sq == 0.f ? 0.f : __builtin_amdgcn_rsqf(sq);
+            erow[j] = j == i ? -INFINITY : (dot * inv_k) * inv_i;   // (Eq. 3: j != i; a zero row has e = 0)
+        }
+        __syncthreads();                          // the row is complete and visible to the workgroup
+        int32_t *out = nbr + item * m;
+        float *vout = nbr_e + item * m;
+        if (P <= 32768)
+            topk_row_lds<kRedoBlock, false, 11>(0, erow, P, P, m, out, 0, vout, 0, nullptr, 0, 0, 0);
+        else
+            topk_stream_row<kRedoBlock, false>(0, erow, P, P, m, out, 0, vout, 0, nullptr, 0, 0, nullptr, 1, 0);
+    }
+}
+
 template <int BLOCK, bool PLAN, int DIG, typename PlanArg>
 static hipError_t launch_lds(const float *x, long ld, int n, int rows, int k, int32_t *idx_out,
                              long idx_ld, float *val_out, long val_ld, float *tau_out,
@@ -702,6 +761,30 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k, int
 {
     return launch_any<false, int>(x, ld, n, rows, k, idx_out, idx_ld, val_out, val_ld, tau_out,
                                   append_from, append_count, gate, rows_per_gate, 0, st);
+}
+
+int redo_rows_workgroups(int heads, int S)
+{
+    const long items = (long)heads * S;
+    return (int)(items < 256 ? items : 256);
+}
+
+size_t redo_rows_scratch_bytes(int heads, int S, int P)
+{
+    return (size_t)redo_rows_workgroups(heads, S) * P * sizeof(float);
+}
+
+hipError_t launch_redo_rows(const void *Ac, const void *Kc, int heads, int N, int P, int S, int m,
+                            const int32_t *src, const int32_t *overflow, float *rows, int32_t *nbr,
+                            float *nbr_e, hipStream_t st)
+{
+    const int items = P <= 32768 ? (P + kRedoBlock - 1) / kRedoBlock : 0;   // keys of a row in LDS
+    const size_t lds = ((size_t)items * kRedoBlock + 2 * (size_t)items * (kRedoBlock / kWave)) * 4;
+    if (lds > 65536 && !allow_big_lds((const void *)redo_rows_kernel, 140 * 1024)) return hipGetLastError();
+    hipLaunchKernelGGL(redo_rows_kernel, dim3(redo_rows_workgroups(heads, S)), dim3(kRedoBlock), lds, st,
+                       (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, m, heads, src, overflow, rows, nbr,
+                       nbr_e);
+    return hipGetLastError();
 }
 
 hipError_t launch_topk_final(const float *scores, int P, int rows, const LayerPlan &plan, int w,

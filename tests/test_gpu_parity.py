@@ -382,6 +382,27 @@ def test_filtered_neighbourhoods_overflow_falls_back(oracle, n_tokens):
     assert np.array_equal(nbr[0, 0, a], want) and (np.abs(ev[0, 0, a] - 1.0) < 1e-6).all()
 
 
+def test_more_overflowed_rows_than_redo_workgroups(oracle):
+    """Six heads of 64 sources all overflow (half of each head's keys are one vector): 384
+    (head, source) rows for the 256 workgroups that redo them, so some take two rows."""
+    cfg = small_bf16_cfg(n_tokens=9000, n_sources=64, n_neighbors=16, n_kv_heads=6, n_q_heads=6)
+    (K, V, Q), _ = util.device_layer(cfg, 1)
+    P = cfg.n_prefix
+    rng = np.random.default_rng(8)
+    s0 = synth.random_scores(cfg)
+    for h in range(6):
+        dup = rng.choice(P, size=P // 2, replace=False)
+        K[h, dup] = K[h, dup[0]]
+        s0[h, dup[:3]] = 50.0
+    Kd = gk.to_device(K, gk.BF16)
+    p = util.params_from_cfg(cfg, rounds=1)
+    s1, src, nbr, ev = run_propagate(p, Kd, s0)
+    util.check_round_staged(oracle, K, "bf16", cfg.window, s0, s1, src[0], nbr[0], ev[0], 64, 16, 1.0)
+    # the scalar kernels (dense block) pick the same neighbours
+    _, src_g, nbr_g, _ = run_propagate(util.params_from_cfg(cfg, rounds=1, impl=gk.IMPL_GENERIC), Kd, s0)
+    assert np.array_equal(src, src_g) and np.count_nonzero((nbr != nbr_g).any(axis=-1)) <= 4
+
+
 @pytest.mark.parametrize("S,m,alpha,signal", [(40, 20, 1.0, 0), (130, 7, 0.7, 0), (64, 32, 1e-3, 0),
                                               (24, 16, 1.0, 2), (48, 12, 0.5, 1)])
 def test_filtered_multi_round_keeps_lists(oracle, S, m, alpha, signal):

@@ -59,6 +59,17 @@ def test_workspace_size_and_mfma_choice(lib):
     assert gk.graphkv_workspace_bytes(good_params(impl=gk.IMPL_GENERIC)) > gk.graphkv_workspace_bytes(p)
 
 
+def test_batched_workspace_stays_bounded(lib):
+    """The edge block of the overflow path is never carved in full: the long-context workload
+    (32 layers x 8 heads, N = 131072, S = m = 128) needs less than 2 GiB of scratch, the 32K one
+    less than 1 GiB."""
+    c5 = good_params(n_tokens=131072, window=64, budget=4096, n_sources=128, n_neighbors=128, rounds=3)
+    c3 = good_params(n_tokens=32768, window=32, budget=2048, n_sources=64, n_neighbors=32, rounds=2)
+    assert 0 < gk.graphkv_workspace_bytes_batched(c5, 32) < 2 << 30
+    assert 0 < gk.graphkv_workspace_bytes_batched(c3, 32) < 1 << 30
+    assert gk.graphkv_workspace_bytes(c3) <= gk.STATIC_SCRATCH_BYTES    # a 32K layer fits the built-in buffer
+
+
 BAD = [dict(n_kv_heads=0), dict(n_q_heads=12), dict(head_dim=100), dict(head_dim=1024),
        dict(window=0), dict(window=4096), dict(pool_kernel=4), dict(pool_kernel=0), dict(pool_mode=2),
        dict(budget=32), dict(budget=4097), dict(n_sources=0), dict(n_sources=4065),
