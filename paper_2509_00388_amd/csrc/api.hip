@@ -45,6 +45,9 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) & ~(kAlign - 1); }
 struct Dims {
     int L, H, Hq, G, d, N, w, P, B, S, m, T;
     bool mfma_score, mfma_cosine, filter;
+    bool speculate;      // speculative rows allowed (dropped when their scratch would not fit)
+    bool keep;           // neighbour lists are kept from one round to the next
+    MfmaFilterPlan fp;   // geometry of the filter route (if `filter`)
     float scale;
     size_t esize;
 };
@@ -53,7 +56,8 @@ struct Dims {
 struct Workspace {
     size_t logits, row_max, row_sum, votes, E, src, nbr, nbr_e, scores, part;
     size_t bound_hist, tau, cand, cand_cnt, overflow;
-    size_t src_b, nbr_b, nbr_e_b, reuse_code, new_src, new_pos, n_new;   // lists kept from one round to the next
+    // lists kept from one round to the next, speculative rows
+    size_t src_b, nbr_b, nbr_e_b, ext, new_src, n_new, sel_row, sel_pos, n_sel, spec_bad;
     size_t total;
 };
 
@@ -115,7 +119,7 @@ bool budget_ok(const graphkv_params *p)
     return p->budget > p->window && p->budget <= p->n_tokens;
 }
 
-Dims dims_of(const graphkv_params *p, int n_layers = 1)
+Dims dims_of(const graphkv_params *p, int n_layers = 1, bool speculate = true)
 {
     Dims D;
     D.L = n_layers;
@@ -133,6 +137,11 @@ Dims dims_of(const graphkv_params *p, int n_layers = 1)
     D.mfma_score = mfma_score_ok(p);
     D.mfma_cosine = mfma_cosine_ok(p);
     D.filter = D.mfma_cosine && D.T > 0 && mfma_filter_applies(D.P, D.m);
+    // The neighbourhood of a source depends on the keys alone (Eq. 1, Eq. 3), not on the
+    // scores: with re-picked sources the lists of returning sources are kept.
+    D.speculate = speculate;
+    D.keep = D.filter && D.T > 1 && p->reselect && source_reuse_applies(D.S);
+    D.fp = D.filter ? mfma_filter_plan(D.H, D.P, D.S, D.m, D.keep, speculate) : MfmaFilterPlan{};
     D.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)D.d);
     D.esize = p->dtype == GRAPHKV_FP32 ? 4 : 2;
     return D;
@@ -158,20 +167,24 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.nbr_e = take((size_t)D.H * D.S * D.m * 4);
     W.scores = take((size_t)D.H * D.P * 4);
     W.part = take(D.mfma_score ? mfma_score_plan(D.H, D.G * D.w, D.N).part_bytes : 0);
-    W.tau = take((size_t)D.H * D.S * 4);
-    W.bound_hist = take(D.filter ? mfma_bound_scratch_bytes(D.H, D.P, D.S) : 0);
-    const MfmaFilterGeom fg = D.filter ? mfma_filter_geom(D.H, D.P, D.S, D.m) : MfmaFilterGeom{0, 0, 0};
-    W.cand = take((size_t)D.H * D.S * fg.chunks * fg.slice_cap * 8);
-    W.cand_cnt = take((size_t)D.H * D.S * fg.chunks * 4);
+    const MfmaFilterPlan &g = D.fp;
+    const size_t frows = D.filter ? (size_t)D.H * g.pitch : 0;   // rows of the per-row buffers
+    W.tau = take(frows * 4);
+    W.bound_hist = take(D.filter ? mfma_bound_scratch_bytes(D.H, D.P, g) : 0);
+    W.cand = take(frows * g.chunks * g.slice_cap * 8);
+    W.cand_cnt = take(frows * g.chunks * 4);
     W.overflow = take((size_t)D.H * 4);
-    const bool keep = D.filter && D.T > 1 && p->reselect && source_reuse_applies(D.S);
+    const bool keep = D.keep;
     W.src_b = take(keep ? (size_t)D.H * D.S * 4 : 0);
     W.nbr_b = take(keep ? (size_t)D.H * D.S * D.m * 4 : 0);
     W.nbr_e_b = take(keep ? (size_t)D.H * D.S * D.m * 4 : 0);
-    W.reuse_code = take(keep ? (size_t)D.H * D.S * 4 : 0);
+    W.ext = take(keep ? (size_t)D.H * (g.S + g.X) * 4 : 0);
     W.new_src = take(keep ? (size_t)D.H * D.S * 4 : 0);
-    W.new_pos = take(keep ? (size_t)D.H * D.S * 4 : 0);
     W.n_new = take(keep ? (size_t)D.H * 4 : 0);
+    W.sel_row = take(keep ? (size_t)D.H * D.S * 4 : 0);
+    W.sel_pos = take(keep ? (size_t)D.H * D.S * 4 : 0);
+    W.n_sel = take(keep ? (size_t)D.H * 4 : 0);
+    W.spec_bad = take(keep ? (size_t)D.H * 4 : 0);
     W.total = off;
     return W;
 }
@@ -284,11 +297,12 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
     int32_t *src0 = dbg_src ? dbg_src : at<int32_t>(ws, W.src);
     int32_t *nbr0 = dbg_nbr ? dbg_nbr : at<int32_t>(ws, W.nbr);
     float *e0 = dbg_e ? dbg_e : at<float>(ws, W.nbr_e);
-    // The neighbourhood of a source depends on the keys alone (Eq. 1, Eq. 3), not on the
-    // scores: a source that comes back in the next round keeps its list, and the bound,
-    // filter and select passes of that round only take the sources that are new.  The lists
-    // of two consecutive rounds live in two buffers that take turns.
-    const bool keep = D.filter && D.T > 1 && p->reselect && source_reuse_applies(D.S);
+    // A source that comes back in the next round keeps its list; of the others, those that
+    // were speculative rows of the first round's pass have their candidates waiting, and only
+    // the rest take the bound and filter passes again.  The lists of two consecutive rounds
+    // live in two buffers that take turns.
+    const bool keep = D.keep;
+    const MfmaFilterPlan &g = D.fp;
     const int32_t *prev_src = nullptr, *prev_nbr = nullptr;
     const float *prev_e = nullptr;
     for (int t = 0; t < D.T; ++t) {
@@ -303,41 +317,66 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
             if (dbg_src) src = dbg_src + t * n_src;
             if (dbg_nbr) nbr = dbg_nbr + t * n_nbr;
             if (dbg_e) ev = dbg_e + t * n_nbr;
-            // Eq. 2: source nodes
-            GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES,
-                       launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, nullptr, 0, 0,
-                                        nullptr, 1, st));
             if (D.filter) {
                 // Eq. 1 + Eq. 3 in one streaming pass over the keys: a bound on each source's
                 // m-th largest edge from a strided sample, then only edges above it are kept.
                 float *tau = at<float>(ws, W.tau);
                 int32_t *cnt = at<int32_t>(ws, W.cand_cnt), *ovf = at<int32_t>(ws, W.overflow);
                 void *cand = at<char>(ws, W.cand);
-                const int32_t *fsrc = src, *n_new = nullptr;
-                SourceReuse ru{};
-                if (keep && prev_src) {
-                    int32_t *code = at<int32_t>(ws, W.reuse_code), *new_src = at<int32_t>(ws, W.new_src);
-                    int32_t *new_pos = at<int32_t>(ws, W.new_pos), *cnt_new = at<int32_t>(ws, W.n_new);
+                int32_t *ext = at<int32_t>(ws, W.ext);
+                if (!(keep && prev_src)) {
+                    // Eq. 2: source nodes; with speculative rows also the nodes ranked right behind
+                    const int32_t *lst = src;
+                    if (g.X > 0) {
+                        GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES,
+                                   launch_pick_sources(scores, D.P, D.P, D.H, D.S, g.X, src, ext, st));
+                        lst = ext;
+                    } else {
+                        GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES,
+                                   launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, nullptr, 0, 0,
+                                                    nullptr, 1, st));
+                    }
+                    GKV_LAUNCH(GRAPHKV_K_COSINE_BOUND,
+                               launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.m, g, true, lst, nullptr,
+                                                        at<char>(ws, W.bound_hist), tau, ovf, st));
+                    GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
+                               launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.m, g, true, lst, nullptr, tau, cand,
+                                                         cnt, ovf, st));
+                    GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
+                               launch_nbr_select(cand, cnt, ovf, src, D.H, D.m, g, nullptr, nbr, ev, st));
+                    // heads whose lists overflowed are redone row by row, exactly
+                    GKV_LAUNCH(GRAPHKV_K_REDO_ROWS,
+                               launch_redo_rows(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, ovf, E, nbr, ev, st));
+                } else {
+                    GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES,
+                               launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, nullptr, 0, 0,
+                                                nullptr, 1, st));
+                    int32_t *new_src = at<int32_t>(ws, W.new_src), *n_new = at<int32_t>(ws, W.n_new);
+                    const SelectRows sel{at<int32_t>(ws, W.n_sel), at<int32_t>(ws, W.sel_row),
+                                         at<int32_t>(ws, W.sel_pos)};
                     GKV_LAUNCH(GRAPHKV_K_MATCH_SOURCES,
-                               launch_match_sources(prev_src, src, D.H, D.S, D.m, prev_nbr, prev_e, code, new_src,
-                                                    new_pos, cnt_new, nbr, ev, st));
-                    ru = SourceReuse{cnt_new, code, new_pos};
-                    fsrc = new_src;
-                    n_new = cnt_new;
+                               launch_match_sources(prev_src, src, D.H, D.m, g, prev_nbr, prev_e, nbr, ev, ext,
+                                                    at<int32_t>(ws, W.spec_bad), ovf, t == 1, new_src, n_new,
+                                                    at<int32_t>(ws, W.sel_row), at<int32_t>(ws, W.sel_pos),
+                                                    at<int32_t>(ws, W.n_sel), st));
+                    // new sources without a kept list (usually none): bound and filter passes
+                    // that return at once for heads that have none
+                    GKV_LAUNCH(GRAPHKV_K_COSINE_BOUND,
+                               launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.m, g, false, new_src, n_new,
+                                                        at<char>(ws, W.bound_hist), tau, ovf, st));
+                    GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
+                               launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.m, g, false, new_src, n_new, tau,
+                                                         cand, cnt, ovf, st));
+                    GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
+                               launch_nbr_select(cand, cnt, ovf, src, D.H, D.m, g, &sel, nbr, ev, st));
+                    GKV_LAUNCH(GRAPHKV_K_REDO_ROWS,
+                               launch_redo_rows(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, ovf, E, nbr, ev, st));
                 }
-                GKV_LAUNCH(GRAPHKV_K_COSINE_BOUND,
-                           launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.S, D.m, fsrc, n_new,
-                                                    at<char>(ws, W.bound_hist), tau, ovf, st));
-                GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
-                           launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.S, D.m, fsrc, n_new, tau, cand,
-                                                     cnt, ovf, st));
-                GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
-                           launch_nbr_select(cand, cnt, ovf, fsrc, D.H, D.P, D.S, D.m, ru.code ? &ru : nullptr,
-                                             nbr, ev, st));
-                // heads whose lists overflowed are redone row by row, exactly
-                GKV_LAUNCH(GRAPHKV_K_REDO_ROWS,
-                           launch_redo_rows(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, ovf, E, nbr, ev, st));
             } else {
+                // Eq. 2: source nodes
+                GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES,
+                           launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, nullptr, 0, 0,
+                                            nullptr, 1, st));
                 // Eq. 1: edges from every source to every node
                 if (D.mfma_cosine)
                     GKV_LAUNCH(GRAPHKV_K_COSINE, launch_mfma_cosine(Ac, Kc, D.H, D.N, D.P, D.S, src, E, nullptr, st));
@@ -389,11 +428,11 @@ int32_t run_select(const Dims &D, const LayerPlan &plan, const float *scores, in
 }
 
 // The whole pass for a batch of n_layers contiguous layers (n_layers <= kMaxLayers).
-int32_t run_compress(const graphkv_params *p, int n_layers, const int32_t *budgets, const void *Kc,
+int32_t run_compress(const graphkv_params *p, int n_layers, bool speculate, const int32_t *budgets, const void *Kc,
                      const void *Vc, const void *Qw, void *Kout, void *Vout, int32_t *idx,
                      float *scores_out, void *ws, hipStream_t st)
 {
-    const Dims D = dims_of(p, n_layers);
+    const Dims D = dims_of(p, n_layers, speculate);
     const Workspace W = carve(p, D);
     int max_budget = 0;
     const LayerPlan plan = make_plan(p, n_layers, budgets, &max_budget);
@@ -416,12 +455,22 @@ int32_t run_compress(const graphkv_params *p, int n_layers, const int32_t *budge
 // while the scratch memory of a group would exceed 1.5 GiB (long prompts: the candidate lists
 // and vote rows grow with the number of heads in flight).
 constexpr size_t kGroupScratchCap = (size_t)1536 << 20;
-int group_layers(const graphkv_params *p, int n_layers)
+// The speculative rows of the filter route cost scratch too: they are dropped before a group is
+// made smaller.
+Dims group_dims(const graphkv_params *p, int n_layers)
 {
     int g = n_layers < kMaxLayers ? n_layers : kMaxLayers;
-    while (g > 1 && ((long)p->n_kv_heads * g > 65535 || carve(p, dims_of(p, g)).total > kGroupScratchCap))
+    while (true) {
+        const bool fits_heads = (long)p->n_kv_heads * g <= 65535;
+        if (fits_heads) {
+            for (int speculate = 1; speculate >= 0; --speculate) {
+                const Dims D = dims_of(p, g, speculate != 0);
+                if (carve(p, D).total <= kGroupScratchCap || (g == 1 && !speculate)) return D;
+            }
+        }
+        if (g == 1) return dims_of(p, 1, false);
         g = (g + 1) / 2;
-    return g;
+    }
 }
 
 bool budgets_ok(const graphkv_params *p, int n_layers, const int32_t *budgets)
@@ -453,7 +502,7 @@ int32_t graphkv_score(const graphkv_params *p, const void *Kc, const void *Qw, f
 {
     if (!base_ok(p) || !score_ok(p)) return GRAPHKV_EINVAL;
     if (!aligned16(Kc) || !aligned16(Qw) || !aligned4(scores)) return GRAPHKV_EINVAL;
-    const Dims D = dims_of(p);
+    const Dims D = group_dims(p, 1);
     const Workspace W = carve(p, D);
     if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
     return run_score(p, D, W, Kc, Qw, scores, ws, (hipStream_t)stream);
@@ -480,7 +529,7 @@ int32_t graphkv_propagate_edges(const graphkv_params *p, const void *Ac, const v
     if ((dbg_src && !aligned4(dbg_src)) || (dbg_nbr && !aligned4(dbg_nbr)) ||
         (dbg_e && !aligned4(dbg_e)))
         return GRAPHKV_EINVAL;
-    const Dims D = dims_of(p);
+    const Dims D = group_dims(p, 1);
     const Workspace W = carve(p, D);
     if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
     return run_propagate(p, D, W, Ac, Bc, scores, dbg_src, dbg_nbr, dbg_e, ws,
@@ -529,7 +578,7 @@ int32_t graphkv_compress_static(const graphkv_params *p, const void *Kc, const v
 size_t graphkv_workspace_bytes_batched(const graphkv_params *p, int32_t n_layers)
 {
     if (!base_ok(p) || n_layers < 1) return 0;
-    return carve(p, dims_of(p, group_layers(p, n_layers))).total;
+    return carve(p, group_dims(p, n_layers)).total;
 }
 
 int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, const int32_t *budgets,
@@ -545,8 +594,9 @@ int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, cons
         !aligned16(Vout) || !aligned4(idx))
         return GRAPHKV_EINVAL;
     if (scores_out && !aligned4(scores_out)) return GRAPHKV_EINVAL;
-    const int group = group_layers(p, n_layers);
-    const Workspace W = carve(p, dims_of(p, group));
+    const Dims DG = group_dims(p, n_layers);   // layers per group, and whether its filter passes speculate
+    const int group = DG.L;
+    const Workspace W = carve(p, DG);
     if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
     hipStream_t st = (hipStream_t)stream;
     const size_t esize = p->dtype == GRAPHKV_FP32 ? 4 : 2;
@@ -558,7 +608,7 @@ int32_t graphkv_compress_batched(const graphkv_params *p, int32_t n_layers, cons
         const int nl = n_layers - l0 < group ? n_layers - l0 : group;
         const int32_t *bl = budgets ? budgets + l0 : nullptr;
         const int32_t rc = run_compress(
-            p, nl, bl, (const char *)Kc + l0 * kv_layer, (const char *)Vc + l0 * kv_layer,
+            p, nl, DG.speculate, bl, (const char *)Kc + l0 * kv_layer, (const char *)Vc + l0 * kv_layer,
             Qw ? (const char *)Qw + l0 * q_layer : nullptr, (char *)Kout + out_rows * p->head_dim * esize,
             (char *)Vout + out_rows * p->head_dim * esize, idx + out_rows,
             scores_out ? scores_out + l0 * s_layer : nullptr, ws, st);

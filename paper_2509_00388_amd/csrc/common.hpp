@@ -83,4 +83,25 @@ __device__ __forceinline__ float block_sum(float v, float *red) {
     return r;
 }
 
+// The m-th largest of the keys in the first NIT registers of every lane (unused registers
+// hold 0, below every key), all between kmin and kmax: built bit by bit from the top; the
+// count of the keys that reach a trial value is one wave vote per register.  Straight-line
+// code for a given NIT: branches between the votes would cost more than the votes.
+template <int NIT, int R>
+__device__ __forceinline__ uint32_t mth_largest_key(const uint32_t (&E)[R], uint32_t kmin, uint32_t kmax, int m)
+{
+    static_assert(NIT <= R, "");
+    uint32_t tau = kmin;
+    if (kmax > kmin) {
+        for (int b = 31 - __clz(kmax - kmin); b >= 0; --b) {
+            const uint32_t trial = tau + (1u << b);   // bits below b of tau - kmin are still 0
+            int reach = 0;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) reach += (int)__popcll(__ballot(E[it] >= trial));
+            if (trial > tau && reach >= m) tau = trial;   // (a trial that wrapped around is beyond every key)
+        }
+    }
+    return tau;
+}
+
 }  // namespace gkv

@@ -27,6 +27,12 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k,
                             float *tau_out, int append_from, int append_count,
                             const int32_t *gate, int rows_per_gate, hipStream_t st);
 
+// Source nodes (Eq. 2) plus the X nodes ranked right behind them: src [rows, S] gets the S
+// best entries of each row (ascending index), ext [rows, S + X] the same S followed by the next
+// X (ascending index), by (value descending, index ascending).  4096 < n, S + X <= kMaxExtSources.
+hipError_t launch_pick_sources(const float *x, long ld, int n, int rows, int S, int X, int32_t *src,
+                               int32_t *ext, hipStream_t st);
+
 // Neighbourhoods of the heads whose overflow flag is set (filter route, bf16, d = 128): a fixed
 // number of workgroups walk the (head, source) rows of those heads, each computing one row of
 // edges into its own scratch row (rows: redo_rows_scratch_bytes()) and taking the exact top-m.
@@ -97,44 +103,61 @@ hipError_t launch_mfma_cosine(const void *Ac, const void *Kc, int Hkv, int N, in
 bool mfma_filter_applies(int P, int m);
 int mfma_sample_cols(int P);          // keys in the strided sample
 int mfma_cand_cap(int P, int m);      // candidates per source the exact select can take
-struct MfmaFilterGeom {
+bool source_reuse_applies(int S);     // lists can be kept from round to round
+constexpr int kSpecRows = 32;         // speculative rows per head: one MFMA row block
+constexpr int kMaxExtSources = 256;   // largest S + kSpecRows the source selection splits
+// Geometry of the filter route for one call.  The per-row buffers (tau [Hkv, pitch], cand
+// [Hkv, pitch, chunks, slice_cap] x 8 bytes, cand_cnt [Hkv, pitch, chunks]) hold, per head,
+// the S sources of the first round, then X speculative rows (the nodes ranked right behind the
+// sources: the likeliest new sources of later rounds, whose candidate lists the first round's
+// pass builds on the side), then fb_rows rows for new sources of later rounds that have no kept
+// list.  Without speculation (X = 0) nothing outlives a round and later rounds reuse rows 0 .. S.
+struct MfmaFilterPlan {
+    int S, X;
+    int sb;           // 32-row groups per workgroup in the passes over the full source list
+    int pitch;        // S + X
     int chunk_cols;   // keys per workgroup of the filter pass
-    int chunks;       // workgroups (= candidate slices) per head
-    int slice_cap;    // entries per (source, chunk) slice
+    int chunks;       // workgroups (= candidate slices) per head and source group
+    int slice_cap;    // entries per (row, chunk) slice
+    int cand_cap;     // entries the exact select can take per row
 };
-MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m);
-// tau [Hkv, S]: a lower bound of each source's m-th largest edge, from the edges to every
-// (P / sample_cols)-th key (within 1/256 of the m-th largest sampled edge); clears overflow [Hkv].
-size_t mfma_bound_scratch_bytes(int Hkv, int P, int S);   // per-chunk histograms (0 if one chunk)
-// n_src (bound and filter pass): null, or [Hkv] rows of each head's source list in use; the
-// arrays keep their pitch of S rows.
-hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                    const int32_t *src, const int32_t *n_src, void *hist_part, float *tau,
-                                    int32_t *overflow, hipStream_t st);
-// Streams all keys; edges that reach tau[h, a] go to cand [Hkv, S, chunks, slice_cap] x 8
-// bytes, their number per slice to cand_cnt [Hkv, S, chunks].
-hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                     const int32_t *src, const int32_t *n_src, const float *tau, void *cand,
-                                     int32_t *cand_cnt, int32_t *overflow, hipStream_t st);
-// Exact top-m over each source's slices -> nbr / nbr_e [Hkv, S, m]; skips heads with
-// overflow[h], and raises overflow[h] itself if a source has more candidates than it can take.
-// Neighbour lists kept from the previous round: Eq. 1 and Eq. 3 depend on the keys alone, so
-// a source that was one in the previous round has the same neighbourhood.
-struct SourceReuse {
-    const int32_t *n_new;      // [Hkv] sources that were none in the previous round
-    const int32_t *code;       // [Hkv, S] per source: its slot in the previous round, or -1 - r (r-th new one)
-    const int32_t *new_pos;    // [Hkv, S] slot of the r-th new source in this round's list
+MfmaFilterPlan mfma_filter_plan(int Hkv, int P, int S, int m, bool keep_lists, bool speculate);
+size_t mfma_bound_scratch_bytes(int Hkv, int P, const MfmaFilterPlan &g);   // per-chunk histograms (0 if one chunk)
+// Bound pass: tau = a lower bound of each row's m-th largest edge, from the edges to every
+// (P / sample_cols)-th key; clears overflow [Hkv].  first_round: src is the extended list
+// [Hkv, S + X] (all rows in use, rows 0 .. of the buffers); otherwise src is the list of new
+// sources [Hkv, S], n_src [Hkv] of them in use, rows 0 .. of the buffers.
+hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int m,
+                                    const MfmaFilterPlan &g, bool first_round, const int32_t *src,
+                                    const int32_t *n_src, void *hist_part, float *tau, int32_t *overflow,
+                                    hipStream_t st);
+// Filter pass: streams all keys; edges that reach a row's tau go to its slices, their number
+// per slice to cand_cnt.  Same source lists and rows as the bound pass.
+hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int m,
+                                     const MfmaFilterPlan &g, bool first_round, const int32_t *src,
+                                     const int32_t *n_src, const float *tau, void *cand, int32_t *cand_cnt,
+                                     int32_t *overflow, hipStream_t st);
+// From the second round on: which sources keep their list from the round before (copied from
+// prev_nbr / prev_e to nbr / nbr_e), which are speculative rows of the first round (the last X
+// entries of ext [Hkv, S + X]; not used for heads that overflowed then: spec_bad [Hkv], set by the first match of
+// a call from the first round's overflow flags), and which need another bound and filter pass
+// (new_src [Hkv, S], n_new [Hkv]).  sel_row / sel_pos [Hkv, S], n_sel [Hkv]: the selections to
+// run as (candidate row, source slot).
+hipError_t launch_match_sources(const int32_t *prev, const int32_t *cur, int Hkv, int m, const MfmaFilterPlan &g,
+                                const int32_t *prev_nbr, const float *prev_e, int32_t *nbr, float *nbr_e,
+                                const int32_t *ext, int32_t *spec_bad, const int32_t *overflow, bool first_match,
+                                int32_t *new_src, int32_t *n_new, int32_t *sel_row, int32_t *sel_pos,
+                                int32_t *n_sel, hipStream_t st);
+// Exact top-m over candidate rows -> nbr / nbr_e [Hkv, S, m]; skips heads with overflow[h], and
+// raises overflow[h] itself if a row has more candidates than it can take.  rows == nullptr:
+// candidate row x -> source slot x for all S sources of src [Hkv, S]; otherwise the listed ones.
+struct SelectRows {
+    const int32_t *n_rows;   // [Hkv] selections per head
+    const int32_t *row;      // [Hkv, S] candidate row of the x-th selection
+    const int32_t *pos;      // [Hkv, S] its source slot in this round's list
 };
-bool source_reuse_applies(int S);
-// prev, cur [Hkv, S] ascending -> code, new_pos as above, new_src [Hkv, S] (the new sources in
-// order, n_new[h] of them); copies the lists of the sources that stay from prev_nbr / prev_e
-// [Hkv, S, m] to their slots in nbr / nbr_e.
-hipError_t launch_match_sources(const int32_t *prev, const int32_t *cur, int Hkv, int S, int m,
-                                const int32_t *prev_nbr, const float *prev_e, int32_t *code, int32_t *new_src,
-                                int32_t *new_pos, int32_t *n_new, int32_t *nbr, float *nbr_e, hipStream_t st);
-// reuse: null, or the candidate rows are those of the new sources (src = new_src).
-hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t *overflow,
-                             const int32_t *src, int Hkv, int P, int S, int m, const SourceReuse *reuse,
-                             int32_t *nbr, float *nbr_e, hipStream_t st);
+hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t *overflow, const int32_t *src,
+                             int Hkv, int m, const MfmaFilterPlan &g, const SelectRows *rows, int32_t *nbr,
+                             float *nbr_e, hipStream_t st);
 
 }  // namespace gkv

@@ -18,9 +18,14 @@
 // A source whose list overflows (masses of equal edges, adversarial order) sets
 // a per-head flag and that head is redone through the dense block instead.
 //
-// From the second round on only the sources that were none in the round before
-// go through these passes (a neighbourhood depends on the keys alone): the others
-// keep their lists, and the kernels take a per-head count of rows in use.
+// A neighbourhood depends on the keys alone, so a source that comes back in a later
+// round keeps its list.  The first round's passes also take a third 32-row group per
+// workgroup: the nodes ranked right behind the sources, which are the likeliest new
+// sources of the following rounds (the decay only lowers scores, so whoever moves up
+// comes from just below the cut).  Their candidate lists are kept, and a later round
+// runs the exact select on them when they are promoted; only a new source without a
+// kept list goes through the bound and filter passes again (a per-head count of rows
+// in use; heads without such a source return at once).
 #include "common.hpp"
 #include "kernels.hpp"
 #include "mfma_tile.hpp"
@@ -35,38 +40,19 @@ constexpr int kSB = 2;            // source blocks of 32 per workgroup = row gro
 constexpr int kRows = kSB * kBlk; // source rows per workgroup
 constexpr int kThreads = 256 * kSB;
 
-// 1/|k| from |k|^2 with the hardware reciprocal square root (1 ulp), 0 for a zero key.
-// Every MFMA-path edge uses this one function, so the sampled bound and the filtered
-// edges are computed bit for bit alike.
-__device__ __forceinline__ float inv_norm(float sq)
-{
-    return sq == 0.f ? 0.f : __builtin_amdgcn_rsqf(sq);
-}
-
-// Sum of squares of the 64 elements a lane holds of its row (8 k-steps x 8),
-// two bf16 products per instruction, fp32 accumulation.
-__device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
-{
-    float a = 0.f;
-#pragma unroll
-    for (int s = 0; s < kSteps; ++s)
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            const bf16x2 v = {r[s][e], r[s][e + 1]};
-            a = __builtin_amdgcn_fdot2_f32_bf16(v, v, a, false);
-        }
-    return a;
-}
-
+// The per-row buffers (tau, cand, cand_cnt) hold `pitch` rows per head; the rows of one launch's
+// source list start at row `row0` of them.
 struct FilterArgs {
     const int32_t *n_src;  // [Hkv] rows of the head's source list in use; null: all S
-    const float *tau;      // [Hkv, S] lower bound of each source's m-th largest edge
-    uint2 *cand;           // [Hkv, S, chunks, slice_cap] (edge bits, key index): one slice per key chunk
-    int32_t *cand_cnt;     // [Hkv, S, chunks] entries in each slice
+    const float *tau;      // [Hkv, pitch] lower bound of each row's m-th largest edge
+    uint2 *cand;           // [Hkv, pitch, chunks, slice_cap] (edge bits, key index): one slice per key chunk
+    int32_t *cand_cnt;     // [Hkv, pitch, chunks] entries in each slice
     int32_t *overflow;     // [Hkv]
     int slice_cap;
     int drain_every;       // tiles between two scheduled drains of the rings
-    int sgroups;           // groups of 64 sources
+    int sgroups;           // workgroups (groups of source rows) per key chunk
+    int src_pitch;         // entries per head of the source list
+    int pitch, row0;
 };
 
 // Both kernels below: a workgroup has 4 key streams (wave & 3) and 2 source row
@@ -79,7 +65,7 @@ struct FilterArgs {
 // Sources are rows of Ac, the streamed rows are rows of Kc (both [Hkv, N, 128]); for
 // Eq. 1 both are the keys, the other pairings of the paper's Discussion pass two tensors.
 // This wave's 32 source rows -> MFMA operand registers (slots beyond S repeat the
-// last source); 1/|k_i| and the source index of the 64 rows of the group go to LDS.
+// last source); 1/|k_i| and the source index of the workgroup's rows go to LDS.
 __device__ __forceinline__ void load_sources(const uint16_t *Ah, const int32_t *src_h, int S,
                                              int s_base, int grp, int stream, int l32, int hh,
                                              bf16x8 (&q)[kSteps], float *inv_s, int32_t *idx_s)
@@ -167,12 +153,11 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
 // from the top reaches m: at most 1/256 below the m-th largest sampled edge.  (An
 // edge a rounding error below a bin edge may be counted into the bin above; the
 // filter pass lowers every bound by far more than that.)  The source's own column
-// is left out (Eq. 3: j != i).  Also clears the head's overflow flag for the filter
-// pass that follows.
-constexpr int kBoundBins = 512;
-
-// One wave, one source: lane L holds the packed counters of bins 8L .. 8L+7 in w4.  Finds
-// the bin in which the count from the top reaches m and writes its lower edge.
+// is taken out of the counts at the end (Eq. 3: j != i).  Also clears the head's
+// overflow flag for the filter pass that follows.
+// One wave, one source: lane L holds the packed counters of bins 8L .. 8L+7 in w4 (zeros beyond
+// the last bin).  Finds the bin in which the count from the top reaches m and writes its lower edge.
+template <int BINS>
 __device__ __forceinline__ void bound_from_histogram(const uint4 w4, int m, int lane, float *tau_row)
 {
     const uint32_t c[8] = {w4.x & 0xffffu, w4.x >> 16, w4.y & 0xffffu, w4.y >> 16,
@@ -194,46 +179,54 @@ __device__ __forceinline__ void bound_from_histogram(const uint4 w4, int m, int 
             if (cum + c[k] >= (uint32_t)m) break;
             cum += c[k];
         }
-        *tau_row = (float)(8 * lane + k) * (2.0f / kBoundBins) - 1.0f;
+        *tau_row = (float)(8 * lane + k) * (2.0f / BINS) - 1.0f;
     }
     if (lane == 0 && from_top < (uint32_t)m) *tau_row = -INFINITY;   // fewer than m sampled edges: no bound
 }
 
-__global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
-    const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride,
-    int S, const int32_t *__restrict__ src, const int32_t *__restrict__ n_src, int m, int chunk_cols,
-    uint32_t *__restrict__ hist_part, float *__restrict__ tau, int32_t *__restrict__ overflow)
+// Lane L's eight packed counters of one histogram row (BINS / 2 words).
+template <int BINS>
+__device__ __forceinline__ uint4 histogram_words(const uint32_t *row, int lane)
 {
-    __shared__ float inv_s[kRows];
-    __shared__ int32_t idx_s[kRows];
+    return lane < BINS / 8 ? *reinterpret_cast<const uint4 *>(row + 4 * lane) : make_uint4(0, 0, 0, 0);
+}
+
+// SB 32-row groups of sources per workgroup (4 SB waves); BINS bins over [-1, 1]: 512 for two
+// groups, 448 for three (the histograms of 96 rows and the two key tiles must fit the LDS), so
+// the bound is at most 2 / BINS below the m-th largest sampled edge.
+template <int SB, int BINS>
+__global__ __launch_bounds__(256 * SB) void cosine_bound_kernel(
+    const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int key_stride,
+    int S, int src_pitch, const int32_t *__restrict__ src, const int32_t *__restrict__ n_src, int m,
+    int chunk_cols, uint32_t *__restrict__ hist_part, float *__restrict__ tau, int pitch, int row0,
+    int32_t *__restrict__ overflow)
+{
+    constexpr int ROWS = SB * kBlk, NT = 256 * SB;
+    __shared__ float inv_s[ROWS];
+    __shared__ int32_t idx_s[ROWS];
     extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the histograms
     unsigned char *kt = smem;
-    uint32_t *hist = reinterpret_cast<uint32_t *>(smem + 2 * kTileBytes);   // [kRows][kBoundBins / 2]
+    uint32_t *hist = reinterpret_cast<uint32_t *>(smem + 2 * kTileBytes);   // [ROWS][BINS / 2]
 
     // with few heads the sample is cut into chunks (blockIdx.z) whose histograms are added up
     // by bound_merge_kernel: otherwise a handful of workgroups would walk the sample alone
-    const int h = blockIdx.y, s_base = blockIdx.x * kRows, chunk = blockIdx.z;
+    const int h = blockIdx.y, s_base = blockIdx.x * ROWS, chunk = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, grp = wv >> 2;
     const uint16_t *Kh = Kc + (long)h * N * kD;
     const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
     if (blockIdx.x == 0 && chunk == 0 && tid == 0) overflow[h] = 0;
-    // rows of this head's source list in use (the arrays keep their pitch of S rows)
+    // rows of this head's source list in use
     const int Sh = n_src ? n_src[h] : S;
     if (s_base >= Sh) return;
 
     bf16x8 q[kSteps];
-    load_sources(Ac + (long)h * N * kD, src + (long)h * S, Sh, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
-    for (int u = tid; u < kRows * (kBoundBins / 2); u += kThreads) hist[u] = 0;
+    load_sources(Ac + (long)h * N * kD, src + (long)h * src_pitch, Sh, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
+    for (int u = tid; u < ROWS * (BINS / 2); u += NT) hist[u] = 0;
     __syncthreads();
     float inv_src[16];
-    int32_t self[16];   // the source's own key; -1 for rows past S: those count nothing
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int row = kBlk * grp + acc_row(i, hh);
-        inv_src[i] = inv_s[row];
-        self[i] = s_base + row < Sh ? idx_s[row] : -1;
-    }
+    for (int i = 0; i < 16; ++i) inv_src[i] = inv_s[kBlk * grp + acc_row(i, hh)];
 
     const int ntile = c1 > c0 ? (c1 - c0 + kTileKeys - 1) / kTileKeys : 0;
     auto multiply_tile = [&](const unsigned char *buf, int t) {
@@ -250,57 +243,67 @@ __global__ __launch_bounds__(kThreads) void cosine_bound_kernel(
         sq += __shfl_xor(sq, 32, kWave);
         const float inv_k = inv_norm(sq);
         const int col = c0 + kTileKeys * t + kBlk * stream + l32;
-        const int key = col * key_stride;
         if (col < c1) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                if (self[i] >= 0 && key != self[i]) {
-                    const float e = (acc[i] * inv_k) * inv_src[i];   // the dense kernel's formula
-                    int b = (int)((e + 1.0f) * (0.5f * kBoundBins));
-                    b = b < 0 ? 0 : (b > kBoundBins - 1 ? kBoundBins - 1 : b);
-                    atomicAdd(&hist[(kBlk * grp + acc_row(i, hh)) * (kBoundBins / 2) + (b >> 1)],
-                              (b & 1) ? 65536u : 1u);
-                }
+                const float e = (acc[i] * inv_k) * inv_src[i];   // the dense kernel's formula
+                int b = (int)((e + 1.0f) * (0.5f * BINS));
+                b = b < 0 ? 0 : (b > BINS - 1 ? BINS - 1 : b);
+                atomicAdd(&hist[(kBlk * grp + acc_row(i, hh)) * (BINS / 2) + (b >> 1)], (b & 1) ? 65536u : 1u);
             }
         }
     };
-    if (ntile > 0) GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, key_stride, ntile, multiply_tile, (void)0);
+    if (ntile > 0) GKV_TILE_PIPELINE(NT, Kh, c0, c1 - 1, key_stride, ntile, multiply_tile, (void)0);
+    __syncthreads();
+    // The source's own column is no neighbour (Eq. 3: j != i).  If it is one of the sampled
+    // keys of this workgroup it was counted into the top bin (its edge is 1 up to rounding;
+    // a zero source, all of whose edges are 0, has nothing there): take it out again.
+    if (tid < ROWS) {
+        const int32_t i = idx_s[tid];
+        const int col = i / key_stride;
+        if (i % key_stride == 0 && col >= c0 && col < c1) {
+            uint32_t &top = hist[tid * (BINS / 2) + (BINS - 1) / 2];
+            if ((top >> 16) > 0u) top -= 65536u;
+        }
+    }
     __syncthreads();
 
     if (gridDim.z > 1) {   // this chunk's counts go to global memory
         uint4 *out = reinterpret_cast<uint4 *>(
-            hist_part + ((((long)h * gridDim.x + blockIdx.x) * gridDim.z + chunk) * kRows) * (kBoundBins / 2));
+            hist_part + ((((long)h * gridDim.x + blockIdx.x) * gridDim.z + chunk) * ROWS) * (BINS / 2));
         const uint4 *in = reinterpret_cast<const uint4 *>(hist);
-        for (int u = tid; u < kRows * (kBoundBins / 2) / 4; u += kThreads) out[u] = in[u];
+        for (int u = tid; u < ROWS * (BINS / 2) / 4; u += NT) out[u] = in[u];
         return;
     }
     // Wave w scans the histograms of rows 8w .. 8w+7 from the top; lane L holds bins 8L .. 8L+7.
-    for (int r = 0; r < kRows / (kThreads / kWave); ++r) {
-        const int row = wv * (kRows / (kThreads / kWave)) + r;
-        const uint4 w4 = *reinterpret_cast<const uint4 *>(&hist[row * (kBoundBins / 2) + 4 * lane]);
-        if (s_base + row < Sh) bound_from_histogram(w4, m, lane, &tau[(long)h * S + s_base + row]);
+    for (int r = 0; r < 8; ++r) {
+        const int row = wv * 8 + r;
+        const uint4 w4 = histogram_words<BINS>(&hist[row * (BINS / 2)], lane);
+        if (s_base + row < Sh) bound_from_histogram<BINS>(w4, m, lane, &tau[(long)h * pitch + row0 + s_base + row]);
     }
 }
 
 // Adds up the histograms of the sample's chunks (16-bit counters, two to a word: a bin's
 // total is at most the sample size, which stays below 65536) and takes the bound.  One
 // wave per source.
+template <int SB, int BINS>
 __global__ __launch_bounds__(256) void bound_merge_kernel(const uint32_t *__restrict__ hist_part,
                                                           int chunks, int sgroups, int S,
                                                           const int32_t *__restrict__ n_src, int m,
-                                                          float *__restrict__ tau)
+                                                          float *__restrict__ tau, int pitch, int row0)
 {
+    constexpr int ROWS = SB * kBlk;
     const int lane = threadIdx.x & 63;
     const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), h = blockIdx.y;
     if (slot >= (n_src ? n_src[h] : S)) return;
-    const int sg = slot / kRows, row = slot % kRows;
+    const int sg = slot / ROWS, row = slot % ROWS;
     uint4 w4 = make_uint4(0, 0, 0, 0);
     for (int c = 0; c < chunks; ++c) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(
-            hist_part + ((((long)h * sgroups + sg) * chunks + c) * kRows + row) * (kBoundBins / 2) + 4 * lane);
+        const uint4 v = histogram_words<BINS>(
+            hist_part + ((((long)h * sgroups + sg) * chunks + c) * ROWS + row) * (BINS / 2), lane);
         w4.x += v.x; w4.y += v.y; w4.z += v.z; w4.w += v.w;
     }
-    bound_from_histogram(w4, m, lane, &tau[(long)h * S + slot]);
+    bound_from_histogram<BINS>(w4, m, lane, &tau[(long)h * pitch + row0 + slot]);
 }
 
 // Filter pass over all keys.  A lane holds, per key block, the 16 dots of its key
@@ -313,29 +316,32 @@ __global__ __launch_bounds__(256) void bound_merge_kernel(const uint32_t *__rest
 // Every few tiles (a schedule the host derives from the expected hit rate, so
 // that most of a half-wave's 32 lanes get a row) all waves drain their rings at
 // the same time -- a drain is a chain of LDS round trips, and a wave that drains
-// alone would keep the other seven waiting at the tile barrier.  A half-wave
+// alone would keep the others waiting at the tile barrier.  A half-wave
 // drains its own ring, so the 16 sources of a parked row are the draining lane's
-// own 16 sources and their 1/|k_i| and bounds sit in registers: the dots become
-// exact edges (the dense kernel's formula, bit for bit), and those that reach the
-// bound are appended to the workgroup's own slice of each source's global
+// own 16 sources and their bounds sit in registers: the same test picks the row's
+// hits, their dots become exact edges (the dense kernel's formula, bit for bit),
+// and they are appended to the workgroup's own slice of each source's global
 // candidate list (one slice per key chunk, so no workgroup ever waits for
-// another: positions come from LDS counters).  A ring holds 64 rows and a wave
-// drains on its own whenever a half has more than 32 waiting, so a tile's 32
-// rows at most always fit.  The source's own column may be among the candidates:
+// another: positions come from LDS counters).  A ring holds RING rows (64 with two
+// row groups per workgroup, 32 with three: the rings share the LDS with the key
+// tiles); before a tile's rows are parked a wave drains on its own if a ring could
+// not take them.  The source's own column may be among the candidates:
 // the exact select drops it.  If a slice (or one of the short LDS lists that take
 // a row's hits beyond its fourth) overflows, the head's overflow flag is raised and
-// the head is redone densely.
-constexpr int kRingRows = 64;      // rows per half-wave ring
+// the head is redone exactly, row by row.
 constexpr int kStagePitch = 80;    // bytes per parked row: 16 dots, |k|^2, key (72, padded)
 constexpr int kLaterCap = 128;     // entries of each of the two LDS lists of hits beyond a row's fourth
 
-__global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
+template <int SB, int RING>
+__global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
     const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int n_cols, int S,
     const int32_t *__restrict__ src, int chunk_cols, FilterArgs fa)
 {
-    __shared__ float inv_s[kRows], lo_s[kRows], det_s[kRows];
-    __shared__ int32_t idx_s[kRows];
-    __shared__ int32_t row_pos[kRows];   // entries written to each source's slice
+    constexpr int ROWS = SB * kBlk, NT = 256 * SB;
+    static_assert(RING == 32 || RING == 64, "a ring takes a tile's 32 rows and is indexed with a mask");
+    __shared__ float inv_s[ROWS], det_s[ROWS];
+    __shared__ int32_t idx_s[ROWS];
+    __shared__ int32_t row_pos[ROWS];   // entries written to each source's slice
     // (edge bits, key, source row) of the hits beyond a row's fourth: one list for even and one
     // for odd tiles, each emptied right after the barrier that ends its tile
     __shared__ uint4 later[2][kLaterCap];
@@ -350,7 +356,7 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     // groups of one (head, chunk) unit sit 8 apart: 8 units x all their groups take 8 x sgroups
     // consecutive numbers.  (Unit counts that are no multiple of 8 keep the plain order.)
     const int n_chunks = gridDim.x / fa.sgroups;
-    int h = blockIdx.y, chunk = blockIdx.x / fa.sgroups, s_base = (blockIdx.x % fa.sgroups) * kRows;
+    int h = blockIdx.y, chunk = blockIdx.x / fa.sgroups, s_base = (blockIdx.x % fa.sgroups) * ROWS;
     if (fa.sgroups > 1 && ((long)gridDim.y * n_chunks) % 8 == 0) {
         const long lin = (long)blockIdx.y * gridDim.x + blockIdx.x;
         const long grp8 = lin / (8 * fa.sgroups);
@@ -358,47 +364,43 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
         const long unit = grp8 * 8 + (r & 7);
         h = (int)(unit / n_chunks);
         chunk = (int)(unit % n_chunks);
-        s_base = (r >> 3) * kRows;
+        s_base = (r >> 3) * ROWS;
     }
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     const int stream = wv & 3, grp = wv >> 2;
     const uint16_t *Kh = Kc + (long)h * N * kD;
     const int c0 = chunk * chunk_cols, c1 = min(n_cols, c0 + chunk_cols);
     if (c0 >= n_cols) return;
-    const int Sh = fa.n_src ? fa.n_src[h] : S;   // the arrays keep their pitch of S rows
+    const int Sh = fa.n_src ? fa.n_src[h] : S;
     if (s_base >= Sh) return;
+    const long buf_row0 = (long)h * fa.pitch + fa.row0 + s_base;   // this workgroup's first row of the per-row buffers
 
     bf16x8 q[kSteps];
-    load_sources(Ac + (long)h * N * kD, src + (long)h * S, Sh, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
-    if (tid < kRows) row_pos[tid] = 0;
+    load_sources(Ac + (long)h * N * kD, src + (long)h * fa.src_pitch, Sh, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
+    if (tid < ROWS) row_pos[tid] = 0;
     if (tid < 2) n_later[tid] = 0;
     if (tid == 0) later_lost = 0;
     __syncthreads();
-    if (tid < kRows) {
-        // lo: what an exact edge must reach to be listed; det: the still lower bound of the
-        // in-loop test, expressed for dot / |k_j| (i.e. divided by 1/|k_i|).  Rows past the
-        // last source and impossible bounds never hit; a zero source (all edges 0) hits everywhere.
+    if (tid < ROWS) {
+        // det: what dot / |k_j| must reach for the edge to be listed, i.e. the source's bound,
+        // lowered by twice the slack, divided by 1/|k_i|.  Rows past the last source and
+        // impossible bounds never hit; a zero source (all edges 0) hits everywhere.
         const int slot = s_base + tid;
-        const float t = fa.tau[(long)h * S + min(slot, Sh - 1)];
+        const float t = fa.tau[buf_row0 + min(tid, Sh - 1 - s_base)];
         const float slack = 4e-6f + 1e-5f * fabsf(t);
         const float inv = inv_s[tid];
-        const float lo = t - slack, lo2 = t - 2.f * slack;
-        lo_s[tid] = slot < Sh ? lo : INFINITY;
+        const float lo2 = t - 2.f * slack;
         det_s[tid] = slot >= Sh ? INFINITY : (inv > 0.f ? lo2 / inv : (lo2 <= 0.f ? -INFINITY : INFINITY));
     }
     __syncthreads();
     // this lane's 16 sources: row acc_row(i, hh) of row group grp
-    float det[16], inv16[16], lo16[16];
+    float det[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        det[i] = det_s[kBlk * grp + acc_row(i, hh)];
-        inv16[i] = inv_s[kBlk * grp + acc_row(i, hh)];
-        lo16[i] = lo_s[kBlk * grp + acc_row(i, hh)];
-    }
+    for (int i = 0; i < 16; ++i) det[i] = det_s[kBlk * grp + acc_row(i, hh)];
 
-    unsigned char *ring = stage_mem + (2 * wv + hh) * (kRingRows * kStagePitch);
+    unsigned char *ring = stage_mem + (2 * wv + hh) * (RING * kStagePitch);
     const uint64_t half_before = (hh ? 0xffffffff00000000ull : 0x00000000ffffffffull) & ((1ull << lane) - 1ull);
-    uint2 *slice0 = fa.cand + (((long)h * S + s_base) * n_chunks + chunk) * fa.slice_cap;
+    uint2 *slice0 = fa.cand + (buf_row0 * n_chunks + chunk) * fa.slice_cap;
     const long slice_row_stride = (long)n_chunks * fa.slice_cap;
     // rows ever parked / ever drained by the lower and the upper half-wave (same in every lane)
     int tail0 = 0, tail1 = 0, head0 = 0, head1 = 0;
@@ -412,27 +414,20 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
     auto drain = [&](int par) {
         const int n0 = min(tail0 - head0, kBlk), n1 = min(tail1 - head1, kBlk);
         if (l32 < (hh ? n1 : n0)) {
-            const unsigned char *row_mem = ring + (((hh ? head1 : head0) + l32) & (kRingRows - 1)) * kStagePitch;
+            const unsigned char *row_mem = ring + (((hh ? head1 : head0) + l32) & (RING - 1)) * kStagePitch;
             const float4 *vals = reinterpret_cast<const float4 *>(row_mem);
             const float2 extra = *reinterpret_cast<const float2 *>(row_mem + 64);   // |k|^2, key
             const float inv_k = inv_norm(extra.x);   // the dense kernel's formula
+            const float norm_k = __builtin_amdgcn_sqrtf(extra.x);
             const uint32_t key = __float_as_uint(extra.y);
-            // Nearly every parked row holds a single hit: its edge is picked up on the way
-            // through the 16 tests.
-            uint32_t hits = 0;
-            float e_first = 0.f;
+            uint32_t hits = 0;   // the test that parked the row, source by source
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float4 dv = vals[v];
                 const float d4[4] = {dv.x, dv.y, dv.z, dv.w};
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = 4 * v + u;
-                    const float e = (d4[u] * inv_k) * inv16[i];
-                    const bool in = e >= lo16[i];
-                    e_first = (in && hits == 0) ? e : e_first;
-                    hits |= (in ? 1u : 0u) << i;
-                }
+                for (int u = 0; u < 4; ++u)
+                    hits |= (fmaf(-det[4 * v + u], norm_k, d4[u]) >= 0.f ? 1u : 0u) << (4 * v + u);
             }
             long off[4];
             float ev[4];
@@ -444,8 +439,7 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
                     const int i = __ffs(hits) - 1;
                     hits &= hits - 1;
                     const int row = kBlk * grp + acc_row(i, hh);
-                    ev[k] = k == 0 ? e_first
-                                   : (reinterpret_cast<const float *>(row_mem)[i] * inv_k) * inv_s[row];
+                    ev[k] = (reinterpret_cast<const float *>(row_mem)[i] * inv_k) * inv_s[row];
                     const int at = atomicAdd(&row_pos[row], 1);
                     if (at < fa.slice_cap) off[k] = row * slice_row_stride + at;
                 }
@@ -496,29 +490,33 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
         const int key = c0 + kTileKeys * t + kBlk * stream + l32;
         const bool hit = best >= 0.f && key < c1;
         const uint64_t hit_lanes = __ballot(hit);
+        const int add0 = (int)__popcll(hit_lanes & 0x00000000ffffffffull), add1 = (int)__popcll(hit_lanes >> 32);
+        // a ring that could not take this tile's rows is drained first: one pass takes up to
+        // 32 rows out, after which the (at most 32) new rows fit
+        if (tail0 - head0 + add0 > RING || tail1 - head1 + add1 > RING) drain(t & 1);
         if (hit) {
             const int at = (hh ? tail1 : tail0) + (int)__popcll(hit_lanes & half_before);
-            unsigned char *row_mem = ring + (at & (kRingRows - 1)) * kStagePitch;
+            unsigned char *row_mem = ring + (at & (RING - 1)) * kStagePitch;
 #pragma unroll
             for (int v = 0; v < 4; ++v)
                 *reinterpret_cast<float4 *>(row_mem + 16 * v) =
                     make_float4(acc[4 * v], acc[4 * v + 1], acc[4 * v + 2], acc[4 * v + 3]);
             *reinterpret_cast<float2 *>(row_mem + 64) = make_float2(sq, __int_as_float(key));
         }
-        tail0 += (int)__popcll(hit_lanes & 0x00000000ffffffffull);
-        tail1 += (int)__popcll(hit_lanes >> 32);
-        // A scheduled drain empties the rings: two passes of 32 rows per half-wave at most.
-        // It sits here, in front of the tile's prefetch loads: the drain's stores are then
-        // older than those loads, and the wait in front of the next LDS store of a key tile
-        // -- a count of memory operations still in flight -- lets the loads stay in flight.
-        // Otherwise a ring must at least be able to take the next tile's 32 rows (at most 64
-        // wait: one pass suffices).
-        if (t % de == de - 1) { drain(t & 1); drain(t & 1); }
-        else if (tail0 - head0 > kRingRows - kBlk || tail1 - head1 > kRingRows - kBlk) drain(t & 1);
+        tail0 += add0;
+        tail1 += add1;
+        // A scheduled drain empties the rings (a pass takes 32 rows per half-wave).  It sits
+        // here, in front of the tile's prefetch loads: the drain's stores are then older than
+        // those loads, and the wait in front of the next LDS store of a key tile -- a count of
+        // memory operations still in flight -- lets the loads stay in flight.
+        if (t % de == de - 1) {
+            drain(t & 1);
+            if (RING > kBlk) drain(t & 1);
+        }
     };
     // Entries listed during the tile that just ended are final behind its barrier, and the next
     // tile lists into the other list: one thread per entry stores them.  A list holds
-    // kLaterCap entries; more than that in one tile and the head is redone densely.
+    // kLaterCap entries; more than that in one tile and the head is redone exactly.
     int later_seen[2] = {0, 0};
     auto store_later = [&](int par) {
         const int n = n_later[par];
@@ -531,15 +529,15 @@ __global__ __launch_bounds__(kThreads) void cosine_filter_kernel(
             if (at < fa.slice_cap) slice0[(long)r.z * slice_row_stride + at] = make_uint2(r.x, r.y);
         }
     };
-    GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, 1, ntile, multiply_tile, store_later((tile_done - 1) & 1));
+    GKV_TILE_PIPELINE(NT, Kh, c0, c1 - 1, 1, ntile, multiply_tile, store_later((tile_done - 1) & 1));
     drain(ntile & 1);
     drain(ntile & 1);
     __syncthreads();
     store_later(ntile & 1);
     __syncthreads();      // every candidate is counted
-    if (tid < kRows && s_base + tid < Sh) {
+    if (tid < ROWS && s_base + tid < Sh) {
         const int c = row_pos[tid];
-        fa.cand_cnt[((long)h * S + s_base + tid) * n_chunks + chunk] = c < fa.slice_cap ? c : fa.slice_cap;
+        fa.cand_cnt[(buf_row0 + tid) * n_chunks + chunk] = c < fa.slice_cap ? c : fa.slice_cap;
         if (c > fa.slice_cap || later_lost) fa.overflow[h] = 1;
     }
 }
@@ -569,15 +567,15 @@ __device__ __forceinline__ uint32_t ord_key_inv(uint32_t k)
 // in, and of the entries equal to it the `need` lowest key indices are in.  The
 // winners' output position is their rank by key index among themselves.
 //
-// With `ru` (lists kept from the previous round) the candidate rows are those of the
-// sources that are new in this round, in their order, and row x is written to the slot
-// that source has in this round's list.
+// The x-th selection of a head takes candidate row sel.row[h, x] of the per-row buffers
+// (`pitch` rows per head) and writes the list of source slot sel.pos[h, x] of this round
+// (src [Hkv, S]); without those lists row x goes to slot x.
 __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict__ cand,
                                                          const int32_t *__restrict__ cand_cnt,
                                                          int32_t *__restrict__ overflow,
-                                                         const int32_t *__restrict__ src, int S,
+                                                         const int32_t *__restrict__ src, int S, int pitch,
                                                          int chunks, int slice_cap, int cap, int m,
-                                                         SourceReuse ru, int32_t *__restrict__ nbr,
+                                                         SelectRows sel, int32_t *__restrict__ nbr,
                                                          float *__restrict__ nbr_e)
 {
     extern __shared__ __align__(8) uint32_t dyn[];
@@ -587,7 +585,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     __shared__ int32_t cnt_s[256], s_pos;
     __shared__ uint32_t s_self;
     const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int n_rows = ru.code ? ru.n_new[h] : S;
+    const int n_rows = sel.n_rows ? sel.n_rows[h] : S;
     if (overflow[h]) return;
     // Only the edge keys of a list stay in LDS (half the footprint, twice the workgroups per
     // compute unit); the key indices of the winners, and of entries tied at the cut, are fetched
@@ -596,24 +594,24 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     uint64_t *win = reinterpret_cast<uint64_t *>(dyn + cap + (cap & 1));   // [m + kTieRoom] winners
     const int win_cap = m + kTieRoom;
 
-    // slice sizes (thread c: chunk c), source index and output slot of a row: independent loads
-    auto ask = [&](int x, int32_t &cnt_r, int32_t &self_r, int32_t &pos_r) {
-        const long row = (long)h * S + x;
-        cnt_r = tid < chunks ? cand_cnt[row * chunks + tid] : 0;
-        if (tid == 0) {
-            self_r = src[row];
-            pos_r = ru.code ? ru.new_pos[row] : x;
-        }
+    // candidate row and output slot of a selection, then its slice sizes (thread c: chunk c) and
+    // the source's own index: two rounds of independent loads, asked for one selection ahead
+    auto ask = [&](int x, int32_t &cnt_r, int32_t &self_r, int32_t &pos_r, int32_t &crow_r) {
+        const long at = (long)h * S + x;
+        crow_r = sel.row ? sel.row[at] : x;
+        pos_r = sel.pos ? sel.pos[at] : x;
+        cnt_r = tid < chunks ? cand_cnt[((long)h * pitch + crow_r) * chunks + tid] : 0;
+        self_r = src[(long)h * S + pos_r];
     };
-    int32_t cnt_r = 0, self_r = 0, pos_r = 0;
-    if ((int)blockIdx.x < n_rows) ask(blockIdx.x, cnt_r, self_r, pos_r);
+    int32_t cnt_r = 0, self_r = 0, pos_r = 0, crow_r = 0;
+    if ((int)blockIdx.x < n_rows) ask(blockIdx.x, cnt_r, self_r, pos_r, crow_r);
 
     for (int x = blockIdx.x; x < n_rows; x += gridDim.x) {
-        const long row = (long)h * S + x;
+        const long row = (long)h * pitch + crow_r;
         cnt_s[tid] = cnt_r;
         if (tid == 0) { s_self = (uint32_t)self_r; s_pos = pos_r; n_win = 0; }
         __syncthreads();
-        if (x + (int)gridDim.x < n_rows) ask(x + gridDim.x, cnt_r, self_r, pos_r);
+        if (x + (int)gridDim.x < n_rows) ask(x + gridDim.x, cnt_r, self_r, pos_r, crow_r);
         int n = 0;
         for (int c = 0; c < chunks; ++c) n += cnt_s[c];
         if (n > cap) {          // more candidates than the select can hold: redo the head densely
@@ -751,27 +749,6 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     }
 }
 
-// The m-th largest of the keys in the first NIT registers of every lane (unused registers
-// hold 0, below every key), all between kmin and kmax: built bit by bit from the top; the
-// count of the keys that reach a trial value is one wave vote per register.  Straight-line
-// code for a given NIT: branches between the votes would cost more than the votes.
-template <int NIT, int R>
-__device__ __forceinline__ uint32_t mth_largest_key(const uint32_t (&E)[R], uint32_t kmin, uint32_t kmax, int m)
-{
-    static_assert(NIT <= R, "");
-    uint32_t tau = kmin;
-    if (kmax > kmin) {
-        for (int b = 31 - __clz(kmax - kmin); b >= 0; --b) {
-            const uint32_t trial = tau + (1u << b);   // bits below b of tau - kmin are still 0
-            int reach = 0;
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) reach += (int)__popcll(__ballot(E[it] >= trial));
-            if (trial > tau && reach >= m) tau = trial;   // (a trial that wrapped around is beyond every key)
-        }
-    }
-    return tau;
-}
-
 // The same select for short lists, one wave per source and no workgroup barrier: a lane
 // keeps the keys of up to R candidates in registers, so that a compute unit works on
 // several times as many sources at once as with a workgroup per source -- the select is
@@ -786,16 +763,16 @@ template <int R>
 __global__ __launch_bounds__(256) void nbr_select_wave_kernel(const uint2 *__restrict__ cand,
                                                               const int32_t *__restrict__ cand_cnt,
                                                               int32_t *__restrict__ overflow,
-                                                              const int32_t *__restrict__ src, int S,
+                                                              const int32_t *__restrict__ src, int S, int pitch,
                                                               int chunks, int slice_cap, int m,
-                                                              SourceReuse ru, int32_t *__restrict__ nbr,
+                                                              int32_t *__restrict__ nbr,
                                                               float *__restrict__ nbr_e)
 {
     static_assert(R == 16 || R == 32, "register groups of 16");
     extern __shared__ __align__(8) uint32_t dyn[];   // per wave: [64] slice starts, [m + kTieRoom] list (64 bit)
     const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);   // (scalar: so are the row and its addresses)
-    const int n_rows = ru.code ? ru.n_new[h] : S;
+    const int n_rows = S;        // candidate row x of the head (pitch rows) -> source slot x
     if (overflow[h]) return;
     const int list_cap = m + kTieRoom;
     uint32_t *start_s = dyn + wv * (64 + 2 * list_cap);
@@ -803,12 +780,12 @@ __global__ __launch_bounds__(256) void nbr_select_wave_kernel(const uint2 *__res
     const uint64_t below = (1ull << lane) - 1ull;
 
     for (int x = blockIdx.x * 4 + wv; x < n_rows; x += gridDim.x * 4) {
-        const long row = (long)h * S + x;
+        const long row = (long)h * pitch + x;
         const uint2 *slices = cand + row * chunks * (long)slice_cap;
         // slice sizes -> where each slice starts in the concatenated list
         const int cnt = lane < chunks ? cand_cnt[row * chunks + lane] : 0;
-        const uint32_t self = (uint32_t)src[row];
-        const long out_row = (long)h * S + (ru.code ? ru.new_pos[row] : x);
+        const uint32_t self = (uint32_t)src[(long)h * S + x];
+        const long out_row = (long)h * S + x;
         int incl = cnt;
 #pragma unroll
         for (int o = 1; o < 64; o <<= 1) {
@@ -954,63 +931,95 @@ __global__ __launch_bounds__(256) void nbr_select_wave_kernel(const uint2 *__res
     }
 }
 
-// Which sources of this round (cur [Hkv, S], ascending) were sources in the previous round
-// (prev, ascending): code[h, a] = slot in prev, or -1 - r for the r-th source that was not;
-// those go, in order, to new_src[h, 0 .. n_new[h]), new_pos[h, r] = a.  The lists of the
-// sources that were there (prev_nbr, prev_e [Hkv, S, m]) are copied to their slots of this
-// round (nbr, nbr_e).  One workgroup per head.
-__global__ __launch_bounds__(256) void match_sources_kernel(const int32_t *__restrict__ prev,
-                                                            const int32_t *__restrict__ cur, int S,
-                                                            int32_t *__restrict__ code,
-                                                            int32_t *__restrict__ new_src,
-                                                            int32_t *__restrict__ new_pos,
-                                                            int32_t *__restrict__ n_new, int m,
-                                                            const int32_t *__restrict__ prev_nbr,
-                                                            const float *__restrict__ prev_e,
-                                                            int32_t *__restrict__ nbr,
-                                                            float *__restrict__ nbr_e)
+// Where each source of this round (cur [Hkv, S], ascending) gets its neighbour list from:
+//   - it was a source in the previous round (prev, ascending): its list (prev_nbr, prev_e
+//     [Hkv, S, m]) is copied to its slot of this round (nbr, nbr_e);
+//   - it is one of the head's speculative rows (entries S .. S + X of ext [Hkv, S + X],
+//     ascending, whose candidate lists the first round's filter pass built in rows
+//     spec_row0 .. of the per-row buffers) and
+//     those lists are complete (the head raised no overflow flag in the first round): the
+//     exact select runs on that row;
+//   - otherwise it goes, in order, to new_src[h, 0 .. n_new[h]) for another bound and filter
+//     pass, which uses rows 0 .. of the per-row buffers (the candidates of the first round's
+//     sources are no longer needed once their lists are selected).
+// The selections to run are listed as (candidate row, source slot) in sel_row / sel_pos
+// [Hkv, S], n_sel[h] of them.  spec_bad [Hkv] remembers across rounds whether a head's
+// speculative lists may be used: the first match of a call sets it from the overflow flags
+// of the first round (first != 0), later ones read it.  One workgroup per head.
+__global__ __launch_bounds__(256) void match_sources_kernel(
+    const int32_t *__restrict__ prev, const int32_t *__restrict__ cur, int S, int m,
+    const int32_t *__restrict__ prev_nbr, const float *__restrict__ prev_e, int32_t *__restrict__ nbr,
+    float *__restrict__ nbr_e, const int32_t *__restrict__ ext, int X, int spec_row0,
+    int32_t *__restrict__ spec_bad, const int32_t *__restrict__ overflow, int first,
+    int32_t *__restrict__ new_src, int32_t *__restrict__ n_new, int32_t *__restrict__ sel_row,
+    int32_t *__restrict__ sel_pos, int32_t *__restrict__ n_sel)
 {
-    extern __shared__ int32_t prev_s[];   // [S] previous sources, then [S] this round's codes
-    int32_t *code_s = prev_s + S;
-    __shared__ int32_t wave_new[4];
+    extern __shared__ int32_t prev_s[];   // [S] previous sources, [S] where this round's lists come from, [X] spec
+    int32_t *code_s = prev_s + S, *spec_s = code_s + S;
+    __shared__ int32_t wave_new[4], wave_fb[4];
     const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const long row0 = (long)h * S;
     for (int b = tid; b < S; b += 256) prev_s[b] = prev[row0 + b];
+    for (int b = tid; b < X; b += 256) spec_s[b] = ext[(long)h * (S + X) + S + b];   // the rows behind the S sources
+    bool bad = X == 0;
+    if (X > 0) {
+        bad = first ? overflow[h] != 0 : spec_bad[h] != 0;
+        if (first && tid == 0) spec_bad[h] = bad ? 1 : 0;
+    }
     __syncthreads();
-    int base = 0;
+    // first slot of a sorted list that holds i or more
+    auto lower_bound = [](const int32_t *list, int n, int32_t i) {
+        int lo = 0, hi = n;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (list[mid] < i) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    };
+    int base = 0, base_fb = 0;
     for (int a0 = 0; a0 < S; a0 += 256) {
         const int a = a0 + tid;
-        int i = 0, found = -1;
+        int i = 0, found = -1, spec_at = -1;
         if (a < S) {
             i = cur[row0 + a];
-            int lo = 0, hi = S;   // first slot of prev that holds i or more
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (prev_s[mid] < i) lo = mid + 1; else hi = mid;
-            }
+            const int lo = lower_bound(prev_s, S, i);
             if (lo < S && prev_s[lo] == i) found = lo;
+            if (found < 0 && !bad) {
+                const int u = lower_bound(spec_s, X, i);
+                if (u < X && spec_s[u] == i) spec_at = u;
+            }
         }
-        const bool is_new = a < S && found < 0;
-        const uint64_t mask = __ballot(is_new);
-        if (lane == 0) wave_new[wv] = (int32_t)__popcll(mask);
+        const bool is_new = a < S && found < 0, is_fb = is_new && spec_at < 0;
+        const uint64_t mask = __ballot(is_new), mask_fb = __ballot(is_fb);
+        if (lane == 0) { wave_new[wv] = (int32_t)__popcll(mask); wave_fb[wv] = (int32_t)__popcll(mask_fb); }
         __syncthreads();
-        int before = base, total = 0;
+        int before = base, total = 0, before_fb = base_fb, total_fb = 0;
         for (int u = 0; u < 4; ++u) {
-            if (u < wv) before += wave_new[u];
+            if (u < wv) { before += wave_new[u]; before_fb += wave_fb[u]; }
             total += wave_new[u];
+            total_fb += wave_fb[u];
         }
+        if (a < S) code_s[a] = found;
         if (is_new) {
-            const int r = before + (int)__popcll(mask & ((1ull << lane) - 1ull));
-            new_src[row0 + r] = i;
-            new_pos[row0 + r] = a;
-            code[row0 + a] = code_s[a] = -1 - r;
-        } else if (a < S) {
-            code[row0 + a] = code_s[a] = found;
+            const uint64_t lower = (1ull << lane) - 1ull;
+            const int x = before + (int)__popcll(mask & lower);
+            int crow = spec_row0 + spec_at;
+            if (is_fb) {
+                const int r = before_fb + (int)__popcll(mask_fb & lower);
+                new_src[row0 + r] = i;
+                crow = r;
+            }
+            sel_row[row0 + x] = crow;
+            sel_pos[row0 + x] = a;
         }
         base += total;
+        base_fb += total_fb;
         __syncthreads();
     }
-    if (tid == 0) n_new[h] = base;
+    if (tid == 0) {
+        n_new[h] = base_fb;
+        n_sel[h] = base;
+    }
     // the lists that stay: the neighbourhood of a source does not depend on the scores
     for (long u = tid; u < (long)S * m; u += 256) {
         const int a = (int)(u / m), r = (int)(u % m);
@@ -1062,12 +1071,22 @@ bool mfma_filter_applies(int P, int m)
     return (size_t)mfma_cand_cap(P, m) * 8 + (size_t)m * 8 + 8 <= 140 * 1024;
 }
 
-// Key chunks per head of the filter pass and the capacity of one (source, chunk) slice:
-// four times the expected share of a chunk, at least 2 m (and 64) entries.
-MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m)
+bool source_reuse_applies(int S) { return S <= 4096; }   // the previous list and the match's bookkeeping sit in LDS
+
+// Geometry of the filter route for a call.  X speculative rows (see the head of this file)
+// ride along in the first round when the lists are kept from round to round and the extended
+// source list still fits the small-k source selection; their workgroups then carry three
+// 32-row groups.  Key chunks per head and the capacity of one (row, chunk) slice: four times
+// the expected share of a chunk, at least 2 m (and 64) entries.
+MfmaFilterPlan mfma_filter_plan(int Hkv, int P, int S, int m, bool keep_lists, bool speculate)
 {
-    MfmaFilterGeom g;
-    const int sgroups = (S + kRows - 1) / kRows;
+    MfmaFilterPlan g{};
+    g.S = S;
+    g.X = (keep_lists && speculate && S + kSpecRows <= kMaxExtSources) ? kSpecRows : 0;
+    g.sb = g.X > 0 ? 3 : 2;
+    g.pitch = S + g.X;
+    const int rows_wg = kBlk * g.sb;
+    const int sgroups = (S + g.X + rows_wg - 1) / rows_wg;
     g.chunk_cols = chunk_cols_for(Hkv, sgroups, P);
     g.chunks = (P + g.chunk_cols - 1) / g.chunk_cols;
     if (g.chunks > 256) {   // the exact select keeps the slice sizes of a source in LDS
@@ -1078,8 +1097,8 @@ MfmaFilterGeom mfma_filter_geom(int Hkv, int P, int S, int m)
     long sc = 4L * ((long)m * stride + g.chunks - 1) / g.chunks;
     if (sc < 2L * m) sc = 2L * m;
     if (sc < 64) sc = 64;
-    const int cap = mfma_cand_cap(P, m);
-    if (sc > cap) sc = cap;
+    g.cand_cap = mfma_cand_cap(P, m);
+    if (sc > g.cand_cap) sc = g.cand_cap;
     g.slice_cap = (int)sc;
     return g;
 }
@@ -1097,102 +1116,146 @@ hipError_t launch_mfma_cosine(const void *Ac, const void *Kc, int Hkv, int N, in
     return hipGetLastError();
 }
 
+namespace {
+
 // Chunks of the sample per (head, source group): 1 when the heads alone give 128 workgroups or
 // more, else enough for about 256 workgroups, at least two key tiles each.
-int mfma_bound_chunks(int Hkv, int P, int S)
+int bound_chunks(int Hkv, int P, int sgroups)
 {
-    const int ps = mfma_sample_cols(P), sgroups = (S + kRows - 1) / kRows;
+    const int ps = mfma_sample_cols(P);
     if (Hkv * sgroups >= 128) return 1;
     int chunks = 256 / (Hkv * sgroups);
     if (chunks > ps / (2 * kTileKeys)) chunks = ps / (2 * kTileKeys);
     return chunks < 1 ? 1 : chunks;
 }
 
-size_t mfma_bound_scratch_bytes(int Hkv, int P, int S)
+template <int SB, int BINS>
+hipError_t launch_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int rows, int m, const int32_t *src,
+                        int src_pitch, const int32_t *n_src, void *hist_part, float *tau, int pitch, int row0,
+                        int32_t *overflow, hipStream_t st)
 {
-    const int chunks = mfma_bound_chunks(Hkv, P, S), sgroups = (S + kRows - 1) / kRows;
-    return chunks > 1 ? (size_t)Hkv * sgroups * chunks * kRows * (kBoundBins / 2) * 4 : 0;
-}
-
-hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                    const int32_t *src, const int32_t *n_src, void *hist_part, float *tau,
-                                    int32_t *overflow, hipStream_t st)
-{
+    constexpr int ROWS = SB * kBlk;
     const int ps = mfma_sample_cols(P), stride = P / ps;
-    const int sgroups = (S + kRows - 1) / kRows;
-    const int chunks = mfma_bound_chunks(Hkv, P, S);
+    const int sgroups = (rows + ROWS - 1) / ROWS;
+    const int chunks = bound_chunks(Hkv, P, sgroups);
     const int chunk_cols = (((ps + chunks - 1) / chunks + kTileKeys - 1) / kTileKeys) * kTileKeys;
-    if (!allow_big_lds((const void *)cosine_bound_kernel)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_bound_kernel, dim3(sgroups, Hkv, chunks), dim3(kThreads),
-                       2 * kTileBytes + kRows * (kBoundBins / 2) * 4, st, (const uint16_t *)Ac,
-                       (const uint16_t *)Kc, N, ps, stride, S, src, n_src, m, chunk_cols, (uint32_t *)hist_part,
-                       tau, overflow);
+    if (!allow_big_lds((const void *)cosine_bound_kernel<SB, BINS>)) return hipGetLastError();
+    hipLaunchKernelGGL((cosine_bound_kernel<SB, BINS>), dim3(sgroups, Hkv, chunks), dim3(256 * SB),
+                       2 * kTileBytes + ROWS * (BINS / 2) * 4, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, ps,
+                       stride, rows, src_pitch, src, n_src, m, chunk_cols, (uint32_t *)hist_part, tau, pitch, row0,
+                       overflow);
     if (chunks > 1)
-        hipLaunchKernelGGL(bound_merge_kernel, dim3((S + 3) / 4, Hkv), dim3(256), 0, st,
-                           (const uint32_t *)hist_part, chunks, sgroups, S, n_src, m, tau);
+        hipLaunchKernelGGL((bound_merge_kernel<SB, BINS>), dim3((rows + 3) / 4, Hkv), dim3(256), 0, st,
+                           (const uint32_t *)hist_part, chunks, sgroups, rows, n_src, m, tau, pitch, row0);
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int S, int m,
-                                     const int32_t *src, const int32_t *n_src, const float *tau, void *cand,
-                                     int32_t *cand_cnt, int32_t *overflow, hipStream_t st)
+template <int SB, int RING>
+hipError_t launch_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int rows, int m, const int32_t *src,
+                         int src_pitch, const int32_t *n_src, const MfmaFilterPlan &g, int row0, const float *tau,
+                         void *cand, int32_t *cand_cnt, int32_t *overflow, hipStream_t st)
 {
-    const int sgroups = (S + kRows - 1) / kRows;
+    constexpr int ROWS = SB * kBlk;
+    const int sgroups = (rows + ROWS - 1) / ROWS;
     const int stride = P / mfma_sample_cols(P);
-    const MfmaFilterGeom g = mfma_filter_geom(Hkv, P, S, m);
     // Rows a half-wave parks per tile: 32 lanes x P(a lane's 16 edges hold a hit), with a
     // per-edge hit rate of about m * stride / P (each source keeps ~m * stride candidates).
-    // Drains are scheduled for when about 30 of a half-wave's 32 lanes get a row.
+    // Drains are scheduled for when most of a half-wave's 32 lanes get a row and the ring
+    // is not yet full.
     const double rate = (double)m * stride / (double)P;
     const double per_tile = 32.0 * (1.0 - pow(1.0 - (rate < 1.0 ? rate : 1.0), 16.0));
-    int drain_every = (int)(30.0 / (per_tile > 0.45 ? per_tile : 0.45));
+    int drain_every = (int)((RING > kBlk ? 30.0 : 24.0) / (per_tile > 0.45 ? per_tile : 0.45));
     if (drain_every < 1) drain_every = 1;
-    FilterArgs fa{n_src, tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, drain_every, sgroups};
-    if (!allow_big_lds((const void *)cosine_filter_kernel)) return hipGetLastError();
-    hipLaunchKernelGGL(cosine_filter_kernel, dim3(g.chunks * sgroups, Hkv), dim3(kThreads),
-                       2 * kTileBytes + 2 * (kThreads / kWave) * kRingRows * kStagePitch, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, src,
-                       g.chunk_cols, fa);
+    FilterArgs fa{n_src, tau, (uint2 *)cand, cand_cnt, overflow, g.slice_cap, drain_every, sgroups, src_pitch,
+                  g.pitch, row0};
+    if (!allow_big_lds((const void *)cosine_filter_kernel<SB, RING>)) return hipGetLastError();
+    hipLaunchKernelGGL((cosine_filter_kernel<SB, RING>), dim3(g.chunks * sgroups, Hkv), dim3(256 * SB),
+                       2 * kTileBytes + 2 * (4 * SB) * RING * kStagePitch, st, (const uint16_t *)Ac,
+                       (const uint16_t *)Kc, N, P, rows, src, g.chunk_cols, fa);
     return hipGetLastError();
 }
 
-bool source_reuse_applies(int S) { return S <= 4096; }   // the previous list and the codes sit in LDS
+}  // namespace
 
-hipError_t launch_match_sources(const int32_t *prev, const int32_t *cur, int Hkv, int S, int m,
-                                const int32_t *prev_nbr, const float *prev_e, int32_t *code, int32_t *new_src,
-                                int32_t *new_pos, int32_t *n_new, int32_t *nbr, float *nbr_e, hipStream_t st)
+size_t mfma_bound_scratch_bytes(int Hkv, int P, const MfmaFilterPlan &g)
 {
-    hipLaunchKernelGGL(match_sources_kernel, dim3(Hkv), dim3(256), (size_t)S * 8, st, prev, cur, S, code,
-                       new_src, new_pos, n_new, m, prev_nbr, prev_e, nbr, nbr_e);
+    // (the first round's launch has the most rows per workgroup and the fewest groups)
+    size_t need = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int sb = pass == 0 ? g.sb : 2, rows = pass == 0 ? g.S + g.X : g.S;
+        const int rows_wg = kBlk * sb, sgroups = (rows + rows_wg - 1) / rows_wg;
+        const int chunks = bound_chunks(Hkv, P, sgroups);
+        const size_t bytes = chunks > 1 ? (size_t)Hkv * sgroups * chunks * rows_wg * 256 * 4 : 0;
+        if (bytes > need) need = bytes;
+    }
+    return need;
+}
+
+hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int m,
+                                    const MfmaFilterPlan &g, bool first_round, const int32_t *src,
+                                    const int32_t *n_src, void *hist_part, float *tau, int32_t *overflow,
+                                    hipStream_t st)
+{
+    if (first_round && g.sb == 3)
+        return launch_bound<3, 448>(Ac, Kc, Hkv, N, P, g.S + g.X, m, src, g.S + g.X, n_src, hist_part, tau, g.pitch,
+                                    0, overflow, st);
+    if (first_round)
+        return launch_bound<2, 512>(Ac, Kc, Hkv, N, P, g.S, m, src, g.S, n_src, hist_part, tau, g.pitch, 0,
+                                    overflow, st);
+    return launch_bound<2, 512>(Ac, Kc, Hkv, N, P, g.S, m, src, g.S, n_src, hist_part, tau, g.pitch, 0, overflow, st);
+}
+
+hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int m,
+                                     const MfmaFilterPlan &g, bool first_round, const int32_t *src,
+                                     const int32_t *n_src, const float *tau, void *cand, int32_t *cand_cnt,
+                                     int32_t *overflow, hipStream_t st)
+{
+    if (first_round && g.sb == 3)
+        return launch_filter<3, 32>(Ac, Kc, Hkv, N, P, g.S + g.X, m, src, g.S + g.X, n_src, g, 0, tau, cand, cand_cnt,
+                                    overflow, st);
+    if (first_round)
+        return launch_filter<2, 64>(Ac, Kc, Hkv, N, P, g.S, m, src, g.S, n_src, g, 0, tau, cand, cand_cnt, overflow, st);
+    return launch_filter<2, 64>(Ac, Kc, Hkv, N, P, g.S, m, src, g.S, n_src, g, 0, tau, cand, cand_cnt, overflow, st);
+}
+
+hipError_t launch_match_sources(const int32_t *prev, const int32_t *cur, int Hkv, int m, const MfmaFilterPlan &g,
+                                const int32_t *prev_nbr, const float *prev_e, int32_t *nbr, float *nbr_e,
+                                const int32_t *ext, int32_t *spec_bad, const int32_t *overflow, bool first_match,
+                                int32_t *new_src, int32_t *n_new, int32_t *sel_row, int32_t *sel_pos,
+                                int32_t *n_sel, hipStream_t st)
+{
+    hipLaunchKernelGGL(match_sources_kernel, dim3(Hkv), dim3(256), (size_t)(2 * g.S + g.X) * 4, st, prev, cur, g.S,
+                       m, prev_nbr, prev_e, nbr, nbr_e, ext, g.X, g.S, spec_bad, overflow, first_match ? 1 : 0, new_src,
+                       n_new, sel_row, sel_pos, n_sel);
     return hipGetLastError();
 }
 
-hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t *overflow,
-                             const int32_t *src, int Hkv, int P, int S, int m, const SourceReuse *reuse,
-                             int32_t *nbr, float *nbr_e, hipStream_t st)
+hipError_t launch_nbr_select(const void *cand, const int32_t *cand_cnt, int32_t *overflow, const int32_t *src,
+                             int Hkv, int m, const MfmaFilterPlan &g, const SelectRows *rows, int32_t *nbr,
+                             float *nbr_e, hipStream_t st)
 {
-    const int cap = mfma_cand_cap(P, m);
-    const MfmaFilterGeom g = mfma_filter_geom(Hkv, P, S, m);
-    const SourceReuse ru = reuse ? *reuse : SourceReuse{};
+    const int S = g.S, cap = g.cand_cap;
     // Every source has a list (first round, or nothing kept) and the lists are short: a wave
     // per source.  That kernel is long straight-line code, which only pays when there are
-    // many lists to go through; the few new sources of a later round take the other one.
-    if (!reuse && cap <= 64 * 32 && g.chunks <= 64) {
+    // many lists to go through; the few selections of a later round take the other one.
+    if (!rows && cap <= 64 * 32 && g.chunks <= 64) {
         int per_head = 8192 / Hkv < 1 ? 1 : 8192 / Hkv;   // four sources per workgroup
         const int wgs = per_head > (S + 3) / 4 ? (S + 3) / 4 : per_head;
         const size_t lds = (size_t)4 * (64 + 2 * (m + kTieRoom)) * 4;
         auto *kernel = cap <= 64 * 16 ? nbr_select_wave_kernel<16> : nbr_select_wave_kernel<32>;
         hipLaunchKernelGGL(kernel, dim3(wgs, Hkv), dim3(256), lds, st, (const uint2 *)cand, cand_cnt, overflow,
-                           src, S, g.chunks, g.slice_cap, m, ru, nbr, nbr_e);
+                           src, S, g.pitch, g.chunks, g.slice_cap, m, nbr, nbr_e);
         return hipGetLastError();
     }
-    // The workgroups of a head share its sources in turn: few workgroups when only the new
-    // sources of a round have lists (most would find nothing to do), many otherwise.
-    int per_head = (reuse ? 3072 : 16384) / Hkv;
+    // The workgroups of a head share its selections in turn: few workgroups when only some
+    // sources of a round need a select (most would find nothing to do), many otherwise.
+    const SelectRows sel = rows ? *rows : SelectRows{};
+    int per_head = (rows ? 3072 : 16384) / Hkv;
     per_head = per_head < 1 ? 1 : (per_head > S ? S : per_head);
     const size_t lds = (size_t)(cap + (cap & 1)) * 4 + (size_t)(m + kTieRoom) * 8;
     if (!allow_big_lds((const void *)nbr_select_kernel)) return hipGetLastError();
     hipLaunchKernelGGL(nbr_select_kernel, dim3(per_head, Hkv), dim3(256), lds, st, (const uint2 *)cand,
-                       cand_cnt, overflow, src, S, g.chunks, g.slice_cap, cap, m, ru, nbr, nbr_e);
+                       cand_cnt, overflow, src, S, g.pitch, g.chunks, g.slice_cap, cap, m, sel, nbr, nbr_e);
     return hipGetLastError();
 }
 

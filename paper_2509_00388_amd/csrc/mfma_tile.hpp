@@ -38,8 +38,16 @@ __device__ __forceinline__ bf16x8 load8(const uint16_t *p)
 // half-wave hh (the column is lane % 32).
 __device__ __forceinline__ int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
 
-// A thread of an NT-thread workgroup moves kTileChunks / NT 16-byte pieces per tile.
-template <int NT> constexpr int tile_pieces() { return kTileChunks / NT; }
+// A thread of an NT-thread workgroup moves ceil(kTileChunks / NT) 16-byte pieces per tile.
+// When NT does not divide the tile (768 threads: three pieces each, 2304 slots for 2048
+// pieces) the threads whose last slot is past the tile move their first piece once more: the
+// same bytes to the same place, so that every thread runs the same unconditional code.
+template <int NT> constexpr int tile_pieces() { return (kTileChunks + NT - 1) / NT; }
+template <int NT> __device__ __forceinline__ int tile_piece(int tid, int u)
+{
+    const int g = tid + u * NT;
+    return (kTileChunks % NT == 0 || g < kTileChunks) ? g : tid;
+}
 
 // Global -> registers.  Tile row t is key (first + t) * stride, clamped to
 // last_key (rows past the range are loaded from a valid address and masked later).
@@ -47,10 +55,10 @@ template <int NT, int PER>
 __device__ __forceinline__ void tile_load(const uint16_t *Kh, int first, int last_key, int stride,
                                           int tid, u32x4 (&r)[PER])
 {
-    static_assert(PER == kTileChunks / NT, "pieces per thread");
+    static_assert(PER == tile_pieces<NT>(), "pieces per thread");
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-        const int g = tid + u * NT, row = g >> 4, c = g & 15;
+        const int g = tile_piece<NT>(tid, u), row = g >> 4, c = g & 15;
         const long key = (long)min(first + row, last_key) * stride;
         r[u] = *reinterpret_cast<const u32x4 *>(Kh + key * kD + c * 8);
     }
@@ -62,7 +70,7 @@ __device__ __forceinline__ void tile_store(unsigned char *buf, int tid, const u3
 {
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-        const int g = tid + u * NT, row = g >> 4, c = g & 15;
+        const int g = tile_piece<NT>(tid, u), row = g >> 4, c = g & 15;
         *reinterpret_cast<u32x4 *>(buf + row * kPitch + c * 16) = r[u];
     }
 }
@@ -74,6 +82,29 @@ __device__ __forceinline__ void tile_read(const unsigned char *buf, int stream, 
     const unsigned char *p = buf + (kBlk * stream + l32) * kPitch + 16 * hh;
 #pragma unroll
     for (int s = 0; s < kSteps; ++s) kc[s] = *reinterpret_cast<const bf16x8 *>(p + 32 * s);
+}
+
+// 1/|k| from |k|^2 with the hardware reciprocal square root (1 ulp), 0 for a zero key.
+// Every MFMA-path edge uses this one function, so the sampled bound and the filtered
+// edges are computed bit for bit alike.
+__device__ __forceinline__ float inv_norm(float sq)
+{
+    return sq == 0.f ? 0.f : __builtin_amdgcn_rsqf(sq);
+}
+
+// Sum of squares of the 64 elements a lane holds of its row (8 k-steps x 8),
+// two bf16 products per instruction, fp32 accumulation.
+__device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
+{
+    float a = 0.f;
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const bf16x2 v = {r[s][e], r[s][e + 1]};
+            a = __builtin_amdgcn_fdot2_f32_bf16(v, v, a, false);
+        }
+    return a;
 }
 
 // The tile loop shared by the streaming kernels.  Tile t is multiplied out of LDS

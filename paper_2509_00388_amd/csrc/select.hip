@@ -14,6 +14,7 @@
 // sweeps; longer rows are re-read from L2 in every sweep.
 #include "common.hpp"
 #include "kernels.hpp"
+#include "mfma_tile.hpp"
 
 #include <type_traits>
 
@@ -122,7 +123,8 @@ __device__ __forceinline__ void topk_row_lds(
 #pragma unroll 8
     for (int i = 0; i < items; ++i) {
         const int j = i * BLOCK + tid;
-        const uint32_t key = ord_key(j < n ? xr[j] : 0.f);
+        const float v = xr[min(j, n - 1)];   // (unconditional: the loads of a batch leave together)
+        const uint32_t key = ord_key(j < n ? v : 0.f);
         keys[j] = key;
         if (j < n) { kmin = min(kmin, key); kmax = max(kmax, key); }
     }
@@ -240,43 +242,169 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_lds_kernel(
 }
 
 // ---- small k out of a long row ------------------------------------------------
-// For k far below the row length (the source nodes: 64 of 32736) the keys need not
-// go through LDS at all.  Every thread keeps its keys (32 with 1024 threads; 512
-// threads measured slower) in registers.  A bound comes almost for free: split the threads into G >= k groups; the smallest
-// of the G group maxima is reached by G different entries, so the k-th largest key
-// is at least that.  Only the few hundred keys that reach the bound take part in
-// the radix select (the same sweeps as above, fed from registers: a compare per key
-// and an LDS atomic for the few that pass), and the emit sweep is the one above.
-constexpr int kSmallK = 256;       // largest k this path takes
+// Winners of a row, (index << 32) | key each, in any order -> the row's outputs.  With
+// ext_out the k winners are the S best and the X = k - S next best: a winner that fewer
+// than S others beat by (key descending, index ascending) is one of the S; src_out gets
+// those in ascending index order, ext_out the same S followed by the others in ascending
+// index order.  Without ext_out (S = k) this is the plain ascending list.  `cls` holds k
+// bytes of LDS; every thread of the workgroup calls this (k <= kSmallK <= blockDim.x).
+constexpr int kSmallK = 256;       // largest k the small-k paths take
+
+__device__ __forceinline__ void emit_sources(const uint64_t *win, int k, int S, int32_t *src_out,
+                                             int32_t *ext_out, uint8_t *cls, int tid)
+{
+    uint64_t mine = 0;
+    bool first_s = true;
+    if (tid < k) {
+        mine = win[tid];
+        const uint32_t key = (uint32_t)mine, idx = (uint32_t)(mine >> 32);
+        int beat = 0;
+        for (int u = 0; u < k; ++u) {
+            const uint64_t w = win[u];
+            const uint32_t ku = (uint32_t)w, iu = (uint32_t)(w >> 32);
+            beat += (ku > key) || (ku == key && iu < idx);
+        }
+        first_s = beat < S;
+        cls[tid] = first_s ? 1 : 0;
+    }
+    __syncthreads();
+    if (tid < k) {
+        int before = 0;   // winners of the same class with a lower index
+        for (int u = 0; u < k; ++u) before += (win[u] >> 32) < (mine >> 32) && (cls[u] != 0) == first_s;
+        const int32_t idx = (int32_t)(mine >> 32);
+        if (first_s) {
+            src_out[before] = idx;
+            if (ext_out) ext_out[before] = idx;
+        } else {
+            ext_out[S + before] = idx;
+        }
+    }
+}
+
+// The same by one wave on its own (no workgroup barrier, no LDS in the loops): lane L keeps
+// winners L, L + 64, L + 128, L + 192 in registers and every winner in turn is broadcast to the
+// wave from its lane.
+__device__ __forceinline__ void emit_sources_wave(const uint64_t *win, int k, int S, int32_t *src_out,
+                                                  int32_t *ext_out, int lane)
+{
+    constexpr int R = kSmallK / kWave;
+    uint32_t key[R], idx[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const uint64_t w = r * kWave + lane < k ? win[r * kWave + lane] : 0ull;
+        key[r] = (uint32_t)w;
+        idx[r] = (uint32_t)(w >> 32);
+    }
+    // how many winners beat each of mine by (key descending, index ascending): fewer than S -> one of the S
+    int beat[R] = {0, 0, 0, 0};
+    if (ext_out) {
+#pragma unroll
+        for (int ru = 0; ru < R; ++ru)
+            for (int l = 0; l < kWave && ru * kWave + l < k; ++l) {
+                const uint32_t ku = (uint32_t)__builtin_amdgcn_readlane((int)key[ru], l);
+                const uint32_t iu = (uint32_t)__builtin_amdgcn_readlane((int)idx[ru], l);
+#pragma unroll
+                for (int r = 0; r < R; ++r) beat[r] += (ku > key[r]) || (ku == key[r] && iu < idx[r]);
+            }
+    }
+    bool first_s[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) first_s[r] = beat[r] < S;
+    // place = winners of the same class with a lower index
+    int before[R] = {0, 0, 0, 0};
+#pragma unroll
+    for (int ru = 0; ru < R; ++ru)
+        for (int l = 0; l < kWave && ru * kWave + l < k; ++l) {
+            const uint32_t iu = (uint32_t)__builtin_amdgcn_readlane((int)idx[ru], l);
+            const bool su = __builtin_amdgcn_readlane(first_s[ru] ? 1 : 0, l) != 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r) before[r] += iu < idx[r] && su == first_s[r];
+        }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+        if (r * kWave + lane < k) {
+            if (first_s[r]) {
+                src_out[before[r]] = (int32_t)idx[r];
+                if (ext_out) ext_out[before[r]] = (int32_t)idx[r];
+            } else {
+                ext_out[S + before[r]] = (int32_t)idx[r];
+            }
+        }
+}
+
+// For k far below the row length (the source nodes: 64 of 32736, with the speculative
+// rows 96) the row is read once into registers (32 keys per thread).  A bound comes almost
+// for free: split the threads into G >= k groups; the smallest of the G group maxima is
+// reached by G different entries, so the k-th largest key is at least that (if too many
+// entries reach it, one radix sweep raises it).  The few hundred
+// keys that reach the bound are compacted into an LDS list (positions from wave votes, one
+// atomic per wave and register), and from there on the registers are free: one wave finds the
+// k-th largest key of the list bit by bit (its keys in registers, a wave vote per register and
+// bit, no barrier), every entry above it and the lowest-index entries equal to it are the
+// winners, and emit_sources() orders them.  A row with more than kPickCap entries at or above
+// the bound (masses of equal values) takes the algorithm that re-reads the row instead.
+constexpr int kPickCap = 2048;     // list entries: 32 registers of a wave
+
+template <int BLOCK, bool PLAN> __device__ __forceinline__ void topk_stream_row(
+    int row, const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld,
+    float *__restrict__ val_out, long val_ld, float *__restrict__ tau_out, int append_from,
+    int append_count, const int32_t *__restrict__ gate, int rows_per_gate,
+    typename std::conditional<PLAN, LayerPlan, int>::type plan);
+
+template <int NIT>
+__device__ __forceinline__ uint32_t pick_tau(const uint32_t *lk, int cnt, int lane, int k, uint32_t kmin,
+                                             uint32_t kmax)
+{
+    uint32_t E[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) E[it] = it * 64 + lane < cnt ? lk[it * 64 + lane] : 0u;
+    return mth_largest_key<NIT>(E, kmin, kmax, k);
+}
 
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void topk_rows_smallk_kernel(
-    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld)
+__global__ __launch_bounds__(BLOCK) void pick_sources_kernel(
+    const float *__restrict__ x, long ld, int n, int k, int S, int32_t *__restrict__ src_out, long src_ld,
+    int32_t *__restrict__ ext_out, long ext_ld)
 {
     constexpr int ITEMS = 32768 / BLOCK, NW = BLOCK / kWave, DIG = 11, NBINS = 1 << DIG;
+    __shared__ uint32_t lk[kPickCap], lj[kPickCap];   // keys and indices of the entries that reach the bound
     __shared__ uint32_t hist[NBINS];
-    __shared__ uint32_t s_bin, s_need, s_grp[kSmallK], s_bound, s_wmax[NW], s_max;
-    __shared__ uint32_t cg[ITEMS * NW], ce[ITEMS * NW];
+    __shared__ uint64_t win[kSmallK];
+    __shared__ uint8_t cls[kSmallK];
+    __shared__ uint32_t s_grp[kSmallK], s_bound, s_wmax[NW], s_max, s_cnt, s_need, s_bin;
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const float *xr = x + (long)row * ld;
-    int32_t *out = idx_out + (long)row * idx_ld;
+    int32_t *src_row = src_out + (long)row * src_ld;
+    int32_t *ext_row = ext_out ? ext_out + (long)row * ext_ld : nullptr;
 
+    // All loads of the row leave together: clamped, unconditional, and their values pinned in
+    // registers before the first use (otherwise the compiler moves every load behind the
+    // test of its index and waits for each in turn).
+    float val[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) val[i] = xr[min(i * BLOCK + tid, n - 1)];
+#pragma unroll
+    for (int i = 0; i < ITEMS; i += 8)
+        asm volatile("" : "+v"(val[i]), "+v"(val[i + 1]), "+v"(val[i + 2]), "+v"(val[i + 3]), "+v"(val[i + 4]),
+                          "+v"(val[i + 5]), "+v"(val[i + 6]), "+v"(val[i + 7]));
     uint32_t key[ITEMS];
     uint32_t best = 0;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        const int j = i * BLOCK + tid;
-        key[i] = j < n ? ord_key(xr[j]) : 0u;          // 0 is below the key of every number
+        key[i] = i * BLOCK + tid < n ? ord_key(val[i]) : 0u;   // 0 is below the key of every number
         best = max(best, key[i]);
     }
-    // G groups of consecutive threads (G a power of two, k <= G <= 256, so a group is 4 to 64
-    // lanes of one wave): group maxima, their minimum = the bound; the row maximum on the way.
+    // G groups (G a power of two, k <= G <= 256): thread t belongs to group t mod G, so a group
+    // owns the entries whose index is t mod G -- scores are smooth along the row (pooling), and
+    // this way the few peaks that hold the winners spread over many groups.  Group maxima (an
+    // LDS atomic per thread), their minimum = the bound; the row maximum on the way.
     int G = 16;
     while (G < k) G <<= 1;
-    const int gs = BLOCK / G;
-    uint32_t gmax = best;
-    for (int o = 1; o < gs; o <<= 1) gmax = max(gmax, (uint32_t)__shfl_xor((int)gmax, o, kWave));
-    if ((tid & (gs - 1)) == 0) s_grp[tid / gs] = gmax;
+    if (tid < G) s_grp[tid] = 0u;
+    if (tid == 0) s_cnt = 0;
+    for (int b = tid; b < NBINS; b += BLOCK) hist[b] = 0;
+    __syncthreads();
+    atomicMax(&s_grp[tid & (G - 1)], best);
     uint32_t wmax = best;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) wmax = max(wmax, (uint32_t)__shfl_xor((int)wmax, o, kWave));
@@ -294,73 +422,88 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_smallk_kernel(
         if (lane == 0) { s_bound = mn; s_max = mx; }
     }
     __syncthreads();
-    const uint32_t kmin = s_bound, kmax = s_max;
+    uint32_t bound = s_bound;
+    const uint32_t kmax = s_max;
 
-    // radix select on (key - bound) among the keys that reach the bound
-    const uint32_t range = kmax - kmin;
-    int remaining = range ? 32 - __clz(range) : 0;
-    uint32_t prefix = 0, mask = 0, need = (uint32_t)k;
-    while (remaining > 0) {
-        const int bits = remaining < DIG ? remaining : DIG;
-        const int shift = remaining - bits;
-        const uint32_t dmask = (1u << bits) - 1u;
-        for (int b = tid; b < NBINS; b += BLOCK) hist[b] = 0;
-        __syncthreads();
+    // One radix sweep over the entries that reach the bound -- 11 bits of key - bound from the
+    // top bit in which they can differ -- raises the bound to the lower edge of the bin in which
+    // the count from the top reaches k: a handful of entries beyond the k winners remain.
+    if (kmax > bound) {   // (the same for every thread)
+        const int remaining = 32 - __clz(kmax - bound);
+        const int bits = remaining < DIG ? remaining : DIG, shift = remaining - bits;
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            const uint32_t rel = key[i] - kmin;
-            if (key[i] >= kmin && (rel & mask) == prefix) atomicAdd(&hist[(rel >> shift) & dmask], 1u);
-        }
+        for (int i = 0; i < ITEMS; ++i)
+            if (key[i] >= bound && key[i] != 0u) atomicAdd(&hist[(key[i] - bound) >> shift], 1u);
         __syncthreads();
-        if (wv == 0) find_bin<NBINS / 64>(hist, need, lane, &s_bin, &s_need);
+        if (wv == 0) find_bin<NBINS / 64>(hist, (uint32_t)k, lane, &s_bin, &s_need);
         __syncthreads();
-        prefix |= s_bin << shift;
-        mask |= dmask << shift;
-        need = s_need;
-        remaining = shift;
+        bound += s_bin << shift;
     }
-    const uint32_t tau = kmin + prefix;   // key of the k-th largest entry; take `need` entries equal to it
 
-    // emit in index order: entries above tau and the first `need` entries equal to it
+    // everything that reaches the bound -> the list (any order)
+    const uint64_t below = (1ull << lane) - 1ull;
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) {
-        const uint32_t ng = __popcll(__ballot(key[i] > tau));
-        const uint32_t ne = __popcll(__ballot(key[i] == tau));
-        if (lane == 0) { cg[i * NW + wv] = ng; ce[i * NW + wv] = ne; }
-    }
-    __syncthreads();
-    if (wv == 0) {   // exclusive scan of the cells in index order; lane L owns a contiguous run
-        constexpr int per = ITEMS * NW / 64;
-        const int c0 = lane * per;
-        uint32_t sg = 0, se = 0;
-#pragma unroll
-        for (int c = 0; c < per; ++c) { sg += cg[c0 + c]; se += ce[c0 + c]; }
-        uint32_t ig = sg, ie = se;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t a = __shfl_up(ig, o, kWave), b = __shfl_up(ie, o, kWave);
-            if (lane >= o) { ig += a; ie += b; }
-        }
-        uint32_t bg = ig - sg, be = ie - se;
-#pragma unroll
-        for (int c = 0; c < per; ++c) {
-            const uint32_t tg = cg[c0 + c], te = ce[c0 + c];
-            cg[c0 + c] = bg; ce[c0 + c] = be;
-            bg += tg; be += te;
+        const bool in = key[i] >= bound && key[i] != 0u;
+        const uint64_t votes = __ballot(in);
+        if (votes) {
+            uint32_t base = 0;
+            const int leader = __ffsll((long long)votes) - 1;
+            if (lane == leader) base = atomicAdd(&s_cnt, (uint32_t)__popcll(votes));
+            base = __shfl(base, leader, kWave);
+            const uint32_t at = base + (uint32_t)__popcll(votes & below);
+            if (in && at < (uint32_t)kPickCap) { lk[at] = key[i]; lj[at] = (uint32_t)(i * BLOCK + tid); }
         }
     }
     __syncthreads();
-    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-#pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const bool g = key[i] > tau, e = key[i] == tau;   // keys of entries past n are 0 < tau
-        const uint64_t mg = __ballot(g), me = __ballot(e);
-        if (g || e) {
-            const uint32_t g_before = cg[i * NW + wv] + __popcll(mg & lt_mask);
-            const uint32_t e_before = ce[i * NW + wv] + __popcll(me & lt_mask);
-            if (g || e_before < need) out[g_before + min(e_before, need)] = i * BLOCK + tid;
+    const int cnt = (int)s_cnt;
+    if (cnt > kPickCap) {   // (the same for every thread) masses of equal values: re-read the row
+        int32_t *tmp = ext_row ? ext_row : src_row;
+        topk_stream_row<BLOCK, false>(row, x, ld, n, k, tmp, 0, nullptr, 0, nullptr, 0, 0, nullptr, 1, 0);
+        if (!ext_row) return;
+        __syncthreads();
+        if (tid < k) {
+            const uint32_t j = (uint32_t)ext_row[tid];
+            win[tid] = ((uint64_t)j << 32) | ord_key(xr[j]);
         }
+        __syncthreads();
+        emit_sources(win, k, S, src_row, ext_row, cls, tid);
+        return;
     }
+    if (wv != 0) return;
+
+    // One wave finishes the row on its own: the k-th largest key of the list, ...
+    const int n_it = (cnt + 63) >> 6;
+    uint32_t tau;
+    if (n_it <= 4) tau = pick_tau<4>(lk, cnt, lane, k, bound, kmax);
+    else if (n_it <= 8) tau = pick_tau<8>(lk, cnt, lane, k, bound, kmax);
+    else if (n_it <= 16) tau = pick_tau<16>(lk, cnt, lane, k, bound, kmax);
+    else tau = pick_tau<32>(lk, cnt, lane, k, bound, kmax);
+    int above = 0, equal = 0;
+    for (int r = lane; r < cnt; r += kWave) { above += lk[r] > tau; equal += lk[r] == tau; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { above += __shfl_xor(above, o, kWave); equal += __shfl_xor(equal, o, kWave); }
+    // ... the winners: every entry above it and, of the entries equal to it, the `need` lowest
+    // indices (usually all of them) ...
+    const int need = k - above;
+    int listed = 0;
+    for (int r0 = 0; r0 < cnt; r0 += kWave) {
+        const int r = r0 + lane;
+        const uint32_t kr = r < cnt ? lk[r] : 0u, jr = r < cnt ? lj[r] : 0u;
+        bool in = r < cnt && kr >= tau;
+        if (in && kr == tau && equal != need) {
+            int rank = 0;
+            for (int u = 0; u < cnt; ++u) rank += (lk[u] == tau) & (lj[u] < jr);
+            in = rank < need;
+        }
+        const uint64_t votes = __ballot(in);
+        if (in) win[listed + (int)__popcll(votes & below)] = ((uint64_t)jr << 32) | kr;
+        listed += (int)__popcll(votes);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    // ... and their order.
+    emit_sources_wave(win, k, S, src_row, ext_row, lane);
 }
 
 // ---- rows of any length: every sweep re-reads the row ------------------------
@@ -403,7 +546,7 @@ __device__ __forceinline__ void topk_stream_row(
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int j = j0 + u * BLOCK + tid;
-                t[u] = j < n ? xr[j] : 0.f;
+                t[u] = xr[min(j, n - 1)];
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -435,7 +578,7 @@ __device__ __forceinline__ void topk_stream_row(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = j0 + u * kWave + lane;
-            t[u] = j < end ? xr[j] : 0.f;
+            t[u] = xr[min(j, n - 1)];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -456,7 +599,7 @@ __device__ __forceinline__ void topk_stream_row(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = j0 + u * kWave + lane;
-            t[u] = j < end ? xr[j] : 0.f;
+            t[u] = xr[min(j, n - 1)];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -510,7 +653,8 @@ constexpr int kLongCap = 4096;
 
 template <int BLOCK>
 __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
-    const float *__restrict__ x, long ld, int n, int k, int32_t *__restrict__ idx_out, long idx_ld)
+    const float *__restrict__ x, long ld, int n, int k, int S, int32_t *__restrict__ idx_out, long idx_ld,
+    int32_t *__restrict__ ext_out, long ext_ld)
 {
     constexpr int NW = BLOCK / kWave, U = 8;
     __shared__ uint32_t lk[kLongCap], lj[kLongCap];   // keys and indices of the candidates
@@ -519,9 +663,11 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
     __shared__ uint32_t hist8[256];
     __shared__ uint32_t s_cnt, s_bin, s_need, s_wmax[NW], s_wmin[NW];
     __shared__ int32_t n_win, n_eq;
+    __shared__ uint8_t cls[kSmallK];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const float *xr = x + (long)blockIdx.x * ld;
     int32_t *out = idx_out + (long)blockIdx.x * idx_ld;
+    int32_t *ext_row = ext_out ? ext_out + (long)blockIdx.x * ext_ld : nullptr;
 
     // first read: the largest key each thread owns (0 is below the key of every number)
     uint32_t mx = 0u;
@@ -530,7 +676,7 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = j0 + u * BLOCK + tid;
-            t[u] = j < n ? xr[j] : 0.f;
+            t[u] = xr[min(j, n - 1)];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -586,7 +732,7 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = j0 + u * BLOCK + tid;
-            t[u] = j < n ? xr[j] : 0.f;
+            t[u] = xr[min(j, n - 1)];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -601,8 +747,17 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
     __syncthreads();
     const int cnt = (int)s_cnt;
     if (cnt > kLongCap) {   // (the same for every thread)
-        topk_stream_row<BLOCK, false>(blockIdx.x, x, ld, n, k, idx_out, idx_ld, nullptr, 0, nullptr, 0, 0, nullptr,
-                                      1, 0);
+        int32_t *tmp = ext_row ? ext_row : out;
+        topk_stream_row<BLOCK, false>(0, x + (long)blockIdx.x * ld, ld, n, k, tmp, 0, nullptr, 0, nullptr, 0, 0,
+                                      nullptr, 1, 0);
+        if (!ext_row) return;
+        __syncthreads();
+        if (tid < k) {
+            const uint32_t j = (uint32_t)ext_row[tid];
+            win[tid] = ((uint64_t)j << 32) | ord_key(xr[j]);
+        }
+        __syncthreads();
+        emit_sources(win, k, S, out, ext_row, cls, tid);
         return;
     }
 
@@ -630,12 +785,7 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
         }
     }
     __syncthreads();
-    for (int r = tid; r < k; r += BLOCK) {   // ascending index order
-        const uint64_t mine = win[r];
-        int pos = 0;
-        for (int u = 0; u < k; ++u) pos += win[u] < mine;
-        out[pos] = (int32_t)(mine >> 32);
-    }
+    emit_sources(win, k, S, out, ext_row, cls, tid);   // ascending index order
 }
 
 // ---- neighbourhoods of heads whose candidate lists overflowed ------------------------
@@ -643,19 +793,19 @@ __global__ __launch_bounds__(BLOCK) void topk_rows_long_smallk_kernel(
 // reaches the bound (masses of equal edges, an adversarial key order) and raises the head's
 // flag.  Such heads are rare, so they are not worth an [heads, S, P] edge block in memory: a
 // fixed number of workgroups walk the (head, source) rows of the flagged heads, and each row's
-// edges (Eq. 1, scalar fused multiply-adds over the bf16 rows, d = 128) go to the workgroup's
-// own scratch row of P floats, out of which the exact top-m (Eq. 3) is taken by the row
-// kernels above.  A launch that finds no flag set returns after one round trip.
+// edges (Eq. 1) go to the workgroup's own scratch row of P floats, out of which the exact top-m
+// (Eq. 3) is taken by the row kernels above.  The edges are formed exactly as in the streaming
+// kernels -- the same matrix-core instruction sequence with the source in every operand row, the
+// same norms -- so that a head gets the same bits whichever route it takes.  A launch that
+// finds no flag set returns after one round trip.
 constexpr int kRedoBlock = 1024;
-constexpr int kRedoDim = 128;
 
 __global__ __launch_bounds__(kRedoBlock) void redo_rows_kernel(
     const uint16_t *__restrict__ Ac, const uint16_t *__restrict__ Kc, int N, int P, int S, int m, int heads,
     const int32_t *__restrict__ src, const int32_t *__restrict__ overflow, float *__restrict__ rows,
     int32_t *__restrict__ nbr, float *__restrict__ nbr_e)
 {
-    __shared__ float s_f32[kRedoDim];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
     int open = 0;
     for (int g = tid; g < heads; g += kRedoBlock) open |= overflow[g] != 0;
     if (!__syncthreads_or(open)) return;
@@ -664,28 +814,31 @@ __global__ __launch_bounds__(kRedoBlock) void redo_rows_kernel(
         const int h = (int)(item / S);
         if (overflow[h] == 0) continue;           // (the same for every thread)
         const int32_t i = src[item];
-        const uint16_t *ah = Ac + (long)h * N * kRedoDim, *kh = Kc + (long)h * N * kRedoDim;
+        const uint16_t *ah = Ac + (long)h * N * kD, *kh = Kc + (long)h * N * kD;
         __syncthreads();                          // the previous row's LDS and scratch row are free
-        if (tid < kRedoDim) s_f32[tid] = bf16_to_f32(ah[(long)i * kRedoDim + tid]);
-        __syncthreads();
-        float sq_i = 0.f;                         // |x_i|^2 in a fixed order, the same in every thread
-        for (int c = 0; c < kRedoDim; ++c) sq_i = fmaf(s_f32[c], s_f32[c], sq_i);
-        const float inv_i = sq_i == 0.f ? 0.f : __builtin_amdgcn_rsqf(sq_i);
-        for (int j = tid; j < P; j += kRedoBlock) {
-            const uint4 *kv = reinterpret_cast<const uint4 *>(kh + (long)j * kRedoDim);
-            float dot = 0.f, sq = 0.f;
-#pragma unroll 4
-            for (int c = 0; c < kRedoDim / 8; ++c) {
-                float t[8];
-                Elem<uint16_t>::unpack(kv[c], t);
+        // the source's row in every row of the operand (a lane holds elements 16 s + 8 hh ..)
+        bf16x8 q[kSteps];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    dot = fmaf(s_f32[c * 8 + u], t[u], dot);
-                    sq = fmaf(t[u], t[u], sq);
-                }
-            }
-            const float inv_k = sq == 0.f ? 0.f : __builtin_amdgcn_rsqf(sq);
-            erow[j] = j == i ? -INFINITY : (dot * inv_k) * inv_i;   // (Eq. 3: j != i; a zero row has e = 0)
+        for (int s = 0; s < kSteps; ++s) q[s] = load8(ah + (long)i * kD + 16 * s + 8 * hh);
+        float sq_i = half_row_sumsq(q);
+        sq_i += __shfl_xor(sq_i, 32, kWave);
+        const float inv_i = inv_norm(sq_i);
+        // blocks of 32 keys, one per wave at a time: key l32 of the block is the operand's column
+        for (int j0 = wv * kBlk; j0 < P; j0 += (kRedoBlock / kWave) * kBlk) {
+            const int j = min(j0 + l32, P - 1);
+            bf16x8 kc[kSteps];
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s) kc[s] = load8(kh + (long)j * kD + 16 * s + 8 * hh);
+            f32x16 acc;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) acc[u] = 0.f;
+#pragma unroll
+            for (int s = 0; s < kSteps; ++s)   // rows = the source (32 times), columns = keys
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[s], kc[s], acc, 0, 0, 0);
+            float sq = half_row_sumsq(kc);
+            sq += __shfl_xor(sq, 32, kWave);
+            const float e = (acc[0] * inv_norm(sq)) * inv_i;
+            if (hh == 0 && j0 + l32 < P) erow[j] = j == i ? -INFINITY : e;   // (Eq. 3: j != i)
         }
         __syncthreads();                          // the row is complete and visible to the workgroup
         int32_t *out = nbr + item * m;
@@ -733,8 +886,8 @@ static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, in
     if constexpr (!PLAN) {
         if (n > 4096 && n <= 32768 && k <= kSmallK && idx_out && !val_out && !tau_out && append_count == 0 &&
             !gate) {
-            hipLaunchKernelGGL(topk_rows_smallk_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, k,
-                               idx_out, idx_ld);
+            hipLaunchKernelGGL(pick_sources_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, k, k, idx_out,
+                               idx_ld, (int32_t *)nullptr, 0L);
             return hipGetLastError();
         }
     }
@@ -743,8 +896,8 @@ static hipError_t launch_any(const float *x, long ld, int n, int rows, int k, in
                                           append_from, append_count, gate, rows_per_gate, plan, st);
     if constexpr (!PLAN) {
         if (k <= kSmallK && idx_out && !val_out && !tau_out && append_count == 0 && !gate) {
-            hipLaunchKernelGGL(topk_rows_long_smallk_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, k,
-                               idx_out, idx_ld);
+            hipLaunchKernelGGL(topk_rows_long_smallk_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, k, k,
+                               idx_out, idx_ld, (int32_t *)nullptr, 0L);
             return hipGetLastError();
         }
     }
@@ -784,6 +937,20 @@ hipError_t launch_redo_rows(const void *Ac, const void *Kc, int heads, int N, in
     hipLaunchKernelGGL(redo_rows_kernel, dim3(redo_rows_workgroups(heads, S)), dim3(kRedoBlock), lds, st,
                        (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, m, heads, src, overflow, rows, nbr,
                        nbr_e);
+    return hipGetLastError();
+}
+
+hipError_t launch_pick_sources(const float *x, long ld, int n, int rows, int S, int X, int32_t *src,
+                               int32_t *ext, hipStream_t st)
+{
+    if (rows <= 0) return hipSuccess;
+    if (n <= 4096 || S + X > kSmallK) return hipErrorInvalidValue;
+    if (n <= 32768)
+        hipLaunchKernelGGL(pick_sources_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, S + X, S, src,
+                           (long)S, ext, (long)(S + X));
+    else
+        hipLaunchKernelGGL(topk_rows_long_smallk_kernel<1024>, dim3(rows), dim3(1024), 0, st, x, ld, n, S + X, S,
+                           src, (long)S, ext, (long)(S + X));
     return hipGetLastError();
 }
 

@@ -151,16 +151,23 @@ __global__ __launch_bounds__(kDecayThreads) void decay_hash_kernel(
 #pragma unroll
     for (int q = 0; q < kDecayPer; ++q) {
         const int t = q * kDecayThreads + tid;
-        node[q] = t < count ? (uint32_t)nb[t] : kNoNode;
-        fac[q] = t < count ? ne[t] : 0.f;
+        const int tc = min(t, count - 1);   // (unconditional loads leave together)
+        const uint32_t nd = (uint32_t)nb[tc];
+        const float ed = ne[tc];
+        node[q] = t < count ? nd : kNoNode;
+        fac[q] = t < count ? ed : 0.f;
     }
     // the sign of each node's score decides the direction of its factors; these loads are in
     // flight while the table is set up
+    static_assert(kDecayPer == 8, "the loads below are pinned eight at a time");
+    float sj[kDecayPer];
 #pragma unroll
-    for (int q = 0; q < kDecayPer; ++q) {
-        const float sj = node[q] != kNoNode ? s[node[q]] : 0.f;
-        fac[q] = node[q] != kNoNode ? signal_factor(fac[q], alpha, signal, sj < 0.f) : 1.0f;
-    }
+    for (int q = 0; q < kDecayPer; ++q) sj[q] = s[node[q] != kNoNode ? node[q] : 0u];   // (unconditional)
+    asm volatile("" : "+v"(sj[0]), "+v"(sj[1]), "+v"(sj[2]), "+v"(sj[3]), "+v"(sj[4]), "+v"(sj[5]), "+v"(sj[6]),
+                      "+v"(sj[7]));
+#pragma unroll
+    for (int q = 0; q < kDecayPer; ++q)
+        fac[q] = node[q] != kNoNode ? signal_factor(fac[q], alpha, signal, sj[q] < 0.f) : 1.0f;
     for (int i = tid; i < Tn; i += kDecayThreads) {
         cell_node[i] = kNoNode;
         low0[i] = kNoNode;
@@ -240,7 +247,7 @@ __global__ __launch_bounds__(NT) void decay_sorted_kernel(
     const float *ne = nbr_e + (long)h * count;
     float *s = scores + (long)h * P;
     for (int t = tid; t < npad; t += NT)
-        keys[t] = t < count ? (((uint64_t)(uint32_t)nb[t] << 32) | (uint32_t)t) : ~0ull;
+        keys[t] = t < count ? (((uint64_t)(uint32_t)nb[min(t, count - 1)] << 32) | (uint32_t)t) : ~0ull;
     __syncthreads();
     bitonic_sort_lds<NT / kWave>(keys, npad, lane, wv);
     for (int t = tid; t < count; t += NT) {
