@@ -11,7 +11,7 @@
 //   1. the same kernel first runs on an evenly strided sample of the keys and
 //      writes that small edge block; the m-th largest sampled edge of a source
 //      is a lower bound of its m-th largest edge overall (a subset's m-th
-//      largest can only be smaller), and a tight one for a sample of P/16 keys;
+//      largest can only be smaller), and a tight one for a sample of P/8 keys;
 //   2. the streaming pass keeps only the edges that reach the bound (a few
 //      hundred per source), staged in LDS and appended to per-source lists;
 //   3. an exact (value desc, index asc) top-m over each short list.
@@ -420,15 +420,18 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
             const float inv_k = inv_norm(extra.x);   // the dense kernel's formula
             const float norm_k = __builtin_amdgcn_sqrtf(extra.x);
             const uint32_t key = __float_as_uint(extra.y);
-            uint32_t hits = 0;   // the test that parked the row, source by source
+            // the test that parked the row, source by source: bit i of `hits` = (dot_i - det_i |k|
+            // is not negative), gathered from the sign bits, source 15 first
+            uint32_t neg = 0;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
+            for (int v = 3; v >= 0; --v) {
                 const float4 dv = vals[v];
                 const float d4[4] = {dv.x, dv.y, dv.z, dv.w};
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    hits |= (fmaf(-det[4 * v + u], norm_k, d4[u]) >= 0.f ? 1u : 0u) << (4 * v + u);
+                for (int u = 3; u >= 0; --u)
+                    neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(fmaf(-det[4 * v + u], norm_k, d4[u])), 31);
             }
+            uint32_t hits = ~neg & 0xffffu;
             long off[4];
             float ev[4];
 #pragma unroll
@@ -1045,9 +1048,12 @@ int chunk_cols_for(int Hkv, int sgroups, int n_cols, int min_chunks = 1)
 
 }  // namespace
 
+// Keys in the strided sample of the bound pass: every 8th key, between 2048 and 8192 keys (one
+// workgroup walks the whole sample of a head's sources).  A denser sample costs the bound pass
+// more and gives a tighter bound, i.e. fewer candidates for the filter pass to park and list.
 int mfma_sample_cols(int P)
 {
-    int ps = ((P / 16 + 127) / 128) * 128;
+    int ps = ((P / 8 + 127) / 128) * 128;
     if (ps < 2048) ps = 2048;
     if (ps > 8192) ps = 8192;
     return ps;
