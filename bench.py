@@ -15,9 +15,20 @@ JSON line.
                    events on the launch stream over a repetition of the timed
                    steps right after them (two event records around each of a
                    step's ~25 launches add 4-5 % to the step time, so they
-                   stay out of the steps that `value` is computed from)
+                   stay out of the steps that `value` is computed from).
+                   Launches that do different work have different names (the
+                   first round's filter pass over every source and the later
+                   rounds' pass over the few sources without a kept list are
+                   two kernels in the table), so no mean mixes them.
   cpu_baseline     the CPU oracle, unchanged, on a bounded sample of the same
-                   layers, extrapolated to the full model
+                   layers: on all host threads it can use (one per KV head),
+                   extrapolated to the full model, and one layer on a single
+                   thread
+  parity_sample    the sampled layers' retained sets against the oracle's; a
+                   head that differs is judged cut by cut (tests/util.py) and
+                   listed
+  other_workloads  a short run of the per-layer-budget workload (c4) on the
+                   same resident tensors
 """
 import argparse
 import contextlib
@@ -49,9 +60,13 @@ def generate_layers(name, layers):
         for l in layers:
             out[l] = _gen_layer((name, l))[1]
         return out
-    with mp.get_context("spawn").Pool(workers) as pool:
+    pool = mp.get_context("spawn").Pool(workers)
+    try:
         for layer, data in pool.imap_unordered(_gen_layer, [(name, l) for l in layers]):
             out[layer] = data
+    finally:
+        pool.close()     # let the workers end by themselves (a terminate() shows up as an abort in profiler logs)
+        pool.join()
     return out
 
 
@@ -69,7 +84,7 @@ def algorithmic_bytes(cfg, B):
         "topk_sources": H * P * 4 + H * S * 4,
         "cosine": H * P * d * e + H * S * d * e,
         "cosine_filter": H * P * d * e + H * S * d * e,
-        "cosine_bound": H * (P // 16) * d * e + H * S * d * e,
+        "cosine_bound": H * (P // 8) * d * e + H * S * d * e,
         "topk_neighbors": H * S * m * 8,
         "decay": 2 * H * S * m * 8,
         "topk_final": H * P * 4 + H * B * 4,
@@ -256,7 +271,11 @@ def main():
         roofline = {
             "kernel": dom, "bound": "hbm", "achieved": kernels[dom]["alg_GBps"], "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": round(kernels[dom]["alg_GBps"] / HBM_PEAK_GBS, 4),
-            "traffic": traffic, "avg_launch_us": kernels[dom]["avg_us"],
+            "traffic": traffic,
+            "traffic_source": "stored: profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                              "command, scaled; not measured in this run)" if traffic is not None else None,
+            "avg_launch_us": kernels[dom]["avg_us"],
+            "launches_per_step": kernels[dom]["launches_per_step"],
             "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"],
             "measured_over": f"{profile_steps} steps with per-kernel events, right after the timed ones",
         }
@@ -266,6 +285,8 @@ def main():
                           if k in ("score_stats", "score_votes", "gather")) +
                       cfg.rounds * algorithmic_bytes(cfg, p.budget)["cosine"] for p in params)   # (2 + T) |K| + gather
     pass_view = {
+        "model": "(2 + T) passes over the keys plus the gather; the kernels stream the keys fewer times when the "
+                 "neighbour lists of later rounds are already there, so the fraction is of the model, not of traffic",
         "model_bytes_per_step": int(model_bytes),
         "model_GBps": round(model_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "frac_of_hbm_peak": round(model_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -274,14 +295,51 @@ def main():
         "frac_of_bf16_mfma_peak": round(model_flops(cfg) * L / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
     }
 
+    # ---- the per-layer-budget workload (c4: budgets 4096 .. 512, three rounds) on the same
+    # resident tensors (its generator is c3's), a few steps ----
+    other = None
+    if args.workload == "c3" and args.mode == "batched" and L == cfg.n_layers and args.streams == 1:
+        c4 = synth.CONFIGS["c4"]
+        b4 = [c4.budget_for_layer(l) for l in range(L)]
+        p4 = gk.Params(n_kv_heads=H, n_q_heads=Hq, head_dim=d, n_tokens=N, window=w, pool_kernel=c4.pool_kernel,
+                       pool_mode=c4.pool_mode, budget=b4[0], n_sources=c4.n_sources, n_neighbors=c4.n_neighbors,
+                       rounds=c4.rounds, decay=c4.decay, reselect=c4.reselect, dtype=dt)
+        rows4 = H * sum(b4)
+        K4 = torch.empty((rows4, d), dtype=tdt, device=dev)
+        V4 = torch.empty((rows4, d), dtype=tdt, device=dev)
+        I4 = torch.empty((rows4,), dtype=torch.int32, device=dev)
+        ws4 = torch.empty(gk.graphkv_workspace_bytes_batched(p4, L), dtype=torch.uint8, device=dev)
+        for _ in range(2):
+            gk.graphkv_compress_batched(p4, L, b4, Kall, Vall, Qall, K4, V4, I4, None, ws4)
+        torch.cuda.synchronize()
+        n4 = 5
+        t4 = time.perf_counter()
+        for _ in range(n4):
+            gk.graphkv_compress_batched(p4, L, b4, Kall, Vall, Qall, K4, V4, I4, None, ws4)
+        torch.cuda.synchronize()
+        ms4 = (time.perf_counter() - t4) * 1e3 / n4
+        gk.graphkv_profile_begin()
+        for _ in range(n4):
+            gk.graphkv_compress_batched(p4, L, b4, Kall, Vall, Qall, K4, V4, I4, None, ws4)
+        prof4 = gk.graphkv_profile_end()
+        torch.cuda.synchronize()
+        other = {"c4": {"workload": f"budgets {b4[0]}..{b4[-1]} per layer, S={c4.n_sources}, m={c4.n_neighbors}, T={c4.rounds}",
+                        "steps": n4, "ms_per_step": round(ms4, 4), "value": round(N / (ms4 * 1e-3), 1),
+                        "unit": "prompt tokens/s",
+                        "kernels_us_per_step": {k: round(ms * 1e3 / n4, 1) for k, (ms, cnt) in prof4.items()}}}
+        del K4, V4, I4, ws4
+
     # ---- CPU baseline: the oracle on a bounded sample of the same layers ----
     cpu = None
     parity = None
     if args.cpu_layers > 0:
+        import ctypes
+        import platform
         import oracle
+        from tests import util as judge       # the cut-by-cut judgement of a differing retained set
         n_s = min(args.cpu_layers, L)
         oracle.lib()
-        differing = 0
+        excused, differing, violations = [], 0, []
         t_cpu = 0.0
         for l in range(n_s):
             K, V, Q = host[l]
@@ -291,15 +349,48 @@ def main():
                                   p.n_neighbors, p.rounds, alpha=p.decay, reselect=p.reselect)
             t_cpu += time.perf_counter() - tc
             got = Iout[row_off[l]:row_off[l + 1]].cpu().numpy().reshape(H, p.budget)
-            differing += int((got != ref["idx"]).any(axis=1).sum())
+            try:
+                diffs = judge.judge_layer(oracle, p, host[l], (Kall[l], Vall[l], Qall[l]), ref, got, layer=l,
+                                          excused=excused)
+                differing += len(diffs)
+            except AssertionError as err:      # a difference that no near-tie explains: reported, not hidden
+                violations.append(f"layer {l}: {err}")
         threads = min(cfg.n_kv_heads, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+        # one layer on a single thread (the oracle parallelises over KV heads only)
+        single = None
+        try:
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            K, V, Q = host[0]
+            p = params[0]
+            tc = time.perf_counter()
+            oracle.compress(K, V, Q, cfg.dtype, p.pool_kernel, p.budget, p.n_sources, p.n_neighbors, p.rounds,
+                            alpha=p.decay, reselect=p.reselect)
+            t1 = time.perf_counter() - tc
+            gomp.omp_set_num_threads(threads)
+            single = {"value": round(cfg.n_tokens / (t1 * cfg.n_layers), 2), "unit": "prompt tokens/s", "cores": 1,
+                      "sample": f"layer 0 of {cfg.n_layers} in {t1:.1f} s, extrapolated x{cfg.n_layers}"}
+        except OSError:
+            pass
+        cpu_model = platform.processor() or ""
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         cpu = {
             "value": round(cfg.n_tokens / (t_cpu / n_s * cfg.n_layers), 2), "unit": "prompt tokens/s",
             "cores": threads, "kind": "oracle",
             "sample": f"layers 0..{n_s - 1} of {cfg.n_layers} in {t_cpu:.1f} s, extrapolated x{cfg.n_layers / n_s:g}",
+            "precision": "fp64", "cpu_model": cpu_model, "host_cpus": os.cpu_count(), "single_thread": single,
         }
-        parity = {"layers_checked": n_s, "heads_with_differing_retained_set": differing,
-                  "heads_checked": n_s * cfg.n_kv_heads}
+        parity = {"layers_checked": n_s, "heads_checked": n_s * cfg.n_kv_heads,
+                  "heads_with_differing_retained_set": differing,
+                  "accepted_at_near_ties": excused, "violations": violations,
+                  "rule": "a head may differ only if the first cut at which its picks leave the oracle's has an "
+                          "oracle gap below 2e-3 and every later stage holds on the GPU's own upstream values"}
 
     out = {
         "metric": "prefix tokens compressed/sec (all layers+heads)",
@@ -315,7 +406,7 @@ def main():
                                         else f" ({args.streams} stream(s))") + (", one HIP graph per step" if args.graph else ""),
                    "token_head_units_per_s": round(tokens_per_s * cfg.n_layers * cfg.n_kv_heads, 1),
                    "input_generation_s": round(t_gen, 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "pass_vs_streaming_model": pass_view,
+        "roofline": roofline, "cpu_baseline": cpu, "pass_vs_streaming_model": pass_view, "other_workloads": other,
         "kernels": kernels, "parity_sample": parity,
     }
     print(json.dumps(out), flush=True)

@@ -259,7 +259,11 @@ enum {
     GRAPHKV_K_GATHER, GRAPHKV_K_GENERIC_LOGITS, GRAPHKV_K_GENERIC_VOTES, GRAPHKV_K_GENERIC_COSINE,
     GRAPHKV_K_KNORM, GRAPHKV_K_COPY, GRAPHKV_K_COSINE_BOUND,
     GRAPHKV_K_COSINE_FILTER, GRAPHKV_K_NBR_SELECT, GRAPHKV_K_REDO_ROWS,
-    GRAPHKV_K_MATCH_SOURCES, GRAPHKV_N_KERNELS
+    GRAPHKV_K_MATCH_SOURCES,
+    /* later rounds when neighbour lists are kept: source selection, and the bound, filter and
+     * select passes over the few sources that have no list yet */
+    GRAPHKV_K_TOPK_SOURCES_LATER, GRAPHKV_K_COSINE_BOUND_NEW, GRAPHKV_K_COSINE_FILTER_NEW,
+    GRAPHKV_K_NBR_SELECT_LATER, GRAPHKV_N_KERNELS
 };
 int32_t graphkv_profile_begin(void);
 int32_t graphkv_profile_end(double *ms, int64_t *launches);

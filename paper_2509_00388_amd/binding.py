@@ -30,7 +30,7 @@ EXPORTS = ("graphkv_workspace_bytes", "graphkv_score", "graphkv_score_knorm", "g
            "graphkv_workspace_bytes_batched", "graphkv_compress_batched", "graphkv_propagate_edges",
            "graphkv_compress_static")
 STATIC_SCRATCH_BYTES = 64 << 20
-N_KERNELS = 19
+N_KERNELS = 23
 
 
 class GraphKVError(RuntimeError):

@@ -225,7 +225,8 @@ const char *const kKernelNames[GRAPHKV_N_KERNELS] = {
     "score_stats", "score_votes", "pool_group", "topk_sources", "cosine", "topk_neighbors",
     "decay", "topk_final", "gather", "generic_logits", "generic_votes", "generic_cosine",
     "knorm", "copy", "cosine_bound", "cosine_filter", "nbr_select",
-    "redo_rows", "match_sources"};
+    "redo_rows", "match_sources", "topk_sources_later", "cosine_bound_new", "cosine_filter_new",
+    "nbr_select_later"};
 
 #define GKV_LAUNCH(id, expr)                                              \
     do {                                                                  \
@@ -348,7 +349,7 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                     GKV_LAUNCH(GRAPHKV_K_REDO_ROWS,
                                launch_redo_rows(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, ovf, E, nbr, ev, st));
                 } else {
-                    GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES,
+                    GKV_LAUNCH(GRAPHKV_K_TOPK_SOURCES_LATER,
                                launch_topk_rows(scores, D.P, D.P, D.H, D.S, src, D.S, nullptr, 0, nullptr, 0, 0,
                                                 nullptr, 1, st));
                     int32_t *new_src = at<int32_t>(ws, W.new_src), *n_new = at<int32_t>(ws, W.n_new);
@@ -361,13 +362,13 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
                                                     at<int32_t>(ws, W.n_sel), st));
                     // new sources without a kept list (usually none): bound and filter passes
                     // that return at once for heads that have none
-                    GKV_LAUNCH(GRAPHKV_K_COSINE_BOUND,
+                    GKV_LAUNCH(GRAPHKV_K_COSINE_BOUND_NEW,
                                launch_mfma_cosine_bound(Ac, Kc, D.H, D.N, D.P, D.m, g, false, new_src, n_new,
                                                         at<char>(ws, W.bound_hist), tau, ovf, st));
-                    GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER,
+                    GKV_LAUNCH(GRAPHKV_K_COSINE_FILTER_NEW,
                                launch_mfma_cosine_filter(Ac, Kc, D.H, D.N, D.P, D.m, g, false, new_src, n_new, tau,
                                                          cand, cnt, ovf, st));
-                    GKV_LAUNCH(GRAPHKV_K_NBR_SELECT,
+                    GKV_LAUNCH(GRAPHKV_K_NBR_SELECT_LATER,
                                launch_nbr_select(cand, cnt, ovf, src, D.H, D.m, g, &sel, nbr, ev, st));
                     GKV_LAUNCH(GRAPHKV_K_REDO_ROWS,
                                launch_redo_rows(Ac, Kc, D.H, D.N, D.P, D.S, D.m, src, ovf, E, nbr, ev, st));
