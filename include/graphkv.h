@@ -211,7 +211,7 @@ int32_t graphkv_compress(const graphkv_params *p, const void *Kc, const void *Vc
  *   scores_out [n_layers, H_kv, P] or NULL
  *   ws         graphkv_workspace_bytes_batched(p, n_layers) bytes
  * Layers are processed in groups: at most 64 layers, fewer while the scratch
- * memory of a group would exceed 1.5 GiB (long prompts).  Results are identical
+ * memory of a group would exceed 2000 MiB (long prompts).  Results are identical
  * to n_layers per-layer calls.
  */
 size_t graphkv_workspace_bytes_batched(const graphkv_params *p, int32_t n_layers);

@@ -453,9 +453,9 @@ int32_t run_compress(const graphkv_params *p, int n_layers, bool speculate, cons
 }
 
 // Layers that go through the kernels together: at most kMaxLayers and 65535 heads, and fewer
-// while the scratch memory of a group would exceed 1.5 GiB (long prompts: the candidate lists
+// while the scratch memory of a group would exceed 2000 MiB (long prompts: the candidate lists
 // and vote rows grow with the number of heads in flight).
-constexpr size_t kGroupScratchCap = (size_t)1536 << 20;
+constexpr size_t kGroupScratchCap = (size_t)2000 << 20;
 // The speculative rows of the filter route cost scratch too: they are dropped before a group is
 // made smaller.
 Dims group_dims(const graphkv_params *p, int n_layers)

@@ -104,7 +104,7 @@ bool mfma_filter_applies(int P, int m);
 int mfma_sample_cols(int P);          // keys in the strided sample
 int mfma_cand_cap(int P, int m);      // candidates per source the exact select can take
 bool source_reuse_applies(int S);     // lists can be kept from round to round
-constexpr int kSpecRows = 32;         // speculative rows per head: one MFMA row block
+constexpr int kSpecRows = 32;         // speculative rows per head: one or two MFMA row blocks of 32
 constexpr int kMaxExtSources = 256;   // largest S + kSpecRows the source selection splits
 // Geometry of the filter route for one call.  The per-row buffers (tau [Hkv, pitch], cand
 // [Hkv, pitch, chunks, slice_cap] x 8 bytes, cand_cnt [Hkv, pitch, chunks]) hold, per head,

@@ -1088,7 +1088,15 @@ MfmaFilterPlan mfma_filter_plan(int Hkv, int P, int S, int m, bool keep_lists, b
 {
     MfmaFilterPlan g{};
     g.S = S;
-    g.X = (keep_lists && speculate && S + kSpecRows <= kMaxExtSources) ? kSpecRows : 0;
+    // speculative rows: at least one 32-row block; the extended list fills whole 96-row workgroups
+    // where that takes at most two blocks
+    g.X = 0;
+    if (keep_lists && speculate && S + kSpecRows <= kMaxExtSources) {
+        int x = (S + kSpecRows + 95) / 96 * 96 - S;
+        if (x > 2 * kSpecRows) x = 2 * kSpecRows;
+        if (S + x > kMaxExtSources) x = (kMaxExtSources - S) / 8 * 8;
+        g.X = x;
+    }
     g.sb = g.X > 0 ? 3 : 2;
     g.pitch = S + g.X;
     const int rows_wg = kBlk * g.sb;
@@ -1099,8 +1107,11 @@ MfmaFilterPlan mfma_filter_plan(int Hkv, int P, int S, int m, bool keep_lists, b
         g.chunk_cols = (((P + 255) / 256 + 127) / 128) * 128;
         g.chunks = (P + g.chunk_cols - 1) / g.chunk_cols;
     }
+    // a slice holds four times its expected share of a row's ~m * stride candidates (three times
+    // for long lists, whose relative spread is small)
     const int stride = P / mfma_sample_cols(P);
-    long sc = 4L * ((long)m * stride + g.chunks - 1) / g.chunks;
+    const long share = ((long)m * stride + g.chunks - 1) / g.chunks;
+    long sc = (share >= 512 ? 3L : 4L) * share;
     if (sc < 2L * m) sc = 2L * m;
     if (sc < 64) sc = 64;
     g.cand_cap = mfma_cand_cap(P, m);

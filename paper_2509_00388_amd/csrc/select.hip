@@ -916,15 +916,19 @@ hipError_t launch_topk_rows(const float *x, long ld, int n, int rows, int k, int
                                   append_from, append_count, gate, rows_per_gate, 0, st);
 }
 
-int redo_rows_workgroups(int heads, int S)
+// Workgroups that walk the rows of flagged heads: one per compute unit, fewer for long rows
+// (their scratch rows stay within 64 MiB), at least 16.
+int redo_rows_workgroups(int heads, int S, int P)
 {
     const long items = (long)heads * S;
-    return (int)(items < 256 ? items : 256);
+    long wgs = ((long)64 << 20) / ((long)P * 4);
+    wgs = wgs < 16 ? 16 : (wgs > 256 ? 256 : wgs);
+    return (int)(items < wgs ? items : wgs);
 }
 
 size_t redo_rows_scratch_bytes(int heads, int S, int P)
 {
-    return (size_t)redo_rows_workgroups(heads, S) * P * sizeof(float);
+    return (size_t)redo_rows_workgroups(heads, S, P) * P * sizeof(float);
 }
 
 hipError_t launch_redo_rows(const void *Ac, const void *Kc, int heads, int N, int P, int S, int m,
@@ -934,7 +938,7 @@ hipError_t launch_redo_rows(const void *Ac, const void *Kc, int heads, int N, in
     const int items = P <= 32768 ? (P + kRedoBlock - 1) / kRedoBlock : 0;   // keys of a row in LDS
     const size_t lds = ((size_t)items * kRedoBlock + 2 * (size_t)items * (kRedoBlock / kWave)) * 4;
     if (lds > 65536 && !allow_big_lds((const void *)redo_rows_kernel, 140 * 1024)) return hipGetLastError();
-    hipLaunchKernelGGL(redo_rows_kernel, dim3(redo_rows_workgroups(heads, S)), dim3(kRedoBlock), lds, st,
+    hipLaunchKernelGGL(redo_rows_kernel, dim3(redo_rows_workgroups(heads, S, P)), dim3(kRedoBlock), lds, st,
                        (const uint16_t *)Ac, (const uint16_t *)Kc, N, P, S, m, heads, src, overflow, rows, nbr,
                        nbr_e);
     return hipGetLastError();

@@ -266,6 +266,118 @@ __global__ __launch_bounds__(NT) void decay_sorted_kernel(
     }
 }
 
+// The same update by a radix sort, for up to BLOCK * ITEMS triples whose (node, triple)
+// pair fits 32 bits (node < 2^(32 - kTripleBits)).  Key = node << kTripleBits | triple id.
+// The triple ids ascend in the input, and a least-significant-digit radix sort is stable, so
+// sorting by the node bits alone (6 bits a pass) leaves the triples of a node in ascending
+// id, i.e. ascending source order -- Eq. 5's fixed order.  Per pass every wave ranks the keys of
+// its own contiguous block: the lanes that hold the same digit find each other with six wave
+// votes, the lowest of them adds their number to the wave's counter of that digit, and a
+// block-wide scan of the (digit, wave) counters gives every key its place; three barriers a
+// pass.  Then the first triple of every node multiplies that node's factors and writes its
+// score once.  Two key buffers in LDS (8 bytes per triple in all).
+constexpr int kTripleBits = 14;   // triple ids below 16384
+
+template <int BLOCK, int ITEMS>
+__global__ __launch_bounds__(BLOCK) void decay_radix_kernel(
+    float *__restrict__ scores, int P, int count, int node_bits, const int32_t *__restrict__ nbr,
+    const float *__restrict__ nbr_e, float alpha, int signal)
+{
+    constexpr int NW = BLOCK / kWave, NPAD = BLOCK * ITEMS;
+    static_assert(NPAD <= (1 << kTripleBits), "triple ids must fit kTripleBits");
+    extern __shared__ uint32_t radix_lds[];
+    uint32_t *buf_a = radix_lds, *buf_b = radix_lds + NPAD;   // [NPAD] each
+    __shared__ uint32_t cnt_s[NW][64];                        // keys of each digit in each wave's block
+    __shared__ uint32_t wave_sum[NW];
+    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int32_t *nb = nbr + (long)h * count;
+    const float *ne = nbr_e + (long)h * count;
+    float *s = scores + (long)h * P;
+    const uint64_t below = (1ull << lane) - 1ull;
+
+    // keys of this wave's block, entry it * 64 + lane of it: registers hold them through a pass
+    uint32_t key[ITEMS];
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int t = (wv * ITEMS + it) * kWave + lane;
+        const uint32_t node = (uint32_t)nb[min(t, count - 1)];
+        key[it] = t < count ? (node << kTripleBits) | (uint32_t)t : 0xffffffffu;   // padding sorts last
+    }
+    uint32_t *src_buf = buf_a, *dst_buf = buf_b;
+    for (int shift = kTripleBits; shift < kTripleBits + node_bits; shift += 6) {
+        for (int i = lane; i < 64; i += kWave) cnt_s[wv][i] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        uint32_t place[ITEMS];   // digit << 16 | rank among the wave's keys of that digit
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const uint32_t d = (key[it] >> shift) & 63u;
+            uint64_t peers = ~0ull;   // lanes whose key has the same digit
+#pragma unroll
+            for (int b = 0; b < 6; ++b) {
+                const uint64_t v = __ballot((d >> b) & 1u);
+                peers &= ((d >> b) & 1u) ? v : ~v;
+            }
+            const int leader = __ffsll((long long)peers) - 1;
+            uint32_t base = 0;
+            if (lane == leader) base = atomicAdd(&cnt_s[wv][d], (uint32_t)__popcll(peers));
+            base = __shfl(base, leader, kWave);
+            place[it] = (d << 16) | (base + (uint32_t)__popcll(peers & below));
+        }
+        __syncthreads();
+        // exclusive scan of the counters in (digit, wave) order: thread t <-> digit t / NW, wave t % NW
+        uint32_t run = 0;
+        {
+            uint32_t v = 0;
+            if (tid < 64 * NW) v = cnt_s[tid % NW][tid / NW];
+            uint32_t incl = v;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t u = __shfl_up(incl, o, kWave);
+                if (lane >= o) incl += u;
+            }
+            if (lane == 63) wave_sum[wv] = incl;
+            __syncthreads();
+            uint32_t before = 0;
+            for (int u = 0; u < wv; ++u) before += wave_sum[u];
+            run = before + incl - v;
+            __syncthreads();      // every counter is read before it is overwritten with its offset
+            if (tid < 64 * NW) cnt_s[tid % NW][tid / NW] = run;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it)
+            dst_buf[cnt_s[wv][place[it] >> 16] + (place[it] & 0xffffu)] = key[it];
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) key[it] = dst_buf[(wv * ITEMS + it) * kWave + lane];
+        uint32_t *tmp = src_buf; src_buf = dst_buf; dst_buf = tmp;
+    }
+    // the sorted keys sit in registers (position (wv * ITEMS + it) * 64 + lane) and in src_buf
+    if (src_buf == buf_a) {   // (no pass at all: node_bits = 0 cannot happen, P >= 2; keep the buffer valid)
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) buf_a[(wv * ITEMS + it) * kWave + lane] = key[it];
+        __syncthreads();
+    }
+    const uint32_t *sorted = src_buf;
+#pragma unroll
+    for (int it = 0; it < ITEMS; ++it) {
+        const int pos = (wv * ITEMS + it) * kWave + lane;
+        const uint32_t k = key[it];
+        if (pos >= count) continue;
+        const uint32_t node = k >> kTripleBits;
+        if (pos > 0 && (sorted[pos - 1] >> kTripleBits) == node) continue;   // not the first of its node
+        if (signal == 2) { s[node] = -INFINITY; continue; }
+        const float sj = s[node];
+        float f = 1.0f;
+        for (int u = pos; u < count; ++u) {
+            const uint32_t ku = sorted[u];
+            if ((ku >> kTripleBits) != node) break;
+            f *= signal_factor(ne[ku & ((1u << kTripleBits) - 1u)], alpha, signal, sj < 0.f);
+        }
+        s[node] = sj * f;
+    }
+}
+
 // Same update without the sort, for S*m beyond the LDS capacity: sources are
 // applied one after the other; inside one source the m neighbours are distinct
 // nodes, so they can be updated in parallel.  Multiplying s_j by the factors one
@@ -374,6 +486,18 @@ hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32
         if (lds > 65536 && !allow_big_lds((const void *)decay_hash_kernel, 8192 * 16)) return hipGetLastError();
         hipLaunchKernelGGL(decay_hash_kernel, dim3(Hkv), dim3(kDecayThreads), lds, st, scores, P,
                            (int)count, table_log2, nbr, nbr_e, alpha, signal);
+    } else if (count <= 16384 && P <= (1 << (32 - kTripleBits))) {
+        int node_bits = 1;
+        while ((1L << node_bits) < P) ++node_bits;
+        if (!allow_big_lds((const void *)decay_radix_kernel<1024, 16>, 16384 * 8) ||
+            !allow_big_lds((const void *)decay_radix_kernel<1024, 8>, 16384 * 8))
+            return hipGetLastError();
+        if (count <= 8192)
+            hipLaunchKernelGGL((decay_radix_kernel<1024, 8>), dim3(Hkv), dim3(1024), (size_t)8192 * 8, st, scores, P,
+                               (int)count, node_bits, nbr, nbr_e, alpha, signal);
+        else
+            hipLaunchKernelGGL((decay_radix_kernel<1024, 16>), dim3(Hkv), dim3(1024), (size_t)16384 * 8, st, scores, P,
+                               (int)count, node_bits, nbr, nbr_e, alpha, signal);
     } else if (npad <= 16384) {
         // 128 KiB of dynamic LDS
         if (npad * 8 > 65536 && !allow_big_lds((const void *)decay_sorted_kernel<1024>, 16384 * 8))
