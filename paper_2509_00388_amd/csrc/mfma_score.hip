@@ -1,11 +1,13 @@
 // Stage I on the matrix cores (bf16 inputs, d = 128, fp32 accumulation).
 //
 // Per KV head the window queries of its G query heads are stacked into one
-// R x 128 operand (R = G*w <= 128 rows), held in registers for the whole kernel.
+// R x 128 operand (R = G*w rows), held in registers for the whole kernel.
 // Keys stream from HBM in tiles of 128 rows through LDS (mfma_tile.hpp); each of
 // the 4 key streams of a workgroup multiplies 32 of those rows, so one key block
 // costs R/32 x 8 v_mfma_f32_32x32x16_bf16 and every key is read from HBM exactly
-// once per pass.
+// once per pass.  256 query rows (long windows) take tiles of 64 keys instead: two key
+// streams and four row groups of 64 rows in the same 8 waves, so that those keys are
+// streamed once too.
 //
 // The column sums of a row softmax need the row statistics first, so there are
 // two passes over the keys:
@@ -77,21 +79,21 @@ __device__ __forceinline__ void unit_of_workgroup(int nparts, int &h, int &chunk
 }
 
 // ---------------------------------------------------------------- pass A ---
-template <int NB, int SPLIT>
-__global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
+template <int NB, int SPLIT, int STREAMS = 4>
+__global__ __launch_bounds__(64 * STREAMS * SPLIT) void score_stats_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w,
     int chunk_keys, float c, float *__restrict__ part, int R_total, int row_base, int nparts)
 {
-    constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
+    constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 64 * STREAMS * SPLIT, TK = kBlk * STREAMS;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
-    __shared__ float sm[4][R], sz[4][R];
+    __shared__ float sm[STREAMS][R], sz[STREAMS][R];
     // nparts > 1: equal parts of 128 rows share one launch
     int h, chunk, row_part;
     unit_of_workgroup(nparts, h, chunk, row_part);
     const int nchunks = gridDim.x / nparts;
     row_base += 128 * row_part;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
-    const int stream = wv & 3, row0 = (wv >> 2) * NBW * kBlk;   // first query row of this wave
+    const int stream = wv % STREAMS, row0 = (wv / STREAMS) * NBW * kBlk;   // first query row of this wave
 
     bf16x8 q[NBW][kSteps];
     load_queries<NBW>(Qw + ((long)h * R_total + row_base + row0) * kD, l32, hh, q);
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
 
     const uint16_t *Kh = Kc + (long)h * N * kD;
     const int k0 = chunk * chunk_keys, k1 = min(N, k0 + chunk_keys);
-    const int ntile = (k1 - k0 + kTileKeys - 1) / kTileKeys;
+    const int ntile = (k1 - k0 + TK - 1) / TK;
 
     auto multiply_tile = [&](const unsigned char *buf, int t) {
         bf16x8 kc[kSteps];
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
             for (int b = 0; b < NBW; ++b)   // rows = keys, columns = queries
                 acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[s], q[b][s], acc[b], 0, 0, 0);
 
-        const int kb = k0 + kTileKeys * t + kBlk * stream;
+        const int kb = k0 + TK * t + kBlk * stream;
         if (kb + kBlk <= P) {   // every key of the block is a prefix key: visible to all rows
 #pragma unroll
             for (int b = 0; b < NBW; ++b) {
@@ -156,9 +158,9 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
             }
         }
     };
-    GKV_TILE_PIPELINE(NT, Kh, k0, k1 - 1, 1, ntile, multiply_tile, (void)0);
+    GKV_TILE_PIPELINE_TK(TK, NT, Kh, k0, k1 - 1, 1, ntile, multiply_tile, (void)0);
 
-    // merge the two half-waves (same query, other key rows), then the 4 key streams
+    // merge the two half-waves (same query, other key rows), then the key streams
 #pragma unroll
     for (int b = 0; b < NBW; ++b) {
         const float m2 = __shfl_xor(m[b], 32, kWave), z2 = __shfl_xor(z[b], 32, kWave);
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
     if (tid < R) {
         float mm = sm[0][tid], zz = sz[0][tid];
 #pragma unroll
-        for (int u = 1; u < 4; ++u) merge_stats(mm, zz, sm[u][tid], sz[u][tid]);
+        for (int u = 1; u < STREAMS; ++u) merge_stats(mm, zz, sm[u][tid], sz[u][tid]);
         float *o = part + (((long)h * nchunks + chunk) * R_total + row_base + tid) * 2;
         o[0] = mm;
         o[1] = zz;
@@ -190,14 +192,14 @@ __global__ __launch_bounds__(256 * SPLIT) void score_stats_kernel(
 // pool_half keys on either side of its chunk, and at the end it writes the pooled, grouped
 // scores of its chunk itself: votes[] is then the score array [Hkv, P].  The sums are
 // formed in the order of the separate pooling kernel, so the bits are the same.
-template <int NB, int SPLIT, bool PERQ>
-__global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
+template <int NB, int SPLIT, bool PERQ, int STREAMS = 4>
+__global__ __launch_bounds__(64 * STREAMS * SPLIT) void score_votes_kernel(
     const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Qw, int N, int P, int w, int G,
     int chunk_keys, float c, const float *__restrict__ part, int part_chunks,
     float *__restrict__ votes, int R_total, int row_base, int vote_rows, int vote_row_base, int nparts,
     int pool_half)
 {
-    constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 256 * SPLIT;
+    constexpr int R = NB * kBlk, NBW = NB / SPLIT, NT = 64 * STREAMS * SPLIT, TK = kBlk * STREAMS;
     extern __shared__ __align__(16) unsigned char kt[];   // two key tiles
     __shared__ float bias_s[R];
     int h, chunk, row_part;
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     row_base += 128 * row_part;
     vote_row_base += SPLIT * row_part;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, l32 = lane & 31, hh = lane >> 5;
-    const int stream = wv & 3, grp = wv >> 2, row0 = grp * NBW * kBlk;
+    const int stream = wv % STREAMS, grp = wv / STREAMS, row0 = grp * NBW * kBlk;
 
     const int k0 = chunk * chunk_keys, k1 = min(P, k0 + chunk_keys);
     if (k0 >= P) return;
@@ -213,7 +215,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
     const int first = fused ? max(0, k0 - pool_half) : k0;      // keys this workgroup multiplies
     const int kend = fused ? min(P, k1 + pool_half) : k1;
     const int span = chunk_keys + 2 * pool_half;
-    float *vs = reinterpret_cast<float *>(kt + 2 * kTileBytes);   // [SPLIT][span], slot 0 = key k0 - pool_half
+    float *vs = reinterpret_cast<float *>(kt + 2 * TK * kPitch);   // [SPLIT][span], slot 0 = key k0 - pool_half
     if (fused)
         for (int u = tid; u < SPLIT * span; u += NT) vs[u] = 0.f;   // zero padding outside the row
 
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
         for (int i = 0; i < 16; ++i) bias[b][i] = bias_s[row0 + kBlk * b + acc_row(i, hh)];
 
     const uint16_t *Kh = Kc + (long)h * N * kD;
-    const int ntile = (kend - first + kTileKeys - 1) / kTileKeys;
+    const int ntile = (kend - first + TK - 1) / TK;
     const int bpq = PERQ ? w / kBlk : 1;   // MFMA row blocks per query head
 
     auto multiply_tile = [&](const unsigned char *buf, int t) {
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
             for (int i = 0; i < 16; ++i) s += fast_exp2(fmaf(acc[b][i], c, -bias[b][i]));
             pb[b] = s;
         }
-        const int key = first + kTileKeys * t + kBlk * stream + l32;
+        const int key = first + TK * t + kBlk * stream + l32;
         if constexpr (!PERQ) {
             float p = pb[0];
 #pragma unroll
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(256 * SPLIT) void score_votes_kernel(
             }
         }
     };
-    GKV_TILE_PIPELINE(NT, Kh, first, kend - 1, 1, ntile, multiply_tile, (void)0);
+    GKV_TILE_PIPELINE_TK(TK, NT, Kh, first, kend - 1, 1, ntile, multiply_tile, (void)0);
     if (fused) {
         __syncthreads();
         const float taps = (float)(2 * pool_half + 1), div = (float)G;
@@ -357,8 +359,14 @@ hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int 
     const int ck = chunk_keys_for(Hkv, N);
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
-    // equal parts of 128 rows go into one launch (see the kernel), other splits one launch per part
-    const int merged = (R > 128 && R % 128 == 0) ? R / 128 : 1;
+    if (R == 256) {   // one workgroup takes all 256 rows: 2 key streams x 4 row groups, tiles of 64 keys
+        if (!allow_big_lds((const void *)score_stats_kernel<8, 4, 2>)) return hipGetLastError();
+        hipLaunchKernelGGL((score_stats_kernel<8, 4, 2>), dim3(plan.chunks, Hkv), dim3(512), 2 * 64 * kPitch, st, K, Q, N,
+                           P, w, ck, c, part, R, 0, 1);
+        return hipGetLastError();
+    }
+    // other row counts beyond 128: parts of at most 128 rows, one launch per part
+    const int merged = 1;
     dim3 grid(plan.chunks * merged, Hkv);
 #define GKV_STATS(NB, SP)                                                                          \
     do {                                                                                           \
@@ -381,21 +389,21 @@ hipError_t launch_mfma_score_stats(const void *Kc, const void *Qw, int Hkv, int 
     return hipGetLastError();
 }
 
-template <int NB, int SPLIT>
+template <int NB, int SPLIT, int STREAMS = 4>
 static void launch_votes_nb(dim3 grid, const uint16_t *K, const uint16_t *Q, int N, int P, int w, int G,
                             int ck, float c, const float *part, int chunks, int per_q, float *votes,
                             int R_total, int row_base, int vote_rows, int vote_row_base, int nparts,
                             int pool_half, hipStream_t st)
 {
-    const size_t lds = 2 * kTileBytes + (pool_half >= 0 ? (size_t)SPLIT * (ck + 2 * pool_half) * 4 : 0);
+    const size_t lds = 2 * (kBlk * STREAMS) * kPitch + (pool_half >= 0 ? (size_t)SPLIT * (ck + 2 * pool_half) * 4 : 0);
     if (per_q) {
-        if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, true>)) return;
-        hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, true>), grid, dim3(256 * SPLIT),
+        if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, true, STREAMS>)) return;
+        hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, true, STREAMS>), grid, dim3(64 * STREAMS * SPLIT),
                            lds, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
                            row_base, vote_rows, vote_row_base, nparts, pool_half);
     } else {
-        if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, false>)) return;
-        hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, false>), grid, dim3(256 * SPLIT),
+        if (!allow_big_lds((const void *)score_votes_kernel<NB, SPLIT, false, STREAMS>)) return;
+        hipLaunchKernelGGL((score_votes_kernel<NB, SPLIT, false, STREAMS>), grid, dim3(64 * STREAMS * SPLIT),
                            lds, st, K, Q, N, P, w, G, ck, c, part, chunks, votes, R_total,
                            row_base, vote_rows, vote_row_base, nparts, pool_half);
     }
@@ -419,10 +427,15 @@ hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int 
     const int ck = pool_half >= 0 ? (P + plan.chunks - 1) / plan.chunks : chunk_keys_for(Hkv, N);
     const float c = scale * 1.4426950408889634f;
     const uint16_t *K = (const uint16_t *)Kc, *Q = (const uint16_t *)Qw;
-    const int merged = (R > 128 && R % 128 == 0) ? R / 128 : 1;   // as in the statistics pass
+    const int merged = 1;
     dim3 grid(plan.chunks * merged, Hkv);
     const int vote_rows = mfma_score_vote_rows(G, w, per_qhead_votes);
     int vote_row_base = 0;
+    if (R == 256 && !per_qhead_votes) {   // all rows in one workgroup (see the statistics pass): four row groups
+        launch_votes_nb<8, 4, 2>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, 0, votes, R, 0, vote_rows, 0, 1,
+                                 pool_half, st);
+        return hipGetLastError();
+    }
 #define GKV_VOTES(NB, SP)                                                                             \
     launch_votes_nb<NB, SP>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, per_qhead_votes, votes, R, \
                             row_base, vote_rows, vote_row_base, merged, pool_half, st)

@@ -38,39 +38,40 @@ __device__ __forceinline__ bf16x8 load8(const uint16_t *p)
 // half-wave hh (the column is lane % 32).
 __device__ __forceinline__ int acc_row(int i, int hh) { return 8 * (i >> 2) + 4 * hh + (i & 3); }
 
-// A thread of an NT-thread workgroup moves ceil(kTileChunks / NT) 16-byte pieces per tile.
-// When NT does not divide the tile (768 threads: three pieces each, 2304 slots for 2048
-// pieces) the threads whose last slot is past the tile move their first piece once more: the
-// same bytes to the same place, so that every thread runs the same unconditional code.
-template <int NT> constexpr int tile_pieces() { return (kTileChunks + NT - 1) / NT; }
-template <int NT> __device__ __forceinline__ int tile_piece(int tid, int u)
+// A thread of an NT-thread workgroup moves ceil(TK * 16 / NT) 16-byte pieces per tile of TK key
+// rows (TK = 128 unless a kernel says otherwise).  When NT does not divide the tile (768 threads:
+// three pieces each, 2304 slots for 2048 pieces) the threads whose last slot is past the tile
+// move their first piece once more: the same bytes to the same place, so that every thread runs
+// the same unconditional code.
+template <int NT, int TK = kTileKeys> constexpr int tile_pieces() { return (TK * 16 + NT - 1) / NT; }
+template <int NT, int TK = kTileKeys> __device__ __forceinline__ int tile_piece(int tid, int u)
 {
     const int g = tid + u * NT;
-    return (kTileChunks % NT == 0 || g < kTileChunks) ? g : tid;
+    return ((TK * 16) % NT == 0 || g < TK * 16) ? g : tid;
 }
 
 // Global -> registers.  Tile row t is key (first + t) * stride, clamped to
 // last_key (rows past the range are loaded from a valid address and masked later).
-template <int NT, int PER>
+template <int NT, int TK = kTileKeys, int PER>
 __device__ __forceinline__ void tile_load(const uint16_t *Kh, int first, int last_key, int stride,
                                           int tid, u32x4 (&r)[PER])
 {
-    static_assert(PER == tile_pieces<NT>(), "pieces per thread");
+    static_assert(PER == tile_pieces<NT, TK>(), "pieces per thread");
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-        const int g = tile_piece<NT>(tid, u), row = g >> 4, c = g & 15;
+        const int g = tile_piece<NT, TK>(tid, u), row = g >> 4, c = g & 15;
         const long key = (long)min(first + row, last_key) * stride;
         r[u] = *reinterpret_cast<const u32x4 *>(Kh + key * kD + c * 8);
     }
 }
 
 // Registers -> LDS tile.
-template <int NT, int PER>
+template <int NT, int TK = kTileKeys, int PER>
 __device__ __forceinline__ void tile_store(unsigned char *buf, int tid, const u32x4 (&r)[PER])
 {
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-        const int g = tile_piece<NT>(tid, u), row = g >> 4, c = g & 15;
+        const int g = tile_piece<NT, TK>(tid, u), row = g >> 4, c = g & 15;
         *reinterpret_cast<u32x4 *>(buf + row * kPitch + c * 16) = r[u];
     }
 }
@@ -122,27 +123,31 @@ __device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
 // wait in front of each LDS store leaves the newer tile's loads outstanding.
 // With conditional loads it has to assume they were skipped and waits for
 // everything.
-#define GKV_TILE_PIPELINE(NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE)                 \
+#define GKV_TILE_PIPELINE_TK(TK_, NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE)         \
     do {                                                                                               \
-        u32x4 stage_a[tile_pieces<NT_>()], stage_b[tile_pieces<NT_>()];                                \
-        tile_load<NT_>(Kh_, first_, clamp_, stride_, tid, stage_a);                                    \
-        tile_store<NT_>(kt, tid, stage_a);                                                             \
-        tile_load<NT_>(Kh_, first_ + kTileKeys, clamp_, stride_, tid, stage_a);                        \
-        tile_load<NT_>(Kh_, first_ + 2 * kTileKeys, clamp_, stride_, tid, stage_b);                    \
+        constexpr int tile_bytes_ = (TK_) * kPitch;                                                    \
+        u32x4 stage_a[tile_pieces<NT_, TK_>()], stage_b[tile_pieces<NT_, TK_>()];                      \
+        tile_load<NT_, TK_>(Kh_, first_, clamp_, stride_, tid, stage_a);                               \
+        tile_store<NT_, TK_>(kt, tid, stage_a);                                                        \
+        tile_load<NT_, TK_>(Kh_, first_ + (TK_), clamp_, stride_, tid, stage_a);                       \
+        tile_load<NT_, TK_>(Kh_, first_ + 2 * (TK_), clamp_, stride_, tid, stage_b);                   \
         __syncthreads();                                                                               \
         for (int t_ = 0; t_ < ntile_; t_ += 2) {                                                       \
             body(kt, t_);                                                                              \
-            tile_store<NT_>(kt + kTileBytes, tid, stage_a);                                            \
-            tile_load<NT_>(Kh_, first_ + kTileKeys * (t_ + 3), clamp_, stride_, tid, stage_a);         \
+            tile_store<NT_, TK_>(kt + tile_bytes_, tid, stage_a);                                      \
+            tile_load<NT_, TK_>(Kh_, first_ + (TK_) * (t_ + 3), clamp_, stride_, tid, stage_a);        \
             __syncthreads();                                                                           \
             { const int tile_done = t_ + 1; (void)tile_done; AFTER_TILE; }                             \
             if (t_ + 1 >= ntile_) break;                                                               \
-            body(kt + kTileBytes, t_ + 1);                                                             \
-            tile_store<NT_>(kt, tid, stage_b);                                                         \
-            tile_load<NT_>(Kh_, first_ + kTileKeys * (t_ + 4), clamp_, stride_, tid, stage_b);         \
+            body(kt + tile_bytes_, t_ + 1);                                                            \
+            tile_store<NT_, TK_>(kt, tid, stage_b);                                                    \
+            tile_load<NT_, TK_>(Kh_, first_ + (TK_) * (t_ + 4), clamp_, stride_, tid, stage_b);        \
             __syncthreads();                                                                           \
             { const int tile_done = t_ + 2; (void)tile_done; AFTER_TILE; }                             \
         }                                                                                              \
     } while (0)
+
+#define GKV_TILE_PIPELINE(NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE) \
+    GKV_TILE_PIPELINE_TK(kTileKeys, NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE)
 
 }  // namespace gkv
