@@ -298,7 +298,8 @@ def main():
     # ---- the per-layer-budget workload (c4: budgets 4096 .. 512, three rounds) on the same
     # resident tensors (its generator is c3's), a few steps ----
     other = None
-    if args.workload == "c3" and args.mode == "batched" and L == cfg.n_layers and args.streams == 1:
+    if (args.workload == "c3" and args.mode == "batched" and L == cfg.n_layers and args.streams == 1
+            and profile_steps > 0):
         c4 = synth.CONFIGS["c4"]
         b4 = [c4.budget_for_layer(l) for l in range(L)]
         p4 = gk.Params(n_kv_heads=H, n_q_heads=Hq, head_dim=d, n_tokens=N, window=w, pool_kernel=c4.pool_kernel,

@@ -479,7 +479,13 @@ hipError_t launch_decay(float *scores, int Hkv, int P, int S, int m, const int32
     const long count = (long)S * m;
     long npad = 512;
     while (npad < count) npad <<= 1;
-    if (count <= 4096) {
+    if (count <= 2048 && P <= (1 << (32 - kTripleBits))) {
+        // few edges: the two-items-per-thread sort beats the hash table by a few microseconds
+        int node_bits = 1;
+        while ((1L << node_bits) < P) ++node_bits;
+        hipLaunchKernelGGL((decay_radix_kernel<1024, 2>), dim3(Hkv), dim3(1024), (size_t)2048 * 8, st, scores, P,
+                           (int)count, node_bits, nbr, nbr_e, alpha, signal);
+    } else if (count <= 4096) {
         int table_log2 = 10;
         while ((1L << table_log2) < 2 * count) ++table_log2;
         const size_t lds = ((size_t)16) << table_log2;
