@@ -585,7 +585,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
     __shared__ uint32_t hist[256];   // 8-bit digits: the lists are short
     __shared__ uint32_t s_bin, s_need, s_min[4], s_max[4];
     __shared__ int32_t n_win;
-    __shared__ int32_t cnt_s[256], s_pos;
+    __shared__ int32_t end_s[256], wave_tot[4], s_pos;   // end_s[c]: entries in slices 0 .. c
     __shared__ uint32_t s_self;
     const int h = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int n_rows = sel.n_rows ? sel.n_rows[h] : S;
@@ -607,31 +607,62 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
         self_r = src[(long)h * S + pos_r];
     };
     int32_t cnt_r = 0, self_r = 0, pos_r = 0, crow_r = 0;
+    int search_steps = 0;   // bisection steps over the slices
+    while ((1 << search_steps) < chunks) ++search_steps;
     if ((int)blockIdx.x < n_rows) ask(blockIdx.x, cnt_r, self_r, pos_r, crow_r);
 
     for (int x = blockIdx.x; x < n_rows; x += gridDim.x) {
         const long row = (long)h * pitch + crow_r;
-        cnt_s[tid] = cnt_r;
+        int incl = cnt_r;   // running total of the slice sizes
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += v;
+        }
+        if (lane == 63) wave_tot[wv] = incl;
         if (tid == 0) { s_self = (uint32_t)self_r; s_pos = pos_r; n_win = 0; }
         __syncthreads();
+        for (int u = 0; u < wv; ++u) incl += wave_tot[u];
+        end_s[tid] = incl;
+        __syncthreads();
         if (x + (int)gridDim.x < n_rows) ask(x + gridDim.x, cnt_r, self_r, pos_r, crow_r);
-        int n = 0;
-        for (int c = 0; c < chunks; ++c) n += cnt_s[c];
+        const int n = end_s[255];
         if (n > cap) {          // more candidates than the select can hold: redo the head densely
             if (tid == 0) overflow[h] = 1;
             return;
         }
         const uint32_t self = s_self;
         const long out_row = (long)h * S + s_pos;
+        const uint2 *slices = cand + row * chunks * (long)slice_cap;
+        // where entry r of the concatenated slices sits: the first slice that ends behind it
+        auto locate = [&](int r) {
+            int lo = 0, hi = chunks - 1;
+            for (int s = 0; s < search_steps; ++s) {
+                const int mid = (lo + hi) >> 1;
+                if (end_s[mid] > r) hi = mid; else lo = mid + 1;
+            }
+            lo = min(lo, chunks - 1);
+            return (long)lo * slice_cap + (r - (lo ? end_s[lo - 1] : 0));
+        };
         uint32_t kmin = 0xffffffffu, kmax = 0u;
-        for (int r = tid; r < n; r += 256) {
-            int c = 0, local = r;                 // entry r of the concatenated slices
-            while (local >= cnt_s[c]) { local -= cnt_s[c]; ++c; }
-            const uint2 v = cand[(row * chunks + c) * (long)slice_cap + local];
-            // the source's own column is no neighbour (Eq. 3: j != i): key 0 sorts below every edge
-            const uint32_t k = v.y == self ? 0u : ord_key_u(v.x);
-            ek[r] = k;
-            if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
+        // four entries per thread and turn, their loads in flight together (entries past the
+        // end read the last one again and are left out below)
+        for (int r0 = tid; r0 < n; r0 += 1024) {
+            uint2 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = slices[locate(min(r0 + 256 * u, n - 1))];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) asm volatile("" : "+v"(v[u].x), "+v"(v[u].y));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = r0 + 256 * u;
+                if (r < n) {
+                    // the source's own column is no neighbour (Eq. 3: j != i): key 0 sorts below every edge
+                    const uint32_t k = v[u].y == self ? 0u : ord_key_u(v[u].x);
+                    ek[r] = k;
+                    if (k) { kmin = min(kmin, k); kmax = max(kmax, k); }
+                }
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
@@ -708,9 +739,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
         // the key indices of the listed entries: (key index, edge bits) from here on
         for (int r = tid; r < listed; r += 256) {
             const uint64_t w = win[r];
-            int c = 0, local = (int)(w >> 32);
-            while (local >= cnt_s[c]) { local -= cnt_s[c]; ++c; }
-            const uint32_t j = cand[(row * chunks + c) * (long)slice_cap + local].y;
+            const uint32_t j = slices[locate((int)(w >> 32))].y;
             win[r] = ((uint64_t)j << 32) | (uint32_t)w;
         }
         __syncthreads();
