@@ -456,22 +456,25 @@ int32_t run_compress(const graphkv_params *p, int n_layers, bool speculate, cons
 // while the scratch memory of a group would exceed 2000 MiB (long prompts: the candidate lists
 // and vote rows grow with the number of heads in flight).
 constexpr size_t kGroupScratchCap = (size_t)2000 << 20;
-// The speculative rows of the filter route cost scratch too: they are dropped before a group is
-// made smaller.
+// The speculative rows of the filter route cost scratch too.  A smaller group that keeps them
+// beats a larger one without (later rounds then stream no keys again), as long as the group
+// still has 64 heads or more to fill the chip with; below that they are dropped before a
+// group is made smaller still.
 Dims group_dims(const graphkv_params *p, int n_layers)
 {
-    int g = n_layers < kMaxLayers ? n_layers : kMaxLayers;
-    while (true) {
-        const bool fits_heads = (long)p->n_kv_heads * g <= 65535;
-        if (fits_heads) {
-            for (int speculate = 1; speculate >= 0; --speculate) {
+    const int g0 = n_layers < kMaxLayers ? n_layers : kMaxLayers;
+    for (int speculate = 1; speculate >= 0; --speculate) {
+        for (int g = g0;; g = (g + 1) / 2) {
+            const bool fits_heads = (long)p->n_kv_heads * g <= 65535;
+            if (speculate && g < g0 && (long)p->n_kv_heads * g < 64) break;
+            if (fits_heads) {
                 const Dims D = dims_of(p, g, speculate != 0);
-                if (carve(p, D).total <= kGroupScratchCap || (g == 1 && !speculate)) return D;
+                if (carve(p, D).total <= kGroupScratchCap) return D;
             }
+            if (g == 1) break;
         }
-        if (g == 1) return dims_of(p, 1, false);
-        g = (g + 1) / 2;
     }
+    return dims_of(p, 1, false);
 }
 
 bool budgets_ok(const graphkv_params *p, int n_layers, const int32_t *budgets)

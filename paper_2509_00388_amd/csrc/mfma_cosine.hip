@@ -1077,14 +1077,14 @@ int chunk_cols_for(int Hkv, int sgroups, int n_cols, int min_chunks = 1)
 
 }  // namespace
 
-// Keys in the strided sample of the bound pass: every 8th key, between 2048 and 8192 keys (one
+// Keys in the strided sample of the bound pass: every 8th key, between 2048 and 16384 keys (one
 // workgroup walks the whole sample of a head's sources).  A denser sample costs the bound pass
 // more and gives a tighter bound, i.e. fewer candidates for the filter pass to park and list.
 int mfma_sample_cols(int P)
 {
     int ps = ((P / 8 + 127) / 128) * 128;
     if (ps < 2048) ps = 2048;
-    if (ps > 8192) ps = 8192;
+    if (ps > 16384) ps = 16384;
     return ps;
 }
 
