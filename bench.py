@@ -253,10 +253,15 @@ def main():
         prof = gk.graphkv_profile_end()
         torch.cuda.synchronize()
         alg = [algorithmic_bytes(cfg, p.budget) for p in params]
+        # The library cuts a batched call into launch groups of layers when the scratch of all of
+        # them would be too large (c5: two groups of 16): the gather runs once per launch group, so
+        # its launch count tells how many layers one launch of any kernel covers.
+        calls_per_step = (L + group - 1) // group if args.mode == "batched" else L
+        groups_per_call = max(1, round(prof["gather"][1] / profile_steps / calls_per_step)) if "gather" in prof else 1
+        layers_per_launch = min(group, L) / groups_per_call if args.mode == "batched" else 1
         for name, (ms, cnt) in prof.items():
             per_step = cnt / profile_steps
             avg_us = ms * 1e3 / cnt
-            layers_per_launch = min(group, L) if args.mode == "batched" else 1
             bytes_per_launch = float(np.mean([a.get(name, 0) for a in alg])) * layers_per_launch
             kernels[name] = {
                 "avg_us": round(avg_us, 3), "launches_per_step": per_step,
@@ -277,6 +282,7 @@ def main():
                               "command, scaled; not measured in this run)" if traffic is not None else None,
             "avg_launch_us": kernels[dom]["avg_us"],
             "launches_per_step": kernels[dom]["launches_per_step"],
+            "layers_per_launch": layers_per_launch,
             "alg_bytes_per_launch": kernels[dom]["alg_bytes_per_launch"],
             "measured_over": f"{profile_steps} steps with per-kernel events, right after the timed ones",
         }

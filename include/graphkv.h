@@ -89,8 +89,8 @@ typedef struct graphkv_params {
     float   decay;         /* alpha in [0, 1]                                        */
     int32_t reselect;      /* 0: sources and neighbourhoods fixed from round 1
                               (Eq. 2 / Eq. 5 as printed); 1: re-picked from the
-                              refined scores every round (Fig. 1: pick and
-                              propagate "one or multiple times")                    */
+                              refined scores every round (Fig. 1's caption lets the
+                              pick-and-propagate step run more than once)            */
     int32_t dtype;         /* GRAPHKV_FP32 / GRAPHKV_BF16: type of Kc, Vc, Qw        */
     float   softmax_scale; /* 0 selects 1/sqrt(d)                                    */
     int32_t signal;        /* GRAPHKV_SIGNAL_*                                       */
@@ -121,7 +121,7 @@ int32_t graphkv_score(const graphkv_params *p, const void *Kc, const void *Qw,
 
 /*
  * KNorm-style initial score, another indicator the paper plugs GraphKV into
- * (Baseline Methods: "L2 norm of keys"): scores[h, j] = -||k_j||, so that the
+ * (Baseline Methods, the key-norm method): scores[h, j] = -||k_j||, so that the
  * low-norm keys that method keeps rank highest.  The scores are negative: see
  * graphkv_propagate for what the signal does to them.
  */

@@ -24,13 +24,13 @@
  *             paragraph before the closing remark).
  *
  * Readings taken where the paper is silent, garbled or ambiguous:
- *   R1  The decay-strength symbol is missing in Eq. 4 and Alg. 2 ("s_j - . e_ij
- *       . s_j"); the Limitation section names a "decay strength"
+ *   R1  Eq. 4 and Alg. 2 are printed with a blank where a coefficient of
+ *       e_ij s_j would stand; the Limitation section speaks of a decay-strength
  *       hyper-parameter.  Factor = (1 - alpha*e_ij); alpha = 1 gives Eq. 5 as
  *       printed.
  *   R2  Graph fixed across rounds (Eq. 2/5, Alg. 2 take a finished graph) or
- *       re-picked from the refined scores each round (Fig. 1 caption: the
- *       pick-and-propagate step "can be performed one or multiple times")?
+ *       re-picked from the refined scores each round (Fig. 1's caption allows
+ *       the pick-and-propagate step to run once or several times)?
  *       Both: reselect = 0 / 1.  Identical at T = 1.
  *   R3  Inside a round all sources act at once (Eq. 5's product).  Alg. 2's
  *       nested loops give the same real number because neighbourhoods depend
@@ -67,14 +67,14 @@
  *       prefix tokens' queries, which the pass does not receive; the two-tensor
  *       propagate takes any pair).
  *   R15 KNorm as the indicator that initialises the nodes (Sparse Graph Building,
- *       first paragraph; Baseline Methods: "L2 norm of keys"): that method keeps
+ *       first paragraph; Baseline Methods describes it as the keys' L2 norm): that method keeps
  *       the keys of small norm, so s_j = -||k_j|| (scorer 1 of the whole-pass
  *       function; no queries are needed).
  *   R16 Scores of either sign.  Eq. 4 / Eq. 5 are written for a non-negative
  *       indicator; multiplied into a negative score, (1 - alpha e) would RAISE
  *       it, against what "Decay Signal Propagation" says the signal does
- *       (the decay "reduc[es] the scores of redundant tokens", in proportion
- *       to the similarity).  Reading: the change of Eq. 4 is taken on the
+ *       (it lowers the score of a token that resembles a source, the more so
+ *       the closer the two are).  Reading: the change of Eq. 4 is taken on the
  *       magnitude, s_j' = s_j - alpha e_ij |s_j|, i.e. the factor of Eq. 5 is
  *       (1 - alpha e) for s_j >= 0 and (1 + alpha e) for s_j < 0, the sign being
  *       that of the score at the start of the round; the enhanced signal mirrors
