@@ -115,6 +115,9 @@ size_t graphkv_workspace_bytes(const graphkv_params *p);
  *   Kc     [H_kv, N, d]  in   keys
  *   Qw     [H_q, w, d]   in   window queries
  *   scores [H_kv, P]     out  fp32
+ * The `scorer` field is ignored here (this call is the attention scorer); the
+ * workspace must have the size graphkv_workspace_bytes() returns for the params
+ * with scorer = GRAPHKV_SCORER_ATTENTION, else GRAPHKV_EWORKSPACE.
  */
 int32_t graphkv_score(const graphkv_params *p, const void *Kc, const void *Qw,
                       float *scores, void *ws, size_t ws_bytes, void *stream);

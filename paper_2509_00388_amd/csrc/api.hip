@@ -158,7 +158,10 @@ Workspace carve(const graphkv_params *p, const Dims &D)
     W.logits = take(!D.mfma_score && scoring ? rows * D.N * 4 : 0);
     W.row_max = take(rows * 4);
     W.row_sum = take(rows * 4);
-    W.votes = take((size_t)D.Hq * D.P * 4);
+    // votes per query head (or row group); not needed when pass B pools and groups them itself
+    const bool votes_stay_in_lds = D.mfma_score && scoring &&
+        mfma_score_fuses_pool(D.G, D.w, p->pool_mode == GRAPHKV_POOL_MAX, p->pool_kernel);
+    W.votes = take(scoring && !votes_stay_in_lds ? (size_t)D.Hq * D.P * 4 : 0);
     // the dense edge block [heads, S, P] of the routes that materialise it; on the filter route
     // only the scratch rows of the workgroups that redo overflowed heads
     W.E = take(D.filter ? redo_rows_scratch_bytes(D.H, D.S, D.P) : (size_t)D.H * D.S * D.P * 4);
@@ -506,10 +509,14 @@ int32_t graphkv_score(const graphkv_params *p, const void *Kc, const void *Qw, f
 {
     if (!base_ok(p) || !score_ok(p)) return GRAPHKV_EINVAL;
     if (!aligned16(Kc) || !aligned16(Qw) || !aligned4(scores)) return GRAPHKV_EINVAL;
-    const Dims D = group_dims(p, 1);
-    const Workspace W = carve(p, D);
+    // this call is the attention scorer whatever `scorer` says: its scratch is carved (and the
+    // caller's workspace checked) for that
+    graphkv_params q = *p;
+    q.scorer = GRAPHKV_SCORER_ATTENTION;
+    const Dims D = group_dims(&q, 1);
+    const Workspace W = carve(&q, D);
     if (int32_t rc = check_ws(W, ws, ws_bytes)) return rc;
-    return run_score(p, D, W, Kc, Qw, scores, ws, (hipStream_t)stream);
+    return run_score(&q, D, W, Kc, Qw, scores, ws, (hipStream_t)stream);
 }
 
 int32_t graphkv_score_knorm(const graphkv_params *p, const void *Kc, float *scores, void *ws,

@@ -187,7 +187,7 @@ __global__ __launch_bounds__(64 * STREAMS * SPLIT) void score_stats_kernel(
 // rows (row_base .. row_base + R of R_total), one launch per part: the keys are then
 // streamed once per part.
 //
-// pool_half >= 0 (average pooling, one part): the votes never leave the workgroup.  Each row
+// pool_half >= 0 (average pooling, all rows of a head in one workgroup): the votes never leave the workgroup.  Each row
 // group keeps the votes of the workgroup's keys in LDS, the workgroup also multiplies the
 // pool_half keys on either side of its chunk, and at the end it writes the pooled, grouped
 // scores of its chunk itself: votes[] is then the score array [Hkv, P].  The sums are
@@ -411,7 +411,7 @@ static void launch_votes_nb(dim3 grid, const uint16_t *K, const uint16_t *Q, int
 
 bool mfma_score_fuses_pool(int G, int w, int per_qhead_votes, int pool_kernel)
 {
-    return !per_qhead_votes && G * w <= 128 && pool_kernel <= 33;
+    return !per_qhead_votes && (G * w <= 128 || G * w == 256) && pool_kernel <= 33;
 }
 
 hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int Hq, int N, int w,
@@ -432,7 +432,10 @@ hipError_t launch_mfma_score_votes(const void *Kc, const void *Qw, int Hkv, int 
     const int vote_rows = mfma_score_vote_rows(G, w, per_qhead_votes);
     int vote_row_base = 0;
     if (R == 256 && !per_qhead_votes) {   // all rows in one workgroup (see the statistics pass): four row groups
-        launch_votes_nb<8, 4, 2>(grid, K, Q, N, P, w, G, ck, c, part, plan.chunks, 0, votes, R, 0, vote_rows, 0, 1,
+        // with fused pooling the votes of four row groups stay in LDS: chunks of 6144 keys
+        const int ckv = pool_half >= 0 ? 6144 : ck;
+        const dim3 gridv = pool_half >= 0 ? dim3((P + ckv - 1) / ckv, Hkv) : grid;
+        launch_votes_nb<8, 4, 2>(gridv, K, Q, N, P, w, G, ckv, c, part, plan.chunks, 0, votes, R, 0, vote_rows, 0, 1,
                                  pool_half, st);
         return hipGetLastError();
     }

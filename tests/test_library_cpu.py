@@ -104,6 +104,22 @@ def test_null_misaligned_and_small_workspace(lib):
     assert gk.graphkv_strerror(-3) and gk.graphkv_strerror(-99)
 
 
+def test_score_call_sizes_its_scratch_for_the_attention_scorer(lib):
+    """graphkv_score is the attention scorer whatever the params' scorer field says: a workspace
+    sized for key-norm params (no logits, no votes) is turned down, not overrun."""
+    fake = ctypes.c_void_p(0x10000)
+    for impl in (gk.IMPL_AUTO, gk.IMPL_GENERIC):
+        att, kn = good_params(impl=impl), good_params(impl=impl, scorer=gk.SCORER_KNORM)
+        need_att, need_kn = gk.graphkv_workspace_bytes(att), gk.graphkv_workspace_bytes(kn)
+        assert need_kn <= need_att
+        cp = kn.c()
+        if need_kn < need_att:
+            assert lib.graphkv_score(ctypes.byref(cp), fake, fake, fake, fake, need_kn, None) == -2
+    generic = good_params(impl=gk.IMPL_GENERIC)
+    assert gk.graphkv_workspace_bytes(good_params(impl=gk.IMPL_GENERIC, scorer=gk.SCORER_KNORM)) < \
+        gk.graphkv_workspace_bytes(generic)
+
+
 def test_static_scratch_entry_checks_on_the_host(lib):
     """graphkv_compress_static: invalid params and problems beyond its built-in buffer are turned
     down before anything touches a GPU."""
