@@ -290,14 +290,25 @@ __global__ __launch_bounds__(64 * STREAMS * SPLIT) void score_votes_kernel(
     GKV_TILE_PIPELINE_TK(TK, NT, Kh, first, kend - 1, 1, ntile, multiply_tile, (void)0);
     if (fused) {
         __syncthreads();
+        // votes of a key summed over the row groups (in group order, into group 0's array), then the
+        // taps of every output in key order: the additions of the separate pooling kernel
+        if (SPLIT > 1) {
+            for (int u = tid; u < span; u += NT) {
+                float v = 0.f;
+#pragma unroll
+                for (int g = 0; g < SPLIT; ++g) v += vs[g * span + u];
+                vs[u] = v;
+            }
+            __syncthreads();
+        }
         const float taps = (float)(2 * pool_half + 1), div = (float)G;
         for (int o = tid; o < k1 - k0; o += NT) {
             float acc = 0.f;
-            for (int t = 0; t <= 2 * pool_half; ++t) {
-                float v = 0.f;
+            if (pool_half == 3) {
 #pragma unroll
-                for (int g = 0; g < SPLIT; ++g) v += vs[g * span + o + t];
-                acc += v;
+                for (int t = 0; t < 7; ++t) acc += vs[o + t];
+            } else {
+                for (int t = 0; t <= 2 * pool_half; ++t) acc += vs[o + t];
             }
             votes[(long)h * P + k0 + o] = acc / taps / div;
         }
