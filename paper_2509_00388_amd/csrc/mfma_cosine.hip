@@ -342,6 +342,7 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
     __shared__ float inv_s[ROWS], det_s[ROWS];
     __shared__ int32_t idx_s[ROWS];
     __shared__ int32_t row_pos[ROWS];   // entries written to each source's slice
+    __shared__ int32_t idle_pos[kWave];  // takes the additions of 0 of hits that are not there
     // (edge bits, key, source row) of the hits beyond a row's fourth: one list for even and one
     // for odd tiles, each emptied right after the barrier that ends its tile
     __shared__ uint4 later[2][kLaterCap];
@@ -432,24 +433,31 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
                     neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(fmaf(-det[4 * v + u], norm_k, d4[u])), 31);
             }
             uint32_t hits = ~neg & 0xffffu;
-            long off[4];
-            float ev[4];
+            // The row's first four hits without a branch, so that their LDS reads and list
+            // positions are asked for together and waited for once: a hit that is not there
+            // reads dot 0 and adds 0 to a counter nobody reads (one per lane).
+            int rowk[4];
+            int32_t atk[4];
+            float dotk[4], invk[4];
+            uint32_t validk = 0;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                off[k] = -1;
-                ev[k] = 0.f;
-                if (hits) {
-                    const int i = __ffs(hits) - 1;
-                    hits &= hits - 1;
-                    const int row = kBlk * grp + acc_row(i, hh);
-                    ev[k] = (reinterpret_cast<const float *>(row_mem)[i] * inv_k) * inv_s[row];
-                    const int at = atomicAdd(&row_pos[row], 1);
-                    if (at < fa.slice_cap) off[k] = row * slice_row_stride + at;
-                }
+                const bool valid = hits != 0;
+                const int i = valid ? __ffs(hits) - 1 : 0;
+                hits &= hits - 1;
+                validk |= valid ? 1u << k : 0u;
+                rowk[k] = kBlk * grp + acc_row(i, hh);
+                dotk[k] = reinterpret_cast<const float *>(row_mem)[i];
+                invk[k] = inv_s[rowk[k]];
+                atk[k] = atomicAdd(valid ? &row_pos[rowk[k]] : &idle_pos[lane], valid ? 1 : 0);
             }
 #pragma unroll
+            for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(dotk[k]), "+v"(invk[k]), "+v"(atk[k]));
+#pragma unroll
             for (int k = 0; k < 4; ++k)
-                if (off[k] >= 0) slice0[off[k]] = make_uint2(__float_as_uint(ev[k]), key);
+                if (((validk >> k) & 1u) && atk[k] < fa.slice_cap)
+                    slice0[rowk[k] * slice_row_stride + atk[k]] =
+                        make_uint2(__float_as_uint((dotk[k] * inv_k) * invk[k]), key);
             while (hits) {
                 const int i = __ffs(hits) - 1;
                 hits &= hits - 1;
