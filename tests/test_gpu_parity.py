@@ -119,6 +119,22 @@ def test_score_bf16_row_shapes(oracle, G, w, pool_mode):
     util.assert_scores_close(s, ref)
 
 
+@pytest.mark.parametrize("pool_kernel", [7, 1, 13])
+def test_score_256_rows_over_several_key_chunks(oracle, pool_kernel):
+    """256 stacked query rows keep their votes in LDS and pool them there: key chunks of 6144
+    with a ragged last one, so that the pooling window straddles chunk ends."""
+    cfg = small_bf16_cfg(n_tokens=13000 + 64, window=64, n_kv_heads=2, n_q_heads=8, budget=64 + 50,
+                         pool_kernel=pool_kernel)
+    say(f"score 256 rows, N={cfg.n_tokens}, pool_kernel={pool_kernel}")
+    (K, V, Q), (Kd, Vd, Qd) = util.device_layer(cfg, 11)
+    p = util.params_from_cfg(cfg)
+    s = gk.graphkv_score(p, Kd, Qd).cpu().numpy()
+    ref = oracle.score(K, Q, "bf16", cfg.pool_kernel, 0)
+    util.assert_scores_close(s, ref)
+    pg = util.params_from_cfg(cfg, impl=gk.IMPL_GENERIC)
+    util.assert_scores_close(gk.graphkv_score(pg, Kd, Qd).cpu().numpy(), ref)
+
+
 def test_score_peaked_logits_and_custom_scale(oracle):
     """Large logits (keys x4): the softmax must not overflow; explicit scale."""
     cfg = small_bf16_cfg(key_scale=4.0)
