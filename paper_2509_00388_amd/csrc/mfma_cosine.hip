@@ -344,7 +344,7 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
     __shared__ int32_t row_pos[ROWS];   // entries written to each source's slice
     __shared__ int32_t idle_pos[kWave];  // takes the additions of 0 of hits that are not there
     // (edge bits, key, source row) of the hits beyond a row's fourth: one list for even and one
-    // for odd tiles, each emptied right after the barrier that ends its tile
+    // for odd drain periods, each emptied right after the barrier that ends its period
     __shared__ uint4 later[2][kLaterCap];
     __shared__ int32_t n_later[2], later_lost;   // entries ever listed (never reset)
     extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the rings
@@ -476,6 +476,10 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
     // list fills the rows in order, four to a lane at a time) the rings fill that much slower.
     const int lane_rows = min(16, 4 * ((min(Sh - s_base, kBlk) + 7) / 8));
     const int de = fa.drain_every * 16 / lane_rows;
+    // Tiles come in periods of `de`, the last tile of a period being the one with the scheduled
+    // drain.  Hits beyond a row's fourth go to the LDS list of the period's parity, which is stored
+    // right after the barrier that ends the period, while the next period fills the other list.
+    int period = 0, period_end = de - 1;   // (the same in every thread)
     // a row group without sources only helps to move the key tiles
     const bool idle = s_base + kBlk * grp >= Sh;
     auto multiply_tile = [&](const unsigned char *buf, int t) {
@@ -504,7 +508,7 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
         const int add0 = (int)__popcll(hit_lanes & 0x00000000ffffffffull), add1 = (int)__popcll(hit_lanes >> 32);
         // a ring that could not take this tile's rows is drained first: one pass takes up to
         // 32 rows out, after which the (at most 32) new rows fit
-        if (tail0 - head0 + add0 > RING || tail1 - head1 + add1 > RING) drain(t & 1);
+        if (tail0 - head0 + add0 > RING || tail1 - head1 + add1 > RING) drain(period & 1);
         if (hit) {
             const int at = (hh ? tail1 : tail0) + (int)__popcll(hit_lanes & half_before);
             unsigned char *row_mem = ring + (at & (RING - 1)) * kStagePitch;
@@ -520,14 +524,16 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
         // here, in front of the tile's prefetch loads: the drain's stores are then older than
         // those loads, and the wait in front of the next LDS store of a key tile -- a count of
         // memory operations still in flight -- lets the loads stay in flight.
-        if (t % de == de - 1) {
-            drain(t & 1);
-            if (RING > kBlk) drain(t & 1);
+        if (t == period_end) {
+            drain(period & 1);
+            if (RING > kBlk) drain(period & 1);
         }
     };
-    // Entries listed during the tile that just ended are final behind its barrier, and the next
-    // tile lists into the other list: one thread per entry stores them.  A list holds
-    // kLaterCap entries; more than that in one tile and the head is redone exactly.
+    // Entries listed during the period that just ended are final behind its last barrier, and the
+    // next period lists into the other list: one thread per entry stores them.  A list holds
+    // kLaterCap entries; more than that in one period and the head is redone exactly.  (Looking at
+    // the list's counter costs an LDS round trip right behind the barrier, which is why this is
+    // done once a period and not after every tile.)
     int later_seen[2] = {0, 0};
     auto store_later = [&](int par) {
         const int n = n_later[par];
@@ -540,11 +546,18 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
             if (at < fa.slice_cap) slice0[(long)r.z * slice_row_stride + at] = make_uint2(r.x, r.y);
         }
     };
-    GKV_TILE_PIPELINE(NT, Kh, c0, c1 - 1, 1, ntile, multiply_tile, store_later((tile_done - 1) & 1));
-    drain(ntile & 1);
-    drain(ntile & 1);
+    auto end_of_tile = [&](int tile_done) {
+        if (tile_done - 1 == period_end) {
+            store_later(period & 1);
+            ++period;
+            period_end += de;
+        }
+    };
+    GKV_TILE_PIPELINE(NT, Kh, c0, c1 - 1, 1, ntile, multiply_tile, end_of_tile(tile_done));
+    drain(period & 1);
+    drain(period & 1);
     __syncthreads();
-    store_later(ntile & 1);
+    store_later(period & 1);
     __syncthreads();      // every candidate is counted
     if (tid < ROWS && s_base + tid < Sh) {
         const int c = row_pos[tid];
