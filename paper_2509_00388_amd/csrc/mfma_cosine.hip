@@ -76,7 +76,7 @@ __device__ __forceinline__ void load_sources(const uint16_t *Ah, const int32_t *
 #pragma unroll
     for (int s = 0; s < kSteps; ++s) q[s] = load8(p + 16 * s);
     float sq = half_row_sumsq(q);
-    sq += __shfl_xor(sq, 32, kWave);
+    sq = add_other_half(sq);
     if (stream == 0 && hh == 0) {
         inv_s[kBlk * grp + l32] = inv_norm(sq);
         idx_s[kBlk * grp + l32] = i;
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[s], kc[s], acc, 0, 0, 0);
 
         float sq = half_row_sumsq(kc);
-        sq += __shfl_xor(sq, 32, kWave);
+        sq = add_other_half(sq);
         const float inv_k = inv_norm(sq);
         const int col = c0 + kTileKeys * t + kBlk * stream + l32;
         const int key = col * key_stride;
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(256 * SB) void cosine_bound_kernel(
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[s], kc[s], acc, 0, 0, 0);
 
         float sq = half_row_sumsq(kc);
-        sq += __shfl_xor(sq, 32, kWave);
+        sq = add_other_half(sq);
         const float inv_k = inv_norm(sq);
         const int col = c0 + kTileKeys * t + kBlk * stream + l32;
         if (col < c1) {
@@ -494,7 +494,7 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[s], kc[s], acc, 0, 0, 0);
 
         float sq = half_row_sumsq(kc);
-        sq += __shfl_xor(sq, 32, kWave);
+        sq = add_other_half(sq);
         const float norm_k = __builtin_amdgcn_sqrtf(sq);
         float d[16];   // dot - bound * |k_j|: >= 0 means the edge may reach the bound
 #pragma unroll

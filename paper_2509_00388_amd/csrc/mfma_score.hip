@@ -269,7 +269,7 @@ __global__ __launch_bounds__(64 * STREAMS * SPLIT) void score_votes_kernel(
             float p = pb[0];
 #pragma unroll
             for (int b = 1; b < NBW; ++b) p += pb[b];
-            p += __shfl_xor(p, 32, kWave);
+            p = add_other_half(p);
             if (hh == 0 && key < kend) {
                 if (fused) vs[grp * span + key - (k0 - pool_half)] = p;
                 else votes[((long)h * vote_rows + vote_row_base + grp) * P + key] = p;
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(64 * STREAMS * SPLIT) void score_votes_kernel(
                 float p = 0.f;
 #pragma unroll
                 for (int b = 0; b < NBW; ++b) p += (b / bpq == g) ? pb[b] : 0.f;
-                p += __shfl_xor(p, 32, kWave);
+                p = add_other_half(p);
                 if (g0 + g < G && g * bpq < NBW && hh == 0 && key < kend)
                     votes[((long)h * G + g0 + g) * P + key] = p;
             }

@@ -85,6 +85,19 @@ __device__ __forceinline__ void tile_read(const unsigned char *buf, int stream, 
     for (int s = 0; s < kSteps; ++s) kc[s] = *reinterpret_cast<const bf16x8 *>(p + 32 * s);
 }
 
+// x of this lane plus x of the lane 32 places away (the other half of the wave), without a
+// trip through the LDS crossbar: gfx950's v_permlane32_swap exchanges the upper half of one
+// register with the lower half of another, so two copies of x become (low half twice) and
+// (high half twice), whose sum is low + high in every lane.  The sums sit between the matrix
+// instructions of every tile; a ds_bpermute there would make each wave wait for a turn in the
+// LDS queue behind the other waves' tile reads.
+__device__ __forceinline__ float add_other_half(float x)
+{
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // 1/|k| from |k|^2 with the hardware reciprocal square root (1 ulp), 0 for a zero key.
 // Every MFMA-path edge uses this one function, so the sampled bound and the filtered
 // edges are computed bit for bit alike.

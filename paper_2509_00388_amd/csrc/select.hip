@@ -821,7 +821,7 @@ __global__ __launch_bounds__(kRedoBlock) void redo_rows_kernel(
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) q[s] = load8(ah + (long)i * kD + 16 * s + 8 * hh);
         float sq_i = half_row_sumsq(q);
-        sq_i += __shfl_xor(sq_i, 32, kWave);
+        sq_i = add_other_half(sq_i);
         const float inv_i = inv_norm(sq_i);
         // blocks of 32 keys, one per wave at a time: key l32 of the block is the operand's column
         for (int j0 = wv * kBlk; j0 < P; j0 += (kRedoBlock / kWave) * kBlk) {
@@ -836,7 +836,7 @@ __global__ __launch_bounds__(kRedoBlock) void redo_rows_kernel(
             for (int s = 0; s < kSteps; ++s)   // rows = the source (32 times), columns = keys
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[s], kc[s], acc, 0, 0, 0);
             float sq = half_row_sumsq(kc);
-            sq += __shfl_xor(sq, 32, kWave);
+            sq = add_other_half(sq);
             const float e = (acc[0] * inv_norm(sq)) * inv_i;
             if (hh == 0 && j0 + l32 < P) erow[j] = j == i ? -INFINITY : e;   // (Eq. 3: j != i)
         }
