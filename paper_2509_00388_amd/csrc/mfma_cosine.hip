@@ -148,23 +148,26 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
 // strided sample of the keys (column c = key c * key_stride) -- a subset's m-th
 // largest can only be smaller than the whole row's.  One workgroup takes the whole
 // sample of a (head, source group): the edges never leave the registers, they are
-// counted into a 512-bin histogram over [-1, 1] per source in LDS (16-bit counters,
-// two to a word), and the bound is the lower edge of the bin in which the count
-// from the top reaches m: at most 1/256 below the m-th largest sampled edge.  (An
-// edge a rounding error below a bin edge may be counted into the bin above; the
-// filter pass lowers every bound by far more than that.)  The source's own column
+// counted into a 256-bin histogram over [-1, 1] per source in LDS, and the bound is
+// the lower edge of the bin in which the count from the top reaches m: at most 1/128
+// below the m-th largest sampled edge.  (The pass is bound by the vector instructions
+// that turn an edge into a bin: a plain counter per bin needs five of them per edge;
+// packed 16-bit counters in twice as many bins needed eleven and made this pass 15 %
+// slower for a bound that saves the filter pass 1 %.  Bins over [0, 1] only, with all
+// negative edges in the lowest bin, are no option: half the updates then hit one LDS
+// word.  An edge a rounding error below a bin edge may be counted into the bin above;
+// the filter pass lowers every bound by far more than that.)  The source's own column
 // is taken out of the counts at the end (Eq. 3: j != i).  Also clears the head's
 // overflow flag for the filter pass that follows.
-// One wave, one source: lane L holds the packed counters of bins 8L .. 8L+7 in w4 (zeros beyond
-// the last bin).  Finds the bin in which the count from the top reaches m and writes its lower edge.
+// One wave, one source: lane L holds the counters of bins 4L .. 4L+3 in w4 (zeros beyond the
+// last bin).  Finds the bin in which the count from the top reaches m and writes its lower edge.
 template <int BINS>
 __device__ __forceinline__ void bound_from_histogram(const uint4 w4, int m, int lane, float *tau_row)
 {
-    const uint32_t c[8] = {w4.x & 0xffffu, w4.x >> 16, w4.y & 0xffffu, w4.y >> 16,
-                           w4.z & 0xffffu, w4.z >> 16, w4.w & 0xffffu, w4.w >> 16};
+    const uint32_t c[4] = {w4.x, w4.y, w4.z, w4.w};
     uint32_t mine = 0;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) mine += c[k];
+    for (int k = 0; k < 4; ++k) mine += c[k];
     uint32_t from_top = mine;   // count in this lane's bins and all higher ones
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -174,25 +177,25 @@ __device__ __forceinline__ void bound_from_histogram(const uint4 w4, int m, int 
     const uint32_t above = from_top - mine;
     if (above < (uint32_t)m && from_top >= (uint32_t)m) {
         uint32_t cum = above;
-        int k = 7;
+        int k = 3;
         for (; k > 0; --k) {
             if (cum + c[k] >= (uint32_t)m) break;
             cum += c[k];
         }
-        *tau_row = (float)(8 * lane + k) * (2.0f / BINS) - 1.0f;
+        *tau_row = (float)(4 * lane + k) * (2.0f / BINS) - 1.0f;
     }
     if (lane == 0 && from_top < (uint32_t)m) *tau_row = -INFINITY;   // fewer than m sampled edges: no bound
 }
 
-// Lane L's eight packed counters of one histogram row (BINS / 2 words).
+// Lane L's four counters of one histogram row (BINS words).
 template <int BINS>
 __device__ __forceinline__ uint4 histogram_words(const uint32_t *row, int lane)
 {
-    return lane < BINS / 8 ? *reinterpret_cast<const uint4 *>(row + 4 * lane) : make_uint4(0, 0, 0, 0);
+    return lane < BINS / 4 ? *reinterpret_cast<const uint4 *>(row + 4 * lane) : make_uint4(0, 0, 0, 0);
 }
 
-// SB 32-row groups of sources per workgroup (4 SB waves); BINS bins over [-1, 1]: 512 for two
-// groups, 448 for three (the histograms of 96 rows and the two key tiles must fit the LDS), so
+// SB 32-row groups of sources per workgroup (4 SB waves); BINS bins over [-1, 1]: 256 for two
+// groups, 224 for three (the histograms of 96 rows and the two key tiles must fit the LDS), so
 // the bound is at most 2 / BINS below the m-th largest sampled edge.
 template <int SB, int BINS>
 __global__ __launch_bounds__(256 * SB) void cosine_bound_kernel(
@@ -206,7 +209,7 @@ __global__ __launch_bounds__(256 * SB) void cosine_bound_kernel(
     __shared__ int32_t idx_s[ROWS];
     extern __shared__ __align__(16) unsigned char smem[];   // two key tiles, then the histograms
     unsigned char *kt = smem;
-    uint32_t *hist = reinterpret_cast<uint32_t *>(smem + 2 * kTileBytes);   // [ROWS][BINS / 2]
+    uint32_t *hist = reinterpret_cast<uint32_t *>(smem + 2 * kTileBytes);   // [ROWS][BINS]
 
     // with few heads the sample is cut into chunks (blockIdx.z) whose histograms are added up
     // by bound_merge_kernel: otherwise a handful of workgroups would walk the sample alone
@@ -222,11 +225,11 @@ __global__ __launch_bounds__(256 * SB) void cosine_bound_kernel(
 
     bf16x8 q[kSteps];
     load_sources(Ac + (long)h * N * kD, src + (long)h * src_pitch, Sh, s_base, grp, stream, l32, hh, q, inv_s, idx_s);
-    for (int u = tid; u < ROWS * (BINS / 2); u += NT) hist[u] = 0;
+    for (int u = tid; u < ROWS * BINS; u += NT) hist[u] = 0;
     __syncthreads();
-    float inv_src[16];
+    float inv_src[16];   // 1/|k_i| times half the number of bins: edge -> bin in one multiply-add
 #pragma unroll
-    for (int i = 0; i < 16; ++i) inv_src[i] = inv_s[kBlk * grp + acc_row(i, hh)];
+    for (int i = 0; i < 16; ++i) inv_src[i] = inv_s[kBlk * grp + acc_row(i, hh)] * (0.5f * BINS);
 
     const int ntile = c1 > c0 ? (c1 - c0 + kTileKeys - 1) / kTileKeys : 0;
     auto multiply_tile = [&](const unsigned char *buf, int t) {
@@ -246,10 +249,10 @@ __global__ __launch_bounds__(256 * SB) void cosine_bound_kernel(
         if (col < c1) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float e = (acc[i] * inv_k) * inv_src[i];   // the dense kernel's formula
-                int b = (int)((e + 1.0f) * (0.5f * BINS));
+                // (e + 1) BINS / 2 with e = (dot / |k_j|) / |k_i|, the dense kernel's edge up to rounding
+                int b = (int)fmaf(acc[i] * inv_k, inv_src[i], 0.5f * BINS);
                 b = b < 0 ? 0 : (b > BINS - 1 ? BINS - 1 : b);
-                atomicAdd(&hist[(kBlk * grp + acc_row(i, hh)) * (BINS / 2) + (b >> 1)], (b & 1) ? 65536u : 1u);
+                atomicAdd(&hist[(kBlk * grp + acc_row(i, hh)) * BINS + b], 1u);
             }
         }
     };
@@ -262,29 +265,28 @@ __global__ __launch_bounds__(256 * SB) void cosine_bound_kernel(
         const int32_t i = idx_s[tid];
         const int col = i / key_stride;
         if (i % key_stride == 0 && col >= c0 && col < c1) {
-            uint32_t &top = hist[tid * (BINS / 2) + (BINS - 1) / 2];
-            if ((top >> 16) > 0u) top -= 65536u;
+            uint32_t &top = hist[tid * BINS + BINS - 1];
+            if (top > 0u) top -= 1u;
         }
     }
     __syncthreads();
 
     if (gridDim.z > 1) {   // this chunk's counts go to global memory
         uint4 *out = reinterpret_cast<uint4 *>(
-            hist_part + ((((long)h * gridDim.x + blockIdx.x) * gridDim.z + chunk) * ROWS) * (BINS / 2));
+            hist_part + ((((long)h * gridDim.x + blockIdx.x) * gridDim.z + chunk) * ROWS) * BINS);
         const uint4 *in = reinterpret_cast<const uint4 *>(hist);
-        for (int u = tid; u < ROWS * (BINS / 2) / 4; u += NT) out[u] = in[u];
+        for (int u = tid; u < ROWS * BINS / 4; u += NT) out[u] = in[u];
         return;
     }
     // Wave w scans the histograms of rows 8w .. 8w+7 from the top; lane L holds bins 8L .. 8L+7.
     for (int r = 0; r < 8; ++r) {
         const int row = wv * 8 + r;
-        const uint4 w4 = histogram_words<BINS>(&hist[row * (BINS / 2)], lane);
+        const uint4 w4 = histogram_words<BINS>(&hist[row * BINS], lane);
         if (s_base + row < Sh) bound_from_histogram<BINS>(w4, m, lane, &tau[(long)h * pitch + row0 + s_base + row]);
     }
 }
 
-// Adds up the histograms of the sample's chunks (16-bit counters, two to a word: a bin's
-// total is at most the sample size, which stays below 65536) and takes the bound.  One
+// Adds up the histograms of the sample's chunks and takes the bound.  One
 // wave per source.
 template <int SB, int BINS>
 __global__ __launch_bounds__(256) void bound_merge_kernel(const uint32_t *__restrict__ hist_part,
@@ -300,7 +302,7 @@ __global__ __launch_bounds__(256) void bound_merge_kernel(const uint32_t *__rest
     uint4 w4 = make_uint4(0, 0, 0, 0);
     for (int c = 0; c < chunks; ++c) {
         const uint4 v = histogram_words<BINS>(
-            hist_part + ((((long)h * sgroups + sg) * chunks + c) * ROWS + row) * (BINS / 2), lane);
+            hist_part + ((((long)h * sgroups + sg) * chunks + c) * ROWS + row) * BINS, lane);
         w4.x += v.x; w4.y += v.y; w4.z += v.z; w4.w += v.w;
     }
     bound_from_histogram<BINS>(w4, m, lane, &tau[(long)h * pitch + row0 + slot]);
@@ -1208,7 +1210,7 @@ hipError_t launch_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, i
     const int chunk_cols = (((ps + chunks - 1) / chunks + kTileKeys - 1) / kTileKeys) * kTileKeys;
     if (!allow_big_lds((const void *)cosine_bound_kernel<SB, BINS>)) return hipGetLastError();
     hipLaunchKernelGGL((cosine_bound_kernel<SB, BINS>), dim3(sgroups, Hkv, chunks), dim3(256 * SB),
-                       2 * kTileBytes + ROWS * (BINS / 2) * 4, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, ps,
+                       2 * kTileBytes + ROWS * BINS * 4, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, ps,
                        stride, rows, src_pitch, src, n_src, m, chunk_cols, (uint32_t *)hist_part, tau, pitch, row0,
                        overflow);
     if (chunks > 1)
@@ -1264,12 +1266,12 @@ hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int
                                     hipStream_t st)
 {
     if (first_round && g.sb == 3)
-        return launch_bound<3, 448>(Ac, Kc, Hkv, N, P, g.S + g.X, m, src, g.S + g.X, n_src, hist_part, tau, g.pitch,
+        return launch_bound<3, 224>(Ac, Kc, Hkv, N, P, g.S + g.X, m, src, g.S + g.X, n_src, hist_part, tau, g.pitch,
                                     0, overflow, st);
     if (first_round)
-        return launch_bound<2, 512>(Ac, Kc, Hkv, N, P, g.S, m, src, g.S, n_src, hist_part, tau, g.pitch, 0,
+        return launch_bound<2, 256>(Ac, Kc, Hkv, N, P, g.S, m, src, g.S, n_src, hist_part, tau, g.pitch, 0,
                                     overflow, st);
-    return launch_bound<2, 512>(Ac, Kc, Hkv, N, P, g.S, m, src, g.S, n_src, hist_part, tau, g.pitch, 0, overflow, st);
+    return launch_bound<2, 256>(Ac, Kc, Hkv, N, P, g.S, m, src, g.S, n_src, hist_part, tau, g.pitch, 0, overflow, st);
 }
 
 hipError_t launch_mfma_cosine_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, int m,
