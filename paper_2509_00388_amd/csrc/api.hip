@@ -62,8 +62,8 @@ struct Workspace {
 };
 
 // The MFMA kernels cover bf16 keys with d = 128.  Scoring additionally needs the
-// stacked query rows G*w to fill whole 32-row MFMA blocks (at most 256 rows, handled
-// in parts of 128); per-query-head votes (max pooling) need w itself to be a multiple
+// stacked query rows G*w to fill whole 32-row MFMA blocks (at most 256 rows: 256 rows
+// in one workgroup, other counts beyond 128 in parts of 128); per-query-head votes (max pooling) need w itself to be a multiple
 // of 32.
 bool mfma_cosine_ok(const graphkv_params *p)
 {

@@ -2,21 +2,21 @@
 // prefix key (bf16 inputs, d = 128, fp32 accumulation), and each source's m
 // largest edges without ever storing the S x P edge block.
 //
-// Up to 64 source rows (two 32-row MFMA blocks) are held in registers; keys
-// stream from HBM in 32-row blocks straight into MFMA operand registers, as in
-// the scoring kernels.  The squared norm of each streamed key is accumulated
-// from the very registers that feed the MFMA, so the keys are read once.
+// Up to 96 source rows (three 32-row MFMA blocks, one per row group of waves) are
+// held in registers; keys stream from HBM through LDS tiles into MFMA operand
+// registers, as in the scoring kernels.  The squared norm of each streamed key is
+// accumulated from the very registers that feed the MFMA, so the keys are read once.
 //
 // Neighbourhoods in one streaming pass:
-//   1. the same kernel first runs on an evenly strided sample of the keys and
-//      writes that small edge block; the m-th largest sampled edge of a source
-//      is a lower bound of its m-th largest edge overall (a subset's m-th
-//      largest can only be smaller), and a tight one for a sample of P/8 keys;
+//   1. a first pass over an evenly strided sample of the keys (every 8th) counts
+//      each source's edges into a histogram; the m-th largest sampled edge of a
+//      source is a lower bound of its m-th largest edge overall (a subset's m-th
+//      largest can only be smaller);
 //   2. the streaming pass keeps only the edges that reach the bound (a few
 //      hundred per source), staged in LDS and appended to per-source lists;
 //   3. an exact (value desc, index asc) top-m over each short list.
 // A source whose list overflows (masses of equal edges, adversarial order) sets
-// a per-head flag and that head is redone through the dense block instead.
+// a per-head flag and that head is redone exactly, row by row (redo_rows in select.hip).
 //
 // A neighbourhood depends on the keys alone, so a source that comes back in a later
 // round keeps its list.  The first round's passes also take a third 32-row group per
@@ -586,7 +586,7 @@ __device__ __forceinline__ uint32_t ord_key_inv(uint32_t k)
 // Exact top-m of one source's candidate list by (edge desc, key index asc),
 // written in ascending key order.  The workgroups of a head share its sources in
 // turn (a workgroup's next list is asked for while it works on the current one);
-// heads whose overflow flag is set are left to the dense path.
+// heads whose overflow flag is set are left to the exact fallback.
 //
 // The m-th largest edge value is found by a radix select over the order-
 // preserving keys of the (short) list, as in the row top-k; entries above it are
@@ -650,7 +650,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
         __syncthreads();
         if (x + (int)gridDim.x < n_rows) ask(x + gridDim.x, cnt_r, self_r, pos_r, crow_r);
         const int n = end_s[255];
-        if (n > cap) {          // more candidates than the select can hold: redo the head densely
+        if (n > cap) {          // more candidates than the select can hold: the head is redone exactly
             if (tid == 0) overflow[h] = 1;
             return;
         }
@@ -745,7 +745,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
         const uint32_t tau = kmin + prefix;
         // Everything that reaches the threshold goes to the list as (entry number, edge bits);
         // its order is fixed by the final ranking.  More entries equal to the threshold than
-        // the list has room for beyond m: the head is redone densely.
+        // the list has room for beyond m: the head is redone exactly.
         for (int r = tid; r < n; r += 256) {
             const uint32_t k = ek[r];
             if (k >= tau && k) {
@@ -813,7 +813,7 @@ __global__ __launch_bounds__(256) void nbr_select_kernel(const uint2 *__restrict
 // indices of the listed entries fetched, the tied entries with the lowest key indices are
 // kept, and the winners are ranked by key index.  Lists longer than 64 R, with fewer than
 // m entries, or with more ties at the cut than the list has room for, raise the head's
-// overflow flag (the head is then redone densely).
+// overflow flag (the head is then redone exactly).
 template <int R>
 __global__ __launch_bounds__(256) void nbr_select_wave_kernel(const uint2 *__restrict__ cand,
                                                               const int32_t *__restrict__ cand_cnt,
@@ -850,7 +850,7 @@ __global__ __launch_bounds__(256) void nbr_select_wave_kernel(const uint2 *__res
         // (values every lane holds alike are moved to scalar registers: the code below then
         // branches as a wave instead of masking lanes)
         const int n = __builtin_amdgcn_readfirstlane(__shfl(incl, 63, kWave));
-        if (n > 64 * R || n < m) {   // too long for the lanes (or short of m): redo the head densely
+        if (n > 64 * R || n < m) {   // too long for the lanes (or short of m): the head is redone exactly
             if (lane == 0) overflow[h] = 1;
             return;
         }

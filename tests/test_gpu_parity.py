@@ -349,7 +349,7 @@ def test_filtered_neighbourhoods_keys_close_to_many_sources(oracle):
 def test_filtered_neighbourhoods_ties_at_the_cut(oracle, n_copies, m):
     """Exact copies of a source's weakest neighbour tie with it at the cut: the lowest key
     indices win (a few ties are settled among the listed candidates, a hundred send the head
-    through the dense block).  m = 20 takes the wave-per-source select, m = 160 (lists of up to
+    through the exact fallback).  m = 20 takes the wave-per-source select, m = 160 (lists of up to
     2560 candidates) the workgroup-per-source one."""
     cfg = small_bf16_cfg(n_tokens=10007, n_sources=40, n_neighbors=m, n_kv_heads=2, n_q_heads=8)
     (K, V, Q), _ = util.device_layer(cfg, 9)
@@ -378,7 +378,7 @@ def test_filtered_neighbourhoods_ties_at_the_cut(oracle, n_copies, m):
 @pytest.mark.parametrize("n_tokens", [12000, 40000])
 def test_filtered_neighbourhoods_overflow_falls_back(oracle, n_tokens):
     """Masses of exactly equal edges defeat any bound: those heads must be redone
-    through the dense block and still give the exact lowest-index answer (edge rows beyond
+    by the exact fallback and still give the exact lowest-index answer (edge rows beyond
     32768 entries take the row top-k that re-reads the row)."""
     cfg = small_bf16_cfg(n_tokens=n_tokens, n_sources=8, n_neighbors=16, n_kv_heads=2, n_q_heads=8)
     (K, V, Q), _ = util.device_layer(cfg, 1)
@@ -456,7 +456,7 @@ def test_filtered_multi_round_keeps_lists(oracle, S, m, alpha, signal):
 
 
 def test_filtered_multi_round_with_overflowing_head(oracle):
-    """A head whose lists overflow is redone densely in every round; the other head
+    """A head whose lists overflow is redone exactly in every round; the other head
     keeps its lists."""
     cfg = small_bf16_cfg(n_tokens=12000, n_sources=8, n_neighbors=16, n_kv_heads=2, n_q_heads=8)
     (K, V, Q), _ = util.device_layer(cfg, 1)
