@@ -251,7 +251,7 @@ def test_propagate_multi_round(oracle, impl, reselect):
                                            gap_nbr=dbg["gap_nbr"], gap_final=np.full(cfg.n_kv_heads, np.inf)),
                                       dict(src=list(src), nbr=list(nbr)), h)
         if first[0] == "final":          # no cut differed
-            util.assert_scores_close(sT[h], ref[h], f"head {h}: scores after {T} rounds")
+            util.assert_scores_close(sT[h], ref[h], f"head {h}: scores after {T} rounds", start=s0[h])
         else:
             say(f"  multi-round reselect={reselect} head {h}: picks leave the oracle's at {first}")
             assert first[3] < util.REL_TOL, f"head {h}: picks differ at a cut that is no near-tie: {first}"
@@ -917,7 +917,7 @@ def test_propagate_negative_scores_staged(oracle, impl, signal, alpha):
         if flips == 0:      # same picks as the oracle: its refined scores are the reference
             ref = oracle.propagate(K, "bf16", cfg.window, s0.astype(np.float64), cfg.n_sources,
                                    cfg.n_neighbors, 1, alpha, 1, signal)
-            util.assert_scores_close(s1, ref, "refined scores")
+            util.assert_scores_close(s1, ref, "refined scores", start=s0)
 
 
 @pytest.mark.parametrize("case", ["dense-auto", "dense-generic", "filter", "c1-fp32"])

@@ -1,0 +1,49 @@
+"""Whole passes at seeded random shapes against the oracle (GPU, through the C ABI).
+
+The fixed cases of test_gpu_parity.py sit on the boundaries the kernels were written around;
+these sit anywhere: prompt lengths on both sides of the filter route's threshold, source and
+neighbour counts that do and do not fill the 32-row blocks, one to three rounds with and without
+re-picked sources, all signals, both scorers, odd budgets.  Every case is judged cut by cut like
+the end-to-end tests (util.judge_layer): a retained set may differ from the oracle's only at a
+near-tie of the oracle's own, and then every later stage must hold on the GPU's own values."""
+import numpy as np
+import pytest
+
+from paper_2509_00388_amd import binding as gk
+from paper_2509_00388_amd import synth
+
+from tests import util
+from tests.test_gpu_parity import end_to_end, say
+
+pytestmark = pytest.mark.gpu
+
+
+def random_case(seed):
+    """A config (c2's key recipe) and parameter overrides drawn from a seeded generator."""
+    rng = np.random.default_rng(90210 + seed)
+    G, w = [(1, 32), (2, 32), (4, 32), (1, 64), (2, 64), (4, 64), (3, 32), (1, 128)][rng.integers(8)]
+    n_kv = int(rng.integers(1, 4))
+    long_prompt = seed % 2 == 0                       # every other case takes the filter route
+    P = int(rng.integers(8192, 20000)) if long_prompt else int(rng.integers(600, 8191))
+    S = int(rng.integers(1, 97))
+    m = int(rng.integers(1, 65))
+    T = int(rng.integers(1, 4))
+    budget = w + int(rng.integers(1, min(P, 3000)))
+    cfg = synth.scaled(synth.CONFIGS["c2"], n_tokens=P + w, window=w, n_kv_heads=n_kv, n_q_heads=n_kv * G,
+                       budget=budget, n_sources=min(S, P), n_neighbors=min(m, P - 1), rounds=T,
+                       pool_kernel=int([1, 5, 7, 13][rng.integers(4)]),
+                       dup_fraction=float([0.0, 0.0, 0.1][rng.integers(3)]))
+    over = dict(signal=int(rng.integers(3)), decay=float([1.0, 1.0, 0.3][rng.integers(3)]),
+                reselect=int(rng.integers(2)), scorer=gk.SCORER_KNORM if seed % 6 == 5 else gk.SCORER_ATTENTION,
+                edges=int([gk.EDGES_KK, gk.EDGES_KK, gk.EDGES_KK, gk.EDGES_KV, gk.EDGES_VV][rng.integers(5)]))
+    return cfg, over
+
+
+@pytest.mark.parametrize("seed", range(64))
+def test_random_shape_whole_pass(oracle, seed):
+    cfg, over = random_case(seed)
+    say(f"random case {seed}: N={cfg.n_tokens} w={cfg.window} H={cfg.n_kv_heads}x{cfg.n_q_heads // cfg.n_kv_heads} "
+        f"S={cfg.n_sources} m={cfg.n_neighbors} T={cfg.rounds} B={cfg.budget} pool={cfg.pool_kernel} {over}")
+    diffs, min_gap, _ = end_to_end(oracle, cfg, seed, gk.IMPL_AUTO, **over)
+    if diffs:
+        say(f"  random case {seed}: accepted at near-ties {diffs}, smallest oracle gap {min_gap:.2e}")

@@ -33,8 +33,19 @@ def device_layer(cfg, layer=0):
     return (K, V, Q), tuple(gk.to_device(a, dt) for a in (K, V, Q))
 
 
-def assert_scores_close(gpu, ref, what="scores"):
-    """|g - o| <= REL_TOL * |o| + 1e-9 * max|o|, element by element."""
+EDGE_NOISE = 2e-5   # fp32 edge against the double-precision cosine (128 bf16 products, two rsqrt)
+
+
+def assert_scores_close(gpu, ref, what="scores", start=None):
+    """|g - o| <= REL_TOL * |o| + 1e-9 * max|o|, element by element.
+
+    For scores that went through the propagation, `start` is the score array it began with and
+    adds EDGE_NOISE * |start| to the bound.  A refined score is s * prod_i (1 -+ alpha e_i)
+    (Eq. 5); an edge that is off by fp32 rounding moves that product by at most alpha times that
+    much times |s|, whatever the other factors of a decay are (they are at most 1) -- which is
+    nothing next to REL_TOL for ordinary neighbours, but a relative error of a per cent for a
+    near-duplicate of a source (1 - e of 1e-4 against an edge error of 1e-6): the conditioning
+    of Eq. 4 in fp32, not an error of the kernel."""
     gpu = np.asarray(gpu, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     finite = np.isfinite(ref)
@@ -43,6 +54,8 @@ def assert_scores_close(gpu, ref, what="scores"):
     scale = np.abs(ref[finite]).max() if finite.any() else 0.0
     err = np.abs(gpu[finite] - ref[finite])
     bound = REL_TOL * np.abs(ref[finite]) + 1e-9 * scale
+    if start is not None:
+        bound = bound + EDGE_NOISE * np.abs(np.asarray(start, dtype=np.float64)[finite])
     bad = err > bound
     assert not bad.any(), (f"{what}: {bad.sum()} of {bad.size} beyond tolerance, worst rel err "
                            f"{(err / np.maximum(np.abs(ref[finite]), 1e-300)).max():.3e}")
@@ -76,14 +89,14 @@ def check_round_staged(orc, K_np, dtype_name, window, s_in, s_out, src, nbr, ev,
             lst = nbr[h, a]
             assert (np.diff(lst) > 0).all() and lst.min() >= 0 and lst.max() < P and i not in lst
             np.testing.assert_allclose(ev[h, a], e_ref[lst], rtol=0, atol=REL_TOL)
-            assert np.abs(ev[h, a] - e_ref[lst]).max() < 2e-5, "edge weights drift beyond fp32 noise"
+            assert np.abs(ev[h, a] - e_ref[lst]).max() < EDGE_NOISE, "edge weights drift beyond fp32 noise"
             want, gap = orc.topk(e_ref, m, skip=i)
             if not np.array_equal(lst, want):
                 flips += 1
                 assert gap < REL_TOL, f"head {h} source {i}: neighbours differ at gap {gap:.3e}"
                 rest = np.ones(P, bool); rest[lst] = False; rest[i] = False
                 if rest.any():
-                    assert e_ref[lst].min() >= e_ref[rest].max() - 2e-5
+                    assert e_ref[lst].min() >= e_ref[rest].max() - EDGE_NOISE
             for j, e in zip(lst, ev[h, a].astype(np.float64)):
                 hit[j] = True
                 a32 = float(np.float32(alpha))
@@ -205,7 +218,8 @@ def judge_layer(orc, p, host, dev, ref, idx_gpu, scores_gpu=None, layer=0, excus
             diffs.append((h, nd))
     same = [h for h in range(H) if h not in [d[0] for d in diffs]]
     if scores_gpu is not None and same:
-        assert_scores_close(scores_gpu[same], ref["scores"][same], f"layer {layer}: refined scores")
+        assert_scores_close(scores_gpu[same], ref["scores"][same], f"layer {layer}: refined scores",
+                            start=ref["s0"][same])
     if not diffs:
         return diffs
     st = staged_gpu_run(p, dev, budget=B)
