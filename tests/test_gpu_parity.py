@@ -841,6 +841,21 @@ def test_full_size_batched_c3(oracle):
         one, _ = run_compress(p, (Kall[l], Vall[l], Qall[l]), want_scores=False)
         assert np.array_equal(one[2], idx_h[l]) and np.array_equal(one[0], Ko[l]) and np.array_equal(one[1], Vo[l])
 
+    # The same cache with so many sources and neighbours that the scratch of 32 layers would pass
+    # the library's bound: the call is cut into two launch groups of 16 layers (the workspace it
+    # asks for is that of 16), each keeping its speculative rows.  Whatever the grouping, a layer's
+    # result is the per-layer call's, byte for byte.
+    p2 = util.params_from_cfg(cfg, n_sources=224, n_neighbors=200)
+    assert gk.graphkv_workspace_bytes_batched(p2, L) == gk.graphkv_workspace_bytes_batched(p2, L // 2)
+    say("  224 sources x 200 neighbours: two launch groups")
+    Kout2, Vout2, idx2 = gk.graphkv_compress_batched(p2, L, None, Kall, Vall, Qall)
+    torch.cuda.synchronize()
+    idx2_h = idx2.cpu().numpy().reshape(L, H, B)
+    Ko2 = gk.to_host_bits(Kout2).reshape(L, H, B, cfg.head_dim)
+    for l in (0, 15, 16, 31):
+        one, _ = run_compress(p2, (Kall[l], Vall[l], Qall[l]), want_scores=False)
+        assert np.array_equal(one[2], idx2_h[l]) and np.array_equal(one[0], Ko2[l]), f"layer {l}"
+
 
 def long_context_head():
     """One KV head (4 query heads) of the long-context workload: N = 131072, w = 64 (256

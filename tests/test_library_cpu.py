@@ -68,6 +68,11 @@ def test_batched_workspace_stays_bounded(lib):
     assert 0 < gk.graphkv_workspace_bytes_batched(c5, 32) < 2 << 30
     assert 0 < gk.graphkv_workspace_bytes_batched(c3, 32) < 1 << 30
     assert gk.graphkv_workspace_bytes(c3) <= gk.STATIC_SCRATCH_BYTES    # a 32K layer fits the built-in buffer
+    # a batch whose scratch would pass the bound is cut into launch groups: 32 layers then ask for
+    # what 16 ask for
+    wide = good_params(n_tokens=32768, window=32, budget=2048, n_sources=224, n_neighbors=200, rounds=2)
+    assert gk.graphkv_workspace_bytes_batched(wide, 32) == gk.graphkv_workspace_bytes_batched(wide, 16) < 2000 << 20
+    assert gk.graphkv_workspace_bytes_batched(wide, 8) < gk.graphkv_workspace_bytes_batched(wide, 16)
 
 
 BAD = [dict(n_kv_heads=0), dict(n_q_heads=12), dict(head_dim=100), dict(head_dim=1024),
