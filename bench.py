@@ -104,6 +104,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--prewarm", type=float, default=0.3,
+                    help="seconds of untimed steps before the warm-up steps, until the clocks have settled (0: none)")
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--layers", type=int, default=0, help="use only the first LAYERS layers (debug)")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers the CPU oracle is timed on (0 = skip)")
@@ -210,6 +212,19 @@ def main():
                 if st is not None:
                     cur.wait_stream(st)
 
+    # The card comes out of seconds of idling (the inputs are generated on the host) and needs
+    # some tens of milliseconds of load before its clocks settle: the steps right after that run
+    # 6-8 % slower than all later ones, and a few warm-up steps of under 2 ms each do not cover
+    # it.  So the same step is first repeated for a fixed time, untimed like the warm-up steps
+    # that follow, and reported as `prewarm` in the result line.
+    prewarm_steps = 0
+    if args.prewarm > 0:
+        tw = time.perf_counter()
+        while time.perf_counter() - tw < args.prewarm:
+            for _ in range(8):
+                step()
+            torch.cuda.synchronize()
+            prewarm_steps += 8
     for _ in range(max(args.warmup, 1 if args.graph else 0)):
         step()
     torch.cuda.synchronize()
@@ -413,7 +428,10 @@ def main():
                    "mode": args.mode + (f" (groups of {group} layers, {args.streams} stream(s))" if args.mode == "batched"
                                         else f" ({args.streams} stream(s))") + (", one HIP graph per step" if args.graph else ""),
                    "token_head_units_per_s": round(tokens_per_s * cfg.n_layers * cfg.n_kv_heads, 1),
-                   "input_generation_s": round(t_gen, 1)},
+                   "input_generation_s": round(t_gen, 1),
+                   "prewarm": {"seconds": args.prewarm, "steps": prewarm_steps,
+                               "note": "untimed repetitions of the step before the warm-up steps, until the clocks "
+                                       "have settled after the idle time of input generation"}},
         "roofline": roofline, "cpu_baseline": cpu, "pass_vs_streaming_model": pass_view, "other_workloads": other,
         "kernels": kernels, "parity_sample": parity,
     }
