@@ -67,7 +67,9 @@ struct Workspace {
 // of 32.
 bool mfma_cosine_ok(const graphkv_params *p)
 {
-    return p->impl == GRAPHKV_IMPL_AUTO && p->dtype == GRAPHKV_BF16 && p->head_dim == 128;
+    // (fewer than 2^24 rows: the tile loads address a head's rows with 32-bit byte offsets)
+    return p->impl == GRAPHKV_IMPL_AUTO && p->dtype == GRAPHKV_BF16 && p->head_dim == 128 &&
+           p->n_tokens < (1 << 24);
 }
 
 bool mfma_score_ok(const graphkv_params *p)

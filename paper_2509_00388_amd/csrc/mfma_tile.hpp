@@ -57,11 +57,14 @@ __device__ __forceinline__ void tile_load(const uint16_t *Kh, int first, int las
                                           int tid, u32x4 (&r)[PER])
 {
     static_assert(PER == tile_pieces<NT, TK>(), "pieces per thread");
+    // (a head's keys span less than 4 GiB -- the MFMA kernels take fewer than 2^24 rows -- so the
+    // byte offset fits 32 bits and the load can take the head's base from scalar registers)
+    const char *base = reinterpret_cast<const char *>(Kh);
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
         const int g = tile_piece<NT, TK>(tid, u), row = g >> 4, c = g & 15;
-        const long key = (long)min(first + row, last_key) * stride;
-        r[u] = *reinterpret_cast<const u32x4 *>(Kh + key * kD + c * 8);
+        const uint32_t off = (uint32_t)(min(first + row, last_key) * stride) * (uint32_t)(kD * 2) + (uint32_t)c * 16u;
+        r[u] = *reinterpret_cast<const u32x4 *>(base + off);
     }
 }
 
