@@ -480,12 +480,33 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
     const int de = fa.drain_every * 16 / lane_rows;
     // Tiles come in periods of `de`, the last tile of a period being the one with the scheduled
     // drain.  Hits beyond a row's fourth go to the LDS list of the period's parity, which is stored
-    // right after the barrier that ends the period, while the next period fills the other list.
+    // once the period has ended, while the next period fills the other list.
     int period = 0, period_end = de - 1;   // (the same in every thread)
     // a row group without sources only helps to move the key tiles
     const bool idle = s_base + kBlk * grp >= Sh;
+    // Entries listed during the period that just ended are final behind its last barrier, and the
+    // next period lists into the other list: one thread per entry stores them.  A list holds
+    // kLaterCap entries; more than that in one period and the head is redone exactly.  The list of
+    // a period is stored during the first tile of the next one, inside the tile's work and in
+    // front of its prefetch loads: a store behind the tile barrier would sit between the loads of
+    // two tiles, and the compiler then makes every other tile wait for all loads in flight
+    // instead of leaving the newer tile's outstanding.  (Threads 0 .. 127 do it: they belong to
+    // the first row group, which always has sources.)
+    int later_seen[2] = {0, 0};
+    auto store_later = [&](int par) {
+        const int n = n_later[par];
+        const int x = later_seen[par] + tid;
+        if (n - later_seen[par] > kLaterCap && tid == 0) later_lost = 1;
+        later_seen[par] = n;
+        if (x < n) {
+            const uint4 r = later[par][x & (kLaterCap - 1)];
+            const int at = atomicAdd(&row_pos[r.z], 1);
+            if (at < fa.slice_cap) slice0[(long)r.z * slice_row_stride + at] = make_uint2(r.x, r.y);
+        }
+    };
     auto multiply_tile = [&](const unsigned char *buf, int t) {
         if (idle) return;
+        if (period > 0 && t == period_end - de + 1) store_later((period - 1) & 1);
         bf16x8 kc[kSteps];
         tile_read(buf, stream, l32, hh, kc);
         f32x16 acc;
@@ -531,26 +552,8 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
             if (RING > kBlk) drain(period & 1);
         }
     };
-    // Entries listed during the period that just ended are final behind its last barrier, and the
-    // next period lists into the other list: one thread per entry stores them.  A list holds
-    // kLaterCap entries; more than that in one period and the head is redone exactly.  (Looking at
-    // the list's counter costs an LDS round trip right behind the barrier, which is why this is
-    // done once a period and not after every tile.)
-    int later_seen[2] = {0, 0};
-    auto store_later = [&](int par) {
-        const int n = n_later[par];
-        const int x = later_seen[par] + tid;
-        if (n - later_seen[par] > kLaterCap && tid == 0) later_lost = 1;
-        later_seen[par] = n;
-        if (x < n) {
-            const uint4 r = later[par][x & (kLaterCap - 1)];
-            const int at = atomicAdd(&row_pos[r.z], 1);
-            if (at < fa.slice_cap) slice0[(long)r.z * slice_row_stride + at] = make_uint2(r.x, r.y);
-        }
-    };
     auto end_of_tile = [&](int tile_done) {
         if (tile_done - 1 == period_end) {
-            store_later(period & 1);
             ++period;
             period_end += de;
         }
@@ -559,7 +562,10 @@ __global__ __launch_bounds__(256 * SB) void cosine_filter_kernel(
     drain(period & 1);
     drain(period & 1);
     __syncthreads();
-    store_later(period & 1);
+    if (!idle) {
+        store_later(0);
+        store_later(1);
+    }
     __syncthreads();      // every candidate is counted
     if (tid < ROWS && s_base + tid < Sh) {
         const int c = row_pos[tid];
