@@ -282,12 +282,12 @@ __device__ __forceinline__ void emit_sources(const uint64_t *win, int k, int S, 
 }
 
 // The same by one wave on its own (no workgroup barrier, no LDS in the loops): lane L keeps
-// winners L, L + 64, L + 128, L + 192 in registers and every winner in turn is broadcast to the
-// wave from its lane.
-__device__ __forceinline__ void emit_sources_wave(const uint64_t *win, int k, int S, int32_t *src_out,
-                                                  int32_t *ext_out, int lane)
+// winners L, L + 64, ... in R registers (k <= 64 R) and every winner in turn is broadcast to
+// the wave from its lane.
+template <int R>
+__device__ __forceinline__ void emit_sources_wave_r(const uint64_t *win, int k, int S, int32_t *src_out,
+                                                    int32_t *ext_out, int lane)
 {
-    constexpr int R = kSmallK / kWave;
     uint32_t key[R], idx[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -296,7 +296,9 @@ __device__ __forceinline__ void emit_sources_wave(const uint64_t *win, int k, in
         idx[r] = (uint32_t)(w >> 32);
     }
     // how many winners beat each of mine by (key descending, index ascending): fewer than S -> one of the S
-    int beat[R] = {0, 0, 0, 0};
+    int beat[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) beat[r] = 0;
     if (ext_out) {
 #pragma unroll
         for (int ru = 0; ru < R; ++ru)
@@ -311,7 +313,9 @@ __device__ __forceinline__ void emit_sources_wave(const uint64_t *win, int k, in
 #pragma unroll
     for (int r = 0; r < R; ++r) first_s[r] = beat[r] < S;
     // place = winners of the same class with a lower index
-    int before[R] = {0, 0, 0, 0};
+    int before[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) before[r] = 0;
 #pragma unroll
     for (int ru = 0; ru < R; ++ru)
         for (int l = 0; l < kWave && ru * kWave + l < k; ++l) {
@@ -330,6 +334,14 @@ __device__ __forceinline__ void emit_sources_wave(const uint64_t *win, int k, in
                 ext_out[S + before[r]] = (int32_t)idx[r];
             }
         }
+}
+
+__device__ __forceinline__ void emit_sources_wave(const uint64_t *win, int k, int S, int32_t *src_out,
+                                                  int32_t *ext_out, int lane)
+{
+    if (k <= kWave) emit_sources_wave_r<1>(win, k, S, src_out, ext_out, lane);
+    else if (k <= 2 * kWave) emit_sources_wave_r<2>(win, k, S, src_out, ext_out, lane);
+    else emit_sources_wave_r<kSmallK / kWave>(win, k, S, src_out, ext_out, lane);
 }
 
 // For k far below the row length (the source nodes: 64 of 32736, with the speculative
@@ -440,19 +452,23 @@ __global__ __launch_bounds__(BLOCK) void pick_sources_kernel(
         bound += s_bin << shift;
     }
 
-    // everything that reaches the bound -> the list (any order)
+    // everything that reaches the bound -> the list (any order): a wave counts its entries with
+    // wave votes, takes its stretch of the list with one atomic, and places them
     const uint64_t below = (1ull << lane) - 1ull;
+    uint32_t mine = 0;
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const bool in = key[i] >= bound && key[i] != 0u;
-        const uint64_t votes = __ballot(in);
-        if (votes) {
-            uint32_t base = 0;
-            const int leader = __ffsll((long long)votes) - 1;
-            if (lane == leader) base = atomicAdd(&s_cnt, (uint32_t)__popcll(votes));
-            base = __shfl(base, leader, kWave);
-            const uint32_t at = base + (uint32_t)__popcll(votes & below);
+    for (int i = 0; i < ITEMS; ++i) mine += (uint32_t)__popcll(__ballot(key[i] >= bound && key[i] != 0u));
+    uint32_t at0 = 0;
+    if (lane == 0 && mine) at0 = atomicAdd(&s_cnt, mine);
+    at0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)at0);
+    if (mine) {   // (the same for every lane of the wave)
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const bool in = key[i] >= bound && key[i] != 0u;
+            const uint64_t votes = __ballot(in);
+            const uint32_t at = at0 + (uint32_t)__popcll(votes & below);
             if (in && at < (uint32_t)kPickCap) { lk[at] = key[i]; lj[at] = (uint32_t)(i * BLOCK + tid); }
+            at0 += (uint32_t)__popcll(votes);
         }
     }
     __syncthreads();
