@@ -295,23 +295,45 @@ __device__ __forceinline__ void emit_sources_wave_r(const uint64_t *win, int k, 
         key[r] = (uint32_t)w;
         idx[r] = (uint32_t)(w >> 32);
     }
-    // how many winners beat each of mine by (key descending, index ascending): fewer than S -> one of the S
-    int beat[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) beat[r] = 0;
-    if (ext_out) {
-#pragma unroll
-        for (int ru = 0; ru < R; ++ru)
-            for (int l = 0; l < kWave && ru * kWave + l < k; ++l) {
-                const uint32_t ku = (uint32_t)__builtin_amdgcn_readlane((int)key[ru], l);
-                const uint32_t iu = (uint32_t)__builtin_amdgcn_readlane((int)idx[ru], l);
-#pragma unroll
-                for (int r = 0; r < R; ++r) beat[r] += (ku > key[r]) || (ku == key[r] && iu < idx[r]);
-            }
-    }
+    // One of the S best: above the S-th largest key of the winners, or equal to it and among the
+    // lowest indices of those (only if the tie straddles the cut are the tied entries ranked).
     bool first_s[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) first_s[r] = beat[r] < S;
+    for (int r = 0; r < R; ++r) first_s[r] = true;
+    if (ext_out && S < k) {
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (r * kWave + lane < k) { kmin = min(kmin, key[r]); kmax = max(kmax, key[r]); }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, kWave));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, kWave));
+        }
+        const uint32_t tau_s = mth_largest_key<R>(key, kmin, kmax, S);
+        int above = 0, equal = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            above += (int)__popcll(__ballot(r * kWave + lane < k && key[r] > tau_s));
+            equal += (int)__popcll(__ballot(r * kWave + lane < k && key[r] == tau_s));
+        }
+        const int need = S - above;   // tied entries that still belong to the S
+        int tied_before[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) tied_before[r] = 0;
+        if (equal != need) {
+#pragma unroll
+            for (int ru = 0; ru < R; ++ru)
+                for (int l = 0; l < kWave && ru * kWave + l < k; ++l) {
+                    const uint32_t ku = (uint32_t)__builtin_amdgcn_readlane((int)key[ru], l);
+                    const uint32_t iu = (uint32_t)__builtin_amdgcn_readlane((int)idx[ru], l);
+#pragma unroll
+                    for (int r = 0; r < R; ++r) tied_before[r] += ku == tau_s && iu < idx[r];
+                }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) first_s[r] = key[r] > tau_s || (key[r] == tau_s && tied_before[r] < need);
+    }
     // place = winners of the same class with a lower index
     int before[R];
 #pragma unroll
