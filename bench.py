@@ -403,11 +403,24 @@ def main():
                     break
         except OSError:
             pass
+        # the two small configurations in full (one layer each), all threads
+        small = {}
+        for name in ("c1", "c2"):
+            sc = synth.CONFIGS[name]
+            K, V, Q = synth.make_layer(sc, 0)
+            tc = time.perf_counter()
+            for _ in range(3):
+                oracle.compress(K, V, Q, sc.dtype, sc.pool_kernel, sc.budget, sc.n_sources, sc.n_neighbors,
+                                sc.rounds, alpha=sc.decay, reselect=sc.reselect)
+            ts = (time.perf_counter() - tc) / 3
+            small[name] = {"value": round(sc.n_tokens / (ts * sc.n_layers), 1), "unit": "prompt tokens/s",
+                           "seconds": round(ts, 4), "sample": f"all {sc.n_layers} layer(s), mean of 3 runs"}
         cpu = {
             "value": round(cfg.n_tokens / (t_cpu / n_s * cfg.n_layers), 2), "unit": "prompt tokens/s",
             "cores": threads, "kind": "oracle",
             "sample": f"layers 0..{n_s - 1} of {cfg.n_layers} in {t_cpu:.1f} s, extrapolated x{cfg.n_layers / n_s:g}",
             "precision": "fp64", "cpu_model": cpu_model, "host_cpus": os.cpu_count(), "single_thread": single,
+            "small_configs": small,
         }
         parity = {"layers_checked": n_s, "heads_checked": n_s * cfg.n_kv_heads,
                   "heads_with_differing_retained_set": differing,
