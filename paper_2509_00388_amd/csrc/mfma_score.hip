@@ -110,32 +110,33 @@ __global__ __launch_bounds__(64 * STREAMS * SPLIT) void score_stats_kernel(
     const int k0 = chunk * chunk_keys, k1 = min(N, k0 + chunk_keys);
     const int ntile = (k1 - k0 + TK - 1) / TK;
 
-    auto multiply_tile = [&](const unsigned char *buf, int t) {
-        bf16x8 kc[kSteps];
-        tile_read(buf, stream, l32, hh, kc);
-
-        f32x16 acc[NBW];
-#pragma unroll
-        for (int b = 0; b < NBW; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+    // Two accumulator sets: the products of tile t are issued between the softmax instructions of
+    // tile t - 1, so that the matrix core works while the vector unit does the exponentials.
+    f32x16 acc[2][NBW];
+    // the kSteps * NBW matrix instructions of one tile; between(j) is placed after the j-th
+    auto multiply = [&](const bf16x8 (&kc)[kSteps], int set, auto &&between) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < kSteps; ++s)
 #pragma unroll
-            for (int b = 0; b < NBW; ++b)   // rows = keys, columns = queries
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[s], q[b][s], acc[b], 0, 0, 0);
-
+            for (int b = 0; b < NBW; ++b) {   // rows = keys, columns = queries
+                acc[set][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[s], q[b][s], s == 0 ? zero : acc[set][b], 0, 0, 0);
+                between(s * NBW + b);
+            }
+    };
+    // running (max, sum) of the lane's queries updated with tile t, whose products are in `set`
+    auto finish = [&](int t, int set) {
         const int kb = k0 + TK * t + kBlk * stream;
         if (kb + kBlk <= P) {   // every key of the block is a prefix key: visible to all rows
 #pragma unroll
             for (int b = 0; b < NBW; ++b) {
-                float tm = acc[b][0];
+                float tm = acc[set][b][0];
 #pragma unroll
-                for (int i = 1; i < 16; ++i) tm = fmaxf(tm, acc[b][i]);
+                for (int i = 1; i < 16; ++i) tm = fmaxf(tm, acc[set][b][i]);
                 const float mn = fmaxf(m[b], tm * c);
                 float zz = z[b] * fast_exp2(m[b] - mn);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) zz += fast_exp2(fmaf(acc[b][i], c, -mn));
+                for (int i = 0; i < 16; ++i) zz += fast_exp2(fmaf(acc[set][b][i], c, -mn));
                 m[b] = mn;
                 z[b] = zz;
             }
@@ -145,20 +146,65 @@ __global__ __launch_bounds__(64 * STREAMS * SPLIT) void score_stats_kernel(
                 float tm = -INFINITY;
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (kb + acc_row(i, hh) <= last_vis[b]) tm = fmaxf(tm, acc[b][i]);
+                    if (kb + acc_row(i, hh) <= last_vis[b]) tm = fmaxf(tm, acc[set][b][i]);
                 const float mn = fmaxf(m[b], tm * c);
                 if (mn != -INFINITY) {
                     float zz = z[b] * fast_exp2(m[b] - mn);
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
-                        if (kb + acc_row(i, hh) <= last_vis[b]) zz += fast_exp2(fmaf(acc[b][i], c, -mn));
+                        if (kb + acc_row(i, hh) <= last_vis[b]) zz += fast_exp2(fmaf(acc[set][b][i], c, -mn));
                     m[b] = mn;
                     z[b] = zz;
                 }
             }
         }
     };
-    GKV_TILE_PIPELINE_TK(TK, NT, Kh, k0, k1 - 1, 1, ntile, multiply_tile, (void)0);
+    auto head = [&](const unsigned char *buf) {
+        bf16x8 kc[kSteps];
+        tile_read(buf, stream, l32, hh, kc);
+        multiply(kc, 0, [](int) {});
+    };
+    auto body = [&](const unsigned char *buf, int t, int set) {
+        bf16x8 kc[kSteps];
+        tile_read(buf, stream, l32, hh, kc);
+        const int kb = k0 + TK * (t - 1) + kBlk * stream;   // the block finished here
+        if (kb + kBlk <= P) {
+            // the same arithmetic as finish(), in the same order, cut into slices: the row maxima
+            // while the LDS reads are on their way, then two exponentials after every matrix
+            // instruction (the scheduling barriers keep the compiler from regrouping them)
+#pragma unroll
+            for (int b = 0; b < NBW; ++b) {
+                float tm = acc[set ^ 1][b][0];
+#pragma unroll
+                for (int i = 1; i < 16; ++i) tm = fmaxf(tm, acc[set ^ 1][b][i]);
+                const float mn = fmaxf(m[b], tm * c);
+                z[b] = z[b] * fast_exp2(m[b] - mn);
+                m[b] = mn;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(kc, set, [&](int j) {
+                constexpr int per = 16 / kSteps;   // NBW * 16 values over NBW * kSteps instructions
+#pragma unroll
+                for (int e = per * j; e < per * j + per; ++e)
+                    z[e / 16] += fast_exp2(fmaf(acc[set ^ 1][e / 16][e % 16], c, -m[e / 16]));
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        } else {
+            multiply(kc, set, [](int) {});
+            finish(t - 1, set ^ 1);
+        }
+    };
+    if constexpr (NBW <= 2) {
+        GKV_TILE_PIPELINE_OVERLAPPED(TK, NT, Kh, k0, k1 - 1, 1, ntile, head, body, finish);
+    } else {   // three row blocks per wave: a second accumulator set does not fit the registers
+        auto one_tile = [&](const unsigned char *buf, int t) {
+            bf16x8 kc[kSteps];
+            tile_read(buf, stream, l32, hh, kc);
+            multiply(kc, 0, [](int) {});
+            finish(t, 0);
+        };
+        GKV_TILE_PIPELINE_TK(TK, NT, Kh, k0, k1 - 1, 1, ntile, one_tile, (void)0);
+    }
 
     // merge the two half-waves (same query, other key rows), then the key streams
 #pragma unroll

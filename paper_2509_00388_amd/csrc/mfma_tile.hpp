@@ -163,6 +163,41 @@ __device__ __forceinline__ float half_row_sumsq(const bf16x8 (&r)[kSteps])
         }                                                                                              \
     } while (0)
 
+// The same loop for kernels that overlap the matrix products of one tile with the vector work on
+// the tile before it (a wave issues instructions in order: vector work placed between the matrix
+// instructions runs while the matrix core is busy, vector work placed after them waits for all of
+// them to be issued).  Such a kernel keeps two sets of accumulators.  `head(buf)` multiplies tile
+// 0 into set 0; `body(buf, t, set)` multiplies tile t into `set` and finishes tile t - 1 from the
+// other set; `tail(t, set)` finishes the last tile.  `set` is a literal at every call, so the
+// accumulator sets stay in registers.
+#define GKV_TILE_PIPELINE_OVERLAPPED(TK_, NT_, Kh_, first_, clamp_, stride_, ntile_, head, body, tail)  \
+    do {                                                                                               \
+        constexpr int tile_bytes_ = (TK_) * kPitch;                                                    \
+        u32x4 stage_a[tile_pieces<NT_, TK_>()], stage_b[tile_pieces<NT_, TK_>()];                      \
+        tile_load<NT_, TK_>(Kh_, first_, clamp_, stride_, tid, stage_a);                               \
+        tile_store<NT_, TK_>(kt, tid, stage_a);                                                        \
+        tile_load<NT_, TK_>(Kh_, first_ + (TK_), clamp_, stride_, tid, stage_a);                       \
+        tile_load<NT_, TK_>(Kh_, first_ + 2 * (TK_), clamp_, stride_, tid, stage_b);                   \
+        __syncthreads();                                                                               \
+        head(kt);                                                                                      \
+        tile_store<NT_, TK_>(kt + tile_bytes_, tid, stage_a);                                          \
+        tile_load<NT_, TK_>(Kh_, first_ + 3 * (TK_), clamp_, stride_, tid, stage_a);                   \
+        __syncthreads();                                                                               \
+        int t_ = 1;                                                                                    \
+        for (; t_ < ntile_; t_ += 2) {                                                                 \
+            body(kt + tile_bytes_, t_, 1);                                                             \
+            tile_store<NT_, TK_>(kt, tid, stage_b);                                                    \
+            tile_load<NT_, TK_>(Kh_, first_ + (TK_) * (t_ + 3), clamp_, stride_, tid, stage_b);        \
+            __syncthreads();                                                                           \
+            if (t_ + 1 >= ntile_) break;                                                               \
+            body(kt, t_ + 1, 0);                                                                       \
+            tile_store<NT_, TK_>(kt + tile_bytes_, tid, stage_a);                                      \
+            tile_load<NT_, TK_>(Kh_, first_ + (TK_) * (t_ + 4), clamp_, stride_, tid, stage_a);        \
+            __syncthreads();                                                                           \
+        }                                                                                              \
+        if ((ntile_ - 1) & 1) tail(ntile_ - 1, 1); else tail(ntile_ - 1, 0);                           \
+    } while (0)
+
 #define GKV_TILE_PIPELINE(NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE) \
     GKV_TILE_PIPELINE_TK(kTileKeys, NT_, Kh_, first_, clamp_, stride_, ntile_, body, AFTER_TILE)
 
