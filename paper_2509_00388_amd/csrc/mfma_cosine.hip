@@ -9,14 +9,19 @@
 //
 // Neighbourhoods in one streaming pass:
 //   1. a first pass over an evenly strided sample of the keys (every 8th) counts
-//      each source's edges into a histogram; the m-th largest sampled edge of a
-//      source is a lower bound of its m-th largest edge overall (a subset's m-th
-//      largest can only be smaller);
-//   2. the streaming pass keeps only the edges that reach the bound (a few
+//      each source's edges into a histogram and takes a bound from it: the sampled
+//      edge of rank r, where r < m is chosen so that all but about one source in 10^7
+//      have at least m edges above it (mfma_bound_rank; r = m would make that certain,
+//      a subset's m-th largest can only be smaller, but lets 8 m keys through
+//      where r lets 8 r);
+//   2. the streaming pass keeps only the edges that reach the bound (a couple of
 //      hundred per source), staged in LDS and appended to per-source lists;
-//   3. an exact (value desc, index asc) top-m over each short list.
-// A source whose list overflows (masses of equal edges, adversarial order) sets
-// a per-head flag and that head is redone exactly, row by row (redo_rows in select.hip).
+//   3. an exact (value desc, index asc) top-m over each short list -- exact whenever
+//      the list holds m entries or more, since it then holds every edge that is at
+//      least the bound and the m largest are among those.
+// A source whose list overflows (masses of equal edges, adversarial order) or comes
+// out short of m entries sets a per-head flag and that head is redone exactly, row by
+// row (redo_rows in select.hip).
 //
 // A neighbourhood depends on the keys alone, so a source that comes back in a later
 // round keeps its list.  The first round's passes also take a third 32-row group per
@@ -44,7 +49,7 @@ constexpr int kThreads = 256 * kSB;
 // source list start at row `row0` of them.
 struct FilterArgs {
     const int32_t *n_src;  // [Hkv] rows of the head's source list in use; null: all S
-    const float *tau;      // [Hkv, pitch] lower bound of each row's m-th largest edge
+    const float *tau;      // [Hkv, pitch] the bound pass's value per row: edges below it are dropped
     uint2 *cand;           // [Hkv, pitch, chunks, slice_cap] (edge bits, key index): one slice per key chunk
     int32_t *cand_cnt;     // [Hkv, pitch, chunks] entries in each slice
     int32_t *overflow;     // [Hkv]
@@ -144,9 +149,10 @@ __global__ __launch_bounds__(kThreads) void cosine_dense_kernel(
     GKV_TILE_PIPELINE(kThreads, Kh, c0, c1 - 1, key_stride, ntile, multiply_tile, (void)0);
 }
 
-// Bound pass: a lower bound of every source's m-th largest edge, from the edges to a
-// strided sample of the keys (column c = key c * key_stride) -- a subset's m-th
-// largest can only be smaller than the whole row's.  One workgroup takes the whole
+// Bound pass: for every source a value that at least m of its edges reach (short of about one
+// source in 10^7, which the select catches), from the edges to a strided sample of the keys
+// (column c = key c * key_stride).  `m` below is the rank in the sample that the host chose
+// (mfma_bound_rank).  One workgroup takes the whole
 // sample of a (head, source group): the edges never leave the registers, they are
 // counted into a 256-bin histogram over [-1, 1] per source in LDS, and the bound is
 // the lower edge of the bin in which the count from the top reaches m: at most 1/128
@@ -1117,6 +1123,21 @@ int mfma_sample_cols(int P)
     return ps;
 }
 
+// Rank of the sampled edge that the bound is taken at.  The bound is useful for a source when at
+// least m of its edges lie above it, i.e. when fewer than `rank` of its m - 1 largest edges fell
+// into the sample.  With every stride-th key sampled that count is binomial, (m - 1) trials at
+// 1 / stride: the rank is its mean plus six standard deviations (and one), at most m, so that
+// about one source in 10^7 comes out short -- which the select notices (fewer than m candidates)
+// and answers by redoing the head exactly, like an overflow.  About rank * stride keys lie above
+// the bound instead of m * stride: fewer rows to park, list and select from.
+int mfma_bound_rank(int m, int stride)
+{
+    if (stride <= 1) return m;
+    const double mean = (m - 1.0) / stride, dev = sqrt(mean * (1.0 - 1.0 / stride));
+    const int rank = (int)ceil(mean + 6.0 * dev) + 1;
+    return rank < m ? rank : m;
+}
+
 int mfma_cand_cap(int P, int m)
 {
     const int stride = P / mfma_sample_cols(P);
@@ -1214,14 +1235,15 @@ hipError_t launch_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, i
     const int sgroups = (rows + ROWS - 1) / ROWS;
     const int chunks = bound_chunks(Hkv, P, sgroups);
     const int chunk_cols = (((ps + chunks - 1) / chunks + kTileKeys - 1) / kTileKeys) * kTileKeys;
+    const int rank = mfma_bound_rank(m, stride);
     if (!allow_big_lds((const void *)cosine_bound_kernel<SB, BINS>)) return hipGetLastError();
     hipLaunchKernelGGL((cosine_bound_kernel<SB, BINS>), dim3(sgroups, Hkv, chunks), dim3(256 * SB),
                        2 * kTileBytes + ROWS * BINS * 4, st, (const uint16_t *)Ac, (const uint16_t *)Kc, N, ps,
-                       stride, rows, src_pitch, src, n_src, m, chunk_cols, (uint32_t *)hist_part, tau, pitch, row0,
+                       stride, rows, src_pitch, src, n_src, rank, chunk_cols, (uint32_t *)hist_part, tau, pitch, row0,
                        overflow);
     if (chunks > 1)
         hipLaunchKernelGGL((bound_merge_kernel<SB, BINS>), dim3((rows + 3) / 4, Hkv), dim3(256), 0, st,
-                           (const uint32_t *)hist_part, chunks, sgroups, rows, n_src, m, tau, pitch, row0);
+                           (const uint32_t *)hist_part, chunks, sgroups, rows, n_src, rank, tau, pitch, row0);
     return hipGetLastError();
 }
 
@@ -1234,10 +1256,10 @@ hipError_t launch_filter(const void *Ac, const void *Kc, int Hkv, int N, int P, 
     const int sgroups = (rows + ROWS - 1) / ROWS;
     const int stride = P / mfma_sample_cols(P);
     // Rows a half-wave parks per tile: 32 lanes x P(a lane's 16 edges hold a hit), with a
-    // per-edge hit rate of about m * stride / P (each source keeps ~m * stride candidates).
-    // Drains are scheduled for when most of a half-wave's 32 lanes get a row and the ring
-    // is not yet full.
-    const double rate = (double)m * stride / (double)P;
+    // per-edge hit rate of about rank * stride / P (each source keeps about that many candidates,
+    // rank = the bound pass's rank in the sample).  Drains are scheduled for when most of a
+    // half-wave's 32 lanes get a row and the ring is not yet full.
+    const double rate = (double)mfma_bound_rank(m, stride) * stride / (double)P;
     const double per_tile = 32.0 * (1.0 - pow(1.0 - (rate < 1.0 ? rate : 1.0), 16.0));
     int drain_every = (int)((RING > kBlk ? 30.0 : 24.0) / (per_tile > 0.45 ? per_tile : 0.45));
     if (drain_every < 1) drain_every = 1;

@@ -419,6 +419,37 @@ def test_more_overflowed_rows_than_redo_workgroups(oracle):
     assert np.array_equal(src, src_g) and np.count_nonzero((nbr != nbr_g).any(axis=-1)) <= 4
 
 
+def test_filtered_neighbourhoods_bound_above_the_cut(oracle):
+    """The bound pass takes its bound at a rank below m in the every-stride-th-key sample, which
+    leaves a source with fewer than m candidates when too many of its strongest edges sit at
+    sampled positions.  Head 0 is built that way: a source with 40 close copies, all of them at
+    sampled positions (40 is above any rank the bound pass may use for m = 64 and below m), and
+    nothing else near it.  Its list comes out short, which must be noticed and the head redone
+    exactly: all rows still equal the oracle's."""
+    m = 64
+    cfg = small_bf16_cfg(n_tokens=16416, n_sources=8, n_neighbors=m, n_kv_heads=2, n_q_heads=8)
+    (K, V, Q), _ = util.device_layer(cfg, 3)
+    P = cfg.n_prefix
+    sample = min(max((P // 8 + 127) // 128 * 128, 2048), 16384)   # the library's sample: every stride-th key
+    stride = P // sample
+    rng = np.random.default_rng(11)
+    sampled = rng.choice(sample - 1, size=41, replace=False) * stride + stride   # positions c * stride, c >= 1
+    a, copies = int(sampled[0]), sampled[1:]
+    base = rng.standard_normal(cfg.head_dim)            # a fresh direction, far from the recipe's clusters
+    K[0, a] = synth.f32_to_bf16_bits(base.astype(np.float32))
+    noise = 0.05 * rng.standard_normal((40, base.size))
+    K[0, copies] = synth.f32_to_bf16_bits((base[None, :] + noise).astype(np.float32))
+    Kd = gk.to_device(K, gk.BF16)
+    s0 = synth.random_scores(cfg)
+    s0[0, a] = 50.0
+    p = util.params_from_cfg(cfg, rounds=1)
+    s1, src, nbr, ev = run_propagate(p, Kd, s0)
+    util.check_round_staged(oracle, K, "bf16", cfg.window, s0, s1, src[0], nbr[0], ev[0], 8, m, 1.0)
+    row = src[0, 0].tolist().index(a)
+    assert set(copies.tolist()) <= set(nbr[0, 0, row].tolist())      # the copies lead the source's list
+    assert np.count_nonzero(ev[0, 0, row] > 0.9) == 40               # ... and nothing else is close
+
+
 @pytest.mark.parametrize("S,m,alpha,signal", [(40, 20, 1.0, 0), (130, 7, 0.7, 0), (64, 32, 1e-3, 0),
                                               (24, 16, 1.0, 2), (48, 12, 0.5, 1)])
 def test_filtered_multi_round_keeps_lists(oracle, S, m, alpha, signal):
