@@ -84,8 +84,8 @@ def algorithmic_bytes(cfg, B):
         "topk_sources": H * P * 4 + H * S * 4,
         "cosine": H * P * d * e + H * S * d * e,
         "cosine_filter": H * P * d * e + H * S * d * e,
-        # the bound pass reads every 8th key: a multiple of 128 keys, between 2048 and 16384
-        "cosine_bound": H * min(max((P // 8 + 127) // 128 * 128, 2048), 16384) * d * e + H * S * d * e,
+        # the bound pass reads every 8th key: a multiple of 128 keys, between 2048 and 8192
+        "cosine_bound": H * min(max((P // 8 + 127) // 128 * 128, 2048), 8192) * d * e + H * S * d * e,
         "topk_neighbors": H * S * m * 8,
         "decay": 2 * H * S * m * 8,
         "topk_final": H * P * 4 + H * B * 4,

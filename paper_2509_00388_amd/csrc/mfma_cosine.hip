@@ -1112,14 +1112,16 @@ int chunk_cols_for(int Hkv, int sgroups, int n_cols, int min_chunks = 1)
 
 }  // namespace
 
-// Keys in the strided sample of the bound pass: every 8th key, between 2048 and 16384 keys (one
+// Keys in the strided sample of the bound pass: every 8th key, between 2048 and 8192 keys (one
 // workgroup walks the whole sample of a head's sources).  A denser sample costs the bound pass
-// more and gives a tighter bound, i.e. fewer candidates for the filter pass to park and list.
+// more and gives a tighter bound, i.e. fewer candidates for the filter pass to park and list
+// (measured at 131008 keys and m = 128: 8192 sampled keys 10.2 ms per 32-layer pass, 16384 keys
+// 10.4 ms, 4096 keys 10.3 ms).
 int mfma_sample_cols(int P)
 {
     int ps = ((P / 8 + 127) / 128) * 128;
     if (ps < 2048) ps = 2048;
-    if (ps > 16384) ps = 16384;
+    if (ps > 8192) ps = 8192;
     return ps;
 }
 
@@ -1140,8 +1142,10 @@ int mfma_bound_rank(int m, int stride)
 
 int mfma_cand_cap(int P, int m)
 {
+    // four times the rank * stride keys expected above the bound (the bin that the bound is
+    // rounded down to adds up to a few hundred more at long prompts)
     const int stride = P / mfma_sample_cols(P);
-    long cap = 4L * m * stride;
+    long cap = 4L * mfma_bound_rank(m, stride) * stride;
     if (cap < 1024) cap = 1024;
     return (int)cap;
 }
@@ -1186,12 +1190,11 @@ MfmaFilterPlan mfma_filter_plan(int Hkv, int P, int S, int m, bool keep_lists, b
         g.chunk_cols = (((P + 255) / 256 + 127) / 128) * 128;
         g.chunks = (P + g.chunk_cols - 1) / g.chunk_cols;
     }
-    // a slice holds four times its expected share of a row's ~m * stride candidates (three times
-    // for long lists, whose relative spread is small)
+    // a slice holds four times its expected share of a row's ~rank * stride candidates (rank: the
+    // bound pass's rank in the sample), and 2 m on top
     const int stride = P / mfma_sample_cols(P);
-    const long share = ((long)m * stride + g.chunks - 1) / g.chunks;
-    long sc = (share >= 512 ? 3L : 4L) * share;
-    if (sc < 2L * m) sc = 2L * m;
+    const long share = ((long)mfma_bound_rank(m, stride) * stride + g.chunks - 1) / g.chunks;
+    long sc = 4L * share + 2L * m;
     if (sc < 64) sc = 64;
     g.cand_cap = mfma_cand_cap(P, m);
     if (sc > g.cand_cap) sc = g.cand_cap;

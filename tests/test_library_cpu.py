@@ -70,7 +70,7 @@ def test_batched_workspace_stays_bounded(lib):
     assert gk.graphkv_workspace_bytes(c3) <= gk.STATIC_SCRATCH_BYTES    # a 32K layer fits the built-in buffer
     # a batch whose scratch would pass the bound is cut into launch groups: 32 layers then ask for
     # what 16 ask for
-    wide = good_params(n_tokens=32768, window=32, budget=2048, n_sources=224, n_neighbors=200, rounds=2)
+    wide = good_params(n_tokens=32768, window=32, budget=2048, n_sources=224, n_neighbors=400, rounds=2)
     assert gk.graphkv_workspace_bytes_batched(wide, 32) == gk.graphkv_workspace_bytes_batched(wide, 16) < 2000 << 20
     assert gk.graphkv_workspace_bytes_batched(wide, 8) < gk.graphkv_workspace_bytes_batched(wide, 16)
 
