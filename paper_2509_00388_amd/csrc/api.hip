@@ -324,8 +324,8 @@ int32_t run_propagate(const graphkv_params *p, const Dims &D, const Workspace &W
             if (dbg_nbr) nbr = dbg_nbr + t * n_nbr;
             if (dbg_e) ev = dbg_e + t * n_nbr;
             if (D.filter) {
-                // Eq. 1 + Eq. 3 in one streaming pass over the keys: a bound on each source's
-                // m-th largest edge from a strided sample, then only edges above it are kept.
+                // Eq. 1 + Eq. 3 in one streaming pass over the keys: a bound per source from a
+                // strided sample that at least m of its edges reach, then only edges above it are kept.
                 float *tau = at<float>(ws, W.tau);
                 int32_t *cnt = at<int32_t>(ws, W.cand_cnt), *ovf = at<int32_t>(ws, W.overflow);
                 void *cand = at<char>(ws, W.cand);

@@ -102,6 +102,7 @@ hipError_t launch_mfma_cosine(const void *Ac, const void *Kc, int Hkv, int N, in
 // Neighbourhoods without the dense block (see mfma_cosine.hip):
 bool mfma_filter_applies(int P, int m);
 int mfma_sample_cols(int P);          // keys in the strided sample
+int mfma_bound_rank(int m, int stride);   // rank in the sample at which a row's bound is taken (<= m)
 int mfma_cand_cap(int P, int m);      // candidates per source the exact select can take
 bool source_reuse_applies(int S);     // lists can be kept from round to round
 constexpr int kSpecRows = 32;         // speculative rows per head: one or two MFMA row blocks of 32
@@ -123,8 +124,9 @@ struct MfmaFilterPlan {
 };
 MfmaFilterPlan mfma_filter_plan(int Hkv, int P, int S, int m, bool keep_lists, bool speculate);
 size_t mfma_bound_scratch_bytes(int Hkv, int P, const MfmaFilterPlan &g);   // per-chunk histograms (0 if one chunk)
-// Bound pass: tau = a lower bound of each row's m-th largest edge, from the edges to every
-// (P / sample_cols)-th key; clears overflow [Hkv].  first_round: src is the extended list
+// Bound pass: tau = a value that at least m of the row's edges reach (but for about one row in
+// 10^7, which the select notices), from the edges to every (P / sample_cols)-th key; clears
+// overflow [Hkv].  first_round: src is the extended list
 // [Hkv, S + X] (all rows in use, rows 0 .. of the buffers); otherwise src is the list of new
 // sources [Hkv, S], n_src [Hkv] of them in use, rows 0 .. of the buffers.
 hipError_t launch_mfma_cosine_bound(const void *Ac, const void *Kc, int Hkv, int N, int P, int m,
