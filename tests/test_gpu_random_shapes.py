@@ -39,7 +39,9 @@ def random_case(seed):
     return cfg, over
 
 
-@pytest.mark.parametrize("seed", range(64))
+# (case 106: a neighbour cut with an oracle gap of 1e-8 goes the other way on the GPU and moves a factor
+# of Eq. 5 from one node to another without changing the retained set)
+@pytest.mark.parametrize("seed", list(range(64)) + [106])
 def test_random_shape_whole_pass(oracle, seed):
     cfg, over = random_case(seed)
     say(f"random case {seed}: N={cfg.n_tokens} w={cfg.window} H={cfg.n_kv_heads}x{cfg.n_q_heads // cfg.n_kv_heads} "

@@ -198,7 +198,10 @@ def judge_layer(orc, p, host, dev, ref, idx_gpu, scores_gpu=None, layer=0, excus
     """Retained sets of one layer against the oracle's whole pass (`ref` = oracle.compress).
 
     Heads whose set equals the oracle's: the refined scores (if given) must be within
-    tolerance.  A head whose set differs is accepted only if
+    tolerance -- unless a near-tie at a source or neighbour cut moved a factor of Eq. 5 from one
+    node to another without changing the retained set: such a head is judged like one whose
+    set differs, and its first differing cut must then lie before the final one.  A head whose
+    set differs is accepted only if
       (1) the stages called one by one reproduce the whole pass's indices bit for bit,
       (2) the FIRST cut of that head at which the GPU's picks leave the oracle's (source cut
           of a round, neighbour cut of one source, or the final cut) is one where the oracle's
@@ -217,20 +220,30 @@ def judge_layer(orc, p, host, dev, ref, idx_gpu, scores_gpu=None, layer=0, excus
         if nd:
             diffs.append((h, nd))
     same = [h for h in range(H) if h not in [d[0] for d in diffs]]
-    if scores_gpu is not None and same:
-        assert_scores_close(scores_gpu[same], ref["scores"][same], f"layer {layer}: refined scores",
-                            start=ref["s0"][same])
-    if not diffs:
+    off = {}      # heads with the oracle's retained set whose refined scores are out of tolerance
+    if scores_gpu is not None:
+        for h in same:
+            try:
+                assert_scores_close(scores_gpu[h:h + 1], ref["scores"][h:h + 1], f"layer {layer} head {h}: refined scores",
+                                    start=ref["s0"][h:h + 1])
+            except AssertionError as err:
+                off[h] = err
+    if not diffs and not off:
         return diffs
     st = staged_gpu_run(p, dev, budget=B)
     assert np.array_equal(st["idx"], idx_gpu), "the stages called one by one give other indices than the whole pass"
     dt = "fp32" if p.dtype == gk.FP32 else "bf16"
     A_np = V if p.edges == gk.EDGES_VV else K
     B_np = None if p.edges == gk.EDGES_KK else V
-    for h, nd in diffs:
+    for h, nd in diffs + [(h, 0) for h in off]:
         stage, t, a, gap = first_divergence(ref, st, h)
         case = dict(layer=layer, head=h, stage=stage, round=t, source_slot=a, gap=gap, n_different=nd)
-        assert gap < REL_TOL, f"retained set differs but the first differing cut is no near-tie: {case}"
+        if h in off:
+            # same retained set, other scores: only an earlier cut that went the other way explains that
+            if stage == "final":
+                raise off[h]
+            assert np.array_equal(st["s"][-1][h], scores_gpu[h]), f"staged and whole-pass scores differ: {case}"
+        assert gap < REL_TOL, f"picks differ but the first differing cut is no near-tie: {case}"
         if not st["noop"]:
             rounds = range(len(st["src"])) if p.reselect else [0]
             for r in rounds:
