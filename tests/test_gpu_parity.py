@@ -888,6 +888,18 @@ def test_full_size_batched_c3(oracle):
         assert np.array_equal(one[2], idx2_h[l]) and np.array_equal(one[0], Ko2[l]), f"layer {l}"
 
 
+def test_million_token_prompt(oracle):
+    """A prompt of 2^20 + 77 tokens on one head (32-bit offsets, 24-bit key numbers in the candidate
+    lists, the streaming top-k, key chunks of 8192 sampled keys): the whole pass against the oracle.
+    (A 4 M-token run of the same script agrees as well; it takes half a minute, mostly the oracle.)"""
+    cfg = synth.scaled(synth.CONFIGS["c2"], n_tokens=(1 << 20) + 77, window=32, n_kv_heads=1, n_q_heads=1,
+                       budget=5000, n_sources=6, n_neighbors=20, rounds=2)
+    say(f"million-token prompt: N={cfg.n_tokens}")
+    diffs, _, (out, sc, ref) = end_to_end(oracle, cfg, 3, gk.IMPL_AUTO)
+    assert gk.graphkv_uses_mfma(util.params_from_cfg(cfg, 3))
+    assert not diffs or util.EXCUSED     # (a differing head has been judged and recorded by end_to_end)
+
+
 def long_context_head():
     """One KV head (4 query heads) of the long-context workload: N = 131072, w = 64 (256
     stacked query rows), S = m = 128, 10 % near-duplicate keys."""
